@@ -1,0 +1,393 @@
+"""Plain CPU oracle for the Parallel Q-Learning (PQL) learner hot path.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of what the
+learner path computes, written in NumPy float64 straight from the paper's description of
+the method (Section 3, Algorithms 1-3, Table B.1).  Only the test-suite, the smoke check
+and the benchmark's CPU-baseline leg may use it; the product never calls it and shares no
+code with it.
+
+Every function states the passage it follows.  Where the paper only names a technique
+(DDPG, double Q-learning, n-step returns, Adam, mean-squared Bellman error) the textbook
+definition of that technique is written out.
+
+Conventions
+-----------
+* A network is one flat vector: per layer ``W[in, out]`` row-major then ``b[out]``
+  (``y = x W + b``).  Hidden layers use ELU (alpha = 1); the critic output is linear and
+  scalar, the actor output passes through tanh.  The critic input is ``concat(s, a)``.
+* The replay memory is a ring of ``T`` rows; one row is one Actor step of all ``N``
+  parallel environments (Section 3.1, "Data Transfer").  Slot = row * N + env.
+* Random draws come from the counter-based generator Philox-4x32-10 (Salmon et al.,
+  SC'11), implemented here from its published definition.
+
+Parity status: the paper prints no numeric value of any loss, Q-value or parameter, so
+agreement with the authors' own implementation is *parity unpinned*; every function below
+is pinned by the definitional checks in ``tests/test_oracle_*.py``.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+MASK32 = 0xFFFFFFFF
+MASK64 = 0xFFFFFFFFFFFFFFFF
+
+STREAM_SAMPLE = 1   # index sampling draws
+STREAM_ACT = 2      # exploration-noise draws
+
+
+# --------------------------------------------------------------------------------------
+# Philox-4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3")
+# --------------------------------------------------------------------------------------
+_PHILOX_M0 = 0xD2511F53
+_PHILOX_M1 = 0xCD9E8D57
+_PHILOX_W0 = 0x9E3779B9
+_PHILOX_W1 = 0xBB67AE85
+
+
+def philox4x32_10(ctr, key):
+    """Ten rounds of Philox-4x32 on arrays of counters.
+
+    ``ctr``: four integer arrays (same shape), each value < 2**32.  ``key``: two Python
+    ints < 2**32.  Returns four uint64 arrays holding 32-bit outputs.
+    """
+    c0, c1, c2, c3 = (np.asarray(c, dtype=np.uint64) & np.uint64(MASK32) for c in ctr)
+    k0, k1 = int(key[0]) & MASK32, int(key[1]) & MASK32
+    m32 = np.uint64(MASK32)
+    s32 = np.uint64(32)
+    for _ in range(10):
+        p0 = np.uint64(_PHILOX_M0) * c0          # 32x32 -> 64 bit products
+        p1 = np.uint64(_PHILOX_M1) * c2
+        hi0, lo0 = p0 >> s32, p0 & m32
+        hi1, lo1 = p1 >> s32, p1 & m32
+        c0, c1, c2, c3 = (hi1 ^ c1 ^ np.uint64(k0), lo1, hi0 ^ c3 ^ np.uint64(k1), lo0)
+        k0 = (k0 + _PHILOX_W0) & MASK32
+        k1 = (k1 + _PHILOX_W1) & MASK32
+    return c0, c1, c2, c3
+
+
+def rng_words(seed: int, stream: int, call: int, k):
+    """Four 32-bit words for element ``k`` of draw ``call`` on ``stream``.
+
+    Counter = (k mod 2^32, stream, call mod 2^32, call >> 32); key = (seed mod 2^32,
+    seed >> 32).  ``k`` is an integer array with values < 2**32.
+    """
+    k = np.asarray(k, dtype=np.uint64)
+    one = np.ones_like(k)
+    ctr = (k, one * np.uint64(stream & MASK32), one * np.uint64(call & MASK32),
+           one * np.uint64((call >> 32) & MASK32))
+    return philox4x32_10(ctr, (seed & MASK32, (seed >> 32) & MASK32))
+
+
+# --------------------------------------------------------------------------------------
+# Replay ring (Section 3.1: the V-learner keeps its replay buffer on the GPU; the Actor
+# sends N tuples (s_t, a_t, s_{t+1}, r_t, d_{t+1}) per step)
+# --------------------------------------------------------------------------------------
+class ReplayRing:
+    """Circular store of Actor steps.  Contents are kept in the dtype they arrive in
+    (fp32): pushing is a copy, so stored values are bit-identical to the inputs."""
+
+    def __init__(self, rows: int, num_envs: int, obs_dim: int, act_dim: int):
+        self.T, self.N, self.o, self.a = int(rows), int(num_envs), int(obs_dim), int(act_dim)
+        n = self.T * self.N
+        self.obs = np.zeros((n, self.o), dtype=np.float32)
+        self.act = np.zeros((n, self.a), dtype=np.float32)
+        self.rew = np.zeros((n,), dtype=np.float32)
+        self.next_obs = np.zeros((n, self.o), dtype=np.float32)
+        self.done = np.zeros((n,), dtype=np.float32)
+        self.head = 0     # row the next push writes
+        self.count = 0    # number of valid rows
+
+    def push(self, obs, act, rew, next_obs, done):
+        """Algorithm 1 (the Actor appends one step of N tuples) / Algorithm 3 (the
+        V-learner adds received tuples to its buffer); the oldest row is overwritten
+        once the ring is full."""
+        lo, hi = self.head * self.N, (self.head + 1) * self.N
+        self.obs[lo:hi] = obs
+        self.act[lo:hi] = act
+        self.rew[lo:hi] = rew
+        self.next_obs[lo:hi] = next_obs
+        self.done[lo:hi] = done
+        self.head = (self.head + 1) % self.T
+        self.count = min(self.count + 1, self.T)
+
+    def physical_row(self, j):
+        """Chronological row j (0 = oldest valid) -> physical ring row."""
+        return (self.head - self.count + j) % self.T
+
+
+def sample_indices(ring: ReplayRing, nstep: int, batch: int, seed: int, call: int):
+    """I.i.d. uniform start slots, with replacement (Section 3.1: the V-learner samples
+    "a batch of I.I.D. training data"; Algorithm 3).
+
+    Valid starts are the (count - n + 1) * N (row, env) pairs whose n-row window lies
+    entirely inside the valid, chronologically contiguous part of the ring.  Sample k:
+    u = 64-bit word (w1 << 32 | w0) of the generator; p = floor(u * V / 2^64);
+    chronological row j = p div N, env e = p mod N; result = physical_row(j) * N + e.
+    """
+    if ring.count < nstep:
+        raise ValueError("not enough rows pushed for an n-step window")
+    V = (ring.count - nstep + 1) * ring.N
+    w0, w1, _, _ = rng_words(seed, STREAM_SAMPLE, call, np.arange(batch, dtype=np.uint64))
+    idx = np.empty(batch, dtype=np.int64)
+    for k in range(batch):                      # exact big-integer arithmetic
+        u = (int(w1[k]) << 32) | int(w0[k])
+        p = (u * V) >> 64
+        j, e = divmod(p, ring.N)
+        idx[k] = ring.physical_row(j) * ring.N + e
+    return idx
+
+
+def gather_nstep(ring: ReplayRing, idx, nstep: int, gamma: float):
+    """n-step return assembly with termination masking (Section 3: the scheme uses
+    n-step returns [Sutton 1988]; d marks termination; Table B.1: n = 3).
+
+    For start slot (row0, e) and rows row_k = row0 + k (mod T), k = 0..n-1:
+        ret  = sum_k gamma^k * r[row_k, e] * alive_k,   alive_0 = 1,
+               alive_{k+1} = alive_k * (1 - d[row_k, e])
+        boot = gamma^n * alive_n
+    s, a come from row_0; s' is the next-state of row_{n-1}.  The bootstrapped target is
+    then ret + boot * Q'(s', .): once a termination occurs inside the window every later
+    reward and the bootstrap are masked out.
+    """
+    idx = np.asarray(idx, dtype=np.int64)
+    N, T = ring.N, ring.T
+    row0, env = idx // N, idx % N
+    B = idx.shape[0]
+    ret = np.zeros(B, dtype=np.float64)
+    alive = np.ones(B, dtype=np.float64)
+    g = 1.0
+    last = idx
+    for k in range(nstep):
+        slot = ((row0 + k) % T) * N + env
+        ret += g * ring.rew[slot].astype(np.float64) * alive
+        alive = alive * (1.0 - ring.done[slot].astype(np.float64))
+        g *= gamma
+        last = slot
+    boot = g * alive
+    return dict(idx=idx, obs=ring.obs[idx].copy(), act=ring.act[idx].copy(), ret=ret,
+                next_obs=ring.next_obs[last].copy(), boot=boot)
+
+
+# --------------------------------------------------------------------------------------
+# Networks
+# --------------------------------------------------------------------------------------
+def unpack(params, dims):
+    """Split a flat parameter vector into [(W[in,out], b[out]), ...] (float64 views)."""
+    p = np.asarray(params, dtype=np.float64)
+    layers, off = [], 0
+    for n_in, n_out in dims:
+        W = p[off:off + n_in * n_out].reshape(n_in, n_out)
+        off += n_in * n_out
+        b = p[off:off + n_out]
+        off += n_out
+        layers.append((W, b))
+    assert off == p.size, "parameter vector length does not match the layer dims"
+    return layers
+
+
+def pack(layers):
+    return np.concatenate([np.concatenate([W.reshape(-1), b.reshape(-1)]) for W, b in layers])
+
+
+def elu(z):
+    return np.where(z > 0, z, np.exp(np.minimum(z, 0.0)) - 1.0)
+
+
+def elu_prime(z):
+    return np.where(z > 0, 1.0, np.exp(np.minimum(z, 0.0)))
+
+
+def mlp_forward(layers, x):
+    """Returns (pre-activations z_l, activations h_l with h_0 = x).  Hidden layers ELU,
+    last layer linear (the caller applies tanh for the actor)."""
+    hs, zs = [np.asarray(x, dtype=np.float64)], []
+    for li, (W, b) in enumerate(layers):
+        z = hs[-1] @ W + b
+        zs.append(z)
+        hs.append(elu(z) if li < len(layers) - 1 else z)
+    return zs, hs
+
+
+def mlp_backward(layers, zs, hs, d_out):
+    """Reverse-mode derivative of ``mlp_forward``.  ``d_out`` = dLoss/d(output).
+    Returns (per-layer (dW, db), dLoss/d(input))."""
+    grads = [None] * len(layers)
+    delta = d_out
+    for li in range(len(layers) - 1, -1, -1):
+        W, _ = layers[li]
+        grads[li] = (hs[li].T @ delta, delta.sum(axis=0))
+        delta = delta @ W.T
+        if li > 0:
+            delta = delta * elu_prime(zs[li - 1])
+    return grads, delta
+
+
+def actor_forward(actor_params, actor_dims, obs):
+    zs, hs = mlp_forward(unpack(actor_params, actor_dims), obs)
+    return np.tanh(hs[-1])
+
+
+def critic_forward(critic_params, critic_dims, obs, act):
+    x = np.concatenate([np.asarray(obs, np.float64), np.asarray(act, np.float64)], axis=1)
+    zs, hs = mlp_forward(unpack(critic_params, critic_dims), x)
+    return hs[-1][:, 0]
+
+
+def split_twin(twin_params):
+    p = np.asarray(twin_params)
+    half = p.size // 2
+    return p[:half], p[half:]
+
+
+# --------------------------------------------------------------------------------------
+# V-learner: target and critic update (Algorithm 3; Section 3.2 "Third": the lagged local
+# policy acts as the target policy; Q' is the target Q network; min over the twin critics
+# as in Algorithm 2)
+# --------------------------------------------------------------------------------------
+def td_target(batch, actor_target_params, critic_target_params, actor_dims, critic_dims):
+    """y = ret + boot * min_i Q'_i(s', pi^v(s'))."""
+    a_next = actor_forward(actor_target_params, actor_dims, batch["next_obs"])
+    t1, t2 = split_twin(critic_target_params)
+    q1 = critic_forward(t1, critic_dims, batch["next_obs"], a_next)
+    q2 = critic_forward(t2, critic_dims, batch["next_obs"], a_next)
+    return np.asarray(batch["ret"], np.float64) + np.asarray(batch["boot"], np.float64) * np.minimum(q1, q2)
+
+
+def critic_loss_and_grads(critic_params, critic_dims, batch, y):
+    """Mean-squared Bellman error of both critics against the shared target y
+    (Algorithm 3).  L_i = mean_b (Q_i(s_b, a_b) - y_b)^2; the optimised loss is L_1 + L_2;
+    y is a constant.  Returns ([L_1, L_2], flat gradient in parameter layout)."""
+    x = np.concatenate([np.asarray(batch["obs"], np.float64), np.asarray(batch["act"], np.float64)], axis=1)
+    B = x.shape[0]
+    losses, flat = [], []
+    for p in split_twin(critic_params):
+        layers = unpack(p, critic_dims)
+        zs, hs = mlp_forward(layers, x)
+        err = hs[-1][:, 0] - y
+        losses.append(float(np.mean(err * err)))
+        grads, _ = mlp_backward(layers, zs, hs, (2.0 * err / B)[:, None])
+        flat.append(pack(grads))
+    return np.array(losses), np.concatenate(flat)
+
+
+# --------------------------------------------------------------------------------------
+# P-learner: policy update (Algorithm 2: maximise min_i Q_i(s, pi(s)))
+# --------------------------------------------------------------------------------------
+def actor_loss_and_grads(actor_params, critic_params, actor_dims, critic_dims, obs):
+    """J = -mean_b min(Q_1(s_b, pi(s_b)), Q_2(s_b, pi(s_b))); gradient w.r.t. the actor
+    parameters only (the critics are constants here).  Ties go to Q_1."""
+    obs = np.asarray(obs, np.float64)
+    B = obs.shape[0]
+    a_layers = unpack(actor_params, actor_dims)
+    a_zs, a_hs = mlp_forward(a_layers, obs)
+    a_pi = np.tanh(a_hs[-1])
+    x = np.concatenate([obs, a_pi], axis=1)
+    qs, caches = [], []
+    for p in split_twin(critic_params):
+        layers = unpack(p, critic_dims)
+        zs, hs = mlp_forward(layers, x)
+        qs.append(hs[-1][:, 0])
+        caches.append((layers, zs, hs))
+    pick1 = qs[0] <= qs[1]
+    J = -float(np.mean(np.where(pick1, qs[0], qs[1])))
+    d_act = np.zeros_like(a_pi)
+    for sel, (layers, zs, hs) in zip((pick1, ~pick1), caches):
+        d_q = np.where(sel, -1.0 / B, 0.0)[:, None]
+        _, d_x = mlp_backward(layers, zs, hs, d_q)
+        d_act += d_x[:, obs.shape[1]:]
+    d_pre = d_act * (1.0 - a_pi * a_pi)           # tanh'
+    grads, _ = mlp_backward(a_layers, a_zs, a_hs, d_pre)
+    return J, pack(grads)
+
+
+# --------------------------------------------------------------------------------------
+# Optimiser and target tracking (Table B.1: Adam, learning rate 5e-4, target update rate
+# tau = 5e-2)
+# --------------------------------------------------------------------------------------
+def adam_step(theta, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One step of Adam (Kingma & Ba, Algorithm 1) with bias correction; ``t`` is the
+    1-based step number.  Returns (theta, m, v)."""
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** t)
+    v_hat = v / (1.0 - beta2 ** t)
+    return theta - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
+
+
+def soft_update(src, dst, tau):
+    """Polyak tracking of the target network: dst <- tau * src + (1 - tau) * dst.
+    tau = 1 is the hard copy used to refresh the V-learner's lagged policy
+    (Section 3.2)."""
+    return tau * np.asarray(src, np.float64) + (1.0 - tau) * np.asarray(dst, np.float64)
+
+
+# --------------------------------------------------------------------------------------
+# Actor: exploration step (Section 3.3; Algorithm 1)
+# --------------------------------------------------------------------------------------
+def exploration_sigma(num_envs: int, sigma_min: float, sigma_max: float):
+    """Mixed exploration: sigma_i = sigma_min + (i-1)/(N-1) (sigma_max - sigma_min),
+    i = 1..N (returned 0-based).  N = 1 gives sigma_min."""
+    if num_envs == 1:
+        return np.array([sigma_min], dtype=np.float64)
+    i = np.arange(num_envs, dtype=np.float64)
+    return sigma_min + (i / (num_envs - 1)) * (sigma_max - sigma_min)
+
+
+def gaussian_noise(seed: int, call: int, count: int):
+    """Standard normal draws, one per element index 0..count-1: Box-Muller on two 24-bit
+    uniforms u = ((word >> 8) + 0.5) / 2^24 taken from generator words 0 and 1."""
+    w0, w1, _, _ = rng_words(seed, STREAM_ACT, call, np.arange(count, dtype=np.uint64))
+    u1 = ((w0 >> np.uint64(8)).astype(np.float64) + 0.5) * 2.0 ** -24
+    u2 = ((w1 >> np.uint64(8)).astype(np.float64) + 0.5) * 2.0 ** -24
+    return np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+
+
+def actor_act(actor_params, actor_dims, obs, sigma_min, sigma_max, seed, call):
+    """a = clip(pi(s) + sigma_i * eps, -1, 1), eps ~ N(0,1) independently per
+    (environment, action dimension); element index = env * act_dim + dim."""
+    mu = actor_forward(actor_params, actor_dims, obs)
+    N, a = mu.shape
+    eps = gaussian_noise(seed, call, N * a).reshape(N, a)
+    sig = exploration_sigma(N, sigma_min, sigma_max)[:, None]
+    return np.clip(mu + sig * eps, -1.0, 1.0)
+
+
+# --------------------------------------------------------------------------------------
+# A whole learner, for multi-step parity runs
+# --------------------------------------------------------------------------------------
+class Learner:
+    """Holds the V-/P-learner state in float64 and applies the steps above in the order
+    the paper's loops do.  Parameters enter as fp32 arrays and are promoted."""
+
+    def __init__(self, actor_dims, critic_dims, actor_params, critic_params, lr, gamma, tau,
+                 beta1=0.9, beta2=0.999, eps=1e-8):
+        self.actor_dims, self.critic_dims = actor_dims, critic_dims
+        self.actor = np.asarray(actor_params, np.float64).copy()
+        self.actor_lag = self.actor.copy()            # pi^v, the V-learner's lagged policy
+        self.critic = np.asarray(critic_params, np.float64).copy()
+        self.critic_target = self.critic.copy()
+        self.c_m = np.zeros_like(self.critic); self.c_v = np.zeros_like(self.critic); self.c_t = 0
+        self.a_m = np.zeros_like(self.actor); self.a_v = np.zeros_like(self.actor); self.a_t = 0
+        self.lr, self.gamma, self.tau = lr, gamma, tau
+        self.beta1, self.beta2, self.eps = beta1, beta2, eps
+
+    def critic_update(self, batch):
+        y = td_target(batch, self.actor_lag, self.critic_target, self.actor_dims, self.critic_dims)
+        losses, g = critic_loss_and_grads(self.critic, self.critic_dims, batch, y)
+        self.c_t += 1
+        self.critic, self.c_m, self.c_v = adam_step(self.critic, g, self.c_m, self.c_v, self.c_t,
+                                                    self.lr, self.beta1, self.beta2, self.eps)
+        return losses, g
+
+    def soft_update_targets(self):
+        self.critic_target = soft_update(self.critic, self.critic_target, self.tau)
+
+    def actor_update(self, obs):
+        J, g = actor_loss_and_grads(self.actor, self.critic, self.actor_dims, self.critic_dims, obs)
+        self.a_t += 1
+        self.actor, self.a_m, self.a_v = adam_step(self.actor, g, self.a_m, self.a_v, self.a_t,
+                                                   self.lr, self.beta1, self.beta2, self.eps)
+        return J, g
+
+    def sync_lagged_policy(self):
+        self.actor_lag = soft_update(self.actor, self.actor_lag, 1.0)
