@@ -1,0 +1,187 @@
+/*
+ * libpql — the learner hot path of Parallel Q-Learning (PQL, Li et al., ICML 2023) for one
+ * AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * What the calls compute follows the paper's own statement of the method:
+ *   - Section 3.1 (Scheme overview, "Data Transfer"): the Actor produces N tuples
+ *     (s_t, a_t, s_{t+1}, r_t, d_{t+1}) per step; the V-learner keeps its replay buffer in GPU
+ *     memory and samples i.i.d. batches from it;
+ *   - Section 3 (Method): built on DDPG with double Q-learning, n-step returns, a target
+ *     network Q';
+ *   - Section 3.2: the V-learner's lagged local policy pi^v plays the role of the target policy
+ *     and is refreshed by hard copies;
+ *   - Section 3.3: mixed exploration noise;
+ *   - Algorithm 1 (Actor), Algorithm 2 (P-learner), Algorithm 3 (V-learner);
+ *   - Table B.1: Adam, target update rate tau, n = 3, gamma = 0.99, batch 8192.
+ *
+ * CONVENTIONS
+ *   Return value   Every function returning int32_t returns PQL_OK (0) or a negative PQL_ERR_*
+ *                  code.  Nothing aborts or throws across this boundary.  Argument errors are
+ *                  found on the host before any kernel is launched and leave all state
+ *                  (context counters and device buffers) unchanged.
+ *   Memory         The library allocates NO device memory.  Every pointer marked [device] is
+ *                  caller-owned device memory (fp32 unless stated) that must stay valid until
+ *                  the stream has drained; the library never frees it.  Pointers marked [host]
+ *                  are ordinary host memory.  The context (pql_ctx) is host memory owned by the
+ *                  library between pql_create and pql_destroy.
+ *   Streams        `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device
+ *                  calls enqueue work and return; none of them synchronises.  Scalar results
+ *                  (losses) are written to caller-provided device floats.
+ *   Workspace      pql_actor_act, pql_critic_update and pql_actor_update take a caller-owned
+ *                  [device] scratch buffer of at least pql_workspace_bytes(cfg) bytes, 256-byte
+ *                  aligned.  Its contents are undefined between calls.  Two calls that use the
+ *                  same workspace must be ordered on one stream.
+ *   Networks       A network is one flat fp32 vector: for each layer in order the weights
+ *                  W[in][out] row-major (y = x W + b), then the bias b[out].  Hidden layers use
+ *                  ELU (alpha = 1).  Actor: in = obs_dim, hidden..., out = act_dim, then tanh.
+ *                  Critic: in = obs_dim + act_dim (s and a concatenated), hidden..., out = 1,
+ *                  linear.  "Twin critics" = the vector of Q_1 immediately followed by that of
+ *                  Q_2.  Gradients and Adam moments use the same layout.  The caller initialises
+ *                  parameters.
+ *   Replay layout  The ring has T = capacity / num_envs rows; a row is one Actor step of all N
+ *                  environments; slot = row * N + env.  Fields are separate arrays:
+ *                  obs[T*N][obs_dim], act[T*N][act_dim], rew[T*N], next_obs[T*N][obs_dim],
+ *                  done[T*N] (0.0 / 1.0), all row-major fp32.
+ *   Random draws   Philox-4x32-10 (Salmon et al., SC'11) with key = the two halves of
+ *                  cfg.seed and counter = (element, stream id, call number low, call number
+ *                  high); stream id 1 = index sampling, 2 = exploration noise.  The call number
+ *                  is the context's sample / act counter, so a run is reproducible from
+ *                  (seed, state).
+ */
+#ifndef PQL_H
+#define PQL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PQL_OK                     0
+#define PQL_ERR_INVALID_ARG       -1   /* a size, dimension or scalar is out of range          */
+#define PQL_ERR_NULL              -2   /* a required pointer is NULL                            */
+#define PQL_ERR_NOT_ENOUGH_DATA   -3   /* fewer than nstep rows have been pushed                */
+#define PQL_ERR_BATCH_TOO_LARGE   -4   /* batch exceeds cfg.max_batch (workspace sizing)        */
+#define PQL_ERR_HIP               -5   /* a HIP runtime call failed; see pql_last_error         */
+#define PQL_ERR_ALIGNMENT         -6   /* a device pointer is not aligned as required           */
+
+#define PQL_MAX_HIDDEN 8
+
+typedef struct pql_ctx pql_ctx;
+
+typedef struct {
+    int32_t  obs_dim;                 /* o >= 1                                                  */
+    int32_t  act_dim;                 /* a >= 1                                                  */
+    int32_t  num_envs;                /* N >= 1 parallel environments                            */
+    int64_t  capacity;                /* replay size in transitions; T = capacity / N >= nstep   */
+    int32_t  nstep;                   /* n >= 1 (Table B.1: 3)                                   */
+    float    gamma;                   /* discount in (0, 1]                                      */
+    int32_t  n_hidden;                /* 1..PQL_MAX_HIDDEN hidden layers, same for actor/critic  */
+    int32_t  hidden[PQL_MAX_HIDDEN];  /* widths, each >= 1                                       */
+    int32_t  max_batch;               /* largest batch_size / num_envs any call will use         */
+    uint64_t seed;                    /* key of the counter-based generator                      */
+} pql_config;
+
+/* [device] replay storage, sizes as under "Replay layout". */
+typedef struct { float *obs, *act, *rew, *next_obs, *done; } pql_replay_storage;
+
+/* [device] one sampled batch of B rows: idx[B] (int64 start slots), obs[B][o], act[B][a],
+ * ret[B] (discounted n-step reward sum), next_obs[B][o] (state after the n-th step),
+ * boot[B] (gamma^n times the product of (1 - d) over the window). */
+typedef struct { int64_t *idx; float *obs, *act, *ret, *next_obs, *boot; } pql_batch;
+
+/* Adam hyper-parameters (Table B.1 names the optimiser and the learning rate). */
+typedef struct { float lr, beta1, beta2, eps; } pql_adam;
+
+/* ---- context and host-side queries (no device work) ------------------------------------ */
+
+/* Validates cfg ([host]) and creates a context holding the ring cursor and call counters.
+ * Errors: PQL_ERR_NULL, PQL_ERR_INVALID_ARG. */
+int32_t pql_create(const pql_config* cfg, pql_ctx** out);
+int32_t pql_destroy(pql_ctx* ctx);
+
+int64_t pql_replay_rows(const pql_config* cfg);        /* T, or negative error                  */
+int64_t pql_actor_param_count(const pql_config* cfg);  /* floats in the actor vector            */
+int64_t pql_critic_param_count(const pql_config* cfg); /* floats in ONE critic vector           */
+int64_t pql_workspace_bytes(const pql_config* cfg);    /* bytes of scratch for max_batch rows   */
+
+/* Text of the last error recorded in ctx; owned by the context, valid until the next call. */
+const char* pql_last_error(const pql_ctx* ctx);
+
+/* Host state: [0] head row, [1] valid rows, [2] pushes so far, [3] sample calls so far,
+ * [4] act calls so far, [5] critic Adam steps, [6] actor Adam steps, [7] reserved (0).
+ * Setting it resumes a run bit-exactly on the same device buffers. */
+int32_t pql_get_state(const pql_ctx* ctx, int64_t out[8]);
+int32_t pql_set_state(pql_ctx* ctx, const int64_t in[8]);
+
+/* ---- replay (Section 3.1; Algorithm 1 append; Algorithm 3 receive + sample) ------------- */
+
+/* Writes one Actor step — N transitions (obs[N][o], act[N][a], rew[N], next_obs[N][o], done[N],
+ * all [device]) — into ring row `head`, then head = (head + 1) mod T and
+ * count = min(count + 1, T).  The oldest row is overwritten when the ring is full.  The copy is
+ * bit-exact.  Source arrays must not alias the storage. */
+int32_t pql_replay_push(pql_ctx* ctx, pql_replay_storage storage, const float* obs, const float* act,
+                        const float* rew, const float* next_obs, const float* done, void* stream);
+
+/* Draws `batch` i.i.d. uniform start slots (with replacement) among the (count - n + 1) * N
+ * windows of n consecutive rows that lie inside the valid part of the ring, and assembles the
+ * n-step batch for them (Section 3: n-step returns; Algorithm 3 "sample a batch"):
+ *     ret  = sum_{k<n} gamma^k r_k prod_{j<k} (1 - d_j),   boot = gamma^n prod_{j<n} (1 - d_j),
+ * obs/act from the first row of the window, next_obs from its last row.
+ * Sample k uses the 64-bit draw u = (word1 << 32) | word0 and position floor(u * V / 2^64).
+ * Advances the sample counter.  Errors: PQL_ERR_NOT_ENOUGH_DATA if count < n,
+ * PQL_ERR_BATCH_TOO_LARGE, PQL_ERR_NULL. */
+int32_t pql_sample_nstep(pql_ctx* ctx, pql_replay_storage storage, int32_t batch, pql_batch out, void* stream);
+
+/* Same assembly for caller-given start slots idx[batch] ([device], each slot must start a
+ * window inside the valid rows; the caller guarantees it).  out.idx is not written.  Does not
+ * touch the sample counter. */
+int32_t pql_gather_nstep(pql_ctx* ctx, pql_replay_storage storage, const int64_t* idx, int32_t batch,
+                         pql_batch out, void* stream);
+
+/* ---- Actor step (Section 3.3; Algorithm 1 "a_t <- pi(s_t) with mixed exploration noise") -- */
+
+/* act_out[n][j] = clip(pi(obs[n]) [j] + sigma_n * eps, -1, 1) for the `num` environments in
+ * obs[num][o] ([device]); sigma_n = sigma_min + n/(num-1) * (sigma_max - sigma_min)
+ * (sigma_min when num == 1); eps ~ N(0,1) by Box-Muller from words 0 and 1 of the draw for
+ * element n * act_dim + j, each turned into a 24-bit uniform ((w >> 8) + 0.5) / 2^24.
+ * num <= cfg.max_batch.  Advances the act counter. */
+int32_t pql_actor_act(pql_ctx* ctx, const float* actor_params, const float* obs, int32_t num,
+                      float sigma_min, float sigma_max, float* act_out, void* workspace, void* stream);
+
+/* ---- V-learner step (Algorithm 3 "update Q_1, Q_2 by minimizing the mean-squared Bellman
+ *      error (with Double Q-learning)"; Section 3.2 for the lagged target policy) ----------- */
+
+/* y = ret + boot * min_i Q'_i(next_obs, pi^v(next_obs));  L_i = mean_b (Q_i(obs, act) - y)^2;
+ * gradient of L_1 + L_2 w.r.t. critic_params (y is a constant) is written to grads_out, then
+ * one Adam step (bias-corrected, eps outside the root) updates critic_params, adam_m, adam_v
+ * in place.  loss_out[2] ([device]) receives L_1, L_2 evaluated before the step.
+ * critic_params / critic_target_params / adam_m / adam_v / grads_out: twin-critic vectors
+ * (2 * pql_critic_param_count floats); actor_target_params: the lagged policy pi^v.
+ * Advances the critic Adam step counter. */
+int32_t pql_critic_update(pql_ctx* ctx, float* critic_params, const float* critic_target_params,
+                          const float* actor_target_params, float* adam_m, float* adam_v, float* grads_out,
+                          pql_batch batch, int32_t batch_size, pql_adam opt, float* loss_out,
+                          void* workspace, void* stream);
+
+/* ---- P-learner step (Algorithm 2 "update pi by maximizing min_i Q_i(s, pi(s))") ---------- */
+
+/* J = -mean_b min(Q_1, Q_2)(obs_b, pi(obs_b)); the gradient w.r.t. actor_params flows through
+ * the action input of whichever critic is smaller per row (ties: Q_1); critics are read-only.
+ * Writes grads_out (actor layout), performs one Adam step on actor_params/adam_m/adam_v,
+ * stores J (before the step) in loss_out[1] ([device]).  Advances the actor Adam counter. */
+int32_t pql_actor_update(pql_ctx* ctx, float* actor_params, const float* critic_params, float* adam_m,
+                         float* adam_v, float* grads_out, const float* obs, int32_t batch_size, pql_adam opt,
+                         float* loss_out, void* workspace, void* stream);
+
+/* ---- target tracking (Table B.1 target update rate; Section 3.2 hard policy sync) -------- */
+
+/* dst[i] = tau * src[i] + (1 - tau) * dst[i] for i < count ([device], may not partially
+ * overlap).  tau = 1 copies src bit-exactly, tau = 0 leaves dst bit-exactly unchanged.
+ * 0 <= tau <= 1. */
+int32_t pql_soft_update(pql_ctx* ctx, const float* src, float* dst, int64_t count, float tau, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PQL_H */

@@ -1,0 +1,227 @@
+"""Thin ctypes binding over ``libpql.so`` (declared in ``include/pql.h``).
+
+Argument marshalling only: every function here forwards device pointers
+(``torch.Tensor.data_ptr()``) and sizes to the C entry point of the same name.  PyTorch is
+used for device memory and streams, nothing else.  There is no CPU fallback: if the HIP
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpql.so")
+
+PQL_MAX_HIDDEN = 8
+ERRORS = {0: "PQL_OK", -1: "PQL_ERR_INVALID_ARG", -2: "PQL_ERR_NULL", -3: "PQL_ERR_NOT_ENOUGH_DATA",
+          -4: "PQL_ERR_BATCH_TOO_LARGE", -5: "PQL_ERR_HIP", -6: "PQL_ERR_ALIGNMENT"}
+
+# every symbol include/pql.h declares
+EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_count", "pql_critic_param_count",
+           "pql_workspace_bytes", "pql_last_error", "pql_get_state", "pql_set_state", "pql_replay_push",
+           "pql_sample_nstep", "pql_gather_nstep", "pql_actor_act", "pql_critic_update", "pql_actor_update",
+           "pql_soft_update"]
+
+
+class PqlConfig(C.Structure):
+    _fields_ = [("obs_dim", C.c_int32), ("act_dim", C.c_int32), ("num_envs", C.c_int32), ("capacity", C.c_int64),
+                ("nstep", C.c_int32), ("gamma", C.c_float), ("n_hidden", C.c_int32),
+                ("hidden", C.c_int32 * PQL_MAX_HIDDEN), ("max_batch", C.c_int32), ("seed", C.c_uint64)]
+
+
+class PqlStorage(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("obs", "act", "rew", "next_obs", "done")]
+
+
+class PqlBatch(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("idx", "obs", "act", "ret", "next_obs", "boot")]
+
+
+class PqlAdam(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
+
+
+class PqlError(RuntimeError):
+    def __init__(self, code: int, msg: str = ""):
+        self.code = code
+        super().__init__("%s (%d) %s" % (ERRORS.get(code, "?"), code, msg))
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libpql.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libpql.so is missing: build it with `python -m paper_2307_12983_amd.build` "
+                           "(the HIP library is the only implementation)")
+    lib = C.CDLL(LIB_PATH)
+    P, I32, I64, F = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    cfgp = C.POINTER(PqlConfig)
+    sig = {
+        "pql_create": (I32, [cfgp, C.POINTER(P)]),
+        "pql_destroy": (I32, [P]),
+        "pql_replay_rows": (I64, [cfgp]),
+        "pql_actor_param_count": (I64, [cfgp]),
+        "pql_critic_param_count": (I64, [cfgp]),
+        "pql_workspace_bytes": (I64, [cfgp]),
+        "pql_last_error": (C.c_char_p, [P]),
+        "pql_get_state": (I32, [P, C.POINTER(I64)]),
+        "pql_set_state": (I32, [P, C.POINTER(I64)]),
+        "pql_replay_push": (I32, [P, PqlStorage, P, P, P, P, P, P]),
+        "pql_sample_nstep": (I32, [P, PqlStorage, I32, PqlBatch, P]),
+        "pql_gather_nstep": (I32, [P, PqlStorage, P, I32, PqlBatch, P]),
+        "pql_actor_act": (I32, [P, P, P, I32, F, F, P, P, P]),
+        "pql_critic_update": (I32, [P, P, P, P, P, P, P, PqlBatch, I32, PqlAdam, P, P, P]),
+        "pql_actor_update": (I32, [P, P, P, P, P, P, P, I32, PqlAdam, P, P, P]),
+        "pql_soft_update": (I32, [P, P, P, I64, F, P]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def make_config(obs_dim, act_dim, num_envs, capacity, nstep, gamma, hidden: Sequence[int], max_batch, seed) -> PqlConfig:
+    cfg = PqlConfig()
+    cfg.obs_dim, cfg.act_dim, cfg.num_envs, cfg.capacity = obs_dim, act_dim, num_envs, capacity
+    cfg.nstep, cfg.gamma, cfg.n_hidden, cfg.max_batch, cfg.seed = nstep, gamma, len(hidden), max_batch, seed
+    for i, h in enumerate(hidden[:PQL_MAX_HIDDEN]):
+        cfg.hidden[i] = int(h)
+    return cfg
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    s = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    return s or None
+
+
+class Storage:
+    """Device tensors of the replay ring (caller-owned memory, allocated with torch)."""
+
+    def __init__(self, rows, num_envs, obs_dim, act_dim, device="cuda"):
+        import torch
+        n = rows * num_envs
+        self.obs = torch.zeros((n, obs_dim), dtype=torch.float32, device=device)
+        self.act = torch.zeros((n, act_dim), dtype=torch.float32, device=device)
+        self.rew = torch.zeros((n,), dtype=torch.float32, device=device)
+        self.next_obs = torch.zeros((n, obs_dim), dtype=torch.float32, device=device)
+        self.done = torch.zeros((n,), dtype=torch.float32, device=device)
+
+    def c(self) -> PqlStorage:
+        return PqlStorage(self.obs.data_ptr(), self.act.data_ptr(), self.rew.data_ptr(),
+                          self.next_obs.data_ptr(), self.done.data_ptr())
+
+
+class Batch:
+    """Device tensors receiving one sampled n-step batch."""
+
+    def __init__(self, batch, obs_dim, act_dim, device="cuda"):
+        import torch
+        self.idx = torch.zeros((batch,), dtype=torch.int64, device=device)
+        self.obs = torch.zeros((batch, obs_dim), dtype=torch.float32, device=device)
+        self.act = torch.zeros((batch, act_dim), dtype=torch.float32, device=device)
+        self.ret = torch.zeros((batch,), dtype=torch.float32, device=device)
+        self.next_obs = torch.zeros((batch, obs_dim), dtype=torch.float32, device=device)
+        self.boot = torch.zeros((batch,), dtype=torch.float32, device=device)
+
+    def c(self) -> PqlBatch:
+        return PqlBatch(self.idx.data_ptr(), self.obs.data_ptr(), self.act.data_ptr(), self.ret.data_ptr(),
+                        self.next_obs.data_ptr(), self.boot.data_ptr())
+
+
+class Context:
+    """Owns a ``pql_ctx`` and exposes the C entry points under their own names."""
+
+    def __init__(self, cfg: PqlConfig):
+        self.lib = load_library()
+        self.cfg = cfg
+        h = C.c_void_p()
+        rc = self.lib.pql_create(C.byref(cfg), C.byref(h))
+        if rc != 0:
+            raise PqlError(rc, "pql_create")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.pql_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc != 0:
+            raise PqlError(rc, (self.lib.pql_last_error(self.h) or b"").decode())
+
+    # ---- host queries
+    def replay_rows(self) -> int:
+        return self.lib.pql_replay_rows(C.byref(self.cfg))
+
+    def actor_param_count(self) -> int:
+        return self.lib.pql_actor_param_count(C.byref(self.cfg))
+
+    def critic_param_count(self) -> int:
+        return self.lib.pql_critic_param_count(C.byref(self.cfg))
+
+    def workspace_bytes(self) -> int:
+        return self.lib.pql_workspace_bytes(C.byref(self.cfg))
+
+    def last_error(self) -> str:
+        return (self.lib.pql_last_error(self.h) or b"").decode()
+
+    def get_state(self):
+        arr = (C.c_int64 * 8)()
+        self._check(self.lib.pql_get_state(self.h, arr))
+        return list(arr)
+
+    def set_state(self, state):
+        arr = (C.c_int64 * 8)(*state)
+        self._check(self.lib.pql_set_state(self.h, arr))
+
+    # ---- device calls
+    def pql_replay_push(self, storage, obs, act, rew, next_obs, done, stream=None):
+        self._check(self.lib.pql_replay_push(self.h, storage.c(), _ptr(obs), _ptr(act), _ptr(rew), _ptr(next_obs),
+                                             _ptr(done), _stream(stream)))
+
+    def pql_sample_nstep(self, storage, batch_size, out, stream=None):
+        self._check(self.lib.pql_sample_nstep(self.h, storage.c(), batch_size, out.c(), _stream(stream)))
+
+    def pql_gather_nstep(self, storage, idx, batch_size, out, stream=None):
+        self._check(self.lib.pql_gather_nstep(self.h, storage.c(), _ptr(idx), batch_size, out.c(), _stream(stream)))
+
+    def pql_actor_act(self, actor_params, obs, num, sigma_min, sigma_max, act_out, workspace, stream=None):
+        self._check(self.lib.pql_actor_act(self.h, _ptr(actor_params), _ptr(obs), num, sigma_min, sigma_max,
+                                           _ptr(act_out), _ptr(workspace), _stream(stream)))
+
+    def pql_critic_update(self, critic_params, critic_target_params, actor_target_params, adam_m, adam_v, grads_out,
+                          batch, batch_size, opt: PqlAdam, loss_out, workspace, stream=None):
+        self._check(self.lib.pql_critic_update(self.h, _ptr(critic_params), _ptr(critic_target_params),
+                                               _ptr(actor_target_params), _ptr(adam_m), _ptr(adam_v), _ptr(grads_out),
+                                               batch.c(), batch_size, opt, _ptr(loss_out), _ptr(workspace),
+                                               _stream(stream)))
+
+    def pql_actor_update(self, actor_params, critic_params, adam_m, adam_v, grads_out, obs, batch_size, opt: PqlAdam,
+                         loss_out, workspace, stream=None):
+        self._check(self.lib.pql_actor_update(self.h, _ptr(actor_params), _ptr(critic_params), _ptr(adam_m),
+                                              _ptr(adam_v), _ptr(grads_out), _ptr(obs), batch_size, opt,
+                                              _ptr(loss_out), _ptr(workspace), _stream(stream)))
+
+    def pql_soft_update(self, src, dst, count, tau, stream=None):
+        self._check(self.lib.pql_soft_update(self.h, _ptr(src), _ptr(dst), count, tau, _stream(stream)))

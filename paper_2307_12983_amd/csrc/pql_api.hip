@@ -1,0 +1,710 @@
+// C interface of libpql: context, argument validation, workspace layout and the launch
+// sequences of the learner steps.  All device work is done by the kernels in pql_gemm.hip and
+// pql_kernels.hip; this file only decides which problems go into which launch.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "pql_internal.h"
+
+using namespace pql;
+
+struct pql_ctx {
+    pql_config cfg;
+    int L;                       // hidden layers
+    int64_t T;                   // ring rows
+    int64_t head, count, pushes, samples, acts, critic_t, actor_t;
+    // parameter offsets (floats) inside one actor / one critic vector: W then b per layer
+    int64_t a_w[PQL_MAX_HIDDEN + 1], a_b[PQL_MAX_HIDDEN + 1], a_total;
+    int64_t c_w[PQL_MAX_HIDDEN + 1], c_b[PQL_MAX_HIDDEN + 1], c_total;
+    std::string err;
+};
+
+namespace {
+
+constexpr size_t ALIGN_F = 64;   // workspace buffers start on 256-byte boundaries
+inline size_t up(size_t x) { return (x + ALIGN_F - 1) / ALIGN_F * ALIGN_F; }
+
+int validate_cfg(const pql_config* c) {
+    if (!c) return PQL_ERR_NULL;
+    if (c->obs_dim < 1 || c->act_dim < 1 || c->num_envs < 1 || c->nstep < 1) return PQL_ERR_INVALID_ARG;
+    if (c->n_hidden < 1 || c->n_hidden > PQL_MAX_HIDDEN) return PQL_ERR_INVALID_ARG;
+    for (int i = 0; i < c->n_hidden; ++i)
+        if (c->hidden[i] < 1 || c->hidden[i] > 65536) return PQL_ERR_INVALID_ARG;
+    if (c->hidden[c->n_hidden - 1] > 1024) return PQL_ERR_INVALID_ARG;   // head kernel register budget
+    if (!(c->gamma > 0.f) || c->gamma > 1.f) return PQL_ERR_INVALID_ARG;
+    if (c->max_batch < 1) return PQL_ERR_INVALID_ARG;
+    if (c->capacity < (int64_t)c->num_envs * c->nstep) return PQL_ERR_INVALID_ARG;
+    if (c->capacity / c->num_envs > 0x7fffffffLL) return PQL_ERR_INVALID_ARG;
+    if ((int64_t)c->max_batch * c->act_dim > 0xffffffffLL) return PQL_ERR_INVALID_ARG;   // 32-bit element counter
+    return PQL_OK;
+}
+
+int64_t net_params(int in, const pql_config* c, int out, int64_t* w, int64_t* b) {
+    int64_t off = 0;
+    int prev = in;
+    for (int l = 0; l <= c->n_hidden; ++l) {
+        const int width = (l < c->n_hidden) ? c->hidden[l] : out;
+        if (w) w[l] = off;
+        off += (int64_t)prev * width;
+        if (b) b[l] = off;
+        off += width;
+        prev = width;
+    }
+    return off;
+}
+
+// ---- tile choice and split-K planning -------------------------------------------------------
+int choose_tile(int mode, const std::vector<GemmProb>& ps) {
+    int max_n = 0, max_m = 0;
+    long tiles128 = 0;
+    for (const GemmProb& p : ps) {
+        max_n = p.N > max_n ? p.N : max_n;
+        max_m = p.M > max_m ? p.M : max_m;
+        tiles128 += (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
+    }
+    if (mode == GEMM_TN) return (max_m >= 128 && max_n >= 128) ? TILE_128x128 : TILE_64x64;
+    if (max_n <= 32) return TILE_128x32;
+    if (max_n <= 64) return TILE_64x64;
+    return tiles128 >= 512 ? TILE_128x128 : TILE_64x64;
+}
+
+int colsum_rows(int tile, int M) { return ((M + gemm_tile_m(tile) - 1) / gemm_tile_m(tile)) * gemm_waves_m(tile); }
+
+// Upper bound on split count for K rows of batch and the given total of output tiles.
+int split_target(long tiles, int K) {
+    long s = (1024 + tiles - 1) / (tiles > 0 ? tiles : 1);
+    const long by_k = (K + 127) / 128;
+    if (s > by_k) s = by_k;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+struct Layout {
+    size_t hA[PQL_MAX_HIDDEN + 1], dA[PQL_MAX_HIDDEN + 1];           // index 1..L
+    size_t hT[2][PQL_MAX_HIDDEN + 1], hQ[2][PQL_MAX_HIDDEN + 1], dQ[2][PQL_MAX_HIDDEN + 1];
+    size_t colQ[2][PQL_MAX_HIDDEN + 1];                               // bias-grad partials of critic layer l
+    size_t colA[PQL_MAX_HIDDEN + 2];                                  // bias-grad partials of actor layer l (1..L+1)
+    size_t aOut, dPre, y, q[2];
+    size_t p_dw[2], p_dbh[2], p_db[2], p_loss;
+    size_t splitk;
+    size_t total;
+};
+
+// Weight-gradient problems are launched in two passes, one per tile shape.
+inline int dw_tile_of(int M, int N) { return (M >= 128 && N >= 128) ? TILE_128x128 : TILE_64x64; }
+inline long dw_tiles(int tile, int M, int N) {
+    return (long)((M + gemm_tile_m(tile) - 1) / gemm_tile_m(tile)) * ((N + gemm_tile_n(tile) - 1) / gemm_tile_n(tile));
+}
+
+// Floats of split-K slab space that a list of (M, N) weight-gradient problems can need for any
+// batch size up to K: per pass, (largest split count) x (sum of M*N).
+size_t dw_slab_bound(const std::vector<std::pair<int, int>>& mn, int K) {
+    size_t total = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tile = pass == 0 ? TILE_128x128 : TILE_64x64;
+        long tiles = 0;
+        size_t elems = 0;
+        for (const auto& d : mn) {
+            if (dw_tile_of(d.first, d.second) != tile) continue;
+            tiles += dw_tiles(tile, d.first, d.second);
+            elems += (size_t)d.first * d.second;
+        }
+        if (tiles > 0) total += (size_t)split_target(tiles, K) * elems;
+    }
+    return total;
+}
+
+size_t splitk_floats(const pql_config* c, int B) {
+    const int L = c->n_hidden;
+    std::vector<std::pair<int, int>> critic, actor;
+    for (int i = 0; i < 2; ++i) {
+        critic.push_back({c->obs_dim, c->hidden[0]});
+        critic.push_back({c->act_dim, c->hidden[0]});
+        for (int l = 1; l < L; ++l) critic.push_back({c->hidden[l - 1], c->hidden[l]});
+    }
+    actor.push_back({c->obs_dim, c->hidden[0]});
+    for (int l = 1; l < L; ++l) actor.push_back({c->hidden[l - 1], c->hidden[l]});
+    actor.push_back({c->hidden[L - 1], c->act_dim});
+    const size_t sc = dw_slab_bound(critic, B), sa = dw_slab_bound(actor, B);
+    return sc > sa ? sc : sa;
+}
+
+void make_layout(const pql_config* c, Layout& w) {
+    std::memset(&w, 0, sizeof(w));
+    const int L = c->n_hidden;
+    const size_t B = (size_t)c->max_batch;
+    size_t off = 0;
+    auto take = [&](size_t n) { const size_t o = off; off += up(n); return o; };
+    const size_t crow = B / 32 + 8;                 // rows of a column-sum partial buffer
+    const size_t nwg = (size_t)head_workgroups((int)B);
+    for (int l = 1; l <= L; ++l) {
+        const size_t h = (size_t)c->hidden[l - 1];
+        w.hA[l] = take(B * h);
+        w.dA[l] = take(B * h);
+        w.colA[l] = take(crow * h);
+        for (int i = 0; i < 2; ++i) {
+            w.hT[i][l] = take(B * h);
+            w.hQ[i][l] = take(B * h);
+            w.dQ[i][l] = take(B * h);
+            w.colQ[i][l] = take(crow * h);
+        }
+    }
+    w.colA[L + 1] = take(crow * (size_t)c->act_dim);
+    w.aOut = take(B * c->act_dim);
+    w.dPre = take(B * c->act_dim);
+    w.y = take(B);
+    const size_t hl = (size_t)c->hidden[L - 1];
+    for (int i = 0; i < 2; ++i) {
+        w.q[i] = take(B);
+        w.p_dw[i] = take(nwg * hl);
+        w.p_dbh[i] = take(nwg * hl);
+        w.p_db[i] = take(nwg);
+    }
+    w.p_loss = take(2 * nwg);
+    w.splitk = take(splitk_floats(c, (int)B));
+    w.total = off;
+}
+
+inline int vec_ok(const float* p, int ld) { return ((((uintptr_t)p) & 15) == 0 && (ld % 4) == 0) ? 1 : 0; }
+
+GemmProb prob(int M, int N, float* C, int ldc, int epi) {
+    GemmProb p;
+    std::memset(&p, 0, sizeof(p));
+    p.M = M; p.N = N; p.C = C; p.ldc = ldc; p.epi = epi; p.splits = 1;
+    return p;
+}
+
+void add_seg(GemmProb& p, const float* A, int lda, const float* Bm, int ldb, int K) {
+    GemmSeg& s = p.seg[p.nseg++];
+    s.A = A; s.lda = lda; s.B = Bm; s.ldb = ldb; s.K = K;
+    s.vec = vec_ok(A, lda) | (vec_ok(Bm, ldb) << 1);
+}
+
+struct Err {
+    pql_ctx* ctx;
+    int fail(int code, const char* what) { ctx->err = what; return code; }
+    int hip(hipError_t e, const char* where) {
+        ctx->err = std::string(where) + ": " + hipGetErrorString(e);
+        return PQL_ERR_HIP;
+    }
+};
+
+// Launches a list of problems of one mode, in chunks that fit one kernel argument block.
+hipError_t run(int mode, int tile, std::vector<GemmProb>& ps, const GemmNoise* nz, hipStream_t st) {
+    for (size_t i = 0; i < ps.size(); i += GEMM_MAX_PROB) {
+        GemmGroup g;
+        std::memset(&g, 0, sizeof(g));
+        if (nz) g.noise = *nz;
+        g.nprob = (int)((ps.size() - i < (size_t)GEMM_MAX_PROB) ? ps.size() - i : GEMM_MAX_PROB);
+        for (int k = 0; k < g.nprob; ++k) g.p[k] = ps[i + k];
+        const hipError_t e = gemm_launch(mode, tile, g, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t run_auto(int mode, std::vector<GemmProb>& ps, hipStream_t st) {
+    return run(mode, choose_tile(mode, ps), ps, nullptr, st);
+}
+
+// Weight-gradient problems: assigns split counts and slab addresses, launches, and appends one
+// reduction entry per problem.  `offsets[i]` is the parameter offset of problem i's tensor.
+hipError_t run_dw(std::vector<GemmProb>& ps, const std::vector<int64_t>& offsets, int K, float* slab,
+                  AdamArgs& ad, hipStream_t st) {
+    // group by preferred tile so that small and large matrices do not share a tiling
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tile = pass == 0 ? TILE_128x128 : TILE_64x64;
+        std::vector<GemmProb> sel;
+        std::vector<int64_t> sel_off;
+        long tiles = 0;
+        for (size_t i = 0; i < ps.size(); ++i) {
+            if (dw_tile_of(ps[i].M, ps[i].N) != tile) continue;
+            sel.push_back(ps[i]);
+            sel_off.push_back(offsets[i]);
+            tiles += dw_tiles(tile, ps[i].M, ps[i].N);
+        }
+        if (sel.empty()) continue;
+        int S = split_target(tiles, K);
+        int chunk = ((K + S - 1) / S + 31) / 32 * 32;
+        S = (K + chunk - 1) / chunk;
+        for (size_t i = 0; i < sel.size(); ++i) {
+            GemmProb& p = sel[i];
+            p.splits = S; p.k_chunk = chunk;
+            p.C = slab; p.ldc = p.N;
+            p.split_stride = (int64_t)p.M * p.N;
+            RedTensor& t = ad.t[ad.ntensors++];
+            t.offset = sel_off[i]; t.stride = p.split_stride; t.partial = slab;
+            t.count = p.M * p.N; t.nparts = S;
+            slab += (size_t)S * p.M * p.N;
+        }
+        const hipError_t e = run(GEMM_TN, tile, sel, nullptr, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+void red(AdamArgs& ad, int64_t offset, const float* partial, int count, int nparts, int64_t stride) {
+    RedTensor& t = ad.t[ad.ntensors++];
+    t.offset = offset; t.partial = partial; t.count = count; t.nparts = nparts; t.stride = stride;
+}
+
+bool adam_ok(const pql_adam& o) {
+    return o.lr >= 0.f && o.beta1 >= 0.f && o.beta1 < 1.f && o.beta2 >= 0.f && o.beta2 < 1.f && o.eps >= 0.f;
+}
+
+void fill_adam(AdamArgs& ad, const pql_adam& o, int64_t t) {
+    ad.lr = o.lr; ad.beta1 = o.beta1; ad.beta2 = o.beta2; ad.eps = o.eps;
+    ad.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)o.beta1, (double)t)));
+    ad.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)o.beta2, (double)t)));
+}
+
+// Forward pass of one hidden layer l (1-based) for a list of networks sharing the layer shape.
+struct FwdNet {
+    const float* params;     // network vector
+    const int64_t* w; const int64_t* b;
+    const float* in0; int ld0; int k0;   // first input segment (layer 1) / previous activations
+    const float* in1; int ld1; int k1;   // optional second segment (layer 1 of a critic)
+    float* out;
+};
+
+}  // namespace
+
+// =============================================================================================
+extern "C" {
+
+int32_t pql_create(const pql_config* cfg, pql_ctx** out) {
+    if (!out) return PQL_ERR_NULL;
+    *out = nullptr;
+    const int rc = validate_cfg(cfg);
+    if (rc != PQL_OK) return rc;
+    pql_ctx* c = new (std::nothrow) pql_ctx();
+    if (!c) return PQL_ERR_INVALID_ARG;
+    c->cfg = *cfg;
+    c->L = cfg->n_hidden;
+    c->T = cfg->capacity / cfg->num_envs;
+    c->head = c->count = c->pushes = c->samples = c->acts = c->critic_t = c->actor_t = 0;
+    c->a_total = net_params(cfg->obs_dim, cfg, cfg->act_dim, c->a_w, c->a_b);
+    c->c_total = net_params(cfg->obs_dim + cfg->act_dim, cfg, 1, c->c_w, c->c_b);
+    *out = c;
+    return PQL_OK;
+}
+
+int32_t pql_destroy(pql_ctx* ctx) {
+    if (!ctx) return PQL_ERR_NULL;
+    delete ctx;
+    return PQL_OK;
+}
+
+int64_t pql_replay_rows(const pql_config* cfg) {
+    const int rc = validate_cfg(cfg);
+    return rc != PQL_OK ? rc : cfg->capacity / cfg->num_envs;
+}
+
+int64_t pql_actor_param_count(const pql_config* cfg) {
+    const int rc = validate_cfg(cfg);
+    return rc != PQL_OK ? rc : net_params(cfg->obs_dim, cfg, cfg->act_dim, nullptr, nullptr);
+}
+
+int64_t pql_critic_param_count(const pql_config* cfg) {
+    const int rc = validate_cfg(cfg);
+    return rc != PQL_OK ? rc : net_params(cfg->obs_dim + cfg->act_dim, cfg, 1, nullptr, nullptr);
+}
+
+int64_t pql_workspace_bytes(const pql_config* cfg) {
+    const int rc = validate_cfg(cfg);
+    if (rc != PQL_OK) return rc;
+    Layout w;
+    make_layout(cfg, w);
+    return (int64_t)(w.total * sizeof(float));
+}
+
+const char* pql_last_error(const pql_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int32_t pql_get_state(const pql_ctx* c, int64_t out[8]) {
+    if (!c || !out) return PQL_ERR_NULL;
+    out[0] = c->head; out[1] = c->count; out[2] = c->pushes; out[3] = c->samples;
+    out[4] = c->acts; out[5] = c->critic_t; out[6] = c->actor_t; out[7] = 0;
+    return PQL_OK;
+}
+
+int32_t pql_set_state(pql_ctx* c, const int64_t in[8]) {
+    if (!c || !in) return PQL_ERR_NULL;
+    Err E{c};
+    if (in[0] < 0 || in[0] >= c->T || in[1] < 0 || in[1] > c->T) return E.fail(PQL_ERR_INVALID_ARG, "ring cursor out of range");
+    for (int i = 2; i < 7; ++i)
+        if (in[i] < 0) return E.fail(PQL_ERR_INVALID_ARG, "negative counter");
+    c->head = in[0]; c->count = in[1]; c->pushes = in[2]; c->samples = in[3];
+    c->acts = in[4]; c->critic_t = in[5]; c->actor_t = in[6];
+    return PQL_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+int32_t pql_replay_push(pql_ctx* c, pql_replay_storage st, const float* obs, const float* act, const float* rew,
+                        const float* next_obs, const float* done, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!st.obs || !st.act || !st.rew || !st.next_obs || !st.done || !obs || !act || !rew || !next_obs || !done)
+        return E.fail(PQL_ERR_NULL, "pql_replay_push: null pointer");
+    const int64_t N = c->cfg.num_envs, o = c->cfg.obs_dim, a = c->cfg.act_dim;
+    const int64_t base = c->head * N;
+    PushArgs p;
+    p.src[0] = obs;      p.dst[0] = st.obs + base * o;       p.count[0] = N * o;
+    p.src[1] = act;      p.dst[1] = st.act + base * a;       p.count[1] = N * a;
+    p.src[2] = rew;      p.dst[2] = st.rew + base;           p.count[2] = N;
+    p.src[3] = next_obs; p.dst[3] = st.next_obs + base * o;  p.count[3] = N * o;
+    p.src[4] = done;     p.dst[4] = st.done + base;          p.count[4] = N;
+    const hipError_t e = push_launch(p, (hipStream_t)stream);
+    if (e != hipSuccess) return E.hip(e, "pql_replay_push");
+    c->head = (c->head + 1) % c->T;
+    c->count = c->count + 1 < c->T ? c->count + 1 : c->T;
+    c->pushes += 1;
+    return PQL_OK;
+}
+
+static int32_t sample_common(pql_ctx* c, pql_replay_storage st, const int64_t* idx_in, int32_t batch, pql_batch out,
+                             void* stream, const char* who) {
+    Err E{c};
+    if (!st.obs || !st.act || !st.rew || !st.next_obs || !st.done || !out.obs || !out.act || !out.ret ||
+        !out.next_obs || !out.boot || (!idx_in && !out.idx))
+        return E.fail(PQL_ERR_NULL, who);
+    if (batch < 0) return E.fail(PQL_ERR_INVALID_ARG, who);
+    if (batch > c->cfg.max_batch) return E.fail(PQL_ERR_BATCH_TOO_LARGE, who);
+    if (c->count < c->cfg.nstep) return E.fail(PQL_ERR_NOT_ENOUGH_DATA, who);
+    SampleArgs a;
+    a.st = st; a.out = out; a.idx_in = idx_in;
+    a.batch = batch; a.o = c->cfg.obs_dim; a.a = c->cfg.act_dim; a.N = c->cfg.num_envs; a.T = (int)c->T;
+    a.nstep = c->cfg.nstep; a.head = (int)c->head; a.count = (int)c->count; a.gamma = c->cfg.gamma;
+    a.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); a.key1 = (uint32_t)(c->cfg.seed >> 32);
+    a.ctr2 = (uint32_t)((uint64_t)c->samples & 0xffffffffu); a.ctr3 = (uint32_t)((uint64_t)c->samples >> 32);
+    const hipError_t e = sample_launch(a, (hipStream_t)stream);
+    if (e != hipSuccess) return E.hip(e, who);
+    return PQL_OK;
+}
+
+int32_t pql_sample_nstep(pql_ctx* c, pql_replay_storage st, int32_t batch, pql_batch out, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    const int32_t rc = sample_common(c, st, nullptr, batch, out, stream, "pql_sample_nstep");
+    if (rc == PQL_OK) c->samples += 1;
+    return rc;
+}
+
+int32_t pql_gather_nstep(pql_ctx* c, pql_replay_storage st, const int64_t* idx, int32_t batch, pql_batch out,
+                         void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    if (!idx) { c->err = "pql_gather_nstep: null idx"; return PQL_ERR_NULL; }
+    return sample_common(c, st, idx, batch, out, stream, "pql_gather_nstep");
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward passes of the policy (hidden layers), shared by act / critic update / policy update.
+static hipError_t actor_hidden_forward(pql_ctx* c, const float* params, const float* obs, int B, float* ws,
+                                       const Layout& w, hipStream_t st) {
+    const int L = c->L;
+    for (int l = 1; l <= L; ++l) {
+        std::vector<GemmProb> ps;
+        const int H = c->cfg.hidden[l - 1];
+        GemmProb p = prob(B, H, ws + w.hA[l], H, EPI_BIAS_ELU);
+        if (l == 1) add_seg(p, obs, c->cfg.obs_dim, params + c->a_w[0], H, c->cfg.obs_dim);
+        else add_seg(p, ws + w.hA[l - 1], c->cfg.hidden[l - 2], params + c->a_w[l - 1], H, c->cfg.hidden[l - 2]);
+        p.bias = params + c->a_b[l - 1];
+        ps.push_back(p);
+        const hipError_t e = run_auto(GEMM_NN, ps, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// One hidden layer of a critic as a forward problem.
+static GemmProb critic_layer(pql_ctx* c, const float* params, int l, const float* s, const float* a, int lda_a,
+                             const float* h_prev, float* h_out, int B) {
+    const int H = c->cfg.hidden[l - 1];
+    GemmProb p = prob(B, H, h_out, H, EPI_BIAS_ELU);
+    if (l == 1) {
+        const int o = c->cfg.obs_dim, ad = c->cfg.act_dim;
+        add_seg(p, s, o, params + c->c_w[0], H, o);
+        add_seg(p, a, lda_a, params + c->c_w[0] + (int64_t)o * H, H, ad);
+    } else {
+        add_seg(p, h_prev, c->cfg.hidden[l - 2], params + c->c_w[l - 1], H, c->cfg.hidden[l - 2]);
+    }
+    p.bias = params + c->c_b[l - 1];
+    return p;
+}
+
+int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, int32_t num, float sigma_min,
+                      float sigma_max, float* act_out, void* workspace, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!actor_params || !obs || !act_out || !workspace) return E.fail(PQL_ERR_NULL, "pql_actor_act: null pointer");
+    if (num < 1 || sigma_min < 0.f || sigma_max < 0.f) return E.fail(PQL_ERR_INVALID_ARG, "pql_actor_act: bad num/sigma");
+    if (num > c->cfg.max_batch) return E.fail(PQL_ERR_BATCH_TOO_LARGE, "pql_actor_act: num > max_batch");
+    if (((uintptr_t)workspace) & 255) return E.fail(PQL_ERR_ALIGNMENT, "pql_actor_act: workspace not 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    float* ws = (float*)workspace;
+    Layout w;
+    make_layout(&c->cfg, w);
+    hipError_t e = actor_hidden_forward(c, actor_params, obs, num, ws, w, st);
+    if (e != hipSuccess) return E.hip(e, "pql_actor_act");
+    const int L = c->L, HL = c->cfg.hidden[L - 1], ad = c->cfg.act_dim;
+    std::vector<GemmProb> ps;
+    GemmProb p = prob(num, ad, act_out, ad, EPI_BIAS_TANH_NOISE);
+    add_seg(p, ws + w.hA[L], HL, actor_params + c->a_w[L], ad, HL);
+    p.bias = actor_params + c->a_b[L];
+    ps.push_back(p);
+    GemmNoise nz;
+    nz.act_dim = ad; nz.sigma_rows = num; nz.sigma_min = sigma_min; nz.sigma_max = sigma_max;
+    nz.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); nz.key1 = (uint32_t)(c->cfg.seed >> 32);
+    nz.ctr2 = (uint32_t)((uint64_t)c->acts & 0xffffffffu); nz.ctr3 = (uint32_t)((uint64_t)c->acts >> 32);
+    e = run(GEMM_NN, TILE_128x32, ps, &nz, st);
+    if (e != hipSuccess) return E.hip(e, "pql_actor_act");
+    c->acts += 1;
+    return PQL_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_target_params,
+                          const float* actor_target_params, float* adam_m, float* adam_v, float* grads_out,
+                          pql_batch batch, int32_t B, pql_adam opt, float* loss_out, void* workspace, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!critic_params || !critic_target_params || !actor_target_params || !adam_m || !adam_v || !grads_out ||
+        !batch.obs || !batch.act || !batch.ret || !batch.next_obs || !batch.boot || !loss_out || !workspace)
+        return E.fail(PQL_ERR_NULL, "pql_critic_update: null pointer");
+    if (B < 1 || !adam_ok(opt)) return E.fail(PQL_ERR_INVALID_ARG, "pql_critic_update: bad batch size or Adam constants");
+    if (B > c->cfg.max_batch) return E.fail(PQL_ERR_BATCH_TOO_LARGE, "pql_critic_update: batch > max_batch");
+    if (((uintptr_t)workspace) & 255) return E.fail(PQL_ERR_ALIGNMENT, "pql_critic_update: workspace not 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    float* ws = (float*)workspace;
+    Layout w;
+    make_layout(&c->cfg, w);
+    const int L = c->L, o = c->cfg.obs_dim, ad = c->cfg.act_dim, HL = c->cfg.hidden[L - 1];
+    const int64_t Pc = c->c_total;
+    hipError_t e;
+    const char* who = "pql_critic_update";
+
+    // 1. lagged policy pi^v on s' (hidden layers) together with the online critics on (s, a)
+    for (int l = 1; l <= L; ++l) {
+        std::vector<GemmProb> ps;
+        const int H = c->cfg.hidden[l - 1];
+        GemmProb p = prob(B, H, ws + w.hA[l], H, EPI_BIAS_ELU);
+        if (l == 1) add_seg(p, batch.next_obs, o, actor_target_params + c->a_w[0], H, o);
+        else add_seg(p, ws + w.hA[l - 1], c->cfg.hidden[l - 2], actor_target_params + c->a_w[l - 1], H, c->cfg.hidden[l - 2]);
+        p.bias = actor_target_params + c->a_b[l - 1];
+        ps.push_back(p);
+        for (int i = 0; i < 2; ++i)
+            ps.push_back(critic_layer(c, critic_params + i * Pc, l, batch.obs, batch.act, ad,
+                                      l > 1 ? ws + w.hQ[i][l - 1] : nullptr, ws + w.hQ[i][l], B));
+        if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
+    }
+    // 2. a' = tanh(output layer of pi^v)
+    {
+        std::vector<GemmProb> ps;
+        GemmProb p = prob(B, ad, ws + w.aOut, ad, EPI_BIAS_TANH);
+        add_seg(p, ws + w.hA[L], HL, actor_target_params + c->a_w[L], ad, HL);
+        p.bias = actor_target_params + c->a_b[L];
+        ps.push_back(p);
+        if ((e = run(GEMM_NN, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+    }
+    // 3. twin target critics on (s', a')
+    for (int l = 1; l <= L; ++l) {
+        std::vector<GemmProb> ps;
+        for (int i = 0; i < 2; ++i)
+            ps.push_back(critic_layer(c, critic_target_params + i * Pc, l, batch.next_obs, ws + w.aOut, ad,
+                                      l > 1 ? ws + w.hT[i][l - 1] : nullptr, ws + w.hT[i][l], B));
+        if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
+    }
+    // 4. heads: y, losses, output deltas, delta of the last hidden layer
+    HeadArgs h;
+    std::memset(&h, 0, sizeof(h));
+    h.B = B; h.H = HL; h.nwg = head_workgroups(B);
+    for (int i = 0; i < 2; ++i) {
+        h.hT[i] = ws + w.hT[i][L]; h.wT[i] = critic_target_params + i * Pc + c->c_w[L]; h.bT[i] = critic_target_params + i * Pc + c->c_b[L];
+        h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L];        h.bQ[i] = critic_params + i * Pc + c->c_b[L];
+        h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
+        h.p_dw[i] = ws + w.p_dw[i]; h.p_dbh[i] = ws + w.p_dbh[i]; h.p_db[i] = ws + w.p_db[i];
+    }
+    h.ret = batch.ret; h.boot = batch.boot; h.y = ws + w.y; h.p_loss = ws + w.p_loss;
+    if ((e = critic_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
+
+    AdamArgs adm;
+    std::memset(&adm, 0, sizeof(adm));
+    // 5. backward data path: delta_{l-1} = (delta_l W_l^T) * ELU'(z_{l-1}), bias grads as column sums
+    for (int l = L; l >= 2; --l) {
+        std::vector<GemmProb> ps;
+        const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
+        for (int i = 0; i < 2; ++i) {
+            GemmProb p = prob(B, Hp, ws + w.dQ[i][l - 1], Hp, EPI_MUL_DELU);
+            add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
+            p.aux = ws + w.hQ[i][l - 1]; p.ldaux = Hp;
+            p.colsum = ws + w.colQ[i][l - 1];
+            ps.push_back(p);
+        }
+        const int tile = choose_tile(GEMM_NT, ps);
+        if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+        for (int i = 0; i < 2; ++i)
+            red(adm, i * Pc + c->c_b[l - 2], ws + w.colQ[i][l - 1], Hp, colsum_rows(tile, B), Hp);
+    }
+    // 6. weight gradients X^T delta (split over the batch)
+    {
+        std::vector<GemmProb> ps;
+        std::vector<int64_t> offs;
+        for (int i = 0; i < 2; ++i) {
+            for (int l = 1; l <= L; ++l) {
+                const int Hl = c->cfg.hidden[l - 1];
+                if (l == 1) {
+                    GemmProb p = prob(o, Hl, nullptr, Hl, EPI_STORE);
+                    add_seg(p, batch.obs, o, ws + w.dQ[i][1], Hl, B);
+                    ps.push_back(p); offs.push_back(i * Pc + c->c_w[0]);
+                    GemmProb p2 = prob(ad, Hl, nullptr, Hl, EPI_STORE);
+                    add_seg(p2, batch.act, ad, ws + w.dQ[i][1], Hl, B);
+                    ps.push_back(p2); offs.push_back(i * Pc + c->c_w[0] + (int64_t)o * Hl);
+                } else {
+                    const int Hp = c->cfg.hidden[l - 2];
+                    GemmProb p = prob(Hp, Hl, nullptr, Hl, EPI_STORE);
+                    add_seg(p, ws + w.hQ[i][l - 1], Hp, ws + w.dQ[i][l], Hl, B);
+                    ps.push_back(p); offs.push_back(i * Pc + c->c_w[l - 1]);
+                }
+            }
+        }
+        if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st)) != hipSuccess) return E.hip(e, who);
+    }
+    // 7. remaining reductions (last hidden bias, output layer) + Adam + loss scalars
+    for (int i = 0; i < 2; ++i) {
+        red(adm, i * Pc + c->c_b[L - 1], ws + w.p_dbh[i], HL, h.nwg, HL);
+        red(adm, i * Pc + c->c_w[L], ws + w.p_dw[i], HL, h.nwg, HL);
+        red(adm, i * Pc + c->c_b[L], ws + w.p_db[i], 1, h.nwg, 1);
+    }
+    adm.nloss = 2; adm.loss_parts = h.nwg; adm.loss_scale = 1.f / (float)B;
+    adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
+    adm.theta = critic_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
+    fill_adam(adm, opt, c->critic_t + 1);
+    if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
+    c->critic_t += 1;
+    return PQL_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_params, float* adam_m, float* adam_v,
+                         float* grads_out, const float* obs, int32_t B, pql_adam opt, float* loss_out,
+                         void* workspace, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!actor_params || !critic_params || !adam_m || !adam_v || !grads_out || !obs || !loss_out || !workspace)
+        return E.fail(PQL_ERR_NULL, "pql_actor_update: null pointer");
+    if (B < 1 || !adam_ok(opt)) return E.fail(PQL_ERR_INVALID_ARG, "pql_actor_update: bad batch size or Adam constants");
+    if (B > c->cfg.max_batch) return E.fail(PQL_ERR_BATCH_TOO_LARGE, "pql_actor_update: batch > max_batch");
+    if (((uintptr_t)workspace) & 255) return E.fail(PQL_ERR_ALIGNMENT, "pql_actor_update: workspace not 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    float* ws = (float*)workspace;
+    Layout w;
+    make_layout(&c->cfg, w);
+    const int L = c->L, o = c->cfg.obs_dim, ad = c->cfg.act_dim, HL = c->cfg.hidden[L - 1], H1 = c->cfg.hidden[0];
+    const int64_t Pc = c->c_total;
+    hipError_t e;
+    const char* who = "pql_actor_update";
+
+    // 1. a = pi(s)
+    if ((e = actor_hidden_forward(c, actor_params, obs, B, ws, w, st)) != hipSuccess) return E.hip(e, who);
+    {
+        std::vector<GemmProb> ps;
+        GemmProb p = prob(B, ad, ws + w.aOut, ad, EPI_BIAS_TANH);
+        add_seg(p, ws + w.hA[L], HL, actor_params + c->a_w[L], ad, HL);
+        p.bias = actor_params + c->a_b[L];
+        ps.push_back(p);
+        if ((e = run(GEMM_NN, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+    }
+    // 2. twin critics on (s, pi(s))
+    for (int l = 1; l <= L; ++l) {
+        std::vector<GemmProb> ps;
+        for (int i = 0; i < 2; ++i)
+            ps.push_back(critic_layer(c, critic_params + i * Pc, l, obs, ws + w.aOut, ad,
+                                      l > 1 ? ws + w.hQ[i][l - 1] : nullptr, ws + w.hQ[i][l], B));
+        if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
+    }
+    // 3. heads: J partials and the delta entering the smaller critic
+    HeadArgs h;
+    std::memset(&h, 0, sizeof(h));
+    h.B = B; h.H = HL; h.nwg = head_workgroups(B);
+    for (int i = 0; i < 2; ++i) {
+        h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L]; h.bQ[i] = critic_params + i * Pc + c->c_b[L];
+        h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
+    }
+    h.p_loss = ws + w.p_loss;
+    if ((e = policy_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
+    // 4. critic backward data path down to layer 1
+    for (int l = L; l >= 2; --l) {
+        std::vector<GemmProb> ps;
+        const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
+        for (int i = 0; i < 2; ++i) {
+            GemmProb p = prob(B, Hp, ws + w.dQ[i][l - 1], Hp, EPI_MUL_DELU);
+            add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
+            p.aux = ws + w.hQ[i][l - 1]; p.ldaux = Hp;
+            ps.push_back(p);
+        }
+        if ((e = run_auto(GEMM_NT, ps, st)) != hipSuccess) return E.hip(e, who);
+    }
+    AdamArgs adm;
+    std::memset(&adm, 0, sizeof(adm));
+    // 5. gradient w.r.t. the action input of both critics, through tanh'
+    {
+        std::vector<GemmProb> ps;
+        GemmProb p = prob(B, ad, ws + w.dPre, ad, EPI_MUL_DTANH);
+        for (int i = 0; i < 2; ++i)
+            add_seg(p, ws + w.dQ[i][1], H1, critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, H1, H1);
+        p.aux = ws + w.aOut; p.ldaux = ad;
+        p.colsum = ws + w.colA[L + 1];
+        ps.push_back(p);
+        if ((e = run(GEMM_NT, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+        red(adm, c->a_b[L], ws + w.colA[L + 1], ad, colsum_rows(TILE_128x32, B), ad);
+    }
+    // 6. policy backward data path
+    for (int l = L + 1; l >= 2; --l) {
+        std::vector<GemmProb> ps;
+        const int Hl = (l == L + 1) ? ad : c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
+        GemmProb p = prob(B, Hp, ws + w.dA[l - 1], Hp, EPI_MUL_DELU);
+        add_seg(p, (l == L + 1) ? ws + w.dPre : ws + w.dA[l], Hl, actor_params + c->a_w[l - 1], Hl, Hl);
+        p.aux = ws + w.hA[l - 1]; p.ldaux = Hp;
+        p.colsum = ws + w.colA[l - 1];
+        ps.push_back(p);
+        const int tile = choose_tile(GEMM_NT, ps);
+        if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+        red(adm, c->a_b[l - 2], ws + w.colA[l - 1], Hp, colsum_rows(tile, B), Hp);
+    }
+    // 7. policy weight gradients
+    {
+        std::vector<GemmProb> ps;
+        std::vector<int64_t> offs;
+        for (int l = 1; l <= L + 1; ++l) {
+            const int Hl = (l == L + 1) ? ad : c->cfg.hidden[l - 1];
+            const int Hp = (l == 1) ? o : c->cfg.hidden[l - 2];
+            GemmProb p = prob(Hp, Hl, nullptr, Hl, EPI_STORE);
+            add_seg(p, (l == 1) ? obs : ws + w.hA[l - 1], Hp, (l == L + 1) ? ws + w.dPre : ws + w.dA[l], Hl, B);
+            ps.push_back(p); offs.push_back(c->a_w[l - 1]);
+        }
+        if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st)) != hipSuccess) return E.hip(e, who);
+    }
+    adm.nloss = 1; adm.loss_parts = h.nwg; adm.loss_scale = -1.f / (float)B;
+    adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
+    adm.theta = actor_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
+    fill_adam(adm, opt, c->actor_t + 1);
+    if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
+    c->actor_t += 1;
+    return PQL_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+int32_t pql_soft_update(pql_ctx* c, const float* src, float* dst, int64_t count, float tau, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!src || !dst) return E.fail(PQL_ERR_NULL, "pql_soft_update: null pointer");
+    if (count < 0 || !(tau >= 0.f) || tau > 1.f) return E.fail(PQL_ERR_INVALID_ARG, "pql_soft_update: bad count or tau");
+    const hipError_t e = soft_update_launch(src, dst, count, tau, (hipStream_t)stream);
+    if (e != hipSuccess) return E.hip(e, "pql_soft_update");
+    return PQL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,306 @@
+// Grouped fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32) with fused epilogues.
+//
+// These are the dense contractions of the learner: every hidden layer of the policy and of the
+// twin critics forward (X W + b, ELU / tanh), the backward data path (delta W^T times the
+// activation derivative) and the weight gradients (X^T delta, reduced over the batch by
+// split-K).  One launch handles a list of independent problems, so the twin critics, the target
+// critics and the policy share launches.
+//
+// Tiling: a workgroup is 4 wavefronts of 64 lanes.  Global tiles are copied to LDS in their
+// natural orientation (the contiguous dimension stays contiguous, 16-byte loads when the
+// operand allows), the next tile is prefetched into registers while the current one feeds the
+// matrix cores.  A 32x32x2 MFMA takes one A value and one B value per lane: lane l supplies
+// A[m = l%32][k = l/32] and B[k = l/32][n = l%32] and owns, in accumulator register r,
+// C[8*(r/4) + 4*(l/32) + r%4][l%32].  The k index inside a group of 8 is assigned as
+// k = 4*(l/32) + i for the i-th of four consecutive MFMAs, so a lane's four A values (or B
+// values) are contiguous in a k-contiguous tile and can be read with one 16-byte LDS load.
+#include "pql_internal.h"
+
+namespace pql {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 32;          // K extent of one LDS tile
+constexpr int KSTRIDE = BK + 4; // row stride (floats) of a k-contiguous LDS tile
+constexpr int NTHREADS = 256;
+
+// Workgroups are handed to the 8 XCDs round-robin by the hardware; renumber them so that a run
+// of consecutive logical tiles (which share operand rows) lands on one XCD and shares its L2.
+__device__ inline int xcd_remap(int bid, int nb) {
+    const int q = nb >> 3, r = nb & 7;
+    const int xcd = bid & 7, pos = bid >> 3;
+    return xcd * q + (xcd < r ? xcd : r) + pos;
+}
+
+// ---- Philox-4x32-10 (Salmon et al., SC'11) and Box-Muller ---------------------------------
+__device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                     uint32_t& o0, uint32_t& o1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    o0 = c0; o1 = c1;
+}
+
+__device__ inline float exploration_noise(const GemmNoise& nz, int m, int n) {
+    uint32_t w0, w1;
+    philox4x32_10((uint32_t)(m * nz.act_dim + n), 2u, nz.ctr2, nz.ctr3, nz.key0, nz.key1, w0, w1);
+    // double precision: (w >> 8) + 0.5 needs 25 significant bits
+    const double u1 = ((double)(w0 >> 8) + 0.5) * 0x1p-24;
+    const double u2 = ((double)(w1 >> 8) + 0.5) * 0x1p-24;
+    const double eps = sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2);
+    double sigma = (double)nz.sigma_min;
+    if (nz.sigma_rows > 1)
+        sigma += ((double)m / (double)(nz.sigma_rows - 1)) * ((double)nz.sigma_max - (double)nz.sigma_min);
+    return (float)(sigma * eps);
+}
+
+// ---- global -> register tile loads ---------------------------------------------------------
+// A ROWS x COLS tile whose COLS dimension is contiguous in memory, spread over 256 threads as
+// float4 pieces; out-of-range elements read as zero.
+template <int ROWS, int COLS>
+struct TileRegs {
+    static constexpr int C4 = COLS / 4;
+    static constexpr int RPP = NTHREADS / C4;             // rows covered per pass
+    static constexpr int NV = (ROWS * COLS) / (4 * NTHREADS);
+    static_assert(NV >= 1 && ROWS % RPP == 0, "tile shape");
+    float4 v[NV];
+
+    __device__ inline void load(const float* __restrict__ src, int ld, int row0, int col0, int row_lim, int col_lim,
+                                bool vec, int tid) {
+        const int c = col0 + (tid % C4) * 4;
+        const int r = row0 + tid / C4;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int rr = r + i * RPP;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (rr < row_lim && c < col_lim) {
+                const float* p = src + (size_t)rr * (size_t)ld + c;
+                if (vec && c + 3 < col_lim) {
+                    x = *reinterpret_cast<const float4*>(p);
+                } else {
+                    x.x = p[0];
+                    if (c + 1 < col_lim) x.y = p[1];
+                    if (c + 2 < col_lim) x.z = p[2];
+                    if (c + 3 < col_lim) x.w = p[3];
+                }
+            }
+            v[i] = x;
+        }
+    }
+
+    __device__ inline void store(float* tile, int stride, int tid) const {
+        const int c = (tid % C4) * 4;
+        const int r = tid / C4;
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            *reinterpret_cast<float4*>(tile + (r + i * RPP) * stride + c) = v[i];
+    }
+};
+
+template <int MODE, int WAVES_M, int WAVES_N, int TM, int TN, bool NOISE>
+__global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup g) {
+    constexpr int BM = WAVES_M * TM * 32;
+    constexpr int BN = WAVES_N * TN * 32;
+    constexpr bool A_KC = (MODE != GEMM_TN);   // A tile k-contiguous: As[m][k]; else As[k][m]
+    constexpr bool B_KC = (MODE == GEMM_NT);   // B tile k-contiguous: Bs[n][k]; else Bs[k][n]
+    constexpr int SA = A_KC ? KSTRIDE : BM;
+    constexpr int SB = B_KC ? KSTRIDE : BN;
+    __shared__ __attribute__((aligned(16))) float As[A_KC ? BM * SA : BK * SA];
+    __shared__ __attribute__((aligned(16))) float Bs[B_KC ? BN * SB : BK * SB];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    const int bid = xcd_remap(blockIdx.x, gridDim.x);
+    int pi = 0;
+    for (int i = 1; i < g.nprob; ++i)
+        if (bid >= g.p[i].tile_begin) pi = i;
+    const GemmProb& P = g.p[pi];
+
+    int local = bid - P.tile_begin;
+    const int per_split = P.tiles_m * P.tiles_n;
+    const int split = local / per_split;
+    local -= split * per_split;
+    const int tile_m = local / P.tiles_n, tile_n = local % P.tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int M = P.M, N = P.N;
+
+    // K range per segment (split-K applies to single-segment problems only)
+    int kbeg0 = 0, kend0 = P.seg[0].K;
+    if (MODE == GEMM_TN) {
+        kbeg0 = split * P.k_chunk;
+        kend0 = min(P.seg[0].K, kbeg0 + P.k_chunk);
+    }
+    const int nt0 = (kend0 - kbeg0 + BK - 1) / BK;
+    const int nt1 = (P.nseg > 1) ? (P.seg[1].K + BK - 1) / BK : 0;
+    const int nt = nt0 + nt1;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    TileRegs<A_KC ? BM : BK, A_KC ? BK : BM> ra;
+    TileRegs<B_KC ? BN : BK, B_KC ? BK : BN> rb;
+
+    auto fetch = [&](int t) {
+        const int s = (t < nt0) ? 0 : 1;
+        const GemmSeg& S = P.seg[s];
+        const int k0 = (s == 0) ? kbeg0 + t * BK : (t - nt0) * BK;
+        const int kend = (s == 0) ? kend0 : S.K;
+        if (A_KC) ra.load(S.A, S.lda, m0, k0, M, kend, (S.vec & 1) != 0, tid);
+        else      ra.load(S.A, S.lda, k0, m0, kend, M, (S.vec & 1) != 0, tid);
+        if (B_KC) rb.load(S.B, S.ldb, n0, k0, N, kend, (S.vec & 2) != 0, tid);
+        else      rb.load(S.B, S.ldb, k0, n0, kend, N, (S.vec & 2) != 0, tid);
+    };
+
+    if (nt > 0) fetch(0);
+    for (int t = 0; t < nt; ++t) {
+        ra.store(As, SA, tid);
+        rb.store(Bs, SB, tid);
+        __syncthreads();
+        if (t + 1 < nt) fetch(t + 1);
+
+        int kvalid;
+        if (t < nt0) kvalid = min(BK, kend0 - (kbeg0 + t * BK));
+        else         kvalid = min(BK, P.seg[1].K - (t - nt0) * BK);
+        const int ngroups = (kvalid + 7) >> 3;
+
+        for (int kg = 0; kg < ngroups; ++kg) {
+            const int kk = kg * 8 + 4 * half;
+            float a[TM][4], b[TN][4];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = (wm * TM + i) * 32 + l32;
+                if (A_KC) {
+                    const float4 x = *reinterpret_cast<const float4*>(As + m * SA + kk);
+                    a[i][0] = x.x; a[i][1] = x.y; a[i][2] = x.z; a[i][3] = x.w;
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) a[i][u] = As[(kk + u) * SA + m];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = (wn * TN + j) * 32 + l32;
+                if (B_KC) {
+                    const float4 x = *reinterpret_cast<const float4*>(Bs + n * SB + kk);
+                    b[j][0] = x.x; b[j][1] = x.y; b[j][2] = x.z; b[j][3] = x.w;
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) b[j][u] = Bs[(kk + u) * SB + n];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][u], b[j][u], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue -------------------------------------------------------------------------
+    const int epi = P.epi;
+    float* __restrict__ C = P.C + (MODE == GEMM_TN ? (size_t)split * (size_t)P.split_stride : (size_t)0);
+    const int ldc = P.ldc;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + (wn * TN + j) * 32 + l32;
+        const bool n_ok = n < N;
+        float bias = 0.f;
+        if (n_ok && (epi == EPI_BIAS_ELU || epi == EPI_BIAS_TANH || epi == EPI_BIAS_TANH_NOISE)) bias = P.bias[n];
+        float csum = 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (!n_ok || m >= M) continue;
+                float x = acc[i][j][r];
+                switch (epi) {
+                    case EPI_BIAS_ELU: x += bias; x = x > 0.f ? x : expm1f(x); break;
+                    case EPI_BIAS_TANH: x = tanhf(x + bias); break;
+                    case EPI_BIAS_TANH_NOISE:
+                        x = tanhf(x + bias);
+                        if (NOISE) x = fminf(fmaxf(x + exploration_noise(g.noise, m, n), -1.f), 1.f);
+                        break;
+                    case EPI_MUL_DELU: {
+                        const float h = P.aux[(size_t)m * P.ldaux + n];
+                        x *= (h > 0.f ? 1.f : h + 1.f);
+                        break;
+                    }
+                    case EPI_MUL_DTANH: {
+                        const float h = P.aux[(size_t)m * P.ldaux + n];
+                        x *= (1.f - h * h);
+                        break;
+                    }
+                    default: break;
+                }
+                C[(size_t)m * ldc + n] = x;
+                csum += x;
+            }
+        }
+        if (P.colsum != nullptr) {
+            csum += __shfl_xor(csum, 32);
+            if (half == 0 && n_ok) P.colsum[(size_t)(tile_m * WAVES_M + wm) * N + n] = csum;
+        }
+    }
+}
+
+// ---- host side ------------------------------------------------------------------------------
+int gemm_tile_m(int tile) { return tile == TILE_64x64 ? 64 : 128; }
+int gemm_tile_n(int tile) { return tile == TILE_128x128 ? 128 : (tile == TILE_64x64 ? 64 : 32); }
+int gemm_waves_m(int tile) { return tile == TILE_128x32 ? 4 : 2; }
+
+template <int MODE>
+static hipError_t launch_mode(int tile, const GemmGroup& g, bool noise, hipStream_t stream) {
+    const dim3 grid(g.total_tiles), block(NTHREADS);
+    switch (tile) {
+        case TILE_128x128: hipLaunchKernelGGL((gemm_grouped_kernel<MODE, 2, 2, 2, 2, false>), grid, block, 0, stream, g); break;
+        case TILE_64x64:   hipLaunchKernelGGL((gemm_grouped_kernel<MODE, 2, 2, 1, 1, false>), grid, block, 0, stream, g); break;
+        default:
+            if (MODE == GEMM_NN && noise)
+                hipLaunchKernelGGL((gemm_grouped_kernel<GEMM_NN, 4, 1, 1, 1, true>), grid, block, 0, stream, g);
+            else
+                hipLaunchKernelGGL((gemm_grouped_kernel<MODE, 4, 1, 1, 1, false>), grid, block, 0, stream, g);
+            break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t gemm_launch(int mode, int tile, GemmGroup& g, hipStream_t stream) {
+    const int bm = gemm_tile_m(tile), bn = gemm_tile_n(tile);
+    int total = 0;
+    bool noise = false;
+    for (int i = 0; i < g.nprob; ++i) {
+        GemmProb& p = g.p[i];
+        if (p.epi == EPI_BIAS_TANH_NOISE) noise = true;
+        p.tiles_m = (p.M + bm - 1) / bm;
+        p.tiles_n = (p.N + bn - 1) / bn;
+        if (mode != GEMM_TN) { p.splits = 1; p.k_chunk = 0; }
+        p.tile_begin = total;
+        total += p.tiles_m * p.tiles_n * p.splits;
+    }
+    g.total_tiles = total;
+    if (total == 0) return hipSuccess;
+    if (noise && (mode != GEMM_NN || tile != TILE_128x32)) return hipErrorInvalidValue;
+    switch (mode) {
+        case GEMM_NN: return launch_mode<GEMM_NN>(tile, g, noise, stream);
+        case GEMM_NT: return launch_mode<GEMM_NT>(tile, g, noise, stream);
+        default:      return launch_mode<GEMM_TN>(tile, g, noise, stream);
+    }
+}
+
+}  // namespace pql

@@ -1,0 +1,148 @@
+// Internal declarations shared by the translation units of libpql.  Nothing here is part of
+// the public C interface (include/pql.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pql.h"
+
+namespace pql {
+
+// ---- grouped fp32 MFMA GEMM ------------------------------------------------------------
+// One launch computes several independent problems C_p = epi(sum_seg A_seg * B_seg).  A problem
+// may contract over up to two K-segments (the critic's first layer reads s and a from two
+// arrays; the action gradient of the policy step sums over the two critics).
+
+enum GemmMode : int {
+    GEMM_NN = 0,   // A[M][K] row-major, B[K][N] row-major              (forward:  X * W)
+    GEMM_NT = 1,   // A[M][K] row-major, B stored [N][K] row-major      (backward: delta * W^T)
+    GEMM_TN = 2    // A stored [K][M] row-major, B[K][N] row-major, K split across workgroups
+                   //                                                    (weight grad: X^T * delta)
+};
+
+enum GemmEpilogue : int {
+    EPI_STORE = 0,          // C = acc  (split-K partial sums)
+    EPI_BIAS_ELU = 1,       // C = ELU(acc + bias[n])
+    EPI_BIAS_TANH = 2,      // C = tanh(acc + bias[n])
+    EPI_BIAS_TANH_NOISE = 3,// C = clip(tanh(acc + bias[n]) + sigma_m * eps, -1, 1)
+    EPI_MUL_DELU = 4,       // C = acc * ELU'(z) with ELU'(z) recovered from aux = ELU(z)
+    EPI_MUL_DTANH = 5       // C = acc * (1 - aux^2), aux = tanh(z)
+};
+
+struct GemmSeg {
+    const float* A;
+    const float* B;
+    int lda, ldb;
+    int K;
+    int vec;                // bit 0 / bit 1: 16-byte vector loads are legal for A / B
+};
+
+struct GemmProb {
+    GemmSeg seg[2];
+    int nseg;
+    int M, N;
+    int ldc;
+    float* C;
+    const float* bias;
+    const float* aux;
+    float* colsum;          // optional per-wave-row column sums of C: [tiles_m * waves_m][N]
+    int ldaux;
+    int epi;
+    int tiles_m, tiles_n;
+    int splits, k_chunk;    // GEMM_TN only: K range of split s is [s*k_chunk, min(K,(s+1)*k_chunk))
+    int tile_begin;         // first linear tile id of this problem within the launch
+    int pad_;
+    int64_t split_stride;   // floats between consecutive split-K partial slabs
+};
+
+constexpr int GEMM_MAX_PROB = 16;
+
+// Exploration-noise parameters for the (single) EPI_BIAS_TANH_NOISE problem of a launch.
+struct GemmNoise {
+    int act_dim;            // element index = m * act_dim + n
+    int sigma_rows;         // number of environments in the sigma schedule
+    float sigma_min, sigma_max;
+    uint32_t key0, key1, ctr2, ctr3;
+};
+
+struct GemmGroup {
+    int nprob;
+    int total_tiles;
+    GemmNoise noise;
+    GemmProb p[GEMM_MAX_PROB];
+};
+
+enum GemmTile : int { TILE_128x128 = 0, TILE_64x64 = 1, TILE_128x32 = 2 };
+
+int gemm_tile_m(int tile);
+int gemm_tile_n(int tile);
+int gemm_waves_m(int tile);
+// Fills tiles_m/tiles_n/tile_begin/total_tiles from M, N, splits; returns hipError.
+hipError_t gemm_launch(int mode, int tile, GemmGroup& g, hipStream_t stream);
+
+// ---- reduction + Adam -------------------------------------------------------------------
+struct RedTensor {
+    int64_t offset;         // first element in the flat parameter vector
+    int64_t stride;         // floats between consecutive partials
+    const float* partial;   // partial[s * stride + i], s < nparts, i < count
+    int count;
+    int nparts;
+};
+
+constexpr int RED_MAX_TENSORS = 48;
+
+struct AdamArgs {
+    int ntensors;
+    int nloss;              // number of loss scalars (2 critic / 1 actor)
+    int loss_parts;         // partials per loss scalar
+    float loss_scale;       // multiplies the summed partials
+    const float* loss_partial;   // [nloss][loss_parts]
+    float* loss_out;
+    float* theta; float* m; float* v; float* g;
+    float lr, beta1, beta2, eps, inv_bc1, inv_bc2;
+    RedTensor t[RED_MAX_TENSORS];
+};
+
+hipError_t adam_reduce_launch(const AdamArgs& a, hipStream_t stream);
+
+// ---- output heads -----------------------------------------------------------------------
+struct HeadArgs {
+    int B, H;               // rows, width of the last hidden layer
+    int nwg;                // workgroups launched == partial rows written
+    // target critics (critic update only)
+    const float* hT[2]; const float* wT[2]; const float* bT[2];
+    const float* ret; const float* boot;
+    // online critics
+    const float* hQ[2]; const float* wQ[2]; const float* bQ[2];
+    float* dQ[2];           // delta at the last hidden layer, [B][H]
+    float* y; float* q[2];  // [B] each (kept for inspection)
+    float* p_dw[2];         // [nwg][H]  partial sums of dL/dW_out
+    float* p_dbh[2];        // [nwg][H]  partial column sums of dQ (bias grad of last hidden)
+    float* p_db[2];         // [nwg]     partial sums of dL/db_out
+    float* p_loss;          // [2][nwg] (critic) or [1][nwg] (policy)
+};
+
+hipError_t critic_head_launch(const HeadArgs& a, hipStream_t stream);
+hipError_t policy_head_launch(const HeadArgs& a, hipStream_t stream);
+int head_workgroups(int B);
+
+// ---- replay + elementwise ---------------------------------------------------------------
+struct PushArgs {
+    const float* src[5]; float* dst[5]; int64_t count[5];   // floats per field
+};
+hipError_t push_launch(const PushArgs& a, hipStream_t stream);
+
+struct SampleArgs {
+    pql_replay_storage st; pql_batch out;
+    const int64_t* idx_in;  // NULL: draw indices; else use these
+    int batch, o, a, N, T, nstep;
+    int head, count;
+    float gamma;
+    uint32_t key0, key1, ctr2, ctr3;
+};
+hipError_t sample_launch(const SampleArgs& a, hipStream_t stream);
+
+hipError_t soft_update_launch(const float* src, float* dst, int64_t count, float tau, hipStream_t stream);
+
+}  // namespace pql

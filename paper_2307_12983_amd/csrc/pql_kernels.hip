@@ -1,0 +1,376 @@
+// Bandwidth-class kernels of the learner path: replay push, index sampling + n-step gather,
+// the scalar output heads of the critics (dot products, min, TD target, loss, output deltas),
+// split-K reduction fused with Adam, and the Polyak target update.
+#include "pql_internal.h"
+
+namespace pql {
+
+// =============================================================================================
+// Replay push: five contiguous row copies into ring row `head` (Section 3.1 "Data Transfer";
+// Algorithm 1 append / Algorithm 3 receive).
+// =============================================================================================
+__global__ __launch_bounds__(256) void push_kernel(const PushArgs a) {
+    const int f = blockIdx.y;
+    const float* __restrict__ src = a.src[f];
+    float* __restrict__ dst = a.dst[f];
+    const int64_t n = a.count[f];
+    const bool vec = ((((uintptr_t)src) | ((uintptr_t)dst)) & 15) == 0;
+    const int64_t n4 = vec ? (n >> 2) : 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = t0; i < n4; i += stride)
+        reinterpret_cast<float4*>(dst)[i] = reinterpret_cast<const float4*>(src)[i];
+    for (int64_t i = n4 * 4 + t0; i < n; i += stride) dst[i] = src[i];
+}
+
+hipError_t push_launch(const PushArgs& a, hipStream_t stream) {
+    int64_t mx = 0;
+    for (int f = 0; f < 5; ++f) mx = a.count[f] > mx ? a.count[f] : mx;
+    int64_t blocks = (mx / 4 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(push_kernel, dim3((unsigned)blocks, 5), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+// =============================================================================================
+// Index sampling + n-step gather (Section 3.1: i.i.d. batches from the GPU-resident buffer;
+// Section 3: n-step returns with termination flag d).
+// =============================================================================================
+__device__ inline void philox4x32_10_w01(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                         uint32_t& o0, uint32_t& o1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    o0 = c0; o1 = c1;
+}
+
+template <int G, bool VEC>
+__device__ inline void copy_row(float* __restrict__ dst, const float* __restrict__ src, int n, int gl) {
+    if (VEC) {
+        const int n4 = n >> 2;
+        for (int c = gl; c < n4; c += G) reinterpret_cast<float4*>(dst)[c] = reinterpret_cast<const float4*>(src)[c];
+    } else {
+        for (int c = gl; c < n; c += G) dst[c] = src[c];
+    }
+}
+
+// G lanes cooperate on one sample; the rows of s, a, s' are copied with coalesced accesses.
+template <int G, bool VEC_O, bool VEC_A>
+__global__ __launch_bounds__(256) void sample_kernel(const SampleArgs a) {
+    const int gl = threadIdx.x % G;
+    const int k = blockIdx.x * (256 / G) + threadIdx.x / G;
+    if (k >= a.batch) return;
+
+    int64_t slot;
+    if (a.idx_in != nullptr) {
+        slot = a.idx_in[k];
+    } else {
+        uint32_t w0, w1;
+        philox4x32_10_w01((uint32_t)k, 1u, a.ctr2, a.ctr3, a.key0, a.key1, w0, w1);
+        const uint64_t u = ((uint64_t)w1 << 32) | (uint64_t)w0;
+        const uint64_t V = (uint64_t)(a.count - a.nstep + 1) * (uint64_t)a.N;
+        const uint64_t p = __umul64hi(u, V);
+        const uint64_t j = p / (uint64_t)a.N;
+        const uint64_t e = p - j * (uint64_t)a.N;
+        const int64_t row = ((int64_t)a.head - (int64_t)a.count + (int64_t)j + (int64_t)a.T) % (int64_t)a.T;
+        slot = row * (int64_t)a.N + (int64_t)e;
+        if (gl == 0) a.out.idx[k] = slot;
+    }
+    const int64_t row0 = slot / a.N;
+    const int64_t env = slot - row0 * a.N;
+
+    // fold rewards and termination flags over the window (every lane of the group reads the
+    // same addresses; lane 0 writes)
+    float ret = 0.f, alive = 1.f, g = 1.f;
+    int64_t last = slot;
+    for (int s = 0; s < a.nstep; ++s) {
+        int64_t r = row0 + s;
+        if (r >= a.T) r -= a.T;
+        last = r * (int64_t)a.N + env;
+        ret += g * a.st.rew[last] * alive;
+        alive *= (1.f - a.st.done[last]);
+        g *= a.gamma;
+    }
+    if (gl == 0) {
+        a.out.ret[k] = ret;
+        a.out.boot[k] = g * alive;
+    }
+    copy_row<G, VEC_O>(a.out.obs + (size_t)k * a.o, a.st.obs + (size_t)slot * a.o, a.o, gl);
+    copy_row<G, VEC_A>(a.out.act + (size_t)k * a.a, a.st.act + (size_t)slot * a.a, a.a, gl);
+    copy_row<G, VEC_O>(a.out.next_obs + (size_t)k * a.o, a.st.next_obs + (size_t)last * a.o, a.o, gl);
+}
+
+template <int G>
+static void sample_dispatch(const SampleArgs& a, bool vo, bool va, hipStream_t stream) {
+    const dim3 grid((a.batch + (256 / G) - 1) / (256 / G)), block(256);
+    if (vo && va)       hipLaunchKernelGGL((sample_kernel<G, true, true>), grid, block, 0, stream, a);
+    else if (vo)        hipLaunchKernelGGL((sample_kernel<G, true, false>), grid, block, 0, stream, a);
+    else if (va)        hipLaunchKernelGGL((sample_kernel<G, false, true>), grid, block, 0, stream, a);
+    else                hipLaunchKernelGGL((sample_kernel<G, false, false>), grid, block, 0, stream, a);
+}
+
+static inline bool al16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
+
+hipError_t sample_launch(const SampleArgs& a, hipStream_t stream) {
+    if (a.batch <= 0) return hipSuccess;
+    const bool vo = (a.o % 4 == 0) && al16(a.st.obs) && al16(a.st.next_obs) && al16(a.out.obs) && al16(a.out.next_obs);
+    const bool va = (a.a % 4 == 0) && al16(a.st.act) && al16(a.out.act);
+    const int per_row = vo ? a.o / 4 : a.o;
+    if (per_row <= 32) sample_dispatch<16>(a, vo, va, stream);
+    else               sample_dispatch<64>(a, vo, va, stream);
+    return hipGetLastError();
+}
+
+// =============================================================================================
+// Critic output heads.  The last critic layer has one output, so it is a dot product per row,
+// done by one wavefront per row with a cross-lane reduction.  The same pass forms the TD target
+// (min of the twin target critics, Algorithm 3 / Section 3.2), the squared Bellman error, the
+// output delta, the delta of the last hidden layer and the partial sums of the output-layer
+// gradients.
+// =============================================================================================
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+constexpr int HEAD_WAVES = 4;
+
+// Sums the per-wave column accumulators of a workgroup through LDS and writes one partial row.
+template <int NJ>
+__device__ inline void block_reduce_cols(float (&acc)[NJ], float* lds, float* __restrict__ out_row, int H, int lane,
+                                         int wave) {
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int c = lane + 64 * j;
+        if (c < H) lds[wave * H + c] = acc[j];
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < H; c += 64 * HEAD_WAVES) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < HEAD_WAVES; ++w) s += lds[w * H + c];
+        out_row[c] = s;
+    }
+}
+
+template <int NJ, bool POLICY>
+__global__ __launch_bounds__(64 * HEAD_WAVES) void head_kernel(const HeadArgs a) {
+    extern __shared__ float lds[];      // HEAD_WAVES * H floats
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int H = a.H, B = a.B;
+    const int gw = blockIdx.x * HEAD_WAVES + wave, nw = gridDim.x * HEAD_WAVES;
+
+    float wq0[NJ], wq1[NJ], wt0[NJ], wt1[NJ];
+    float dw0[NJ], dw1[NJ], dbh0[NJ], dbh1[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int c = lane + 64 * j;
+        const bool ok = c < H;
+        wq0[j] = ok ? a.wQ[0][c] : 0.f;
+        wq1[j] = ok ? a.wQ[1][c] : 0.f;
+        wt0[j] = (!POLICY && ok) ? a.wT[0][c] : 0.f;
+        wt1[j] = (!POLICY && ok) ? a.wT[1][c] : 0.f;
+        dw0[j] = dw1[j] = dbh0[j] = dbh1[j] = 0.f;
+    }
+    const float bq0 = a.bQ[0][0], bq1 = a.bQ[1][0];
+    const float bt0 = POLICY ? 0.f : a.bT[0][0], bt1 = POLICY ? 0.f : a.bT[1][0];
+    const float invB = 1.f / (float)B;
+    float loss0 = 0.f, loss1 = 0.f, db0 = 0.f, db1 = 0.f;
+
+    for (int row = gw; row < B; row += nw) {
+        const size_t base = (size_t)row * H;
+        float h0[NJ], h1[NJ];
+        float q0 = 0.f, q1 = 0.f, t0 = 0.f, t1 = 0.f;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int c = lane + 64 * j;
+            const bool ok = c < H;
+            h0[j] = ok ? a.hQ[0][base + c] : 0.f;
+            h1[j] = ok ? a.hQ[1][base + c] : 0.f;
+            q0 += h0[j] * wq0[j];
+            q1 += h1[j] * wq1[j];
+            if (!POLICY) {
+                t0 += (ok ? a.hT[0][base + c] : 0.f) * wt0[j];
+                t1 += (ok ? a.hT[1][base + c] : 0.f) * wt1[j];
+            }
+        }
+        q0 = wave_sum(q0) + bq0;
+        q1 = wave_sum(q1) + bq1;
+        float d0, d1;
+        if (POLICY) {
+            // maximise min(Q_1, Q_2): the gradient -1/B enters the smaller critic (ties: Q_1)
+            const bool pick0 = q0 <= q1;
+            loss0 += pick0 ? q0 : q1;
+            d0 = pick0 ? -invB : 0.f;
+            d1 = pick0 ? 0.f : -invB;
+        } else {
+            t0 = wave_sum(t0) + bt0;
+            t1 = wave_sum(t1) + bt1;
+            const float y = a.ret[row] + a.boot[row] * fminf(t0, t1);
+            const float e0 = q0 - y, e1 = q1 - y;
+            loss0 += e0 * e0;
+            loss1 += e1 * e1;
+            d0 = 2.f * e0 * invB;
+            d1 = 2.f * e1 * invB;
+            db0 += d0;
+            db1 += d1;
+            if (lane == 0) a.y[row] = y;
+        }
+        if (lane == 0) { a.q[0][row] = q0; a.q[1][row] = q1; }
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int c = lane + 64 * j;
+            if (c < H) {
+                const float g0 = d0 * wq0[j] * (h0[j] > 0.f ? 1.f : h0[j] + 1.f);
+                const float g1 = d1 * wq1[j] * (h1[j] > 0.f ? 1.f : h1[j] + 1.f);
+                a.dQ[0][base + c] = g0;
+                a.dQ[1][base + c] = g1;
+                if (!POLICY) {
+                    dbh0[j] += g0; dbh1[j] += g1;
+                    dw0[j] += d0 * h0[j]; dw1[j] += d1 * h1[j];
+                }
+            }
+        }
+    }
+
+    const int wg = blockIdx.x, nwg = gridDim.x;
+    if (!POLICY) {
+        block_reduce_cols<NJ>(dw0, lds, a.p_dw[0] + (size_t)wg * H, H, lane, wave);
+        block_reduce_cols<NJ>(dw1, lds, a.p_dw[1] + (size_t)wg * H, H, lane, wave);
+        block_reduce_cols<NJ>(dbh0, lds, a.p_dbh[0] + (size_t)wg * H, H, lane, wave);
+        block_reduce_cols<NJ>(dbh1, lds, a.p_dbh[1] + (size_t)wg * H, H, lane, wave);
+    }
+    // scalars: loss and output-bias gradient (identical in every lane of a wave)
+    __syncthreads();
+    if (lane == 0) {
+        lds[wave * 4 + 0] = loss0; lds[wave * 4 + 1] = loss1;
+        lds[wave * 4 + 2] = db0;   lds[wave * 4 + 3] = db1;
+    }
+    __syncthreads();
+    if (threadIdx.x < 4) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < HEAD_WAVES; ++w) s += lds[w * 4 + threadIdx.x];
+        if (threadIdx.x == 0) a.p_loss[wg] = s;
+        if (!POLICY) {
+            if (threadIdx.x == 1) a.p_loss[nwg + wg] = s;
+            if (threadIdx.x == 2) a.p_db[0][wg] = s;
+            if (threadIdx.x == 3) a.p_db[1][wg] = s;
+        }
+    }
+}
+
+int head_workgroups(int B) {
+    int n = (B + HEAD_WAVES * 8 - 1) / (HEAD_WAVES * 8);   // about 8 rows per wavefront
+    if (n < 1) n = 1;
+    if (n > 512) n = 512;
+    return n;
+}
+
+template <bool POLICY>
+static hipError_t head_launch(const HeadArgs& a, hipStream_t stream) {
+    const dim3 grid(a.nwg), block(64 * HEAD_WAVES);
+    const size_t lds = (size_t)HEAD_WAVES * (a.H > 4 ? a.H : 4) * sizeof(float);
+    const int nj = (a.H + 63) / 64;
+    if (nj <= 1)       hipLaunchKernelGGL((head_kernel<1, POLICY>), grid, block, lds, stream, a);
+    else if (nj <= 2)  hipLaunchKernelGGL((head_kernel<2, POLICY>), grid, block, lds, stream, a);
+    else if (nj <= 4)  hipLaunchKernelGGL((head_kernel<4, POLICY>), grid, block, lds, stream, a);
+    else if (nj <= 8)  hipLaunchKernelGGL((head_kernel<8, POLICY>), grid, block, lds, stream, a);
+    else if (nj <= 16) hipLaunchKernelGGL((head_kernel<16, POLICY>), grid, block, lds, stream, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t critic_head_launch(const HeadArgs& a, hipStream_t stream) { return head_launch<false>(a, stream); }
+hipError_t policy_head_launch(const HeadArgs& a, hipStream_t stream) { return head_launch<true>(a, stream); }
+
+// =============================================================================================
+// Gradient reduction + Adam (Table B.1 "Optimizer: Adam"; Kingma & Ba, Algorithm 1).
+// Each parameter's gradient is the ordered sum of its partial results (split-K slabs of the
+// weight-gradient GEMMs, per-tile column sums for biases); the Adam step is applied in the
+// same pass.  Block (0,0) also finalises the loss scalars.
+// =============================================================================================
+__global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
+    const RedTensor& T = a.t[blockIdx.y];
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < T.count) {
+        float g = 0.f;
+        const float* __restrict__ p = T.partial + i;
+        for (int s = 0; s < T.nparts; ++s) g += p[(size_t)s * (size_t)T.stride];
+        const int64_t k = T.offset + i;
+        const float m = a.beta1 * a.m[k] + (1.f - a.beta1) * g;
+        const float v = a.beta2 * a.v[k] + (1.f - a.beta2) * g * g;
+        const float m_hat = m * a.inv_bc1;
+        const float v_hat = v * a.inv_bc2;
+        a.theta[k] = a.theta[k] - a.lr * m_hat / (sqrtf(v_hat) + a.eps);
+        a.m[k] = m;
+        a.v[k] = v;
+        a.g[k] = g;
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0) {
+        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        if (wave < a.nloss) {
+            float s = 0.f;
+            for (int j = lane; j < a.loss_parts; j += 64) s += a.loss_partial[wave * a.loss_parts + j];
+            s = wave_sum(s);
+            if (lane == 0) a.loss_out[wave] = s * a.loss_scale;
+        }
+    }
+}
+
+hipError_t adam_reduce_launch(const AdamArgs& a, hipStream_t stream) {
+    int mx = 1;
+    for (int i = 0; i < a.ntensors; ++i) mx = a.t[i].count > mx ? a.t[i].count : mx;
+    const dim3 grid((mx + 255) / 256, a.ntensors), block(256);
+    hipLaunchKernelGGL(adam_reduce_kernel, grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+// =============================================================================================
+// Polyak target update (Table B.1 target update rate tau; tau = 1 is the hard policy sync of
+// Section 3.2).
+// =============================================================================================
+__global__ __launch_bounds__(256) void soft_update_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                          int64_t n, float tau, int vec) {
+    const float keep = 1.f - tau;
+    const int64_t n4 = vec ? (n >> 2) : 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = t0; i < n4; i += stride) {
+        const float4 s = reinterpret_cast<const float4*>(src)[i];
+        float4 d = reinterpret_cast<float4*>(dst)[i];
+        d.x = tau * s.x + keep * d.x; d.y = tau * s.y + keep * d.y;
+        d.z = tau * s.z + keep * d.z; d.w = tau * s.w + keep * d.w;
+        reinterpret_cast<float4*>(dst)[i] = d;
+    }
+    for (int64_t i = n4 * 4 + t0; i < n; i += stride) dst[i] = tau * src[i] + keep * dst[i];
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n,
+                                                   int vec) {
+    const int64_t n4 = vec ? (n >> 2) : 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = t0; i < n4; i += stride) reinterpret_cast<float4*>(dst)[i] = reinterpret_cast<const float4*>(src)[i];
+    for (int64_t i = n4 * 4 + t0; i < n; i += stride) dst[i] = src[i];
+}
+
+hipError_t soft_update_launch(const float* src, float* dst, int64_t count, float tau, hipStream_t stream) {
+    if (count <= 0 || tau == 0.f) return hipSuccess;           // tau = 0 leaves dst untouched
+    const int vec = (al16(src) && al16(dst)) ? 1 : 0;
+    int64_t blocks = (count / 4 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 2048) blocks = 2048;
+    if (tau == 1.f) hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count, vec);
+    else hipLaunchKernelGGL(soft_update_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count, tau, vec);
+    return hipGetLastError();
+}
+
+}  // namespace pql

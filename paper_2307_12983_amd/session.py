@@ -1,0 +1,82 @@
+"""Device-memory plumbing for one learner: allocates the caller-owned buffers the C interface
+expects (replay ring, batch, parameters, Adam moments, gradients, workspace) with torch and
+forwards each step to the C entry point of the same name.  No arithmetic happens here.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+
+from . import binding as B
+from .workloads import Workload, init_networks
+
+
+class LearnerSession:
+    def __init__(self, w: Workload, device: str = "cuda", max_batch: Optional[int] = None, seed: Optional[int] = None):
+        import torch
+        self.torch = torch
+        self.w = w
+        self.device = device
+        self.max_batch = int(max_batch or max(w.batch, w.num_envs))
+        self.cfg = B.make_config(w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.nstep, w.gamma, w.hidden,
+                                 self.max_batch, w.rng_seed if seed is None else seed)
+        self.ctx = B.Context(self.cfg)
+        self.rows = self.ctx.replay_rows()
+        self.storage = B.Storage(self.rows, w.num_envs, w.obs_dim, w.act_dim, device)
+        self.batch = B.Batch(self.max_batch, w.obs_dim, w.act_dim, device)
+        actor, critic = init_networks(w)
+        self.actor_init, self.critic_init = actor, critic
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+        self.actor = t(actor)
+        self.actor_lag = t(actor)            # pi^v: the V-learner's lagged copy of the policy
+        self.critic = t(critic)
+        self.critic_target = t(critic)
+        z = lambda n: torch.zeros(n, dtype=torch.float32, device=device)
+        self.c_m, self.c_v, self.c_g = z(critic.size), z(critic.size), z(critic.size)
+        self.a_m, self.a_v, self.a_g = z(actor.size), z(actor.size), z(actor.size)
+        self.critic_loss = z(2)
+        self.actor_loss = z(1)
+        self.workspace = torch.zeros(self.ctx.workspace_bytes() // 4 + 64, dtype=torch.float32, device=device)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.act_out = torch.zeros((self.max_batch, w.act_dim), dtype=torch.float32, device=device)
+        self.opt = B.PqlAdam(w.lr, w.beta1, w.beta2, w.eps)
+
+    # ---- steps, one C call each ----------------------------------------------------------
+    def to_device(self, row):
+        t = self.torch
+        return {k: (v if isinstance(v, t.Tensor) else t.from_numpy(np.ascontiguousarray(v))).to(self.device)
+                for k, v in row.items()}
+
+    def push(self, row, stream=None):
+        r = self.to_device(row)
+        self.ctx.pql_replay_push(self.storage, r["obs"], r["act"], r["rew"], r["next_obs"], r["done"], stream)
+
+    def sample(self, batch_size: Optional[int] = None, stream=None):
+        self.ctx.pql_sample_nstep(self.storage, int(batch_size or self.w.batch), self.batch, stream)
+
+    def gather(self, idx, stream=None):
+        self.ctx.pql_gather_nstep(self.storage, idx, int(idx.numel()), self.batch, stream)
+
+    def critic_update(self, batch_size: Optional[int] = None, stream=None):
+        self.ctx.pql_critic_update(self.critic, self.critic_target, self.actor_lag, self.c_m, self.c_v, self.c_g,
+                                   self.batch, int(batch_size or self.w.batch), self.opt, self.critic_loss,
+                                   self.workspace, stream)
+
+    def soft_update_targets(self, stream=None):
+        self.ctx.pql_soft_update(self.critic, self.critic_target, self.critic.numel(), self.w.tau, stream)
+
+    def actor_update(self, obs=None, batch_size: Optional[int] = None, stream=None):
+        obs = self.batch.obs if obs is None else obs
+        self.ctx.pql_actor_update(self.actor, self.critic, self.a_m, self.a_v, self.a_g, obs,
+                                  int(batch_size or self.w.batch), self.opt, self.actor_loss, self.workspace, stream)
+
+    def sync_lagged_policy(self, stream=None):
+        self.ctx.pql_soft_update(self.actor, self.actor_lag, self.actor.numel(), 1.0, stream)
+
+    def act(self, obs, sigma_min=None, sigma_max=None, stream=None):
+        n = int(obs.shape[0])
+        self.ctx.pql_actor_act(self.actor, obs, n, self.w.sigma_min if sigma_min is None else sigma_min,
+                               self.w.sigma_max if sigma_max is None else sigma_max, self.act_out, self.workspace,
+                               stream)
+        return self.act_out[:n]

@@ -1,0 +1,75 @@
+"""Shared helpers of the GPU parity tests: run the same seeded inputs through the HIP path
+(LearnerSession -> C-ABI) and through the CPU oracle, and compare tensor by tensor."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import pql_oracle as O
+from paper_2307_12983_amd import workloads as W
+
+TOL_ONE_STEP = 1e-4     # max relative error after one step (per tensor, max-norm)
+TOL_100_STEPS = 1e-3    # after 100 steps
+
+
+def rel_err(x, ref):
+    """max_i |x_i - ref_i| / max(max_i |ref_i|, 1e-30): the per-tensor max-norm relative error.
+    Element-wise relative error is meaningless for gradients that pass through zero."""
+    x = np.asarray(x, np.float64).ravel()
+    ref = np.asarray(ref, np.float64).ravel()
+    assert x.shape == ref.shape
+    if x.size == 0:
+        return 0.0
+    return float(np.max(np.abs(x - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+
+
+def split_tensors(flat, dims, nets=1):
+    """Flat vector(s) -> list of (name, array) per W_l / b_l of each network."""
+    flat = np.asarray(flat)
+    out, off = [], 0
+    for n in range(nets):
+        for li, (i, o) in enumerate(dims):
+            out.append(("net%d.W%d" % (n, li), flat[off:off + i * o])); off += i * o
+            out.append(("net%d.b%d" % (n, li), flat[off:off + o])); off += o
+    assert off == flat.size
+    return out
+
+
+def assert_params_close(got, ref, dims, nets, tol, what):
+    worst = 0.0
+    for (name, g), (_, r) in zip(split_tensors(got, dims, nets), split_tensors(ref, dims, nets)):
+        e = rel_err(g, r)
+        worst = max(worst, e)
+        assert e <= tol, "%s %s: rel err %.3e > %.1e" % (what, name, e, tol)
+    return worst
+
+
+def oracle_ring(w: W.Workload):
+    return O.ReplayRing(w.rows, w.num_envs, w.obs_dim, w.act_dim)
+
+
+def oracle_learner(w: W.Workload, actor, critic):
+    return O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps)
+
+
+def fill_both(sess, ring, w: W.Workload, rows: int, rng=None):
+    """Pushes the same `rows` synthetic Actor steps into the device ring and the oracle ring."""
+    rng = rng or W.data_rng(w)
+    for row in W.transition_rows(w, rng, rows):
+        sess.push(row)
+        ring.push(row["obs"], row["act"], row["rew"], row["next_obs"], row["done"])
+    return rng
+
+
+def batch_to_numpy(batch, B):
+    return dict(idx=batch.idx[:B].cpu().numpy(), obs=batch.obs[:B].cpu().numpy(), act=batch.act[:B].cpu().numpy(),
+                ret=batch.ret[:B].cpu().numpy(), next_obs=batch.next_obs[:B].cpu().numpy(),
+                boot=batch.boot[:B].cpu().numpy())
+
+
+def assert_batch_matches(got, ref):
+    assert np.array_equal(got["idx"], ref["idx"]), "sampled indices differ"
+    for k in ("obs", "act", "next_obs"):
+        assert np.array_equal(got[k], ref[k]), "gathered %s differs (must be bit-exact)" % k
+    assert rel_err(got["ret"], ref["ret"]) <= 1e-6
+    assert rel_err(got["boot"], ref["boot"]) <= 1e-6
+    assert np.array_equal(got["boot"] == 0.0, ref["boot"] == 0.0)

@@ -1,0 +1,112 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, answers the size queries and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2307_12983_amd import binding as B
+from paper_2307_12983_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "pql.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pql_[a-z_]+)\s*\(", text)))
+
+
+def cfg_of(w, max_batch=None):
+    return B.make_config(w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.nstep, w.gamma, w.hidden,
+                         max_batch or max(w.batch, w.num_envs), w.rng_seed)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    names = header_functions()
+    assert len(names) == 16 and sorted(B.EXPORTS) == names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+@pytest.mark.parametrize("name", list(W.WORKLOADS))
+def test_size_queries(name):
+    w = W.WORKLOADS[name]
+    ctx = B.Context(cfg_of(w))
+    assert ctx.replay_rows() == w.capacity // w.num_envs
+    assert ctx.actor_param_count() == W.param_count(w.actor_dims())
+    assert ctx.critic_param_count() == W.param_count(w.critic_dims())
+    ws = ctx.workspace_bytes()
+    assert ws > 0 and ws % 256 == 0
+    # workspace grows with the batch bound
+    assert B.Context(cfg_of(w, 2 * max(w.batch, w.num_envs))).workspace_bytes() > ws
+    assert ctx.get_state() == [0] * 8
+    ctx.close()
+
+
+def test_create_rejects_bad_configs():
+    lib = B.load_library()
+    w = W.WORKLOADS["tiny"]
+    h = C.c_void_p()
+    assert lib.pql_create(None, C.byref(h)) == -2
+    assert lib.pql_create(C.byref(cfg_of(w)), None) == -2
+    for field, value in [("obs_dim", 0), ("act_dim", 0), ("num_envs", 0), ("nstep", 0), ("n_hidden", 0),
+                         ("n_hidden", 9), ("gamma", 0.0), ("gamma", 1.5), ("max_batch", 0), ("capacity", 64 * 2)]:
+        cfg = cfg_of(w)
+        setattr(cfg, field, value)
+        assert lib.pql_create(C.byref(cfg), C.byref(h)) == -1, field
+        assert lib.pql_workspace_bytes(C.byref(cfg)) == -1, field
+    cfg = cfg_of(w)
+    cfg.hidden[1] = 2048                       # last hidden layer wider than the head kernel supports
+    assert lib.pql_create(C.byref(cfg), C.byref(h)) == -1
+
+
+def test_argument_errors_are_caught_on_the_host_and_leave_state_unchanged():
+    """Null pointers, oversize batches and bad scalars return before any kernel launch, so
+    these calls are safe without a GPU."""
+    w = W.WORKLOADS["tiny"]
+    ctx = B.Context(cfg_of(w))
+    lib = ctx.lib
+    fake = 0x1000                               # never dereferenced: validation fails first
+    st_null = B.PqlStorage(None, None, None, None, None)
+    st = B.PqlStorage(fake, fake, fake, fake, fake)
+    bt = B.PqlBatch(fake, fake, fake, fake, fake, fake)
+    opt = B.PqlAdam(1e-3, 0.9, 0.999, 1e-8)
+    assert lib.pql_replay_push(ctx.h, st_null, fake, fake, fake, fake, fake, None) == -2
+    assert lib.pql_replay_push(ctx.h, st, fake, None, fake, fake, fake, None) == -2
+    assert lib.pql_sample_nstep(ctx.h, st, 16, bt, None) == -3            # nothing pushed yet
+    assert lib.pql_sample_nstep(ctx.h, st, w.batch + 1, bt, None) == -4
+    assert lib.pql_sample_nstep(ctx.h, st, -1, bt, None) == -1
+    assert lib.pql_gather_nstep(ctx.h, st, None, 4, bt, None) == -2
+    assert lib.pql_actor_act(ctx.h, fake, fake, 0, 0.1, 0.1, fake, 0x1000, None) == -1
+    assert lib.pql_actor_act(ctx.h, fake, fake, w.batch + 1, 0.1, 0.1, fake, 0x1000, None) == -4
+    assert lib.pql_actor_act(ctx.h, fake, fake, 8, 0.1, 0.1, fake, 0x1010, None) == -6
+    assert lib.pql_actor_act(ctx.h, None, fake, 8, 0.1, 0.1, fake, 0x1000, None) == -2
+    assert lib.pql_critic_update(ctx.h, fake, fake, fake, fake, fake, fake, bt, w.batch + 1, opt, fake, 0x1000, None) == -4
+    assert lib.pql_critic_update(ctx.h, fake, fake, fake, fake, fake, fake, bt, 0, opt, fake, 0x1000, None) == -1
+    assert lib.pql_critic_update(ctx.h, fake, fake, None, fake, fake, fake, bt, 8, opt, fake, 0x1000, None) == -2
+    bad = B.PqlAdam(1e-3, 1.0, 0.999, 1e-8)
+    assert lib.pql_critic_update(ctx.h, fake, fake, fake, fake, fake, fake, bt, 8, bad, fake, 0x1000, None) == -1
+    assert lib.pql_actor_update(ctx.h, fake, fake, fake, fake, fake, fake, 8, bad, fake, 0x1000, None) == -1
+    assert lib.pql_actor_update(ctx.h, fake, fake, fake, fake, fake, None, 8, opt, fake, 0x1000, None) == -2
+    assert lib.pql_actor_update(ctx.h, fake, fake, fake, fake, fake, fake, 8, opt, fake, 0x1008, None) == -6
+    assert lib.pql_soft_update(ctx.h, fake, fake, 10, 1.5, None) == -1
+    assert lib.pql_soft_update(ctx.h, fake, fake, -1, 0.5, None) == -1
+    assert lib.pql_soft_update(ctx.h, None, fake, 10, 0.5, None) == -2
+    assert lib.pql_soft_update(ctx.h, fake, fake, 10, 0.0, None) == 0      # tau = 0: nothing to do
+    assert ctx.get_state() == [0] * 8
+    assert "pql_" in ctx.last_error()
+
+
+def test_state_roundtrip_and_validation():
+    w = W.WORKLOADS["tiny"]
+    ctx = B.Context(cfg_of(w))
+    ctx.set_state([3, 10, 99, 7, 5, 4, 2, 0])
+    assert ctx.get_state() == [3, 10, 99, 7, 5, 4, 2, 0]
+    with pytest.raises(B.PqlError):
+        ctx.set_state([w.rows, 0, 0, 0, 0, 0, 0, 0])
+    with pytest.raises(B.PqlError):
+        ctx.set_state([0, 0, -1, 0, 0, 0, 0, 0])
+    assert ctx.get_state() == [3, 10, 99, 7, 5, 4, 2, 0]

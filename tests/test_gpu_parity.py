@@ -1,0 +1,264 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle on identical
+seeded inputs.  Integer / copy work must be bit-exact; floats within the per-tensor max-norm
+relative error 1e-4 after one step and 1e-3 after 100 steps.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import pql_oracle as O
+from paper_2307_12983_amd import workloads as W
+
+from parity_util import (TOL_100_STEPS, TOL_ONE_STEP, assert_batch_matches, assert_params_close, batch_to_numpy,
+                         fill_both, oracle_learner, oracle_ring, rel_err)
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the gpu-marked tests need a real MI355X")
+    return torch
+
+
+def make_session(w, **kw):
+    from paper_2307_12983_amd.session import LearnerSession
+    return LearnerSession(w, **kw)
+
+
+# Reduced cases: the network shapes of each workload at batch sizes the oracle handles in well
+# under a second, chosen so that rows/columns are not multiples of the 32/64/128 tile sizes.
+def small_cases():
+    Wk = W.WORKLOADS
+    return {
+        "tiny": Wk["tiny"],
+        "ragged": Wk["tiny"].replace(name="ragged", obs_dim=13, act_dim=3, num_envs=50, capacity=50 * 11, batch=333,
+                                     hidden=(96, 40), index=10),
+        "ant_s": Wk["ant"].replace(name="ant_s", num_envs=96, capacity=96 * 13, batch=1000),
+        "humanoid_s": Wk["humanoid"].replace(name="humanoid_s", num_envs=64, capacity=64 * 9, batch=777),
+        "shadow_s": Wk["shadow"].replace(name="shadow_s", num_envs=40, capacity=40 * 10, batch=640),
+        "scale_s": Wk["scale"].replace(name="scale_s", num_envs=48, capacity=48 * 12, batch=520),
+    }
+
+
+SMALL = small_cases()
+
+
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["tiny", "ragged", "shadow_s"])
+def test_push_ring_contents_bit_exact(torch_cuda, case):
+    w = SMALL[case]
+    say("case", case, "push 2.5*T rows, T =", w.rows)
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, int(2.5 * w.rows) + 1)
+    torch_cuda.cuda.synchronize()
+    st = s.ctx.get_state()
+    assert st[0] == ring.head and st[1] == ring.count and st[2] == int(2.5 * w.rows) + 1
+    for f in ("obs", "act", "rew", "next_obs", "done"):
+        assert np.array_equal(getattr(s.storage, f).cpu().numpy(), getattr(ring, f)), f
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged", "ant_s", "shadow_s", "scale_s"])
+@pytest.mark.parametrize("fill", ["partial", "wrapped"])
+def test_sample_nstep_indices_and_gather(torch_cuda, case, fill):
+    w = SMALL[case]
+    rows = w.nstep + 2 if fill == "partial" else 2 * w.rows + 3
+    say("case", case, fill, "rows pushed", rows)
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, rows)
+    for call in range(3):
+        Bsz = w.batch if call < 2 else 7
+        s.sample(Bsz)
+        ref = O.gather_nstep(ring, O.sample_indices(ring, w.nstep, Bsz, w.rng_seed, call), w.nstep, w.gamma)
+        assert_batch_matches(batch_to_numpy(s.batch, Bsz), ref)
+    assert s.ctx.get_state()[3] == 3
+
+
+def test_gather_with_given_indices_and_degenerate_window(torch_cuda):
+    w = SMALL["ragged"]
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, w.nstep)          # exactly one valid start row
+    s.sample(64)
+    ref_idx = O.sample_indices(ring, w.nstep, 64, w.rng_seed, 0)
+    assert np.all(ref_idx // w.num_envs == ring.physical_row(0))
+    assert_batch_matches(batch_to_numpy(s.batch, 64), O.gather_nstep(ring, ref_idx, w.nstep, w.gamma))
+    idx = np.arange(w.num_envs, dtype=np.int64)[::-1].copy()
+    s.gather(torch_cuda.from_numpy(idx).cuda())
+    got = batch_to_numpy(s.batch, idx.size)
+    got["idx"] = idx
+    assert_batch_matches(got, O.gather_nstep(ring, idx, w.nstep, w.gamma))
+    assert s.ctx.get_state()[3] == 1        # gather does not advance the sample counter
+
+
+def test_sample_errors_leave_state_unchanged(torch_cuda):
+    from paper_2307_12983_amd.binding import PqlError
+    w = SMALL["tiny"]
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, w.nstep - 1)
+    before = s.ctx.get_state()
+    with pytest.raises(PqlError) as e:
+        s.sample(16)
+    assert e.value.code == -3
+    with pytest.raises(PqlError) as e:
+        s.ctx.pql_sample_nstep(s.storage, s.max_batch + 1, s.batch)
+    assert e.value.code == -4
+    assert s.ctx.get_state() == before
+
+
+# ---------------------------------------------------------------------------------------------
+def test_soft_update_pins_and_values(torch_cuda):
+    torch = torch_cuda
+    s = make_session(SMALL["tiny"])
+    g = torch.Generator(device="cpu").manual_seed(0)
+    for n in (1, 3, 4, 1023, 4096 + 5, 300001):
+        src = torch.randn(n + 1, generator=g).cuda()
+        dst = torch.randn(n + 1, generator=g).cuda()
+        for off in (0, 1):                   # 16-byte aligned and unaligned views
+            a, b = src[off:off + n], dst[off:off + n].clone()
+            b0 = b.clone()
+            s.ctx.pql_soft_update(a, b, n, 1.0)
+            assert torch.equal(a, b)
+            b = b0.clone()
+            s.ctx.pql_soft_update(a, b, n, 0.0)
+            assert torch.equal(b, b0)
+            b = b0.clone()
+            s.ctx.pql_soft_update(a, b, n, 0.05)
+            ref = O.soft_update(a.cpu().numpy(), b0.cpu().numpy(), float(np.float32(0.05)))
+            assert rel_err(b.cpu().numpy(), ref) <= 1e-6
+
+
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["tiny", "ragged", "ant_s", "humanoid_s", "shadow_s", "scale_s"])
+def test_actor_act_matches_oracle(torch_cuda, case):
+    torch = torch_cuda
+    w = SMALL[case]
+    s = make_session(w)
+    rng = np.random.default_rng(7)
+    for call, num in enumerate((w.num_envs, 1, min(s.max_batch, 333))):
+        obs = rng.standard_normal((num, w.obs_dim), dtype=np.float32)
+        got = s.act(torch.from_numpy(obs).cuda(), 0.05, 0.8).cpu().numpy()
+        ref = O.actor_act(s.actor_init, w.actor_dims(), obs, float(np.float32(0.05)), float(np.float32(0.8)),
+                          w.rng_seed, call)
+        e = rel_err(got, ref)
+        say(case, "act call", call, "num", num, "rel err %.2e" % e)
+        assert e <= TOL_ONE_STEP and got.min() >= -1.0 and got.max() <= 1.0
+    obs = rng.standard_normal((w.num_envs, w.obs_dim), dtype=np.float32)
+    got = s.act(torch.from_numpy(obs).cuda(), 0.0, 0.0).cpu().numpy()
+    assert rel_err(got, O.actor_forward(s.actor_init, w.actor_dims(), obs)) <= TOL_ONE_STEP
+
+
+# ---------------------------------------------------------------------------------------------
+def one_step(torch, w, rows, check_all=True):
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, rows)
+    L = oracle_learner(w, s.actor_init, s.critic_init)
+    Bsz = w.batch
+    s.sample(Bsz)
+    batch = O.gather_nstep(ring, O.sample_indices(ring, w.nstep, Bsz, w.rng_seed, 0), w.nstep, w.gamma)
+    assert_batch_matches(batch_to_numpy(s.batch, Bsz), batch)
+    # critic update
+    s.critic_update(Bsz)
+    losses, g = L.critic_update(batch)
+    res = {}
+    res["loss"] = rel_err(s.critic_loss.cpu().numpy(), losses)
+    res["grad"] = assert_params_close(s.c_g.cpu().numpy(), g, w.critic_dims(), 2, TOL_ONE_STEP, "critic grad")
+    res["theta"] = assert_params_close(s.critic.cpu().numpy(), L.critic, w.critic_dims(), 2, TOL_ONE_STEP, "critic params")
+    res["m"] = assert_params_close(s.c_m.cpu().numpy(), L.c_m, w.critic_dims(), 2, TOL_ONE_STEP, "critic adam m")
+    res["v"] = assert_params_close(s.c_v.cpu().numpy(), L.c_v, w.critic_dims(), 2, TOL_ONE_STEP, "critic adam v")
+    assert res["loss"] <= TOL_ONE_STEP
+    # Polyak
+    s.soft_update_targets()
+    L.soft_update_targets()
+    res["target"] = assert_params_close(s.critic_target.cpu().numpy(), L.critic_target, w.critic_dims(), 2,
+                                        TOL_ONE_STEP, "critic target")
+    # policy update on the sampled states, then hard sync of the lagged policy
+    s.actor_update(None, Bsz)
+    J, ga = L.actor_update(batch["obs"])
+    res["J"] = abs(float(s.actor_loss.cpu().numpy()[0]) - J) / max(abs(J), 1e-30)
+    res["a_grad"] = assert_params_close(s.a_g.cpu().numpy(), ga, w.actor_dims(), 1, TOL_ONE_STEP, "actor grad")
+    res["a_theta"] = assert_params_close(s.actor.cpu().numpy(), L.actor, w.actor_dims(), 1, TOL_ONE_STEP, "actor params")
+    assert res["J"] <= TOL_ONE_STEP
+    s.sync_lagged_policy()
+    assert torch.equal(s.actor, s.actor_lag)
+    st = s.ctx.get_state()
+    assert st[5] == 1 and st[6] == 1
+    return res
+
+
+@pytest.mark.parametrize("case", list(SMALL))
+def test_one_update_small_cases(torch_cuda, case):
+    w = SMALL[case]
+    say("case", case, "B", w.batch, "hidden", w.hidden)
+    res = one_step(torch_cuda, w, min(w.rows, w.nstep + 4))
+    say(case, " ".join("%s=%.2e" % kv for kv in res.items()))
+
+
+@pytest.mark.parametrize("name", ["ant", "humanoid", "shadow", "scale"])
+def test_one_update_full_size(torch_cuda, name):
+    """Full batch and network sizes of each workload.  The ring keeps its full number of rows
+    but only n + 8 of them are filled, which bounds host memory and generation time."""
+    w = W.WORKLOADS[name]
+    say("workload", name, "B", w.batch, "hidden", w.hidden, "rows filled", w.nstep + 8)
+    res = one_step(torch_cuda, w, w.nstep + 8)
+    say(name, " ".join("%s=%.2e" % kv for kv in res.items()))
+
+
+# ---------------------------------------------------------------------------------------------
+def many_steps(torch, w, rows, steps, actor_every=0):
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, rows)
+    L = oracle_learner(w, s.actor_init, s.critic_init)
+    Bsz = w.batch
+    worst_loss = 0.0
+    for it in range(steps):
+        s.sample(Bsz)
+        s.critic_update(Bsz)
+        s.soft_update_targets()
+        batch = O.gather_nstep(ring, O.sample_indices(ring, w.nstep, Bsz, w.rng_seed, it), w.nstep, w.gamma)
+        losses, _ = L.critic_update(batch)
+        L.soft_update_targets()
+        if actor_every and (it + 1) % actor_every == 0:
+            s.actor_update(None, Bsz)
+            s.sync_lagged_policy()
+            L.actor_update(batch["obs"])
+            L.sync_lagged_policy()
+        if it % 10 == 9 or it == steps - 1:
+            e = rel_err(s.critic_loss.cpu().numpy(), losses)
+            worst_loss = max(worst_loss, e)
+            say("  step", it + 1, "loss", losses, "rel err %.2e" % e)
+    assert np.array_equal(s.batch.idx[:Bsz].cpu().numpy(), batch["idx"])
+    res = dict(loss=worst_loss)
+    res["theta"] = assert_params_close(s.critic.cpu().numpy(), L.critic, w.critic_dims(), 2, TOL_100_STEPS, "critic params")
+    res["target"] = assert_params_close(s.critic_target.cpu().numpy(), L.critic_target, w.critic_dims(), 2, TOL_100_STEPS, "critic target")
+    res["actor"] = assert_params_close(s.actor.cpu().numpy(), L.actor, w.actor_dims(), 1, TOL_100_STEPS, "actor params")
+    assert worst_loss <= TOL_100_STEPS
+    return res
+
+
+def test_100_updates_tiny(torch_cuda):
+    w = W.WORKLOADS["tiny"]
+    res = many_steps(torch_cuda, w, w.rows, 100, actor_every=2)
+    say("tiny 100 steps", res)
+
+
+def test_100_critic_10_actor_updates_ant_full_batch(torch_cuda):
+    w = W.WORKLOADS["ant"]
+    res = many_steps(torch_cuda, w, w.nstep + 8, 100, actor_every=10)
+    say("ant 100 steps", res)
+
+
+@pytest.mark.parametrize("name", ["humanoid", "shadow", "scale"])
+def test_100_updates_reduced_batch(torch_cuda, name):
+    """100 critic updates with the full network shapes at batch 1024 (the full-batch float64
+    oracle would need minutes per workload; full batch is covered by the one-step test)."""
+    w = W.WORKLOADS[name].replace(num_envs=256, capacity=256 * 16, batch=1024)
+    res = many_steps(torch_cuda, w, w.rows, 100, actor_every=0)
+    say(name, "100 steps", res)
