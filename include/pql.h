@@ -174,6 +174,16 @@ int32_t pql_actor_update(pql_ctx* ctx, float* actor_params, const float* critic_
                          float* adam_v, float* grads_out, const float* obs, int32_t batch_size, pql_adam opt,
                          float* loss_out, void* workspace, void* stream);
 
+/* ---- optimiser (Table B.1 "Optimizer: Adam", learning rate 5e-4) ------------------------ */
+
+/* One Adam step (Kingma & Ba, Algorithm 1: bias-corrected moments, eps added outside the
+ * square root) on a flat vector with a caller-given gradient; the same kernel performs the fused
+ * step inside pql_critic_update / pql_actor_update.  params/grads/adam_m/adam_v: [device],
+ * `count` floats each (count < 2^31); `t` >= 1 is the step number used for the bias correction.
+ * Context counters are not touched. */
+int32_t pql_adam_step(pql_ctx* ctx, float* params, const float* grads, float* adam_m, float* adam_v,
+                      int64_t count, pql_adam opt, int64_t t, void* stream);
+
 /* ---- target tracking (Table B.1 target update rate; Section 3.2 hard policy sync) -------- */
 
 /* dst[i] = tau * src[i] + (1 - tau) * dst[i] for i < count ([device], may not partially

@@ -22,7 +22,7 @@ ERRORS = {0: "PQL_OK", -1: "PQL_ERR_INVALID_ARG", -2: "PQL_ERR_NULL", -3: "PQL_E
 EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_count", "pql_critic_param_count",
            "pql_workspace_bytes", "pql_last_error", "pql_get_state", "pql_set_state", "pql_replay_push",
            "pql_sample_nstep", "pql_gather_nstep", "pql_actor_act", "pql_critic_update", "pql_actor_update",
-           "pql_soft_update"]
+           "pql_soft_update", "pql_adam_step"]
 
 
 class PqlConfig(C.Structure):
@@ -80,6 +80,7 @@ def load_library() -> C.CDLL:
         "pql_critic_update": (I32, [P, P, P, P, P, P, P, PqlBatch, I32, PqlAdam, P, P, P]),
         "pql_actor_update": (I32, [P, P, P, P, P, P, P, I32, PqlAdam, P, P, P]),
         "pql_soft_update": (I32, [P, P, P, I64, F, P]),
+        "pql_adam_step": (I32, [P, P, P, P, P, I64, PqlAdam, I64, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -222,6 +223,10 @@ class Context:
         self._check(self.lib.pql_actor_update(self.h, _ptr(actor_params), _ptr(critic_params), _ptr(adam_m),
                                               _ptr(adam_v), _ptr(grads_out), _ptr(obs), batch_size, opt,
                                               _ptr(loss_out), _ptr(workspace), _stream(stream)))
+
+    def pql_adam_step(self, params, grads, adam_m, adam_v, count, opt: PqlAdam, t, stream=None):
+        self._check(self.lib.pql_adam_step(self.h, _ptr(params), _ptr(grads), _ptr(adam_m), _ptr(adam_v), count, opt, t,
+                                           _stream(stream)))
 
     def pql_soft_update(self, src, dst, count, tau, stream=None):
         self._check(self.lib.pql_soft_update(self.h, _ptr(src), _ptr(dst), count, tau, _stream(stream)))

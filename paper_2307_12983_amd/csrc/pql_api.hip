@@ -697,6 +697,25 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
 }
 
 // ---------------------------------------------------------------------------------------------
+int32_t pql_adam_step(pql_ctx* c, float* params, const float* grads, float* adam_m, float* adam_v, int64_t count,
+                      pql_adam opt, int64_t t, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!params || !grads || !adam_m || !adam_v) return E.fail(PQL_ERR_NULL, "pql_adam_step: null pointer");
+    if (count < 0 || count > 0x7fffffffLL || t < 1 || !adam_ok(opt))
+        return E.fail(PQL_ERR_INVALID_ARG, "pql_adam_step: bad count, step number or Adam constants");
+    if (count == 0) return PQL_OK;
+    AdamArgs adm;
+    std::memset(&adm, 0, sizeof(adm));
+    red(adm, 0, grads, (int)count, 1, 0);
+    adm.theta = params; adm.m = adam_m; adm.v = adam_v; adm.g = nullptr;
+    fill_adam(adm, opt, t);
+    const hipError_t e = adam_reduce_launch(adm, (hipStream_t)stream);
+    if (e != hipSuccess) return E.hip(e, "pql_adam_step");
+    return PQL_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 int32_t pql_soft_update(pql_ctx* c, const float* src, float* dst, int64_t count, float tau, void* stream) {
     if (!c) return PQL_ERR_NULL;
     Err E{c};

@@ -312,7 +312,7 @@ __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
         a.theta[k] = a.theta[k] - a.lr * m_hat / (sqrtf(v_hat) + a.eps);
         a.m[k] = m;
         a.v[k] = v;
-        a.g[k] = g;
+        if (a.g != nullptr) a.g[k] = g;
     }
     if (blockIdx.x == 0 && blockIdx.y == 0) {
         const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;

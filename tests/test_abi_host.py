@@ -26,7 +26,7 @@ def cfg_of(w, max_batch=None):
 def test_library_exports_every_declared_symbol():
     lib = B.load_library()
     names = header_functions()
-    assert len(names) == 16 and sorted(B.EXPORTS) == names
+    assert len(names) == 17 and sorted(B.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -92,6 +92,9 @@ def test_argument_errors_are_caught_on_the_host_and_leave_state_unchanged():
     assert lib.pql_actor_update(ctx.h, fake, fake, fake, fake, fake, fake, 8, bad, fake, 0x1000, None) == -1
     assert lib.pql_actor_update(ctx.h, fake, fake, fake, fake, fake, None, 8, opt, fake, 0x1000, None) == -2
     assert lib.pql_actor_update(ctx.h, fake, fake, fake, fake, fake, fake, 8, opt, fake, 0x1008, None) == -6
+    assert lib.pql_adam_step(ctx.h, fake, fake, fake, fake, 10, opt, 0, None) == -1
+    assert lib.pql_adam_step(ctx.h, fake, None, fake, fake, 10, opt, 1, None) == -2
+    assert lib.pql_adam_step(ctx.h, fake, fake, fake, fake, 10, bad, 1, None) == -1
     assert lib.pql_soft_update(ctx.h, fake, fake, 10, 1.5, None) == -1
     assert lib.pql_soft_update(ctx.h, fake, fake, -1, 0.5, None) == -1
     assert lib.pql_soft_update(ctx.h, None, fake, 10, 0.5, None) == -2
