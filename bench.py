@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Throughput of the PQL learner hot path on one MI355X.
+
+One "step" is one V-learner critic update together with everything else on the hot path at
+the paper's default rates (Table B.1 / Section 4: 8 critic updates per Actor step, one policy
+update per 2 critic updates):
+
+    every 8th step : pql_actor_act on N environments + pql_replay_push of that Actor step
+    every step     : pql_sample_nstep + pql_critic_update + pql_soft_update (Polyak on Q')
+    every 2nd step : pql_actor_update + hard sync of the lagged policy (pql_soft_update, tau = 1)
+
+All inputs are synthetic and resident in HBM before the timed region starts.  Prints ONE JSON
+line.  `value` = critic updates per second of that whole schedule.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2307_12983_amd import workloads as W  # noqa: E402
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+ACTOR_EVERY = 8                   # critic updates per Actor step (beta_a:v = 1:8)
+POLICY_EVERY = 2                  # critic updates per policy update (beta_p:v = 1:2)
+
+
+def flops_per_sample(w: W.Workload):
+    """Algorithmic FLOPs (2 per multiply-add on weight matrices only)."""
+    pc = sum(i * o for i, o in w.critic_dims())
+    pa = sum(i * o for i, o in w.actor_dims())
+    pc_first = w.critic_dims()[0][0] * w.critic_dims()[0][1]
+    pa_first = w.actor_dims()[0][0] * w.actor_dims()[0][1]
+    act_cols = w.act_dim * w.critic_dims()[0][1]
+    target = 2 * pa + 2 * 2 * pc
+    fwd = 2 * 2 * pc
+    bwd = 2 * (2 * pc + 2 * (pc - pc_first))            # dW for all layers + dX for all but the first
+    critic_update = target + fwd + bwd
+    # policy update: policy fwd, twin critic fwd, critic dX down to the action columns, policy bwd
+    actor_update = 2 * pa + 2 * 2 * pc + 2 * 2 * (pc - pc_first + act_cols) + 2 * pa + 2 * (pa - pa_first)
+    return dict(critic_update=critic_update, actor_update=actor_update, act=2 * pa)
+
+
+class Schedule:
+    """Issues the hot-path calls of step i; device-side synthetic environment data is cycled."""
+
+    def __init__(self, sess, env_rows):
+        self.s, self.env, self.tick = sess, env_rows, 0
+
+    def step(self, i):
+        s, w = self.s, self.s.w
+        if i % ACTOR_EVERY == 0:
+            row = self.env[self.tick % len(self.env)]
+            self.tick += 1
+            act = s.act(row["obs"])
+            s.ctx.pql_replay_push(s.storage, row["obs"], act, row["rew"], row["next_obs"], row["done"])
+        s.sample(w.batch)
+        s.critic_update(w.batch)
+        s.soft_update_targets()
+        if i % POLICY_EVERY == POLICY_EVERY - 1:
+            s.actor_update(None, w.batch)
+            s.sync_lagged_policy()
+
+
+def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0):
+    """The float64 oracle on the host, same schedule, on a bounded number of steps."""
+    from oracle import pql_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    ring = O.ReplayRing(w.rows, w.num_envs, w.obs_dim, w.act_dim)
+    for row in fill_rows:
+        ring.push(row["obs"], row["act"], row["rew"], row["next_obs"], row["done"])
+    actor, critic = W.init_networks(w)
+    L = O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps)
+    done_steps, tick, acts = 0, 0, 0
+    t0 = time.perf_counter()
+    while True:
+        i = done_steps
+        if i % ACTOR_EVERY == 0:
+            row = env_rows_host[tick % len(env_rows_host)]
+            tick += 1
+            a = O.actor_act(L.actor, w.actor_dims(), row["obs"], w.sigma_min, w.sigma_max, w.rng_seed, acts)
+            acts += 1
+            ring.push(row["obs"], a.astype(np.float32), row["rew"], row["next_obs"], row["done"])
+        batch = O.gather_nstep(ring, O.sample_indices(ring, w.nstep, w.batch, w.rng_seed, i), w.nstep, w.gamma)
+        L.critic_update(batch)
+        L.soft_update_targets()
+        if i % POLICY_EVERY == POLICY_EVERY - 1:
+            L.actor_update(batch["obs"])
+            L.sync_lagged_policy()
+        done_steps += 1
+        el = time.perf_counter() - t0
+        if done_steps % ACTOR_EVERY == 0 and (el >= budget_s or done_steps >= 64):
+            break
+    return dict(value=done_steps / el, unit="updates/s", cores=int(threads), kind="oracle",
+                sample="%d steps of the same schedule at batch %d (numpy float64, %.1f s)" % (done_steps, w.batch, el))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=800)
+    ap.add_argument("--warmup", type=int, default=80)
+    ap.add_argument("--workload", default="ant", choices=list(W.WORKLOADS))
+    ap.add_argument("--fill-rows", type=int, default=0, help="ring rows to fill before timing (0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=48)
+    ap.add_argument("--isolated", action="store_true",
+                    help="also time a critic-only loop and a policy-update-only loop (changes the launch mix "
+                         "that a profiler sees)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2307_12983_amd.session import LearnerSession
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+
+    w = W.WORKLOADS[args.workload]
+    sess = LearnerSession(w)
+    rng = W.data_rng(w)
+    n_fill = args.fill_rows or w.rows
+    keep = []                                   # host copy of the filled rows for the CPU baseline
+    keep_all = not args.no_cpu_baseline
+    for r in range(n_fill):
+        row = W.transition_rows(w, rng, 1)[0]
+        sess.push(row)
+        if keep_all:
+            keep.append(row)
+    env_host = W.transition_rows(w, rng, 8)
+    env_dev = [sess.to_device(r) for r in env_host]
+    torch.cuda.synchronize()
+
+    sched = Schedule(sess, env_dev)
+    for i in range(args.warmup):
+        sched.step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.warmup, args.warmup + args.steps):
+        sched.step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    value = args.steps / dt
+
+    # ---- isolated rates (same buffers): critic-only loop and the Actor step
+    def timed(fn, reps):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / reps
+
+    def critic_only():
+        sess.sample(w.batch); sess.critic_update(w.batch); sess.soft_update_targets()
+    t_act = timed(lambda: sess.act(env_dev[0]["obs"]), 100)
+    t_critic = timed(critic_only, max(50, args.steps // 4)) if args.isolated else None
+    t_actor_upd = timed(lambda: sess.actor_update(None, w.batch), max(50, args.steps // 8)) if args.isolated else None
+
+    # ---- per-kernel durations from HIP events on the launch stream, same schedule
+    sess.ctx.pql_profile_begin(4096 * 4)
+    base = args.warmup + args.steps
+    base += (-base) % ACTOR_EVERY
+    for i in range(base, base + args.profile_steps):
+        sched.step(i)
+    torch.cuda.synchronize()
+    stats = sess.ctx.pql_profile_end()
+    gemm = [k for k in stats if k["name"].startswith("gemm")]
+    tot_gemm_ms = sum(k["total_ms"] for k in gemm)
+    tot_gemm_flops = sum(k["flops"] for k in gemm)
+    dom = max(gemm, key=lambda k: k["total_ms"])
+    achieved = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
+    fl = flops_per_sample(w)
+    flops_step = w.batch * (fl["critic_update"] + fl["actor_update"] / POLICY_EVERY) + w.num_envs * fl["act"] / ACTOR_EVERY
+    kernels = []
+    for k in stats:
+        e = dict(name=k["name"], launches=k["launches"], avg_us=1e3 * k["total_ms"] / k["launches"])
+        if k["flops"] > 0:
+            e["tflops"] = k["flops"] / (k["total_ms"] * 1e-3) / 1e12
+        if k["bytes"] > 0:
+            e["gbs"] = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9
+        kernels.append(e)
+
+    out = {
+        "metric": "V-learner critic updates/s at batch %d" % w.batch,
+        "value": value, "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s-shaped: obs %d, act %d, %d envs, replay %d, batch %d, n=%d, MLP %s ELU fp32; "
+                               "per critic update: sample + update + Polyak, policy update every %d, "
+                               "Actor step + push every %d" % (w.name, w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.batch,
+                                                              w.nstep, list(w.hidden), POLICY_EVERY, ACTOR_EVERY),
+                   "rows_filled": n_fill},
+        "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "avg_launch_us": 1e3 * dom["total_ms"] / dom["launches"], "launches": dom["launches"],
+                     "all_gemm_tflops": tot_gemm_flops / (tot_gemm_ms * 1e-3) / 1e12},
+        "mfma_util_pct": 100.0 * flops_step * value / (PEAK_FP32_MFMA_TFLOPS * 1e12),
+        "actor_actions_per_s": w.num_envs / t_act,
+        "actor_act_us": 1e6 * t_act,
+        "kernels": kernels,
+    }
+    if args.isolated:
+        out["critic_only_updates_per_s"] = 1.0 / t_critic
+        out["critic_only_mfma_util_pct"] = 100.0 * w.batch * fl["critic_update"] / t_critic / (PEAK_FP32_MFMA_TFLOPS * 1e12)
+        out["actor_update_per_s"] = 1.0 / t_actor_upd
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, keep, env_host)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

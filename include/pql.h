@@ -191,6 +191,28 @@ int32_t pql_adam_step(pql_ctx* ctx, float* params, const float* grads, float* ad
  * 0 <= tau <= 1. */
 int32_t pql_soft_update(pql_ctx* ctx, const float* src, float* dst, int64_t count, float tau, void* stream);
 
+/* ---- measurement aid -------------------------------------------------------------------- */
+
+/* Per-kernel timing with HIP events on the stream each kernel is launched on.  Between
+ * pql_profile_begin and pql_profile_end every kernel launch made by this library (any context,
+ * one thread) carries a start and a stop event attached to the dispatch itself, up to
+ * max_launches launches; later launches run untimed.  pql_profile_end waits for the recorded events and returns one entry per kernel that
+ * ran ([host] array `out` of max_out entries; *n_out = number of kernels seen): launches, summed
+ * duration in ms, and the summed ALGORITHMIC work of those launches: flops = 2 * M * N * K of the
+ * real (unpadded) matrices for the GEMM kernels; bytes = minimum traffic the step implies for
+ * the copy / gather / optimiser kernels.  Event recording perturbs timing: do not use it inside
+ * a throughput measurement. */
+typedef struct {
+    char    name[64];
+    int64_t launches;
+    double  total_ms;
+    double  flops;
+    double  bytes;
+} pql_kernel_stat;
+
+int32_t pql_profile_begin(pql_ctx* ctx, int32_t max_launches);
+int32_t pql_profile_end(pql_ctx* ctx, pql_kernel_stat* out, int32_t max_out, int32_t* n_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ ERRORS = {0: "PQL_OK", -1: "PQL_ERR_INVALID_ARG", -2: "PQL_ERR_NULL", -3: "PQL_E
 EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_count", "pql_critic_param_count",
            "pql_workspace_bytes", "pql_last_error", "pql_get_state", "pql_set_state", "pql_replay_push",
            "pql_sample_nstep", "pql_gather_nstep", "pql_actor_act", "pql_critic_update", "pql_actor_update",
-           "pql_soft_update", "pql_adam_step"]
+           "pql_soft_update", "pql_adam_step", "pql_profile_begin", "pql_profile_end"]
 
 
 class PqlConfig(C.Structure):
@@ -43,6 +43,11 @@ class PqlAdam(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
 
 
+class PqlKernelStat(C.Structure):
+    _fields_ = [("name", C.c_char * 64), ("launches", C.c_int64), ("total_ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
 class PqlError(RuntimeError):
     def __init__(self, code: int, msg: str = ""):
         self.code = code
@@ -60,6 +65,9 @@ def load_library() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libpql.so is missing: build it with `python -m paper_2307_12983_amd.build` "
                            "(the HIP library is the only implementation)")
+    # torch first: libpql.so must bind to the HIP runtime that torch has loaded (both carry the
+    # soname libamdhip64.so.7); two runtimes in one process do not see each other's device state.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     P, I32, I64, F = C.c_void_p, C.c_int32, C.c_int64, C.c_float
     cfgp = C.POINTER(PqlConfig)
@@ -81,6 +89,8 @@ def load_library() -> C.CDLL:
         "pql_actor_update": (I32, [P, P, P, P, P, P, P, I32, PqlAdam, P, P, P]),
         "pql_soft_update": (I32, [P, P, P, I64, F, P]),
         "pql_adam_step": (I32, [P, P, P, P, P, I64, PqlAdam, I64, P]),
+        "pql_profile_begin": (I32, [P, I32]),
+        "pql_profile_end": (I32, [P, C.POINTER(PqlKernelStat), I32, C.POINTER(I32)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -227,6 +237,16 @@ class Context:
     def pql_adam_step(self, params, grads, adam_m, adam_v, count, opt: PqlAdam, t, stream=None):
         self._check(self.lib.pql_adam_step(self.h, _ptr(params), _ptr(grads), _ptr(adam_m), _ptr(adam_v), count, opt, t,
                                            _stream(stream)))
+
+    def pql_profile_begin(self, max_launches):
+        self._check(self.lib.pql_profile_begin(self.h, max_launches))
+
+    def pql_profile_end(self):
+        arr = (PqlKernelStat * 32)()
+        n = C.c_int32(0)
+        self._check(self.lib.pql_profile_end(self.h, arr, 32, C.byref(n)))
+        return [dict(name=arr[i].name.decode(), launches=arr[i].launches, total_ms=arr[i].total_ms,
+                     flops=arr[i].flops, bytes=arr[i].bytes) for i in range(min(n.value, 32))]
 
     def pql_soft_update(self, src, dst, count, tau, stream=None):
         self._check(self.lib.pql_soft_update(self.h, _ptr(src), _ptr(dst), count, tau, _stream(stream)))

@@ -13,6 +13,54 @@
 
 using namespace pql;
 
+// ---- per-launch timing ----------------------------------------------------------------------
+namespace pql {
+namespace {
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> ev;      // 2 events per recorded launch
+    struct Rec { int kid; double flops, bytes; };
+    std::vector<Rec> recs;
+    size_t cap = 0;
+} g_prof;
+const char* const k_gemm_mode[3] = {"nn", "nt", "tn"};
+const char* const k_gemm_tile[5] = {"128x128", "64x64", "128x32", "128x64", "128x32_noise"};
+char g_name_buf[64];
+}  // namespace
+
+const char* kernel_name(int kid) {
+    if (kid >= KID_GEMM && kid < KID_GEMM + 15) {
+        std::snprintf(g_name_buf, sizeof(g_name_buf), "gemm_grouped_%s_%s", k_gemm_mode[kid / 5], k_gemm_tile[kid % 5]);
+        return g_name_buf;
+    }
+    switch (kid) {
+        case KID_PUSH: return "push_kernel";
+        case KID_SAMPLE: return "sample_kernel";
+        case KID_HEAD_CRITIC: return "head_kernel_critic";
+        case KID_HEAD_POLICY: return "head_kernel_policy";
+        case KID_ADAM: return "adam_reduce_kernel";
+        case KID_SOFT_UPDATE: return "soft_update_kernel";
+        case KID_COPY: return "copy_kernel";
+        default: return "?";
+    }
+}
+
+bool prof_active() { return g_prof.on && g_prof.recs.size() < g_prof.cap; }
+
+ProfSlot prof_slot() {
+    ProfSlot s{nullptr, nullptr, false};
+    if (!prof_active()) return s;
+    s.start = g_prof.ev[2 * g_prof.recs.size()];
+    s.stop = g_prof.ev[2 * g_prof.recs.size() + 1];
+    s.on = true;
+    return s;
+}
+
+void prof_commit(const ProfSlot& s, int kid, double flops, double bytes) {
+    if (s.on) g_prof.recs.push_back({kid, flops, bytes});
+}
+}  // namespace pql
+
 struct pql_ctx {
     pql_config cfg;
     int L;                       // hidden layers
@@ -77,6 +125,7 @@ int colsum_rows(int tile, int M) { return ((M + gemm_tile_m(tile) - 1) / gemm_ti
 
 // Upper bound on split count for K rows of batch and the given total of output tiles.
 int split_target(long tiles, int K) {
+    // about four workgroups per compute unit, but at least 128 batch rows per split
     long s = (1024 + tiles - 1) / (tiles > 0 ? tiles : 1);
     const long by_k = (K + 127) / 128;
     if (s > by_k) s = by_k;
@@ -694,6 +743,60 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
     c->actor_t += 1;
     return PQL_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+int32_t pql_profile_begin(pql_ctx* c, int32_t max_launches) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (max_launches < 1 || max_launches > (1 << 20)) return E.fail(PQL_ERR_INVALID_ARG, "pql_profile_begin: bad max_launches");
+    if (g_prof.on) return E.fail(PQL_ERR_INVALID_ARG, "pql_profile_begin: already profiling");
+    g_prof.ev.assign((size_t)2 * max_launches, nullptr);
+    for (size_t i = 0; i < g_prof.ev.size(); ++i) {
+        const hipError_t e = hipEventCreate(&g_prof.ev[i]);
+        if (e != hipSuccess) {
+            for (size_t k = 0; k < i; ++k) (void)hipEventDestroy(g_prof.ev[k]);
+            g_prof.ev.clear();
+            return E.hip(e, "pql_profile_begin");
+        }
+    }
+    g_prof.recs.clear();
+    g_prof.cap = (size_t)max_launches;
+    g_prof.on = true;
+    return PQL_OK;
+}
+
+int32_t pql_profile_end(pql_ctx* c, pql_kernel_stat* out, int32_t max_out, int32_t* n_out) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!out || !n_out) return E.fail(PQL_ERR_NULL, "pql_profile_end: null pointer");
+    if (!g_prof.on) return E.fail(PQL_ERR_INVALID_ARG, "pql_profile_end: profiling is not on");
+    g_prof.on = false;
+    int32_t rc = PQL_OK;
+    pql_kernel_stat acc[KID_COUNT];
+    std::memset(acc, 0, sizeof(acc));
+    for (size_t i = 0; i < g_prof.recs.size(); ++i) {
+        hipError_t e = hipEventSynchronize(g_prof.ev[2 * i + 1]);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]);
+        if (e != hipSuccess) { rc = E.hip(e, "pql_profile_end"); break; }
+        pql_kernel_stat& a = acc[g_prof.recs[i].kid];
+        a.launches += 1; a.total_ms += ms; a.flops += g_prof.recs[i].flops; a.bytes += g_prof.recs[i].bytes;
+    }
+    for (hipEvent_t ev : g_prof.ev) (void)hipEventDestroy(ev);
+    g_prof.ev.clear();
+    g_prof.recs.clear();
+    int32_t n = 0;
+    for (int k = 0; k < KID_COUNT && rc == PQL_OK; ++k) {
+        if (acc[k].launches == 0) continue;
+        if (n < max_out) {
+            out[n] = acc[k];
+            std::snprintf(out[n].name, sizeof(out[n].name), "%s", kernel_name(k));
+        }
+        ++n;
+    }
+    *n_out = n;
+    return rc;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -73,6 +73,14 @@ struct TileRegs {
                                 bool vec, int tid) {
         const int c = col0 + (tid % C4) * 4;
         const int r = row0 + tid / C4;
+        // interior tile with aligned rows: straight 16-byte loads (uniform branch)
+        if (vec && row0 + ROWS <= row_lim && col0 + COLS <= col_lim) {
+            const float* p = src + (size_t)r * (size_t)ld + c;
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+                v[i] = *reinterpret_cast<const float4*>(p + (size_t)(i * RPP) * (size_t)ld);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int rr = r + i * RPP;
@@ -101,6 +109,15 @@ struct TileRegs {
     }
 };
 
+// One K-segment of a problem, copied to registers so that the main loop issues no descriptor
+// loads.
+struct SegRegs {
+    const float* A;
+    const float* B;
+    int lda, ldb, kbeg, kend;
+    bool va, vb;
+};
+
 template <int MODE, int WAVES_M, int WAVES_N, int TM, int TN, bool NOISE>
 __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup g) {
     constexpr int BM = WAVES_M * TM * 32;
@@ -109,8 +126,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
     constexpr bool B_KC = (MODE == GEMM_NT);   // B tile k-contiguous: Bs[n][k]; else Bs[k][n]
     constexpr int SA = A_KC ? KSTRIDE : BM;
     constexpr int SB = B_KC ? KSTRIDE : BN;
-    __shared__ __attribute__((aligned(16))) float As[A_KC ? BM * SA : BK * SA];
-    __shared__ __attribute__((aligned(16))) float Bs[B_KC ? BN * SB : BK * SB];
+    constexpr int A_TILE = A_KC ? BM * SA : BK * SA;
+    constexpr int B_TILE = B_KC ? BN * SB : BK * SB;
+    // two LDS stages: tile t is consumed from stage t&1 while tile t+1 is written to the other
+    __shared__ __attribute__((aligned(16))) float As[2][A_TILE];
+    __shared__ __attribute__((aligned(16))) float Bs[2][B_TILE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -132,13 +152,23 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
     const int M = P.M, N = P.N;
 
     // K range per segment (split-K applies to single-segment problems only)
-    int kbeg0 = 0, kend0 = P.seg[0].K;
+    SegRegs s0, s1;
+    s0.A = P.seg[0].A; s0.B = P.seg[0].B; s0.lda = P.seg[0].lda; s0.ldb = P.seg[0].ldb;
+    s0.va = (P.seg[0].vec & 1) != 0; s0.vb = (P.seg[0].vec & 2) != 0;
+    s0.kbeg = 0; s0.kend = P.seg[0].K;
     if (MODE == GEMM_TN) {
-        kbeg0 = split * P.k_chunk;
-        kend0 = min(P.seg[0].K, kbeg0 + P.k_chunk);
+        s0.kbeg = split * P.k_chunk;
+        s0.kend = min(P.seg[0].K, s0.kbeg + P.k_chunk);
     }
-    const int nt0 = (kend0 - kbeg0 + BK - 1) / BK;
-    const int nt1 = (P.nseg > 1) ? (P.seg[1].K + BK - 1) / BK : 0;
+    s1 = s0;
+    int nt1 = 0;
+    if (P.nseg > 1) {
+        s1.A = P.seg[1].A; s1.B = P.seg[1].B; s1.lda = P.seg[1].lda; s1.ldb = P.seg[1].ldb;
+        s1.va = (P.seg[1].vec & 1) != 0; s1.vb = (P.seg[1].vec & 2) != 0;
+        s1.kbeg = 0; s1.kend = P.seg[1].K;
+        nt1 = (s1.kend + BK - 1) / BK;
+    }
+    const int nt0 = (s0.kend - s0.kbeg + BK - 1) / BK;
     const int nt = nt0 + nt1;
 
     floatx16 acc[TM][TN];
@@ -149,72 +179,97 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    TileRegs<A_KC ? BM : BK, A_KC ? BK : BM> ra;
-    TileRegs<B_KC ? BN : BK, B_KC ? BK : BN> rb;
+    typedef TileRegs<A_KC ? BM : BK, A_KC ? BK : BM> RegsA;
+    typedef TileRegs<B_KC ? BN : BK, B_KC ? BK : BN> RegsB;
+    RegsA ra0, ra1;      // even / odd K-tiles in flight
+    RegsB rb0, rb1;
 
-    auto fetch = [&](int t) {
-        const int s = (t < nt0) ? 0 : 1;
-        const GemmSeg& S = P.seg[s];
-        const int k0 = (s == 0) ? kbeg0 + t * BK : (t - nt0) * BK;
-        const int kend = (s == 0) ? kend0 : S.K;
-        if (A_KC) ra.load(S.A, S.lda, m0, k0, M, kend, (S.vec & 1) != 0, tid);
-        else      ra.load(S.A, S.lda, k0, m0, kend, M, (S.vec & 1) != 0, tid);
-        if (B_KC) rb.load(S.B, S.ldb, n0, k0, N, kend, (S.vec & 2) != 0, tid);
-        else      rb.load(S.B, S.ldb, k0, n0, kend, N, (S.vec & 2) != 0, tid);
+    auto fetch = [&](int t, RegsA& ra, RegsB& rb) {
+        const bool first = t < nt0;
+        const SegRegs& S = first ? s0 : s1;
+        const int k0 = first ? s0.kbeg + t * BK : (t - nt0) * BK;
+        if (A_KC) ra.load(S.A, S.lda, m0, k0, M, S.kend, S.va, tid);
+        else      ra.load(S.A, S.lda, k0, m0, S.kend, M, S.va, tid);
+        if (B_KC) rb.load(S.B, S.ldb, n0, k0, N, S.kend, S.vb, tid);
+        else      rb.load(S.B, S.ldb, k0, n0, S.kend, N, S.vb, tid);
     };
 
-    if (nt > 0) fetch(0);
-    for (int t = 0; t < nt; ++t) {
-        ra.store(As, SA, tid);
-        rb.store(Bs, SB, tid);
-        __syncthreads();
-        if (t + 1 < nt) fetch(t + 1);
-
-        int kvalid;
-        if (t < nt0) kvalid = min(BK, kend0 - (kbeg0 + t * BK));
-        else         kvalid = min(BK, P.seg[1].K - (t - nt0) * BK);
-        const int ngroups = (kvalid + 7) >> 3;
-
-        for (int kg = 0; kg < ngroups; ++kg) {
-            const int kk = kg * 8 + 4 * half;
-            float a[TM][4], b[TN][4];
+    auto kgroup = [&](const float* __restrict__ Asm, const float* __restrict__ Bsm, int kg) {
+        const int kk = kg * 8 + 4 * half;
+        float a[TM][4], b[TN][4];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int m = (wm * TM + i) * 32 + l32;
-                if (A_KC) {
-                    const float4 x = *reinterpret_cast<const float4*>(As + m * SA + kk);
-                    a[i][0] = x.x; a[i][1] = x.y; a[i][2] = x.z; a[i][3] = x.w;
-                } else {
+        for (int i = 0; i < TM; ++i) {
+            const int m = (wm * TM + i) * 32 + l32;
+            if (A_KC) {
+                const float4 x = *reinterpret_cast<const float4*>(Asm + m * SA + kk);
+                a[i][0] = x.x; a[i][1] = x.y; a[i][2] = x.z; a[i][3] = x.w;
+            } else {
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) a[i][u] = As[(kk + u) * SA + m];
-                }
+                for (int u = 0; u < 4; ++u) a[i][u] = Asm[(kk + u) * SA + m];
             }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int n = (wn * TN + j) * 32 + l32;
-                if (B_KC) {
-                    const float4 x = *reinterpret_cast<const float4*>(Bs + n * SB + kk);
-                    b[j][0] = x.x; b[j][1] = x.y; b[j][2] = x.z; b[j][3] = x.w;
-                } else {
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) b[j][u] = Bs[(kk + u) * SB + n];
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][u], b[j][u], acc[i][j], 0, 0, 0);
         }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = (wn * TN + j) * 32 + l32;
+            if (B_KC) {
+                const float4 x = *reinterpret_cast<const float4*>(Bsm + n * SB + kk);
+                b[j][0] = x.x; b[j][1] = x.y; b[j][2] = x.z; b[j][3] = x.w;
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) b[j][u] = Bsm[(kk + u) * SB + n];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][u], b[j][u], acc[i][j], 0, 0, 0);
+    };
+
+    auto compute = [&](int t) {
+        const float* Asm = As[t & 1];
+        const float* Bsm = Bs[t & 1];
+        const int kvalid = (t < nt0) ? min(BK, s0.kend - (s0.kbeg + t * BK)) : min(BK, s1.kend - (t - nt0) * BK);
+        if (kvalid == BK) {
+#pragma unroll
+            for (int kg = 0; kg < BK / 8; ++kg) kgroup(Asm, Bsm, kg);
+        } else {
+            const int ngroups = (kvalid + 7) >> 3;
+            for (int kg = 0; kg < ngroups; ++kg) kgroup(Asm, Bsm, kg);
+        }
+    };
+
+    // Software pipeline: while tile t feeds the matrix cores from LDS stage t&1, tile t+1 moves
+    // from registers into the other stage and tile t+2 is in flight from memory.
+    if (nt > 0) {
+        fetch(0, ra0, rb0);
+        if (nt > 1) fetch(1, ra1, rb1);
+        ra0.store(As[0], SA, tid);
+        rb0.store(Bs[0], SB, tid);
         __syncthreads();
+    }
+    for (int t = 0; t < nt; t += 2) {
+        if (t + 1 < nt) { ra1.store(As[1], SA, tid); rb1.store(Bs[1], SB, tid); }
+        if (t + 2 < nt) fetch(t + 2, ra0, rb0);
+        compute(t);
+        __syncthreads();
+        if (t + 1 < nt) {
+            if (t + 2 < nt) { ra0.store(As[0], SA, tid); rb0.store(Bs[0], SB, tid); }
+            if (t + 3 < nt) fetch(t + 3, ra1, rb1);
+            compute(t + 1);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue -------------------------------------------------------------------------
     const int epi = P.epi;
     float* __restrict__ C = P.C + (MODE == GEMM_TN ? (size_t)split * (size_t)P.split_stride : (size_t)0);
     const int ldc = P.ldc;
+    const float* __restrict__ aux = P.aux;
+    const int ldaux = P.ldaux;
+    float* __restrict__ colsum = P.colsum;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int n = n0 + (wn * TN + j) * 32 + l32;
@@ -230,19 +285,21 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
                 if (!n_ok || m >= M) continue;
                 float x = acc[i][j][r];
                 switch (epi) {
-                    case EPI_BIAS_ELU: x += bias; x = x > 0.f ? x : expm1f(x); break;
+                    // ELU: exp(x) - 1 has absolute error ~1e-7 for x <= 0, the same size as the
+                    // rounding of the accumulation that produced x
+                    case EPI_BIAS_ELU: x += bias; x = x > 0.f ? x : __expf(x) - 1.f; break;
                     case EPI_BIAS_TANH: x = tanhf(x + bias); break;
                     case EPI_BIAS_TANH_NOISE:
                         x = tanhf(x + bias);
                         if (NOISE) x = fminf(fmaxf(x + exploration_noise(g.noise, m, n), -1.f), 1.f);
                         break;
                     case EPI_MUL_DELU: {
-                        const float h = P.aux[(size_t)m * P.ldaux + n];
+                        const float h = aux[(size_t)m * ldaux + n];
                         x *= (h > 0.f ? 1.f : h + 1.f);
                         break;
                     }
                     case EPI_MUL_DTANH: {
-                        const float h = P.aux[(size_t)m * P.ldaux + n];
+                        const float h = aux[(size_t)m * ldaux + n];
                         x *= (1.f - h * h);
                         break;
                     }
@@ -252,29 +309,30 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
                 csum += x;
             }
         }
-        if (P.colsum != nullptr) {
+        if (colsum != nullptr) {
             csum += __shfl_xor(csum, 32);
-            if (half == 0 && n_ok) P.colsum[(size_t)(tile_m * WAVES_M + wm) * N + n] = csum;
+            if (half == 0 && n_ok) colsum[(size_t)(tile_m * WAVES_M + wm) * N + n] = csum;
         }
     }
 }
 
 // ---- host side ------------------------------------------------------------------------------
 int gemm_tile_m(int tile) { return tile == TILE_64x64 ? 64 : 128; }
-int gemm_tile_n(int tile) { return tile == TILE_128x128 ? 128 : (tile == TILE_64x64 ? 64 : 32); }
+int gemm_tile_n(int tile) { return tile == TILE_128x128 ? 128 : (tile == TILE_128x32 ? 32 : 64); }
 int gemm_waves_m(int tile) { return tile == TILE_128x32 ? 4 : 2; }
 
 template <int MODE>
-static hipError_t launch_mode(int tile, const GemmGroup& g, bool noise, hipStream_t stream) {
+static hipError_t launch_mode(int tile, const GemmGroup& g, bool noise, const ProfSlot& ps, hipStream_t stream) {
     const dim3 grid(g.total_tiles), block(NTHREADS);
     switch (tile) {
-        case TILE_128x128: hipLaunchKernelGGL((gemm_grouped_kernel<MODE, 2, 2, 2, 2, false>), grid, block, 0, stream, g); break;
-        case TILE_64x64:   hipLaunchKernelGGL((gemm_grouped_kernel<MODE, 2, 2, 1, 1, false>), grid, block, 0, stream, g); break;
+        case TILE_128x128: PQL_LAUNCH(ps, (gemm_grouped_kernel<MODE, 2, 2, 2, 2, false>), grid, block, 0, stream, g); break;
+        case TILE_64x64:   PQL_LAUNCH(ps, (gemm_grouped_kernel<MODE, 2, 2, 1, 1, false>), grid, block, 0, stream, g); break;
+        case TILE_128x64:  PQL_LAUNCH(ps, (gemm_grouped_kernel<MODE, 2, 2, 2, 1, false>), grid, block, 0, stream, g); break;
         default:
             if (MODE == GEMM_NN && noise)
-                hipLaunchKernelGGL((gemm_grouped_kernel<GEMM_NN, 4, 1, 1, 1, true>), grid, block, 0, stream, g);
+                PQL_LAUNCH(ps, (gemm_grouped_kernel<GEMM_NN, 4, 1, 1, 1, true>), grid, block, 0, stream, g);
             else
-                hipLaunchKernelGGL((gemm_grouped_kernel<MODE, 4, 1, 1, 1, false>), grid, block, 0, stream, g);
+                PQL_LAUNCH(ps, (gemm_grouped_kernel<MODE, 4, 1, 1, 1, false>), grid, block, 0, stream, g);
             break;
     }
     return hipGetLastError();
@@ -296,11 +354,19 @@ hipError_t gemm_launch(int mode, int tile, GemmGroup& g, hipStream_t stream) {
     g.total_tiles = total;
     if (total == 0) return hipSuccess;
     if (noise && (mode != GEMM_NN || tile != TILE_128x32)) return hipErrorInvalidValue;
+    double flops = 0.0;
+    const ProfSlot ps = prof_slot();
+    if (ps.on)
+        for (int i = 0; i < g.nprob; ++i)
+            for (int s = 0; s < g.p[i].nseg; ++s) flops += 2.0 * g.p[i].M * (double)g.p[i].N * g.p[i].seg[s].K;
+    hipError_t e;
     switch (mode) {
-        case GEMM_NN: return launch_mode<GEMM_NN>(tile, g, noise, stream);
-        case GEMM_NT: return launch_mode<GEMM_NT>(tile, g, noise, stream);
-        default:      return launch_mode<GEMM_TN>(tile, g, noise, stream);
+        case GEMM_NN: e = launch_mode<GEMM_NN>(tile, g, noise, ps, stream); break;
+        case GEMM_NT: e = launch_mode<GEMM_NT>(tile, g, noise, ps, stream); break;
+        default:      e = launch_mode<GEMM_TN>(tile, g, noise, ps, stream); break;
     }
+    prof_commit(ps, KID_GEMM + mode * 5 + (noise ? 4 : tile), flops, 0.0);
+    return e;
 }
 
 }  // namespace pql

@@ -3,11 +3,37 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "pql.h"
 
 namespace pql {
+
+// ---- optional per-launch timing (HIP events on the launch stream) ---------------------------
+// Kernel classes reported by pql_profile_end.  GEMM ids are KID_GEMM + mode * 5 + tile, with
+// tile 4 = the 128x32 instantiation that carries the exploration-noise epilogue.
+enum KernelId : int {
+    KID_GEMM = 0, KID_PUSH = 15, KID_SAMPLE = 16, KID_HEAD_CRITIC = 17, KID_HEAD_POLICY = 18,
+    KID_ADAM = 19, KID_SOFT_UPDATE = 20, KID_COPY = 21, KID_COUNT = 22
+};
+const char* kernel_name(int kid);
+bool prof_active();
+// One timed launch: when profiling is on, prof_slot() hands out an event pair that PQL_LAUNCH
+// attaches to the kernel dispatch itself (the events then carry the dispatch's own begin / end
+// timestamps, with no marker commands in between); prof_commit() files the launch under its
+// kernel class with its algorithmic work.  All no-ops unless profiling is on.
+struct ProfSlot { hipEvent_t start, stop; bool on; };
+ProfSlot prof_slot();
+void prof_commit(const ProfSlot& s, int kid, double flops, double bytes);
+
+#define PQL_LAUNCH(slot, kernel, grid, block, lds, stream, ...)                                              \
+    do {                                                                                                     \
+        if ((slot).on)                                                                                       \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, (slot).start, (slot).stop, 0, __VA_ARGS__); \
+        else                                                                                                 \
+            hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                               \
+    } while (0)
 
 // ---- grouped fp32 MFMA GEMM ------------------------------------------------------------
 // One launch computes several independent problems C_p = epi(sum_seg A_seg * B_seg).  A problem
@@ -73,7 +99,7 @@ struct GemmGroup {
     GemmProb p[GEMM_MAX_PROB];
 };
 
-enum GemmTile : int { TILE_128x128 = 0, TILE_64x64 = 1, TILE_128x32 = 2 };
+enum GemmTile : int { TILE_128x128 = 0, TILE_64x64 = 1, TILE_128x32 = 2, TILE_128x64 = 3 };
 
 int gemm_tile_m(int tile);
 int gemm_tile_n(int tile);
@@ -88,6 +114,8 @@ struct RedTensor {
     const float* partial;   // partial[s * stride + i], s < nparts, i < count
     int count;
     int nparts;
+    int block_begin;        // first workgroup of this tensor (filled by adam_reduce_launch)
+    int qlog2;              // log2 of the number of lanes that share one element's partial sum
 };
 
 constexpr int RED_MAX_TENSORS = 48;
@@ -131,6 +159,7 @@ int head_workgroups(int B);
 struct PushArgs {
     const float* src[5]; float* dst[5]; int64_t count[5];   // floats per field
 };
+double adam_bytes(const AdamArgs& a);
 hipError_t push_launch(const PushArgs& a, hipStream_t stream);
 
 struct SampleArgs {

@@ -29,7 +29,11 @@ hipError_t push_launch(const PushArgs& a, hipStream_t stream) {
     int64_t blocks = (mx / 4 + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(push_kernel, dim3((unsigned)blocks, 5), dim3(256), 0, stream, a);
+    double bytes = 0.0;
+    for (int f = 0; f < 5; ++f) bytes += 8.0 * (double)a.count[f];      // read + write
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, push_kernel, dim3((unsigned)blocks, 5), dim3(256), 0, stream, a);
+    prof_commit(ps, KID_PUSH, 0.0, bytes);
     return hipGetLastError();
 }
 
@@ -106,12 +110,12 @@ __global__ __launch_bounds__(256) void sample_kernel(const SampleArgs a) {
 }
 
 template <int G>
-static void sample_dispatch(const SampleArgs& a, bool vo, bool va, hipStream_t stream) {
+static void sample_dispatch(const SampleArgs& a, bool vo, bool va, const ProfSlot& ps, hipStream_t stream) {
     const dim3 grid((a.batch + (256 / G) - 1) / (256 / G)), block(256);
-    if (vo && va)       hipLaunchKernelGGL((sample_kernel<G, true, true>), grid, block, 0, stream, a);
-    else if (vo)        hipLaunchKernelGGL((sample_kernel<G, true, false>), grid, block, 0, stream, a);
-    else if (va)        hipLaunchKernelGGL((sample_kernel<G, false, true>), grid, block, 0, stream, a);
-    else                hipLaunchKernelGGL((sample_kernel<G, false, false>), grid, block, 0, stream, a);
+    if (vo && va)       PQL_LAUNCH(ps, (sample_kernel<G, true, true>), grid, block, 0, stream, a);
+    else if (vo)        PQL_LAUNCH(ps, (sample_kernel<G, true, false>), grid, block, 0, stream, a);
+    else if (va)        PQL_LAUNCH(ps, (sample_kernel<G, false, true>), grid, block, 0, stream, a);
+    else                PQL_LAUNCH(ps, (sample_kernel<G, false, false>), grid, block, 0, stream, a);
 }
 
 static inline bool al16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
@@ -121,8 +125,12 @@ hipError_t sample_launch(const SampleArgs& a, hipStream_t stream) {
     const bool vo = (a.o % 4 == 0) && al16(a.st.obs) && al16(a.st.next_obs) && al16(a.out.obs) && al16(a.out.next_obs);
     const bool va = (a.a % 4 == 0) && al16(a.st.act) && al16(a.out.act);
     const int per_row = vo ? a.o / 4 : a.o;
-    if (per_row <= 32) sample_dispatch<16>(a, vo, va, stream);
-    else               sample_dispatch<64>(a, vo, va, stream);
+    // per sample: read s, a, s' and n (r, d) pairs; write s, a, s', ret, boot and the index
+    const double bytes = (double)a.batch * (4.0 * (2 * a.o + a.a + 2 * a.nstep) + 4.0 * (2 * a.o + a.a + 2) + 8.0);
+    const ProfSlot ps = prof_slot();
+    if (per_row <= 32) sample_dispatch<16>(a, vo, va, ps, stream);
+    else               sample_dispatch<64>(a, vo, va, ps, stream);
+    prof_commit(ps, KID_SAMPLE, 0.0, bytes);
     return hipGetLastError();
 }
 
@@ -279,12 +287,16 @@ static hipError_t head_launch(const HeadArgs& a, hipStream_t stream) {
     const dim3 grid(a.nwg), block(64 * HEAD_WAVES);
     const size_t lds = (size_t)HEAD_WAVES * (a.H > 4 ? a.H : 4) * sizeof(float);
     const int nj = (a.H + 63) / 64;
-    if (nj <= 1)       hipLaunchKernelGGL((head_kernel<1, POLICY>), grid, block, lds, stream, a);
-    else if (nj <= 2)  hipLaunchKernelGGL((head_kernel<2, POLICY>), grid, block, lds, stream, a);
-    else if (nj <= 4)  hipLaunchKernelGGL((head_kernel<4, POLICY>), grid, block, lds, stream, a);
-    else if (nj <= 8)  hipLaunchKernelGGL((head_kernel<8, POLICY>), grid, block, lds, stream, a);
-    else if (nj <= 16) hipLaunchKernelGGL((head_kernel<16, POLICY>), grid, block, lds, stream, a);
-    else return hipErrorInvalidValue;
+    // reads of the last hidden activations (online + target critics), write of the deltas
+    const double bytes = 4.0 * (double)a.B * a.H * (POLICY ? 4.0 : 6.0);
+    if (nj > 16) return hipErrorInvalidValue;
+    const ProfSlot ps = prof_slot();
+    if (nj <= 1)       PQL_LAUNCH(ps, (head_kernel<1, POLICY>), grid, block, lds, stream, a);
+    else if (nj <= 2)  PQL_LAUNCH(ps, (head_kernel<2, POLICY>), grid, block, lds, stream, a);
+    else if (nj <= 4)  PQL_LAUNCH(ps, (head_kernel<4, POLICY>), grid, block, lds, stream, a);
+    else if (nj <= 8)  PQL_LAUNCH(ps, (head_kernel<8, POLICY>), grid, block, lds, stream, a);
+    else               PQL_LAUNCH(ps, (head_kernel<16, POLICY>), grid, block, lds, stream, a);
+    prof_commit(ps, POLICY ? KID_HEAD_POLICY : KID_HEAD_CRITIC, 0.0, bytes);
     return hipGetLastError();
 }
 
@@ -297,13 +309,39 @@ hipError_t policy_head_launch(const HeadArgs& a, hipStream_t stream) { return he
 // weight-gradient GEMMs, per-tile column sums for biases); the Adam step is applied in the
 // same pass.  Block (0,0) also finalises the loss scalars.
 // =============================================================================================
+// A workgroup covers E = 256 / Q consecutive elements of one tensor; the Q lanes that share an
+// element each sum every Q-th partial (four loads in flight), then combine through LDS in a
+// fixed order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
-    const RedTensor& T = a.t[blockIdx.y];
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < T.count) {
-        float g = 0.f;
+    __shared__ float sm[256];
+    const int b = blockIdx.x;
+    int ti = 0;
+    for (int i = 1; i < a.ntensors; ++i)
+        if (b >= a.t[i].block_begin) ti = i;
+    const RedTensor& T = a.t[ti];
+    const int ql = T.qlog2, Q = 1 << ql, E = 256 >> ql;
+    const int e = threadIdx.x & (E - 1), q = threadIdx.x >> (8 - ql);
+    const int i = (b - T.block_begin) * E + e;
+    const bool live = i < T.count;
+    float g = 0.f;
+    if (live) {
         const float* __restrict__ p = T.partial + i;
-        for (int s = 0; s < T.nparts; ++s) g += p[(size_t)s * (size_t)T.stride];
+        const size_t st = (size_t)T.stride;
+        int s = q;
+        for (; s + 3 * Q < T.nparts; s += 4 * Q) {
+            const float x0 = p[(size_t)s * st], x1 = p[(size_t)(s + Q) * st];
+            const float x2 = p[(size_t)(s + 2 * Q) * st], x3 = p[(size_t)(s + 3 * Q) * st];
+            g += (x0 + x1) + (x2 + x3);
+        }
+        for (; s < T.nparts; s += Q) g += p[(size_t)s * st];
+    }
+    if (Q > 1) {
+        sm[threadIdx.x] = g;
+        __syncthreads();
+        if (q == 0)
+            for (int k = 1; k < Q; ++k) g += sm[k * E + e];
+    }
+    if (live && q == 0) {
         const int64_t k = T.offset + i;
         const float m = a.beta1 * a.m[k] + (1.f - a.beta1) * g;
         const float v = a.beta2 * a.v[k] + (1.f - a.beta2) * g * g;
@@ -314,7 +352,7 @@ __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
         a.v[k] = v;
         if (a.g != nullptr) a.g[k] = g;
     }
-    if (blockIdx.x == 0 && blockIdx.y == 0) {
+    if (b == 0) {
         const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
         if (wave < a.nloss) {
             float s = 0.f;
@@ -325,11 +363,29 @@ __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
     }
 }
 
-hipError_t adam_reduce_launch(const AdamArgs& a, hipStream_t stream) {
-    int mx = 1;
-    for (int i = 0; i < a.ntensors; ++i) mx = a.t[i].count > mx ? a.t[i].count : mx;
-    const dim3 grid((mx + 255) / 256, a.ntensors), block(256);
-    hipLaunchKernelGGL(adam_reduce_kernel, grid, block, 0, stream, a);
+// Algorithmic traffic of the optimiser: read theta, g, m, v and write theta, m, v = 28 bytes per
+// parameter (the partial-sum reads that replace the single read of g are not counted).
+double adam_bytes(const AdamArgs& a) {
+    double n = 0.0;
+    for (int i = 0; i < a.ntensors; ++i) n += a.t[i].count;
+    return 28.0 * n;
+}
+
+hipError_t adam_reduce_launch(const AdamArgs& args, hipStream_t stream) {
+    AdamArgs a = args;
+    int blocks = 0;
+    for (int i = 0; i < a.ntensors; ++i) {
+        RedTensor& t = a.t[i];
+        t.qlog2 = t.nparts <= 16 ? 0 : (t.nparts <= 64 ? 2 : 4);
+        t.block_begin = blocks;
+        const int E = 256 >> t.qlog2;
+        blocks += (t.count + E - 1) / E;
+    }
+    if (blocks == 0) blocks = 1;
+    const dim3 grid(blocks), block(256);
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, adam_reduce_kernel, grid, block, 0, stream, a);
+    prof_commit(ps, KID_ADAM, 0.0, ps.on ? adam_bytes(a) : 0.0);
     return hipGetLastError();
 }
 
@@ -368,8 +424,10 @@ hipError_t soft_update_launch(const float* src, float* dst, int64_t count, float
     int64_t blocks = (count / 4 + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 2048) blocks = 2048;
-    if (tau == 1.f) hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count, vec);
-    else hipLaunchKernelGGL(soft_update_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count, tau, vec);
+    const ProfSlot ps = prof_slot();
+    if (tau == 1.f) PQL_LAUNCH(ps, copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count, vec);
+    else PQL_LAUNCH(ps, soft_update_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count, tau, vec);
+    prof_commit(ps, tau == 1.f ? KID_COPY : KID_SOFT_UPDATE, 0.0, (tau == 1.f ? 8.0 : 12.0) * (double)count);
     return hipGetLastError();
 }
 
