@@ -41,6 +41,10 @@ const char* kernel_name(int kid) {
         case KID_ADAM: return "adam_reduce_kernel";
         case KID_SOFT_UPDATE: return "soft_update_kernel";
         case KID_COPY: return "copy_kernel";
+        case KID_FUSED_CRITIC: return "fused_critic_kernel";
+        case KID_FUSED_POLICY: return "fused_policy_kernel";
+        case KID_FUSED_ACT: return "fused_act_kernel";
+        case KID_TRANSPOSE: return "transpose_kernel";
         default: return "?";
     }
 }
@@ -140,9 +144,27 @@ struct Layout {
     size_t colA[PQL_MAX_HIDDEN + 2];                                  // bias-grad partials of actor layer l (1..L+1)
     size_t aOut, dPre, y, q[2];
     size_t p_dw[2], p_dbh[2], p_db[2], p_loss;
+    size_t wT[2][PQL_MAX_HIDDEN + 1];                                 // transposed critic weights, layer l = 1..L-1
     size_t splitk;
     size_t total;
 };
+
+// The row-tile fused kernels apply when every hidden layer is a multiple of 32 and at most
+// FUSED_MAXW wide, the action vector fits one MFMA tile and the tile's LDS footprint fits a CU.
+bool fused_ok(const pql_config* c) {
+    int hmax = 0;
+    for (int l = 0; l < c->n_hidden; ++l) {
+        if (c->hidden[l] % 32 != 0 || c->hidden[l] > FUSED_MAXW) return false;
+        hmax = c->hidden[l] > hmax ? c->hidden[l] : hmax;
+    }
+    if (c->act_dim > FUSED_MAX_ACT || c->obs_dim > 1024) return false;
+    return fused_lds_bytes(c->obs_dim, c->act_dim, hmax) <= 160 * 1024;
+}
+int max_hidden(const pql_config* c) {
+    int hmax = 0;
+    for (int l = 0; l < c->n_hidden; ++l) hmax = c->hidden[l] > hmax ? c->hidden[l] : hmax;
+    return hmax;
+}
 
 // Weight-gradient problems are launched in two passes, one per tile shape.
 inline int dw_tile_of(int M, int N) { return (M >= 128 && N >= 128) ? TILE_128x128 : TILE_64x64; }
@@ -190,7 +212,8 @@ void make_layout(const pql_config* c, Layout& w) {
     size_t off = 0;
     auto take = [&](size_t n) { const size_t o = off; off += up(n); return o; };
     const size_t crow = B / 32 + 8;                 // rows of a column-sum partial buffer
-    const size_t nwg = (size_t)head_workgroups((int)B);
+    size_t nwg = (size_t)head_workgroups((int)B);
+    if (nwg < (B + FUSED_BM - 1) / FUSED_BM) nwg = (B + FUSED_BM - 1) / FUSED_BM;   // one partial row per row tile
     for (int l = 1; l <= L; ++l) {
         const size_t h = (size_t)c->hidden[l - 1];
         w.hA[l] = take(B * h);
@@ -215,6 +238,8 @@ void make_layout(const pql_config* c, Layout& w) {
         w.p_db[i] = take(nwg);
     }
     w.p_loss = take(2 * nwg);
+    for (int i = 0; i < 2; ++i)
+        for (int l = 1; l < L; ++l) w.wT[i][l] = take((size_t)c->hidden[l - 1] * c->hidden[l]);
     w.splitk = take(splitk_floats(c, (int)B));
     w.total = off;
 }
@@ -535,67 +560,107 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
     hipError_t e;
     const char* who = "pql_critic_update";
 
-    // 1. lagged policy pi^v on s' (hidden layers) together with the online critics on (s, a)
-    for (int l = 1; l <= L; ++l) {
-        std::vector<GemmProb> ps;
-        const int H = c->cfg.hidden[l - 1];
-        GemmProb p = prob(B, H, ws + w.hA[l], H, EPI_BIAS_ELU);
-        if (l == 1) add_seg(p, batch.next_obs, o, actor_target_params + c->a_w[0], H, o);
-        else add_seg(p, ws + w.hA[l - 1], c->cfg.hidden[l - 2], actor_target_params + c->a_w[l - 1], H, c->cfg.hidden[l - 2]);
-        p.bias = actor_target_params + c->a_b[l - 1];
-        ps.push_back(p);
-        for (int i = 0; i < 2; ++i)
-            ps.push_back(critic_layer(c, critic_params + i * Pc, l, batch.obs, batch.act, ad,
-                                      l > 1 ? ws + w.hQ[i][l - 1] : nullptr, ws + w.hQ[i][l], B));
-        if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
-    }
-    // 2. a' = tanh(output layer of pi^v)
-    {
-        std::vector<GemmProb> ps;
-        GemmProb p = prob(B, ad, ws + w.aOut, ad, EPI_BIAS_TANH);
-        add_seg(p, ws + w.hA[L], HL, actor_target_params + c->a_w[L], ad, HL);
-        p.bias = actor_target_params + c->a_b[L];
-        ps.push_back(p);
-        if ((e = run(GEMM_NN, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
-    }
-    // 3. twin target critics on (s', a')
-    for (int l = 1; l <= L; ++l) {
-        std::vector<GemmProb> ps;
-        for (int i = 0; i < 2; ++i)
-            ps.push_back(critic_layer(c, critic_target_params + i * Pc, l, batch.next_obs, ws + w.aOut, ad,
-                                      l > 1 ? ws + w.hT[i][l - 1] : nullptr, ws + w.hT[i][l], B));
-        if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
-    }
-    // 4. heads: y, losses, output deltas, delta of the last hidden layer
-    HeadArgs h;
-    std::memset(&h, 0, sizeof(h));
-    h.B = B; h.H = HL; h.nwg = head_workgroups(B);
-    for (int i = 0; i < 2; ++i) {
-        h.hT[i] = ws + w.hT[i][L]; h.wT[i] = critic_target_params + i * Pc + c->c_w[L]; h.bT[i] = critic_target_params + i * Pc + c->c_b[L];
-        h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L];        h.bQ[i] = critic_params + i * Pc + c->c_b[L];
-        h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
-        h.p_dw[i] = ws + w.p_dw[i]; h.p_dbh[i] = ws + w.p_dbh[i]; h.p_db[i] = ws + w.p_db[i];
-    }
-    h.ret = batch.ret; h.boot = batch.boot; h.y = ws + w.y; h.p_loss = ws + w.p_loss;
-    if ((e = critic_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
-
     AdamArgs adm;
     std::memset(&adm, 0, sizeof(adm));
-    // 5. backward data path: delta_{l-1} = (delta_l W_l^T) * ELU'(z_{l-1}), bias grads as column sums
-    for (int l = L; l >= 2; --l) {
-        std::vector<GemmProb> ps;
-        const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
-        for (int i = 0; i < 2; ++i) {
-            GemmProb p = prob(B, Hp, ws + w.dQ[i][l - 1], Hp, EPI_MUL_DELU);
-            add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
-            p.aux = ws + w.hQ[i][l - 1]; p.ldaux = Hp;
-            p.colsum = ws + w.colQ[i][l - 1];
-            ps.push_back(p);
+    int head_parts = 0;
+    if (fused_ok(&c->cfg)) {
+        // One launch per row tile: target path, forward, heads and backward data path.
+        TransposeArgs tr;
+        tr.n = 0;
+        FusedCriticArgs fa;
+        std::memset(&fa, 0, sizeof(fa));
+        fa.B = B; fa.o = o; fa.a = ad; fa.L = L; fa.nwg = (B + FUSED_BM - 1) / FUSED_BM; fa.hmax = max_hidden(&c->cfg);
+        for (int l = 0; l < L; ++l) fa.H[l] = c->cfg.hidden[l];
+        for (int l = 0; l <= L; ++l) {
+            fa.pi.w[l] = actor_target_params + c->a_w[l]; fa.pi.b[l] = actor_target_params + c->a_b[l];
+            for (int i = 0; i < 2; ++i) {
+                fa.qt[i].w[l] = critic_target_params + i * Pc + c->c_w[l]; fa.qt[i].b[l] = critic_target_params + i * Pc + c->c_b[l];
+                fa.q[i].w[l] = critic_params + i * Pc + c->c_w[l];        fa.q[i].b[l] = critic_params + i * Pc + c->c_b[l];
+            }
         }
-        const int tile = choose_tile(GEMM_NT, ps);
-        if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+        for (int i = 0; i < 2; ++i) {
+            for (int l = 1; l < L; ++l) {
+                TransposeArgs::Mat& mt = tr.m[tr.n++];
+                mt.src = critic_params + i * Pc + c->c_w[l]; mt.dst = ws + w.wT[i][l];
+                mt.rows = c->cfg.hidden[l - 1]; mt.cols = c->cfg.hidden[l];
+                fa.wT[i][l] = ws + w.wT[i][l];
+            }
+            for (int l = 1; l <= L; ++l) {
+                fa.hQ[i][l] = ws + w.hQ[i][l]; fa.dQ[i][l] = ws + w.dQ[i][l]; fa.colQ[i][l] = ws + w.colQ[i][l];
+            }
+            fa.q_out[i] = ws + w.q[i];
+            fa.p_dw[i] = ws + w.p_dw[i]; fa.p_dbh[i] = ws + w.p_dbh[i]; fa.p_db[i] = ws + w.p_db[i];
+        }
+        fa.obs = batch.obs; fa.act = batch.act; fa.ret = batch.ret; fa.next_obs = batch.next_obs; fa.boot = batch.boot;
+        fa.y = ws + w.y; fa.p_loss = ws + w.p_loss;
+        if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
+        if ((e = fused_critic_launch(fa, st)) != hipSuccess) return E.hip(e, who);
+        head_parts = fa.nwg;
         for (int i = 0; i < 2; ++i)
-            red(adm, i * Pc + c->c_b[l - 2], ws + w.colQ[i][l - 1], Hp, colsum_rows(tile, B), Hp);
+            for (int l = 1; l < L; ++l)
+                red(adm, i * Pc + c->c_b[l - 1], ws + w.colQ[i][l], c->cfg.hidden[l - 1], fa.nwg, c->cfg.hidden[l - 1]);
+    } else {
+        // 1. lagged policy pi^v on s' (hidden layers) together with the online critics on (s, a)
+        for (int l = 1; l <= L; ++l) {
+            std::vector<GemmProb> ps;
+            const int H = c->cfg.hidden[l - 1];
+            GemmProb p = prob(B, H, ws + w.hA[l], H, EPI_BIAS_ELU);
+            if (l == 1) add_seg(p, batch.next_obs, o, actor_target_params + c->a_w[0], H, o);
+            else add_seg(p, ws + w.hA[l - 1], c->cfg.hidden[l - 2], actor_target_params + c->a_w[l - 1], H, c->cfg.hidden[l - 2]);
+            p.bias = actor_target_params + c->a_b[l - 1];
+            ps.push_back(p);
+            for (int i = 0; i < 2; ++i)
+                ps.push_back(critic_layer(c, critic_params + i * Pc, l, batch.obs, batch.act, ad,
+                                          l > 1 ? ws + w.hQ[i][l - 1] : nullptr, ws + w.hQ[i][l], B));
+            if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
+        }
+        // 2. a' = tanh(output layer of pi^v)
+        {
+            std::vector<GemmProb> ps;
+            GemmProb p = prob(B, ad, ws + w.aOut, ad, EPI_BIAS_TANH);
+            add_seg(p, ws + w.hA[L], HL, actor_target_params + c->a_w[L], ad, HL);
+            p.bias = actor_target_params + c->a_b[L];
+            ps.push_back(p);
+            if ((e = run(GEMM_NN, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+        }
+        // 3. twin target critics on (s', a')
+        for (int l = 1; l <= L; ++l) {
+            std::vector<GemmProb> ps;
+            for (int i = 0; i < 2; ++i)
+                ps.push_back(critic_layer(c, critic_target_params + i * Pc, l, batch.next_obs, ws + w.aOut, ad,
+                                          l > 1 ? ws + w.hT[i][l - 1] : nullptr, ws + w.hT[i][l], B));
+            if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
+        }
+        // 4. heads: y, losses, output deltas, delta of the last hidden layer
+        HeadArgs h;
+        std::memset(&h, 0, sizeof(h));
+        h.B = B; h.H = HL; h.nwg = head_workgroups(B);
+        for (int i = 0; i < 2; ++i) {
+            h.hT[i] = ws + w.hT[i][L]; h.wT[i] = critic_target_params + i * Pc + c->c_w[L]; h.bT[i] = critic_target_params + i * Pc + c->c_b[L];
+            h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L];        h.bQ[i] = critic_params + i * Pc + c->c_b[L];
+            h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
+            h.p_dw[i] = ws + w.p_dw[i]; h.p_dbh[i] = ws + w.p_dbh[i]; h.p_db[i] = ws + w.p_db[i];
+        }
+        h.ret = batch.ret; h.boot = batch.boot; h.y = ws + w.y; h.p_loss = ws + w.p_loss;
+        if ((e = critic_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
+        head_parts = h.nwg;
+
+        // 5. backward data path: delta_{l-1} = (delta_l W_l^T) * ELU'(z_{l-1}), bias grads as column sums
+        for (int l = L; l >= 2; --l) {
+            std::vector<GemmProb> ps;
+            const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
+            for (int i = 0; i < 2; ++i) {
+                GemmProb p = prob(B, Hp, ws + w.dQ[i][l - 1], Hp, EPI_MUL_DELU);
+                add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
+                p.aux = ws + w.hQ[i][l - 1]; p.ldaux = Hp;
+                p.colsum = ws + w.colQ[i][l - 1];
+                ps.push_back(p);
+            }
+            const int tile = choose_tile(GEMM_NT, ps);
+            if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+            for (int i = 0; i < 2; ++i)
+                red(adm, i * Pc + c->c_b[l - 2], ws + w.colQ[i][l - 1], Hp, colsum_rows(tile, B), Hp);
+        }
     }
     // 6. weight gradients X^T delta (split over the batch)
     {
@@ -623,11 +688,11 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
     }
     // 7. remaining reductions (last hidden bias, output layer) + Adam + loss scalars
     for (int i = 0; i < 2; ++i) {
-        red(adm, i * Pc + c->c_b[L - 1], ws + w.p_dbh[i], HL, h.nwg, HL);
-        red(adm, i * Pc + c->c_w[L], ws + w.p_dw[i], HL, h.nwg, HL);
-        red(adm, i * Pc + c->c_b[L], ws + w.p_db[i], 1, h.nwg, 1);
+        red(adm, i * Pc + c->c_b[L - 1], ws + w.p_dbh[i], HL, head_parts, HL);
+        red(adm, i * Pc + c->c_w[L], ws + w.p_dw[i], HL, head_parts, HL);
+        red(adm, i * Pc + c->c_b[L], ws + w.p_db[i], 1, head_parts, 1);
     }
-    adm.nloss = 2; adm.loss_parts = h.nwg; adm.loss_scale = 1.f / (float)B;
+    adm.nloss = 2; adm.loss_parts = head_parts; adm.loss_scale = 1.f / (float)B;
     adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
     adm.theta = critic_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
     fill_adam(adm, opt, c->critic_t + 1);

@@ -1,0 +1,542 @@
+// Row-tile fused learner kernels for networks whose layers are at most 256 wide.
+//
+// A workgroup (8 wavefronts) owns 32 batch rows and carries them through a whole chain of
+// layers: the activations of the tile live in LDS (two ping-pong buffers), the weights are
+// streamed straight from L2 into registers as the B operand of v_mfma_f32_32x32x2_f32 (each
+// wavefront owns 32 output columns, lanes run along the contiguous output dimension of W, so
+// every load is a coalesced 128-byte row piece), and only what a later kernel needs (activations
+// and deltas for the weight-gradient GEMMs) is written to memory.  For the V-learner step this
+// replaces the per-layer launches of the target policy, the twin target critics, the twin online
+// critics, the output heads and the backward data path by one launch; weight gradients (a
+// contraction over the whole batch) stay in the split-K GEMM kernel.
+//
+// Backward products delta * W^T are computed as delta * (W^T) with W^T materialised once per
+// call by transpose_kernel, so that they use the same coalesced operand path.
+#include "pql_internal.h"
+
+namespace pql {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int FW = 8;                // wavefronts per workgroup
+constexpr int FT = 64 * FW;          // threads per workgroup
+constexpr int BMF = FUSED_BM;        // rows per workgroup (32)
+constexpr int SCRATCH_F = FW * 1024; // floats of LDS scratch (one 32x32 partial tile per wavefront)
+
+struct Lanes { int tid, lane, wave, l32, half; };
+
+// The row tile's LDS.  Tiles are addressed as offsets (in floats) into this array rather than
+// through pointers, so that every access is compiled as an LDS instruction (a generic pointer
+// would turn them into flat memory operations that also wait on the global-load counter).
+extern __shared__ __attribute__((aligned(16))) float smem[];
+
+__device__ inline float elu_f(float x) { return x > 0.f ? x : __expf(x) - 1.f; }
+__device__ inline float delu_h(float h) { return h > 0.f ? 1.f : h + 1.f; }   // ELU'(z) from h = ELU(z)
+__device__ inline float wsum(float x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+__device__ inline int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
+
+// acc[n] += in[n][32 x K] * W[n][K x .] for NN networks at once, for the output column `ncol`
+// of this lane.  `in` are LDS tiles with row stride ld whose columns are zero up to the next
+// multiple of 8; W are row-major in memory with leading dimension ldw.  The contraction runs in
+// chunks of 32 k-values (16 MFMAs per network); chunks are taken with stride c_step starting at
+// c_begin (c_step > 1 splits the contraction across wavefronts).  The weights of the next chunk
+// are loaded (unconditionally, with a clamped chunk index, so the number of loads in flight is
+// the same on every path) while the current chunk feeds the matrix core.
+template <int NN>
+__device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], const int (&in)[NN], int ld,
+                                   int K, const float* const (&W)[NN], int ldw, int ncol, const Lanes& T, int c_begin,
+                                   int c_step) {
+    const int nch = (K + 31) >> 5;
+    int c = c_begin;
+    if (c >= nch) return;
+    const int a_off = T.l32 * ld + 4 * T.half;
+    // Every workgroup of the launch streams the same weight matrix.  Starting each workgroup at a
+    // different chunk spreads the simultaneous requests over the L2 channels instead of piling
+    // all compute units onto the same few cache lines.
+    const int rot = (int)(blockIdx.x % (unsigned)nch);
+    const int lane_off = 4 * T.half * ldw + ncol;     // this lane's fixed offset inside a group of rows
+    float b0[NN][16], b1[NN][16];
+    auto loadc = [&](int ci, float (&b)[NN][16]) {
+        int cc = ci + rot;
+        cc = cc >= nch ? cc - nch : cc;
+        const int kbase = cc * 32;
+        if (kbase + 32 <= K) {
+            // full chunk: uniform row base + per-lane constant offset (scalar address arithmetic)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int n = 0; n < NN; ++n)
+                        b[n][g * 4 + u] = (W[n] + (size_t)(kbase + g * 8 + u) * (size_t)ldw)[lane_off];
+        } else {
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    int k = kbase + g * 8 + 4 * T.half + u;
+                    k = k < K ? k : K - 1;                // clamped rows meet zero columns of `in`
+#pragma unroll
+                    for (int n = 0; n < NN; ++n) b[n][g * 4 + u] = W[n][(size_t)k * (size_t)ldw + ncol];
+                }
+        }
+    };
+    auto compute = [&](int ci, const float (&b)[NN][16]) {
+        int cr = ci + rot;
+        cr = cr >= nch ? cr - nch : cr;
+        const int ng = min(4, (K - cr * 32 + 7) >> 3);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            if (g < ng) {
+#pragma unroll
+                for (int n = 0; n < NN; ++n) {
+                    const float4 a = *reinterpret_cast<const float4*>(&smem[in[n] + a_off + cr * 32 + g * 8]);
+                    acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b[n][g * 4 + 0], acc0[n], 0, 0, 0);
+                    acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b[n][g * 4 + 1], acc1[n], 0, 0, 0);
+                    acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b[n][g * 4 + 2], acc0[n], 0, 0, 0);
+                    acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b[n][g * 4 + 3], acc1[n], 0, 0, 0);
+                }
+            }
+        }
+    };
+    loadc(c, b0);
+    while (true) {
+        int cn = c + c_step;
+        loadc(cn < nch ? cn : c, b1);
+        compute(c, b0);
+        if (cn >= nch) break;
+        c = cn;
+        cn = c + c_step;
+        loadc(cn < nch ? cn : c, b0);
+        compute(c, b1);
+        if (cn >= nch) break;
+        c = cn;
+    }
+}
+
+enum WideEpi : int { WIDE_BIAS_ELU = 0, WIDE_MUL_DELU = 1 };
+
+// One layer for NN networks of equal shape (the twin critics run as a pair).
+template <int NN>
+struct WideArgs {
+    int in0[NN]; const float* W0[NN]; int ld0, K0;               // first input segment (LDS offset)
+    int in1[NN]; const float* W1[NN]; int ld1, K1;               // optional second segment (K1 = 0: none)
+    int ldw, N;
+    const float* bias[NN];                                       // WIDE_BIAS_ELU
+    int aux[NN]; int ldaux;                                      // WIDE_MUL_DELU: LDS tile of activations (offset)
+    int outL[NN]; int ldo;                                       // LDS output tile (offset; may be aux, never an input)
+    float* outG[NN]; int ldg;                                    // optional copy in memory
+    float* colsum[NN];                                           // optional column sums over the tile's rows
+    int epi;
+};
+
+// out[32 x N] (N <= 256, one 32-column tile per wavefront).  WIDE_BIAS_ELU: out = ELU(acc + bias).
+// WIDE_MUL_DELU: out = acc * ELU'(.) with the activation taken from the LDS tile `aux`.  Rows
+// beyond the batch are written as zero.
+template <int NN>
+__device__ inline void wide_linear(const Lanes& T, const WideArgs<NN>& w, int r0, int B) {
+    const int n0 = T.wave * 32, N = w.N;
+    if (n0 >= N) return;
+    const int n = n0 + T.l32;
+    const bool n_ok = n < N;
+    const int ncol = n_ok ? n : N - 1;
+    float bv[NN];
+#pragma unroll
+    for (int i = 0; i < NN; ++i) bv[i] = (w.epi == WIDE_BIAS_ELU) ? w.bias[i][ncol] : 0.f;   // in flight during the MFMAs
+    floatx16 acc0[NN], acc1[NN];
+#pragma unroll
+    for (int i = 0; i < NN; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc0[i][r] = 0.f; acc1[i][r] = 0.f; }
+    mac_segment<NN>(acc0, acc1, w.in0, w.ld0, w.K0, w.W0, w.ldw, ncol, T, 0, 1);
+    if (w.K1 > 0) mac_segment<NN>(acc0, acc1, w.in1, w.ld1, w.K1, w.W1, w.ldw, ncol, T, 0, 1);
+#pragma unroll
+    for (int i = 0; i < NN; ++i) {
+        float cs = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = acc_row(r, T.half);
+            float x = acc0[i][r] + acc1[i][r];
+            if (w.epi == WIDE_BIAS_ELU) x = elu_f(x + bv[i]);
+            else x *= delu_h(smem[w.aux[i] + row * w.ldaux + ncol]);
+            const bool rv = r0 + row < B;
+            if (!rv) x = 0.f;
+            if (n_ok) {
+                smem[w.outL[i] + row * w.ldo + n] = x;
+                if (w.outG[i] && rv) w.outG[i][(size_t)(r0 + row) * (size_t)w.ldg + n] = x;
+                cs += x;
+            }
+        }
+        if (w.colsum[i]) {
+            cs += __shfl_xor(cs, 32);
+            if (T.half == 0 && n_ok) w.colsum[i][n] = cs;
+        }
+    }
+}
+
+// Partial products of a narrow layer (N <= 32): the contraction is split across the wavefronts,
+// each leaves its 32x32 partial tile in `scratch` (accumulator layout: index r * 64 + lane).
+// The caller synchronises and finishes with small_sum().
+__device__ inline void small_partial(const Lanes& T, int in0, int ld0, int K0, const float* W0, int ldw, int N,
+                                     int scratch) {
+    floatx16 acc0[1], acc1[1];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc0[0][r] = 0.f; acc1[0][r] = 0.f; }
+    const int ncol = T.l32 < N ? T.l32 : N - 1;
+    const int ins[1] = {in0};
+    const float* const ws[1] = {W0};
+    mac_segment<1>(acc0, acc1, ins, ld0, K0, ws, ldw, ncol, T, T.wave, FW);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) smem[scratch + T.wave * 1024 + r * 64 + T.lane] = acc0[0][r] + acc1[0][r];
+}
+
+// Sum of the FW partial tiles for output element e (0..1023): returns the value and its (row, col).
+__device__ inline float small_sum(int scratch, int e, int& row, int& col) {
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < FW; ++w) s += smem[scratch + w * 1024 + e];
+    const int r = e >> 6, ln = e & 63;
+    row = acc_row(r, ln >> 5);
+    col = ln & 31;
+    return s;
+}
+
+// Copies rows r0..r0+31 of a row-major [B][ncols] array into an LDS tile, zero-filling rows
+// beyond B and the columns up to the next multiple of 8.
+__device__ inline void load_rows(const Lanes& T, int dst, int stride, const float* __restrict__ src, int ncols,
+                                 int r0, int B) {
+    const int kp = (ncols + 7) & ~7;
+    for (int i = T.tid; i < BMF * kp; i += FT) {
+        const int row = i / kp, col = i - row * kp;
+        float v = 0.f;
+        if (col < ncols && r0 + row < B) v = src[(size_t)(r0 + row) * (size_t)ncols + col];
+        smem[dst + row * stride + col] = v;
+    }
+}
+
+// LDS of one row tile: XA (state-like input), XB (action-like input), two ping-pong activation
+// tiles for each of two networks, scratch for split contractions (aliased onto the second
+// network's tiles when those are large enough), small per-row arrays.
+struct TileMem {
+    int XA, XB, H[2][2], scratch, sm;     // offsets into smem, in floats
+    int SXA, SXB, SH;
+};
+
+__host__ __device__ inline int tile_floats(int o, int a, int hmax, bool with_small) {
+    const int sxa = ((o + 7) & ~7) + 4, sxb = ((a + 7) & ~7) + 4, sh = hmax + 4;
+    const int scratch = (2 * BMF * sh >= SCRATCH_F) ? 0 : SCRATCH_F;
+    return BMF * (sxa + sxb + 4 * sh) + scratch + (with_small ? 16 * BMF : 0);
+}
+
+__device__ inline TileMem carve(int o, int a, int hmax) {
+    TileMem m;
+    m.SXA = ((o + 7) & ~7) + 4;
+    m.SXB = ((a + 7) & ~7) + 4;
+    m.SH = hmax + 4;
+    m.XA = 0;
+    m.XB = m.XA + BMF * m.SXA;
+    int p = m.XB + BMF * m.SXB;
+    for (int n = 0; n < 2; ++n)
+        for (int k = 0; k < 2; ++k) { m.H[n][k] = p; p += BMF * m.SH; }
+    if (2 * BMF * m.SH >= SCRATCH_F) m.scratch = m.H[1][0];
+    else { m.scratch = p; p += SCRATCH_F; }
+    m.sm = p;
+    return m;
+}
+
+size_t fused_lds_bytes(int o, int a, int hmax) { return sizeof(float) * (size_t)tile_floats(o, a, hmax, true); }
+
+// Hidden layers of NN equally shaped networks on the tile: layer 1 reads XA (and XB when
+// a_cols > 0), later layers ping-pong between the two tiles of each network.  Returns the index of
+// the tile holding the last hidden activations.  hG[n][l] (l = 1..L-1, may be null) receives h_l.
+template <int NN>
+__device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const FusedNet* const (&nets)[NN], const int* Hw,
+                                     int L, int o, int a_cols, float* const* const (&hG)[NN], int r0, int B) {
+    int cur = 0;
+    for (int l = 0; l < L; ++l) {
+        const int N = Hw[l];
+        WideArgs<NN> w;
+        w.ldw = N; w.N = N; w.epi = WIDE_BIAS_ELU; w.ldaux = 0; w.ldo = m.SH; w.ldg = N;
+        const int dst = (l == 0) ? 0 : (cur ^ 1);
+#pragma unroll
+        for (int n = 0; n < NN; ++n) {
+            if (l == 0) {
+                w.in0[n] = m.XA; w.W0[n] = nets[n]->w[0];
+                w.in1[n] = m.XB; w.W1[n] = nets[n]->w[0] + (size_t)o * N;
+            } else {
+                w.in0[n] = m.H[n][cur]; w.W0[n] = nets[n]->w[l];
+                w.in1[n] = 0; w.W1[n] = nullptr;
+            }
+            w.bias[n] = nets[n]->b[l]; w.aux[n] = 0;
+            w.outL[n] = m.H[n][dst];
+            w.outG[n] = (hG[n] && l < L - 1) ? hG[n][l + 1] : nullptr;
+            w.colsum[n] = nullptr;
+        }
+        if (l == 0) { w.ld0 = m.SXA; w.K0 = o; w.ld1 = m.SXB; w.K1 = a_cols; }
+        else        { w.ld0 = m.SH; w.K0 = Hw[l - 1]; w.ld1 = 0; w.K1 = 0; }
+        wide_linear<NN>(T, w, r0, B);
+        cur = dst;
+        __syncthreads();
+    }
+    return cur;
+}
+
+// =============================================================================================
+// V-learner step on one row tile (Algorithm 3; Section 3.2 for the lagged target policy):
+// a' = pi^v(s'), t_i = Q'_i(s', a'), y = ret + boot * min(t_1, t_2); q_i = Q_i(s, a);
+// loss partials, output deltas, and the deltas of every hidden layer of both critics.  The twin
+// critics always run as a pair: each wavefront carries one 32-column tile of both.
+// =============================================================================================
+__global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs A) {
+    Lanes T;
+    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
+    const int o = A.o, a = A.a, L = A.L, B = A.B;
+    const TileMem m = carve(o, a, A.hmax);
+    const int r0 = blockIdx.x * BMF;
+    const int HL = A.H[L - 1];
+    float* sm_ret = &smem[m.sm];           // [32]
+    float* sm_boot = &smem[m.sm + 32];     // [32]
+    float* sm_y = &smem[m.sm + 64];        // [32]
+    float* sm_red = &smem[m.sm + 128];     // [FW][4]
+
+    // ---- target path ------------------------------------------------------------------------
+    load_rows(T, m.XA, m.SXA, A.next_obs, o, r0, B);
+    if (T.tid < 32) {
+        const bool rv = r0 + T.tid < B;
+        sm_ret[T.tid] = rv ? A.ret[r0 + T.tid] : 0.f;
+        sm_boot[T.tid] = rv ? A.boot[r0 + T.tid] : 0.f;
+    }
+    __syncthreads();
+    int cur;
+    {
+        const FusedNet* const nets[1] = {&A.pi};
+        float* const* const hg[1] = {nullptr};
+        cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, hg, r0, B);
+    }
+    small_partial(T, m.H[0][cur], m.SH, HL, A.pi.w[L], a, a, m.scratch);
+    __syncthreads();
+    for (int e = T.tid; e < 1024; e += FT) {
+        int row, col;
+        const float s = small_sum(m.scratch, e, row, col);
+        if (col < m.SXB - 4) smem[m.XB + row * m.SXB + col] = col < a ? tanhf(s + A.pi.b[L][col]) : 0.f;
+    }
+    __syncthreads();
+    {
+        const FusedNet* const nets[2] = {&A.qt[0], &A.qt[1]};
+        float* const* const hg[2] = {nullptr, nullptr};
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B);
+    }
+    {   // scalar heads of the target critics, min, TD target: one wavefront per row
+        float wt0[4], wt1[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = T.lane + 64 * j;
+            wt0[j] = c < HL ? A.qt[0].w[L][c] : 0.f;
+            wt1[j] = c < HL ? A.qt[1].w[L][c] : 0.f;
+        }
+        const float bt0 = A.qt[0].b[L][0], bt1 = A.qt[1].b[L][0];
+        for (int rr = 0; rr < BMF / FW; ++rr) {
+            const int row = T.wave * (BMF / FW) + rr;
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = T.lane + 64 * j;
+                if (c < HL) {
+                    s0 += smem[m.H[0][cur] + row * m.SH + c] * wt0[j];
+                    s1 += smem[m.H[1][cur] + row * m.SH + c] * wt1[j];
+                }
+            }
+            s0 = wsum(s0) + bt0;
+            s1 = wsum(s1) + bt1;
+            if (T.lane == 0) {
+                const float y = sm_ret[row] + sm_boot[row] * fminf(s0, s1);
+                sm_y[row] = y;
+                if (r0 + row < B) A.y[r0 + row] = y;
+            }
+        }
+    }
+    __syncthreads();
+    // ---- online critics ---------------------------------------------------------------------
+    load_rows(T, m.XA, m.SXA, A.obs, o, r0, B);
+    load_rows(T, m.XB, m.SXB, A.act, a, r0, B);
+    __syncthreads();
+    {
+        const FusedNet* const nets[2] = {&A.q[0], &A.q[1]};
+        float* const* const hg[2] = {A.hQ[0], A.hQ[1]};
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B);
+    }
+    const float invB = 1.f / (float)B;
+    float loss_acc[2] = {0.f, 0.f}, db_acc[2] = {0.f, 0.f};
+    float dw_acc[2][4], dbh_acc[2][4];
+    {   // heads: q, Bellman error, output delta; delta of the last hidden layer written in place
+        float wq[2][4], bq[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            bq[i] = A.q[i].b[L][0];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                wq[i][j] = (T.lane + 64 * j < HL) ? A.q[i].w[L][T.lane + 64 * j] : 0.f;
+                dw_acc[i][j] = 0.f; dbh_acc[i][j] = 0.f;
+            }
+        }
+        for (int rr = 0; rr < BMF / FW; ++rr) {
+            const int row = T.wave * (BMF / FW) + rr;
+            const bool rv = r0 + row < B;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                float* hrow = &smem[m.H[i][cur] + row * m.SH];
+                float h[4];
+                float s = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int c = T.lane + 64 * j;
+                    h[j] = c < HL ? hrow[c] : 0.f;
+                    s += h[j] * wq[i][j];
+                }
+                const float q = wsum(s) + bq[i];
+                const float e = rv ? q - sm_y[row] : 0.f;
+                const float d = 2.f * e * invB;
+                loss_acc[i] += e * e;
+                db_acc[i] += d;
+                if (T.lane == 0 && rv) A.q_out[i][r0 + row] = q;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int c = T.lane + 64 * j;
+                    if (c < HL) {
+                        const float g = d * wq[i][j] * delu_h(h[j]);
+                        hrow[c] = g;
+                        if (rv) A.dQ[i][L][(size_t)(r0 + row) * HL + c] = g;
+                        dbh_acc[i][j] += g;
+                        dw_acc[i][j] += d * h[j];
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // backward data path: delta_{l-1} = (delta_l W_l^T) * ELU'(z_{l-1}), l = L..2 (layers from 1)
+    for (int l = L; l >= 2; --l) {
+        const int Hl = A.H[l - 1], Hp = A.H[l - 2];
+        if (l < L) {       // h_{l-1} is no longer on chip: bring it back from memory
+            load_rows(T, m.H[0][cur ^ 1], m.SH, A.hQ[0][l - 1], Hp, r0, B);
+            load_rows(T, m.H[1][cur ^ 1], m.SH, A.hQ[1][l - 1], Hp, r0, B);
+            __syncthreads();
+        }
+        WideArgs<2> w;
+        w.ld0 = m.SH; w.K0 = Hl; w.ld1 = 0; w.K1 = 0; w.ldw = Hp; w.N = Hp; w.epi = WIDE_MUL_DELU;
+        w.ldaux = m.SH; w.ldo = m.SH; w.ldg = Hp;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            w.in0[i] = m.H[i][cur]; w.W0[i] = A.wT[i][l - 1]; w.in1[i] = 0; w.W1[i] = nullptr;
+            w.bias[i] = nullptr; w.aux[i] = m.H[i][cur ^ 1]; w.outL[i] = m.H[i][cur ^ 1];
+            w.outG[i] = A.dQ[i][l - 1];
+            w.colsum[i] = A.colQ[i][l - 1] + (size_t)blockIdx.x * Hp;
+        }
+        wide_linear<2>(T, w, r0, B);
+        cur ^= 1;
+        __syncthreads();
+    }
+    // ---- per-workgroup partial sums -----------------------------------------------------------
+    // scratch[(arr * FW + wave) * 256 + c], arr = 0..3: dW_out(Q1), dW_out(Q2), db_L(Q1), db_L(Q2)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int c = T.lane + 64 * j;
+        smem[m.scratch + (0 * FW + T.wave) * 256 + c] = dw_acc[0][j];
+        smem[m.scratch + (1 * FW + T.wave) * 256 + c] = dw_acc[1][j];
+        smem[m.scratch + (2 * FW + T.wave) * 256 + c] = dbh_acc[0][j];
+        smem[m.scratch + (3 * FW + T.wave) * 256 + c] = dbh_acc[1][j];
+    }
+    if (T.lane == 0) {
+        sm_red[T.wave * 4 + 0] = loss_acc[0]; sm_red[T.wave * 4 + 1] = loss_acc[1];
+        sm_red[T.wave * 4 + 2] = db_acc[0];   sm_red[T.wave * 4 + 3] = db_acc[1];
+    }
+    __syncthreads();
+    const int wg = blockIdx.x, nwg = gridDim.x;
+    for (int e = T.tid; e < 4 * 256; e += FT) {
+        const int arr = e >> 8, c = e & 255;
+        if (c < HL) {
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < FW; ++w) s += smem[m.scratch + (arr * FW + w) * 256 + c];
+            float* dst = arr == 0 ? A.p_dw[0] : (arr == 1 ? A.p_dw[1] : (arr == 2 ? A.p_dbh[0] : A.p_dbh[1]));
+            dst[(size_t)wg * HL + c] = s;
+        }
+    }
+    if (T.tid < 4) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < FW; ++w) s += sm_red[w * 4 + T.tid];
+        if (T.tid == 0) A.p_loss[wg] = s;
+        if (T.tid == 1) A.p_loss[nwg + wg] = s;
+        if (T.tid == 2) A.p_db[0][wg] = s;
+        if (T.tid == 3) A.p_db[1][wg] = s;
+    }
+}
+
+hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream) {
+    const size_t lds = fused_lds_bytes(a.o, a.a, a.hmax);
+    static size_t configured = 0;
+    if (lds > configured) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_critic_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = lds;
+    }
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, fused_critic_kernel, dim3(a.nwg), dim3(FT), lds, stream, a);
+    // 2 flops per multiply-add of every layer the tile passes through (no weight gradients here)
+    double flops = 0.0;
+    if (ps.on) {
+        double pa = (double)a.o * a.H[0], pc = (double)(a.o + a.a) * a.H[0], pb = 0.0;
+        for (int l = 1; l < a.L; ++l) { pa += (double)a.H[l - 1] * a.H[l]; pc += (double)a.H[l - 1] * a.H[l]; pb += (double)a.H[l - 1] * a.H[l]; }
+        pa += (double)a.H[a.L - 1] * a.a; pc += a.H[a.L - 1]; pb += a.H[a.L - 1];
+        flops = 2.0 * a.B * (pa + 4.0 * pc + 2.0 * pb);
+    }
+    prof_commit(ps, KID_FUSED_CRITIC, flops, 0.0);
+    return hipGetLastError();
+}
+
+// =============================================================================================
+// Batched 2-D transposes: dst[c][r] = src[r][c] for a list of small matrices.
+// =============================================================================================
+__global__ __launch_bounds__(256) void transpose_kernel(const TransposeArgs a) {
+    __shared__ float tile[32][33];
+    int b = blockIdx.x, mi = 0;
+    for (int i = 1; i < a.n; ++i)
+        if (b >= a.m[i].block_begin) mi = i;
+    const TransposeArgs::Mat& M = a.m[mi];
+    b -= M.block_begin;
+    const int tiles_c = (M.cols + 31) / 32;
+    const int tr = b / tiles_c, tc = b - tr * tiles_c;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int j = ty; j < 32; j += 8) {
+        const int r = tr * 32 + j, c = tc * 32 + tx;
+        tile[j][tx] = (r < M.rows && c < M.cols) ? M.src[(size_t)r * M.cols + c] : 0.f;
+    }
+    __syncthreads();
+    for (int j = ty; j < 32; j += 8) {
+        const int c = tc * 32 + j, r = tr * 32 + tx;
+        if (r < M.rows && c < M.cols) M.dst[(size_t)c * M.rows + r] = tile[tx][j];
+    }
+}
+
+hipError_t transpose_launch(TransposeArgs& a, hipStream_t stream) {
+    int blocks = 0;
+    double bytes = 0.0;
+    for (int i = 0; i < a.n; ++i) {
+        a.m[i].block_begin = blocks;
+        blocks += ((a.m[i].rows + 31) / 32) * ((a.m[i].cols + 31) / 32);
+        bytes += 8.0 * a.m[i].rows * a.m[i].cols;
+    }
+    if (blocks == 0) return hipSuccess;
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, transpose_kernel, dim3(blocks), dim3(256), 0, stream, a);
+    prof_commit(ps, KID_TRANSPOSE, 0.0, bytes);
+    return hipGetLastError();
+}
+
+}  // namespace pql

@@ -15,7 +15,8 @@ namespace pql {
 // tile 4 = the 128x32 instantiation that carries the exploration-noise epilogue.
 enum KernelId : int {
     KID_GEMM = 0, KID_PUSH = 15, KID_SAMPLE = 16, KID_HEAD_CRITIC = 17, KID_HEAD_POLICY = 18,
-    KID_ADAM = 19, KID_SOFT_UPDATE = 20, KID_COPY = 21, KID_COUNT = 22
+    KID_ADAM = 19, KID_SOFT_UPDATE = 20, KID_COPY = 21, KID_FUSED_CRITIC = 22, KID_FUSED_POLICY = 23,
+    KID_FUSED_ACT = 24, KID_TRANSPOSE = 25, KID_COUNT = 26
 };
 const char* kernel_name(int kid);
 bool prof_active();
@@ -173,5 +174,39 @@ struct SampleArgs {
 hipError_t sample_launch(const SampleArgs& a, hipStream_t stream);
 
 hipError_t soft_update_launch(const float* src, float* dst, int64_t count, float tau, hipStream_t stream);
+
+// ---- row-tile fused kernels (layers at most FUSED_MAXW wide) ------------------------------
+constexpr int FUSED_BM = 32;        // batch rows per workgroup
+constexpr int FUSED_MAXW = 256;     // widest hidden layer
+constexpr int FUSED_MAX_ACT = 32;   // widest action vector
+
+struct FusedNet {                   // per layer l = 0..L: weights W_l[in][out] and bias b_l[out]
+    const float* w[PQL_MAX_HIDDEN + 1];
+    const float* b[PQL_MAX_HIDDEN + 1];
+};
+
+struct FusedCriticArgs {
+    int B, o, a, L, nwg, hmax;
+    int H[PQL_MAX_HIDDEN];
+    FusedNet pi;                    // lagged policy pi^v
+    FusedNet qt[2];                 // target critics
+    FusedNet q[2];                  // online critics
+    const float* wT[2][PQL_MAX_HIDDEN + 1];   // [i][l]: transpose of W_l of online critic i, l = 1..L-1
+    const float *obs, *act, *ret, *next_obs, *boot;
+    float* hQ[2][PQL_MAX_HIDDEN + 1];          // [i][l], l = 1..L-1: hidden activations (layer numbers from 1)
+    float* dQ[2][PQL_MAX_HIDDEN + 1];          // [i][l], l = 1..L: deltas
+    float* colQ[2][PQL_MAX_HIDDEN + 1];        // [i][l], l = 1..L-1: bias-gradient partials [nwg][H_l]
+    float* y; float* q_out[2];
+    float* p_dw[2]; float* p_dbh[2]; float* p_db[2]; float* p_loss;
+};
+hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream);
+size_t fused_lds_bytes(int o, int a, int hmax);
+
+struct TransposeArgs {
+    struct Mat { const float* src; float* dst; int rows, cols, block_begin, pad_; };
+    int n;
+    Mat m[24];
+};
+hipError_t transpose_launch(TransposeArgs& a, hipStream_t stream);
 
 }  // namespace pql
