@@ -128,10 +128,10 @@ int choose_tile(int mode, const std::vector<GemmProb>& ps) {
 int colsum_rows(int tile, int M) { return ((M + gemm_tile_m(tile) - 1) / gemm_tile_m(tile)) * gemm_waves_m(tile); }
 
 // Upper bound on split count for K rows of batch and the given total of output tiles.
-int split_target(long tiles, int K) {
-    // about four workgroups per compute unit, but at least 128 batch rows per split
+int split_target(long tiles, int K, int kmin) {
+    // about four workgroups per compute unit, but at least kmin batch rows per split
     long s = (1024 + tiles - 1) / (tiles > 0 ? tiles : 1);
-    const long by_k = (K + 127) / 128;
+    const long by_k = (K + kmin - 1) / kmin;
     if (s > by_k) s = by_k;
     if (s < 1) s = 1;
     return (int)s;
@@ -145,6 +145,8 @@ struct Layout {
     size_t aOut, dPre, y, q[2];
     size_t p_dw[2], p_dbh[2], p_db[2], p_loss;
     size_t wT[2][PQL_MAX_HIDDEN + 1];                                 // transposed critic weights, layer l = 1..L-1
+    size_t w1aT[2];                                                   // transposed action rows of the critics' first layer
+    size_t waT[PQL_MAX_HIDDEN + 1];                                   // transposed policy weights, layer l = 1..L
     size_t splitk;
     size_t total;
 };
@@ -166,8 +168,23 @@ int max_hidden(const pql_config* c) {
     return hmax;
 }
 
-// Weight-gradient problems are launched in two passes, one per tile shape.
-inline int dw_tile_of(int M, int N) { return (M >= 128 && N >= 128) ? TILE_128x128 : TILE_64x64; }
+// Weight-gradient problems: a small set (few 128x128 output tiles in total) goes into one launch
+// of 64x64 tiles with long K ranges per split; otherwise large matrices take 128x128 tiles and the
+// rest 64x64 tiles, in two launches.
+struct DwPlan { bool single; int kmin; };
+inline DwPlan dw_plan(const std::vector<std::pair<int, int>>& mn) {
+    long big = 0;
+    for (const auto& d : mn)
+        if (d.first >= 128 && d.second >= 128) big += (long)((d.first + 127) / 128) * ((d.second + 127) / 128);
+    DwPlan p;
+    p.single = big < 32;
+    p.kmin = p.single ? 512 : 128;
+    return p;
+}
+inline int dw_tile_of(const DwPlan& p, int M, int N) {
+    if (p.single) return TILE_64x64;
+    return (M >= 128 && N >= 128) ? TILE_128x128 : TILE_64x64;
+}
 inline long dw_tiles(int tile, int M, int N) {
     return (long)((M + gemm_tile_m(tile) - 1) / gemm_tile_m(tile)) * ((N + gemm_tile_n(tile) - 1) / gemm_tile_n(tile));
 }
@@ -176,16 +193,17 @@ inline long dw_tiles(int tile, int M, int N) {
 // batch size up to K: per pass, (largest split count) x (sum of M*N).
 size_t dw_slab_bound(const std::vector<std::pair<int, int>>& mn, int K) {
     size_t total = 0;
+    const DwPlan plan = dw_plan(mn);
     for (int pass = 0; pass < 2; ++pass) {
         const int tile = pass == 0 ? TILE_128x128 : TILE_64x64;
         long tiles = 0;
         size_t elems = 0;
         for (const auto& d : mn) {
-            if (dw_tile_of(d.first, d.second) != tile) continue;
+            if (dw_tile_of(plan, d.first, d.second) != tile) continue;
             tiles += dw_tiles(tile, d.first, d.second);
             elems += (size_t)d.first * d.second;
         }
-        if (tiles > 0) total += (size_t)split_target(tiles, K) * elems;
+        if (tiles > 0) total += (size_t)split_target(tiles, K, plan.kmin) * elems;
     }
     return total;
 }
@@ -238,8 +256,11 @@ void make_layout(const pql_config* c, Layout& w) {
         w.p_db[i] = take(nwg);
     }
     w.p_loss = take(2 * nwg);
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
         for (int l = 1; l < L; ++l) w.wT[i][l] = take((size_t)c->hidden[l - 1] * c->hidden[l]);
+        w.w1aT[i] = take((size_t)c->act_dim * c->hidden[0]);
+    }
+    for (int l = 1; l <= L; ++l) w.waT[l] = take((size_t)c->hidden[l - 1] * (l < L ? c->hidden[l] : c->act_dim));
     w.splitk = take(splitk_floats(c, (int)B));
     w.total = off;
 }
@@ -290,20 +311,22 @@ hipError_t run_auto(int mode, std::vector<GemmProb>& ps, hipStream_t st) {
 // reduction entry per problem.  `offsets[i]` is the parameter offset of problem i's tensor.
 hipError_t run_dw(std::vector<GemmProb>& ps, const std::vector<int64_t>& offsets, int K, float* slab,
                   AdamArgs& ad, hipStream_t st) {
-    // group by preferred tile so that small and large matrices do not share a tiling
+    std::vector<std::pair<int, int>> mn;
+    for (const GemmProb& p : ps) mn.push_back({p.M, p.N});
+    const DwPlan plan = dw_plan(mn);
     for (int pass = 0; pass < 2; ++pass) {
         const int tile = pass == 0 ? TILE_128x128 : TILE_64x64;
         std::vector<GemmProb> sel;
         std::vector<int64_t> sel_off;
         long tiles = 0;
         for (size_t i = 0; i < ps.size(); ++i) {
-            if (dw_tile_of(ps[i].M, ps[i].N) != tile) continue;
+            if (dw_tile_of(plan, ps[i].M, ps[i].N) != tile) continue;
             sel.push_back(ps[i]);
             sel_off.push_back(offsets[i]);
             tiles += dw_tiles(tile, ps[i].M, ps[i].N);
         }
         if (sel.empty()) continue;
-        int S = split_target(tiles, K);
+        int S = split_target(tiles, K, plan.kmin);
         int chunk = ((K + S - 1) / S + 31) / 32 * 32;
         S = (K + chunk - 1) / chunk;
         for (size_t i = 0; i < sel.size(); ++i) {
@@ -521,6 +544,21 @@ int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, i
     float* ws = (float*)workspace;
     Layout w;
     make_layout(&c->cfg, w);
+    if (fused_ok(&c->cfg)) {
+        FusedActArgs fa;
+        std::memset(&fa, 0, sizeof(fa));
+        fa.B = num; fa.o = c->cfg.obs_dim; fa.a = c->cfg.act_dim; fa.L = c->L; fa.hmax = max_hidden(&c->cfg);
+        for (int l = 0; l < c->L; ++l) fa.H[l] = c->cfg.hidden[l];
+        for (int l = 0; l <= c->L; ++l) { fa.pi.w[l] = actor_params + c->a_w[l]; fa.pi.b[l] = actor_params + c->a_b[l]; }
+        fa.obs = obs; fa.act_out = act_out;
+        fa.noise.act_dim = c->cfg.act_dim; fa.noise.sigma_rows = num; fa.noise.sigma_min = sigma_min; fa.noise.sigma_max = sigma_max;
+        fa.noise.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); fa.noise.key1 = (uint32_t)(c->cfg.seed >> 32);
+        fa.noise.ctr2 = (uint32_t)((uint64_t)c->acts & 0xffffffffu); fa.noise.ctr3 = (uint32_t)((uint64_t)c->acts >> 32);
+        const hipError_t fe = fused_act_launch(fa, st);
+        if (fe != hipSuccess) return E.hip(fe, "pql_actor_act");
+        c->acts += 1;
+        return PQL_OK;
+    }
     hipError_t e = actor_hidden_forward(c, actor_params, obs, num, ws, w, st);
     if (e != hipSuccess) return E.hip(e, "pql_actor_act");
     const int L = c->L, HL = c->cfg.hidden[L - 1], ad = c->cfg.act_dim;
@@ -721,72 +759,113 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     hipError_t e;
     const char* who = "pql_actor_update";
 
-    // 1. a = pi(s)
-    if ((e = actor_hidden_forward(c, actor_params, obs, B, ws, w, st)) != hipSuccess) return E.hip(e, who);
-    {
-        std::vector<GemmProb> ps;
-        GemmProb p = prob(B, ad, ws + w.aOut, ad, EPI_BIAS_TANH);
-        add_seg(p, ws + w.hA[L], HL, actor_params + c->a_w[L], ad, HL);
-        p.bias = actor_params + c->a_b[L];
-        ps.push_back(p);
-        if ((e = run(GEMM_NN, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
-    }
-    // 2. twin critics on (s, pi(s))
-    for (int l = 1; l <= L; ++l) {
-        std::vector<GemmProb> ps;
-        for (int i = 0; i < 2; ++i)
-            ps.push_back(critic_layer(c, critic_params + i * Pc, l, obs, ws + w.aOut, ad,
-                                      l > 1 ? ws + w.hQ[i][l - 1] : nullptr, ws + w.hQ[i][l], B));
-        if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
-    }
-    // 3. heads: J partials and the delta entering the smaller critic
-    HeadArgs h;
-    std::memset(&h, 0, sizeof(h));
-    h.B = B; h.H = HL; h.nwg = head_workgroups(B);
-    for (int i = 0; i < 2; ++i) {
-        h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L]; h.bQ[i] = critic_params + i * Pc + c->c_b[L];
-        h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
-    }
-    h.p_loss = ws + w.p_loss;
-    if ((e = policy_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
-    // 4. critic backward data path down to layer 1
-    for (int l = L; l >= 2; --l) {
-        std::vector<GemmProb> ps;
-        const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
-        for (int i = 0; i < 2; ++i) {
-            GemmProb p = prob(B, Hp, ws + w.dQ[i][l - 1], Hp, EPI_MUL_DELU);
-            add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
-            p.aux = ws + w.hQ[i][l - 1]; p.ldaux = Hp;
-            ps.push_back(p);
-        }
-        if ((e = run_auto(GEMM_NT, ps, st)) != hipSuccess) return E.hip(e, who);
-    }
     AdamArgs adm;
     std::memset(&adm, 0, sizeof(adm));
-    // 5. gradient w.r.t. the action input of both critics, through tanh'
-    {
-        std::vector<GemmProb> ps;
-        GemmProb p = prob(B, ad, ws + w.dPre, ad, EPI_MUL_DTANH);
-        for (int i = 0; i < 2; ++i)
-            add_seg(p, ws + w.dQ[i][1], H1, critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, H1, H1);
-        p.aux = ws + w.aOut; p.ldaux = ad;
-        p.colsum = ws + w.colA[L + 1];
-        ps.push_back(p);
-        if ((e = run(GEMM_NT, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
-        red(adm, c->a_b[L], ws + w.colA[L + 1], ad, colsum_rows(TILE_128x32, B), ad);
-    }
-    // 6. policy backward data path
-    for (int l = L + 1; l >= 2; --l) {
-        std::vector<GemmProb> ps;
-        const int Hl = (l == L + 1) ? ad : c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
-        GemmProb p = prob(B, Hp, ws + w.dA[l - 1], Hp, EPI_MUL_DELU);
-        add_seg(p, (l == L + 1) ? ws + w.dPre : ws + w.dA[l], Hl, actor_params + c->a_w[l - 1], Hl, Hl);
-        p.aux = ws + w.hA[l - 1]; p.ldaux = Hp;
-        p.colsum = ws + w.colA[l - 1];
-        ps.push_back(p);
-        const int tile = choose_tile(GEMM_NT, ps);
-        if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
-        red(adm, c->a_b[l - 2], ws + w.colA[l - 1], Hp, colsum_rows(tile, B), Hp);
+    int loss_parts = 0;
+    if (fused_ok(&c->cfg)) {
+        TransposeArgs tr;
+        tr.n = 0;
+        FusedPolicyArgs fa;
+        std::memset(&fa, 0, sizeof(fa));
+        fa.B = B; fa.o = o; fa.a = ad; fa.L = L; fa.nwg = (B + FUSED_BM - 1) / FUSED_BM; fa.hmax = max_hidden(&c->cfg);
+        for (int l = 0; l < L; ++l) fa.H[l] = c->cfg.hidden[l];
+        for (int l = 0; l <= L; ++l) {
+            fa.pi.w[l] = actor_params + c->a_w[l]; fa.pi.b[l] = actor_params + c->a_b[l];
+            for (int i = 0; i < 2; ++i) { fa.q[i].w[l] = critic_params + i * Pc + c->c_w[l]; fa.q[i].b[l] = critic_params + i * Pc + c->c_b[l]; }
+        }
+        auto add_tr = [&](const float* src, float* dst, int rows, int cols) {
+            TransposeArgs::Mat& mt = tr.m[tr.n++];
+            mt.src = src; mt.dst = dst; mt.rows = rows; mt.cols = cols;
+        };
+        for (int i = 0; i < 2; ++i) {
+            for (int l = 1; l < L; ++l) {
+                add_tr(critic_params + i * Pc + c->c_w[l], ws + w.wT[i][l], c->cfg.hidden[l - 1], c->cfg.hidden[l]);
+                fa.wT[i][l] = ws + w.wT[i][l];
+            }
+            add_tr(critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, ws + w.w1aT[i], ad, H1);
+            fa.w1aT[i] = ws + w.w1aT[i];
+            for (int l = 1; l <= L; ++l) fa.hQ[i][l] = ws + w.hQ[i][l];
+            fa.q_out[i] = ws + w.q[i];
+        }
+        for (int l = 1; l <= L; ++l) {
+            add_tr(actor_params + c->a_w[l], ws + w.waT[l], c->cfg.hidden[l - 1], l < L ? c->cfg.hidden[l] : ad);
+            fa.waT[l] = ws + w.waT[l];
+            fa.hA[l] = ws + w.hA[l]; fa.dA[l] = ws + w.dA[l]; fa.colA[l] = ws + w.colA[l];
+        }
+        fa.colA[L + 1] = ws + w.colA[L + 1];
+        fa.obs = obs; fa.dPre = ws + w.dPre; fa.p_loss = ws + w.p_loss;
+        if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
+        if ((e = fused_policy_launch(fa, st)) != hipSuccess) return E.hip(e, who);
+        loss_parts = fa.nwg;
+        red(adm, c->a_b[L], ws + w.colA[L + 1], ad, fa.nwg, ad);
+        for (int l = 1; l <= L; ++l) red(adm, c->a_b[l - 1], ws + w.colA[l], c->cfg.hidden[l - 1], fa.nwg, c->cfg.hidden[l - 1]);
+    } else {
+        // 1. a = pi(s)
+        if ((e = actor_hidden_forward(c, actor_params, obs, B, ws, w, st)) != hipSuccess) return E.hip(e, who);
+        {
+            std::vector<GemmProb> ps;
+            GemmProb p = prob(B, ad, ws + w.aOut, ad, EPI_BIAS_TANH);
+            add_seg(p, ws + w.hA[L], HL, actor_params + c->a_w[L], ad, HL);
+            p.bias = actor_params + c->a_b[L];
+            ps.push_back(p);
+            if ((e = run(GEMM_NN, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+        }
+        // 2. twin critics on (s, pi(s))
+        for (int l = 1; l <= L; ++l) {
+            std::vector<GemmProb> ps;
+            for (int i = 0; i < 2; ++i)
+                ps.push_back(critic_layer(c, critic_params + i * Pc, l, obs, ws + w.aOut, ad,
+                                          l > 1 ? ws + w.hQ[i][l - 1] : nullptr, ws + w.hQ[i][l], B));
+            if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
+        }
+        // 3. heads: J partials and the delta entering the smaller critic
+        HeadArgs h;
+        std::memset(&h, 0, sizeof(h));
+        h.B = B; h.H = HL; h.nwg = head_workgroups(B);
+        for (int i = 0; i < 2; ++i) {
+            h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L]; h.bQ[i] = critic_params + i * Pc + c->c_b[L];
+            h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
+        }
+        h.p_loss = ws + w.p_loss;
+        if ((e = policy_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
+        loss_parts = h.nwg;
+        // 4. critic backward data path down to layer 1
+        for (int l = L; l >= 2; --l) {
+            std::vector<GemmProb> ps;
+            const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
+            for (int i = 0; i < 2; ++i) {
+                GemmProb p = prob(B, Hp, ws + w.dQ[i][l - 1], Hp, EPI_MUL_DELU);
+                add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
+                p.aux = ws + w.hQ[i][l - 1]; p.ldaux = Hp;
+                ps.push_back(p);
+            }
+            if ((e = run_auto(GEMM_NT, ps, st)) != hipSuccess) return E.hip(e, who);
+        }
+        // 5. gradient w.r.t. the action input of both critics, through tanh'
+        {
+            std::vector<GemmProb> ps;
+            GemmProb p = prob(B, ad, ws + w.dPre, ad, EPI_MUL_DTANH);
+            for (int i = 0; i < 2; ++i)
+                add_seg(p, ws + w.dQ[i][1], H1, critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, H1, H1);
+            p.aux = ws + w.aOut; p.ldaux = ad;
+            p.colsum = ws + w.colA[L + 1];
+            ps.push_back(p);
+            if ((e = run(GEMM_NT, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+            red(adm, c->a_b[L], ws + w.colA[L + 1], ad, colsum_rows(TILE_128x32, B), ad);
+        }
+        // 6. policy backward data path
+        for (int l = L + 1; l >= 2; --l) {
+            std::vector<GemmProb> ps;
+            const int Hl = (l == L + 1) ? ad : c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
+            GemmProb p = prob(B, Hp, ws + w.dA[l - 1], Hp, EPI_MUL_DELU);
+            add_seg(p, (l == L + 1) ? ws + w.dPre : ws + w.dA[l], Hl, actor_params + c->a_w[l - 1], Hl, Hl);
+            p.aux = ws + w.hA[l - 1]; p.ldaux = Hp;
+            p.colsum = ws + w.colA[l - 1];
+            ps.push_back(p);
+            const int tile = choose_tile(GEMM_NT, ps);
+            if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+            red(adm, c->a_b[l - 2], ws + w.colA[l - 1], Hp, colsum_rows(tile, B), Hp);
+        }
     }
     // 7. policy weight gradients
     {
@@ -801,7 +880,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
         }
         if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st)) != hipSuccess) return E.hip(e, who);
     }
-    adm.nloss = 1; adm.loss_parts = h.nwg; adm.loss_scale = -1.f / (float)B;
+    adm.nloss = 1; adm.loss_parts = loss_parts; adm.loss_scale = -1.f / (float)B;
     adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
     adm.theta = actor_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
     fill_adam(adm, opt, c->actor_t + 1);

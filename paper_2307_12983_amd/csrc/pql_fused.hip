@@ -255,7 +255,8 @@ size_t fused_lds_bytes(int o, int a, int hmax) { return sizeof(float) * (size_t)
 // the tile holding the last hidden activations.  hG[n][l] (l = 1..L-1, may be null) receives h_l.
 template <int NN>
 __device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const FusedNet* const (&nets)[NN], const int* Hw,
-                                     int L, int o, int a_cols, float* const* const (&hG)[NN], int r0, int B) {
+                                     int L, int o, int a_cols, float* const* const (&hG)[NN], int r0, int B,
+                                     bool store_last = false) {
     int cur = 0;
     for (int l = 0; l < L; ++l) {
         const int N = Hw[l];
@@ -273,7 +274,7 @@ __device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const Fus
             }
             w.bias[n] = nets[n]->b[l]; w.aux[n] = 0;
             w.outL[n] = m.H[n][dst];
-            w.outG[n] = (hG[n] && l < L - 1) ? hG[n][l + 1] : nullptr;
+            w.outG[n] = (hG[n] && (l < L - 1 || store_last)) ? hG[n][l + 1] : nullptr;
             w.colsum[n] = nullptr;
         }
         if (l == 0) { w.ld0 = m.SXA; w.K0 = o; w.ld1 = m.SXB; w.K1 = a_cols; }
@@ -475,6 +476,266 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         if (T.tid == 2) A.p_db[0][wg] = s;
         if (T.tid == 3) A.p_db[1][wg] = s;
     }
+}
+
+// =============================================================================================
+// P-learner step on one row tile (Algorithm 2: maximise min_i Q_i(s, pi(s))): a = pi(s), both
+// critics on (s, a), the gradient -1/B through the smaller critic down to its action input,
+// through tanh' and back through the policy.  Leaves the policy's activations and deltas in
+// memory for the weight-gradient GEMMs.
+// =============================================================================================
+__global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs A) {
+    Lanes T;
+    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
+    const int o = A.o, a = A.a, L = A.L, B = A.B;
+    const TileMem m = carve(o, a, A.hmax);
+    const int r0 = blockIdx.x * BMF;
+    const int HL = A.H[L - 1], H1 = A.H[0];
+    float* sm_red = &smem[m.sm + 128];     // [FW]
+    const int wg = blockIdx.x;
+
+    load_rows(T, m.XA, m.SXA, A.obs, o, r0, B);
+    __syncthreads();
+    int cur;
+    {
+        const FusedNet* const nets[1] = {&A.pi};
+        float* const* const hg[1] = {A.hA};
+        cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, hg, r0, B, true);
+    }
+    small_partial(T, m.H[0][cur], m.SH, HL, A.pi.w[L], a, a, m.scratch);
+    __syncthreads();
+    for (int e = T.tid; e < 1024; e += FT) {
+        int row, col;
+        const float s = small_sum(m.scratch, e, row, col);
+        if (col < m.SXB - 4) smem[m.XB + row * m.SXB + col] = col < a ? tanhf(s + A.pi.b[L][col]) : 0.f;
+    }
+    __syncthreads();
+    {
+        const FusedNet* const nets[2] = {&A.q[0], &A.q[1]};
+        float* const* const hg[2] = {A.hQ[0], A.hQ[1]};
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B);
+    }
+    float loss_acc = 0.f;
+    {   // heads: q_1, q_2, the smaller one receives -1/B; delta of the last hidden layer in place
+        const float invB = 1.f / (float)B;
+        float wq[2][4], bq[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            bq[i] = A.q[i].b[L][0];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wq[i][j] = (T.lane + 64 * j < HL) ? A.q[i].w[L][T.lane + 64 * j] : 0.f;
+        }
+        for (int rr = 0; rr < BMF / FW; ++rr) {
+            const int row = T.wave * (BMF / FW) + rr;
+            const bool rv = r0 + row < B;
+            float h[2][4], q[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                float s = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int c = T.lane + 64 * j;
+                    h[i][j] = c < HL ? smem[m.H[i][cur] + row * m.SH + c] : 0.f;
+                    s += h[i][j] * wq[i][j];
+                }
+                q[i] = wsum(s) + bq[i];
+                if (T.lane == 0 && rv) A.q_out[i][r0 + row] = q[i];
+            }
+            const bool pick0 = q[0] <= q[1];
+            if (rv) loss_acc += pick0 ? q[0] : q[1];
+            const float d[2] = {(rv && pick0) ? -invB : 0.f, (rv && !pick0) ? -invB : 0.f};
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int c = T.lane + 64 * j;
+                    if (c < HL) smem[m.H[i][cur] + row * m.SH + c] = d[i] * wq[i][j] * delu_h(h[i][j]);
+                }
+        }
+    }
+    __syncthreads();
+    // critic backward data path down to the first hidden layer (no parameter gradients here)
+    for (int l = L; l >= 2; --l) {
+        const int Hl = A.H[l - 1], Hp = A.H[l - 2];
+        if (l < L) {
+            load_rows(T, m.H[0][cur ^ 1], m.SH, A.hQ[0][l - 1], Hp, r0, B);
+            load_rows(T, m.H[1][cur ^ 1], m.SH, A.hQ[1][l - 1], Hp, r0, B);
+            __syncthreads();
+        }
+        WideArgs<2> w;
+        w.ld0 = m.SH; w.K0 = Hl; w.ld1 = 0; w.K1 = 0; w.ldw = Hp; w.N = Hp; w.epi = WIDE_MUL_DELU;
+        w.ldaux = m.SH; w.ldo = m.SH; w.ldg = Hp;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            w.in0[i] = m.H[i][cur]; w.W0[i] = A.wT[i][l - 1]; w.in1[i] = 0; w.W1[i] = nullptr;
+            w.bias[i] = nullptr; w.aux[i] = m.H[i][cur ^ 1]; w.outL[i] = m.H[i][cur ^ 1];
+            w.outG[i] = nullptr; w.colsum[i] = nullptr;
+        }
+        wide_linear<2>(T, w, r0, B);
+        cur ^= 1;
+        __syncthreads();
+    }
+    // gradient w.r.t. the action input, summed over both critics, through tanh'
+    {
+        floatx16 acc0[1], acc1[1];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc0[0][r] = 0.f; acc1[0][r] = 0.f; }
+        const int ncol = T.l32 < a ? T.l32 : a - 1;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int ins[1] = {m.H[i][cur]};
+            const float* const ws[1] = {A.w1aT[i]};
+            mac_segment<1>(acc0, acc1, ins, m.SH, H1, ws, a, ncol, T, T.wave, FW);
+        }
+        // the scratch region may alias the second network's tiles: everyone must be done reading
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 16; ++r) smem[m.scratch + T.wave * 1024 + r * 64 + T.lane] = acc0[0][r] + acc1[0][r];
+    }
+    __syncthreads();
+    for (int e = T.tid; e < 1024; e += FT) {
+        int row, col;
+        const float s = small_sum(m.scratch, e, row, col);
+        if (col < m.SXB - 4) {
+            const float ap = smem[m.XB + row * m.SXB + col];
+            const float g = (col < a && r0 + row < B) ? s * (1.f - ap * ap) : 0.f;
+            smem[m.XB + row * m.SXB + col] = g;
+            if (col < a && r0 + row < B) A.dPre[(size_t)(r0 + row) * a + col] = g;
+        }
+    }
+    __syncthreads();
+    if (T.tid < a) {       // bias gradient of the output layer: column sums of dPre over the tile
+        float s = 0.f;
+        for (int row = 0; row < BMF; ++row) s += smem[m.XB + row * m.SXB + T.tid];
+        A.colA[L + 1][(size_t)wg * a + T.tid] = s;
+    }
+    // policy backward data path: delta_L = (dPre W_out^T) * ELU'(z_L), then down the hidden layers
+    int pc = 0;
+    load_rows(T, m.H[0][pc], m.SH, A.hA[L], HL, r0, B);
+    __syncthreads();
+    {
+        WideArgs<1> w;
+        w.in0[0] = m.XB; w.W0[0] = A.waT[L]; w.ld0 = m.SXB; w.K0 = a; w.in1[0] = 0; w.W1[0] = nullptr; w.ld1 = 0; w.K1 = 0;
+        w.ldw = HL; w.N = HL; w.bias[0] = nullptr; w.aux[0] = m.H[0][pc]; w.ldaux = m.SH; w.outL[0] = m.H[0][pc]; w.ldo = m.SH;
+        w.outG[0] = A.dA[L]; w.ldg = HL; w.colsum[0] = A.colA[L] + (size_t)wg * HL; w.epi = WIDE_MUL_DELU;
+        wide_linear<1>(T, w, r0, B);
+    }
+    __syncthreads();
+    for (int l = L; l >= 2; --l) {
+        const int Hl = A.H[l - 1], Hp = A.H[l - 2];
+        load_rows(T, m.H[0][pc ^ 1], m.SH, A.hA[l - 1], Hp, r0, B);
+        __syncthreads();
+        WideArgs<1> w;
+        w.in0[0] = m.H[0][pc]; w.W0[0] = A.waT[l - 1]; w.ld0 = m.SH; w.K0 = Hl; w.in1[0] = 0; w.W1[0] = nullptr; w.ld1 = 0; w.K1 = 0;
+        w.ldw = Hp; w.N = Hp; w.bias[0] = nullptr; w.aux[0] = m.H[0][pc ^ 1]; w.ldaux = m.SH; w.outL[0] = m.H[0][pc ^ 1]; w.ldo = m.SH;
+        w.outG[0] = A.dA[l - 1]; w.ldg = Hp; w.colsum[0] = A.colA[l - 1] + (size_t)wg * Hp; w.epi = WIDE_MUL_DELU;
+        wide_linear<1>(T, w, r0, B);
+        pc ^= 1;
+        __syncthreads();
+    }
+    if (T.lane == 0) sm_red[T.wave] = loss_acc;
+    __syncthreads();
+    if (T.tid == 0) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < FW; ++w) s += sm_red[w];
+        A.p_loss[wg] = s;
+    }
+}
+
+// =============================================================================================
+// Actor step on one row tile (Section 3.3, Algorithm 1): a = clip(pi(s) + sigma_i * eps, -1, 1).
+// =============================================================================================
+__device__ inline void philox4x32_10_f(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                       uint32_t& o0, uint32_t& o1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    o0 = c0; o1 = c1;
+}
+
+__global__ __launch_bounds__(FT) void fused_act_kernel(const FusedActArgs A) {
+    Lanes T;
+    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
+    const int o = A.o, a = A.a, L = A.L, B = A.B;
+    const TileMem m = carve(o, a, A.hmax);
+    const int r0 = blockIdx.x * BMF;
+    load_rows(T, m.XA, m.SXA, A.obs, o, r0, B);
+    __syncthreads();
+    const FusedNet* const nets[1] = {&A.pi};
+    float* const* const hg[1] = {nullptr};
+    const int cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, hg, r0, B);
+    small_partial(T, m.H[0][cur], m.SH, A.H[L - 1], A.pi.w[L], a, a, m.scratch);
+    __syncthreads();
+    const GemmNoise& nz = A.noise;
+    for (int e = T.tid; e < 1024; e += FT) {
+        int row, col;
+        const float s = small_sum(m.scratch, e, row, col);
+        const int env = r0 + row;
+        if (col < a && env < B) {
+            uint32_t w0, w1;
+            philox4x32_10_f((uint32_t)(env * a + col), 2u, nz.ctr2, nz.ctr3, nz.key0, nz.key1, w0, w1);
+            // double precision: (w >> 8) + 0.5 needs 25 significant bits
+            const double u1 = ((double)(w0 >> 8) + 0.5) * 0x1p-24;
+            const double u2 = ((double)(w1 >> 8) + 0.5) * 0x1p-24;
+            const double eps = sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2);
+            double sigma = (double)nz.sigma_min;
+            if (nz.sigma_rows > 1)
+                sigma += ((double)env / (double)(nz.sigma_rows - 1)) * ((double)nz.sigma_max - (double)nz.sigma_min);
+            const float x = tanhf(s + A.pi.b[L][col]) + (float)(sigma * eps);
+            A.act_out[(size_t)env * a + col] = fminf(fmaxf(x, -1.f), 1.f);
+        }
+    }
+}
+
+static hipError_t set_lds_limit(const void* fn, size_t lds, size_t& configured) {
+    if (lds <= configured) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) configured = lds;
+    return e;
+}
+
+hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream) {
+    const size_t lds = fused_lds_bytes(a.o, a.a, a.hmax);
+    static size_t configured = 0;
+    const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(fused_policy_kernel), lds, configured);
+    if (e != hipSuccess) return e;
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, fused_policy_kernel, dim3(a.nwg), dim3(FT), lds, stream, a);
+    double flops = 0.0;
+    if (ps.on) {
+        double pa = (double)a.o * a.H[0], pc = (double)(a.o + a.a) * a.H[0], pb = (double)a.a * a.H[0], pab = 0.0;
+        for (int l = 1; l < a.L; ++l) {
+            const double w = (double)a.H[l - 1] * a.H[l];
+            pa += w; pc += w; pb += w; pab += w;
+        }
+        pa += (double)a.H[a.L - 1] * a.a; pab += (double)a.H[a.L - 1] * a.a; pc += a.H[a.L - 1]; pb += a.H[a.L - 1];
+        flops = 2.0 * a.B * (pa + 2.0 * pc + 2.0 * pb + pab);
+    }
+    prof_commit(ps, KID_FUSED_POLICY, flops, 0.0);
+    return hipGetLastError();
+}
+
+hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream) {
+    const size_t lds = fused_lds_bytes(a.o, a.a, a.hmax);
+    static size_t configured = 0;
+    const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(fused_act_kernel), lds, configured);
+    if (e != hipSuccess) return e;
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, fused_act_kernel, dim3((a.B + BMF - 1) / BMF), dim3(FT), lds, stream, a);
+    double flops = 0.0;
+    if (ps.on) {
+        double pa = (double)a.o * a.H[0];
+        for (int l = 1; l < a.L; ++l) pa += (double)a.H[l - 1] * a.H[l];
+        pa += (double)a.H[a.L - 1] * a.a;
+        flops = 2.0 * a.B * pa;
+    }
+    prof_commit(ps, KID_FUSED_ACT, flops, 0.0);
+    return hipGetLastError();
 }
 
 hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream) {

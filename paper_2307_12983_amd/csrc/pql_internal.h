@@ -202,6 +202,35 @@ struct FusedCriticArgs {
 hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream);
 size_t fused_lds_bytes(int o, int a, int hmax);
 
+struct FusedPolicyArgs {
+    int B, o, a, L, nwg, hmax;
+    int H[PQL_MAX_HIDDEN];
+    FusedNet pi;                    // policy being updated
+    FusedNet q[2];                  // online critics (read-only)
+    const float* wT[2][PQL_MAX_HIDDEN + 1];   // [i][l]: transpose of critic W_l, l = 1..L-1
+    const float* w1aT[2];                      // transpose of the action rows of critic W_0: [H_1][a]
+    const float* waT[PQL_MAX_HIDDEN + 1];      // [l]: transpose of policy W_l, l = 1..L
+    const float* obs;
+    float* hA[PQL_MAX_HIDDEN + 1];             // [l], l = 1..L: policy activations
+    float* dA[PQL_MAX_HIDDEN + 1];             // [l], l = 1..L: policy deltas
+    float* colA[PQL_MAX_HIDDEN + 2];           // [l], l = 1..L+1: bias-gradient partials [nwg][width]
+    float* hQ[2][PQL_MAX_HIDDEN + 1];          // [i][l], l = 1..L-1: critic activations (scratch for L > 2)
+    float* dPre;                               // [B][a]: delta at the policy's pre-tanh output
+    float* q_out[2];
+    float* p_loss;                             // [nwg]
+};
+hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream);
+
+struct FusedActArgs {
+    int B, o, a, L, hmax;
+    int H[PQL_MAX_HIDDEN];
+    FusedNet pi;
+    const float* obs;
+    float* act_out;
+    GemmNoise noise;
+};
+hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream);
+
 struct TransposeArgs {
     struct Mat { const float* src; float* dst; int rows, cols, block_begin, pad_; };
     int n;
