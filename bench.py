@@ -27,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 from paper_2307_12983_amd import workloads as W  # noqa: E402
+from paper_2307_12983_amd import profile_tools  # noqa: E402
 
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
@@ -146,6 +147,14 @@ def main():
     env_dev = [sess.to_device(r) for r in env_host]
     torch.cuda.synchronize()
 
+    # One plain copy of known size (tau = 1 is a copy): the yardstick that scales the HBM byte
+    # counters when this command runs under a counter-collecting profiler.  Outside the timed region.
+    cal_src = torch.ones(profile_tools.CAL_COPY_FLOATS, dtype=torch.float32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    sess.ctx.pql_soft_update(cal_src, cal_dst, cal_src.numel(), 1.0)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     sched = Schedule(sess, env_dev)
     for i in range(args.warmup):
         sched.step(i)
@@ -186,6 +195,7 @@ def main():
     tot_gemm_flops = sum(k["flops"] for k in gemm)
     dom = max(gemm, key=lambda k: k["total_ms"])
     achieved = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
+    traffic = profile_tools.stored_traffic(os.path.join(ROOT, "profiles", "bench_%s_traffic.txt" % w.name), dom["name"])
     fl = flops_per_sample(w)
     flops_step = w.batch * (fl["critic_update"] + fl["actor_update"] / POLICY_EVERY) + w.num_envs * fl["act"] / ACTOR_EVERY
     kernels = []
@@ -208,7 +218,7 @@ def main():
                                                               w.nstep, list(w.hidden), POLICY_EVERY, ACTOR_EVERY),
                    "rows_filled": n_fill},
         "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
                      "avg_launch_us": 1e3 * dom["total_ms"] / dom["launches"], "launches": dom["launches"],
                      "all_gemm_tflops": tot_gemm_flops / (tot_gemm_ms * 1e-3) / 1e12},
         "mfma_util_pct": 100.0 * flops_step * value / (PEAK_FP32_MFMA_TFLOPS * 1e12),

@@ -53,7 +53,11 @@ __device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], c
     const int nch = (K + 31) >> 5;
     int c = c_begin;
     if (c >= nch) return;
-    const int a_off = T.l32 * ld + 4 * T.half;
+    // A operand: one 16-byte LDS read per group (tile offsets and strides are multiples of 4 floats;
+    // indexing the array as float4 lets the compiler prove the alignment and emit ds_read_b128, which
+    // the stride-(width + 4) layout serves without bank conflicts)
+    const int a_off4 = T.l32 * (ld >> 2) + T.half;
+    const float4* smem4 = reinterpret_cast<const float4*>(smem);
     // Every workgroup of the launch streams the same weight matrix.  Starting each workgroup at a
     // different chunk spreads the simultaneous requests over the L2 channels instead of piling
     // all compute units onto the same few cache lines.
@@ -94,7 +98,7 @@ __device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], c
             if (g < ng) {
 #pragma unroll
                 for (int n = 0; n < NN; ++n) {
-                    const float4 a = *reinterpret_cast<const float4*>(&smem[in[n] + a_off + cr * 32 + g * 8]);
+                    const float4 a = smem4[(in[n] >> 2) + a_off4 + cr * 8 + g * 2];
                     acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b[n][g * 4 + 0], acc0[n], 0, 0, 0);
                     acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b[n][g * 4 + 1], acc1[n], 0, 0, 0);
                     acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b[n][g * 4 + 2], acc0[n], 0, 0, 0);
