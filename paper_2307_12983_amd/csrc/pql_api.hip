@@ -122,7 +122,10 @@ int choose_tile(int mode, const std::vector<GemmProb>& ps) {
     if (mode == GEMM_TN) return (max_m >= 128 && max_n >= 128) ? TILE_128x128 : TILE_64x64;
     if (max_n <= 32) return TILE_128x32;
     if (max_n <= 64) return TILE_64x64;
-    return tiles128 >= 512 ? TILE_128x128 : TILE_64x64;
+    // measured: the backward-data kernel is at its best with 64x64 tiles at every size; the forward
+    // kernel gains from 128x128 tiles once there are several of them per compute unit
+    if (mode == GEMM_NT) return TILE_64x64;
+    return tiles128 >= 1024 ? TILE_128x128 : TILE_64x64;
 }
 
 int colsum_rows(int tile, int M) { return ((M + gemm_tile_m(tile) - 1) / gemm_tile_m(tile)) * gemm_waves_m(tile); }

@@ -20,8 +20,6 @@ namespace pql {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 32;          // K extent of one LDS tile
-constexpr int KSTRIDE = BK + 4; // row stride (floats) of a k-contiguous LDS tile
 constexpr int NTHREADS = 256;
 
 // Workgroups are handed to the 8 XCDs round-robin by the hardware; renumber them so that a run
@@ -118,12 +116,13 @@ struct SegRegs {
     bool va, vb;
 };
 
-template <int MODE, int WAVES_M, int WAVES_N, int TM, int TN, bool NOISE>
+template <int MODE, int WAVES_M, int WAVES_N, int TM, int TN, bool NOISE, int BK = 32>
 __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup g) {
     constexpr int BM = WAVES_M * TM * 32;
     constexpr int BN = WAVES_N * TN * 32;
     constexpr bool A_KC = (MODE != GEMM_TN);   // A tile k-contiguous: As[m][k]; else As[k][m]
     constexpr bool B_KC = (MODE == GEMM_NT);   // B tile k-contiguous: Bs[n][k]; else Bs[k][n]
+    constexpr int KSTRIDE = BK + 4;            // row stride (floats) of a k-contiguous LDS tile
     constexpr int SA = A_KC ? KSTRIDE : BM;
     constexpr int SB = B_KC ? KSTRIDE : BN;
     constexpr int A_TILE = A_KC ? BM * SA : BK * SA;
