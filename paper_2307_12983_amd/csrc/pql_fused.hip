@@ -158,20 +158,27 @@ __device__ inline void wide_linear(const Lanes& T, const WideArgs<NN>& w, int r0
         for (int r = 0; r < 16; ++r) { acc0[i][r] = 0.f; acc1[i][r] = 0.f; }
     mac_segment<NN>(acc0, acc1, w.in0, w.ld0, w.K0, w.W0, w.ldw, ncol, T, 0, 1);
     if (w.K1 > 0) mac_segment<NN>(acc0, acc1, w.in1, w.ld1, w.K1, w.W1, w.ldw, ncol, T, 0, 1);
+    // Epilogue.  Row r of the accumulator sits (8 * (r / 4) + r % 4) rows below the lane's first row
+    // (4 * half): offsets from per-lane bases are compile-time multiples of the strides.
+    const bool full = r0 + BMF <= B;                      // uniform: every row of the tile is in the batch
+    const int lrow = 4 * T.half;
 #pragma unroll
     for (int i = 0; i < NN; ++i) {
         float cs = 0.f;
+        const int lbase = w.outL[i] + lrow * w.ldo + n;
+        const int abase = w.aux[i] + lrow * w.ldaux + ncol;
+        float* __restrict__ gbase = w.outG[i] ? w.outG[i] + (size_t)(r0 + lrow) * (size_t)w.ldg + n : nullptr;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int row = acc_row(r, T.half);
+            const int dr = 8 * (r >> 2) + (r & 3);
             float x = acc0[i][r] + acc1[i][r];
             if (w.epi == WIDE_BIAS_ELU) x = elu_f(x + bv[i]);
-            else x *= delu_h(smem[w.aux[i] + row * w.ldaux + ncol]);
-            const bool rv = r0 + row < B;
+            else x *= delu_h(smem[abase + dr * w.ldaux]);
+            const bool rv = full || (r0 + lrow + dr < B);
             if (!rv) x = 0.f;
             if (n_ok) {
-                smem[w.outL[i] + row * w.ldo + n] = x;
-                if (w.outG[i] && rv) w.outG[i][(size_t)(r0 + row) * (size_t)w.ldg + n] = x;
+                smem[lbase + dr * w.ldo] = x;
+                if (gbase && rv) gbase[dr * w.ldg] = x;
                 cs += x;
             }
         }

@@ -46,6 +46,12 @@ def small_cases():
         "humanoid_s": Wk["humanoid"].replace(name="humanoid_s", num_envs=64, capacity=64 * 9, batch=777),
         "shadow_s": Wk["shadow"].replace(name="shadow_s", num_envs=40, capacity=40 * 10, batch=640),
         "scale_s": Wk["scale"].replace(name="scale_s", num_envs=48, capacity=48 * 12, batch=520),
+        # shapes that take the row-tile fused kernels (all widths multiples of 32, at most 256) with one
+        # and with three hidden layers, odd input widths and a batch that is not a multiple of 32
+        "fused_l1": Wk["tiny"].replace(name="fused_l1", obs_dim=37, act_dim=5, num_envs=70, capacity=70 * 9, batch=333,
+                                       hidden=(160,), index=11),
+        "fused_l3": Wk["tiny"].replace(name="fused_l3", obs_dim=45, act_dim=11, num_envs=33, capacity=33 * 12, batch=451,
+                                       hidden=(128, 96, 64), index=12),
     }
 
 
@@ -159,7 +165,7 @@ def test_adam_step_on_oracle_gradients(torch_cuda):
 
 
 # ---------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("case", ["tiny", "ragged", "ant_s", "humanoid_s", "shadow_s", "scale_s"])
+@pytest.mark.parametrize("case", list(small_cases()))
 def test_actor_act_matches_oracle(torch_cuda, case):
     torch = torch_cuda
     w = SMALL[case]
