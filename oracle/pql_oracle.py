@@ -169,6 +169,58 @@ def gather_nstep(ring: ReplayRing, idx, nstep: int, gamma: float):
 
 
 # --------------------------------------------------------------------------------------
+# Running observation statistics (Table B.1: "Normalized Observations: True"; the paper
+# does not describe the mechanism)
+# --------------------------------------------------------------------------------------
+class ObsNormalizer:
+    """Per-dimension mean and population variance of every observation s_t handed to
+    ``update`` so far, and the standardisation x -> (x - mean) / sqrt(var + eps).
+
+    The statistics are those of the concatenation of all batches seen; they are carried
+    as (count, mean, M2 = sum of squared deviations) and a new batch is merged with the
+    pairwise formulas of Chan, Golub and LeVeque (1979).  Before the first batch the mean
+    is 0 and the variance 1.
+    """
+
+    def __init__(self, dim: int, eps: float = 1e-5):
+        self.count = 0
+        self.mean = np.zeros(dim, dtype=np.float64)
+        self.m2 = np.zeros(dim, dtype=np.float64)
+        self.eps = float(eps)
+
+    def update(self, obs):
+        x = np.asarray(obs, dtype=np.float64)
+        nb = x.shape[0]
+        if nb == 0:
+            return
+        mean_b = x.mean(axis=0)
+        m2_b = ((x - mean_b) ** 2).sum(axis=0)
+        tot = self.count + nb
+        delta = mean_b - self.mean
+        self.mean = self.mean + delta * (nb / tot)
+        self.m2 = self.m2 + m2_b + delta * delta * (self.count * nb / tot)
+        self.count = tot
+
+    @property
+    def var(self):
+        if self.count == 0:
+            return np.ones_like(self.mean)
+        return self.m2 / self.count
+
+    def normalize(self, x):
+        return (np.asarray(x, dtype=np.float64) - self.mean) / np.sqrt(self.var + self.eps)
+
+
+def normalize_batch(batch, normalizer: ObsNormalizer):
+    """A sampled batch with s and s' standardised by the statistics current at sampling
+    time (the replay memory keeps raw observations)."""
+    out = dict(batch)
+    out["obs"] = normalizer.normalize(batch["obs"])
+    out["next_obs"] = normalizer.normalize(batch["next_obs"])
+    return out
+
+
+# --------------------------------------------------------------------------------------
 # Networks
 # --------------------------------------------------------------------------------------
 def unpack(params, dims):
@@ -314,6 +366,18 @@ def adam_step(theta, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8):
     return theta - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
 
 
+def clip_grad_norm(g, max_norm):
+    """Gradient clipping by global L2 norm (Table B.1: "Gradient Clipping 0.5"; the kind of
+    clipping is not stated): the whole gradient of one optimiser step is rescaled so that
+    its Euclidean norm does not exceed ``max_norm``; gradients inside the ball are left
+    as they are.  Returns (clipped gradient, norm before clipping)."""
+    g = np.asarray(g, dtype=np.float64)
+    norm = float(np.sqrt(np.sum(g * g)))
+    if max_norm is None or norm <= max_norm:
+        return g, norm
+    return g * (max_norm / norm), norm
+
+
 def soft_update(src, dst, tau):
     """Polyak tracking of the target network: dst <- tau * src + (1 - tau) * dst.
     tau = 1 is the hard copy used to refresh the V-learner's lagged policy
@@ -360,8 +424,10 @@ class Learner:
     the paper's loops do.  Parameters enter as fp32 arrays and are promoted."""
 
     def __init__(self, actor_dims, critic_dims, actor_params, critic_params, lr, gamma, tau,
-                 beta1=0.9, beta2=0.999, eps=1e-8):
+                 beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=None):
         self.actor_dims, self.critic_dims = actor_dims, critic_dims
+        self.max_grad_norm = max_grad_norm            # None: no clipping
+        self.critic_grad_norm = self.actor_grad_norm = 0.0
         self.actor = np.asarray(actor_params, np.float64).copy()
         self.actor_lag = self.actor.copy()            # pi^v, the V-learner's lagged policy
         self.critic = np.asarray(critic_params, np.float64).copy()
@@ -374,6 +440,7 @@ class Learner:
     def critic_update(self, batch):
         y = td_target(batch, self.actor_lag, self.critic_target, self.actor_dims, self.critic_dims)
         losses, g = critic_loss_and_grads(self.critic, self.critic_dims, batch, y)
+        g, self.critic_grad_norm = clip_grad_norm(g, self.max_grad_norm)   # both critics: one step, one norm
         self.c_t += 1
         self.critic, self.c_m, self.c_v = adam_step(self.critic, g, self.c_m, self.c_v, self.c_t,
                                                     self.lr, self.beta1, self.beta2, self.eps)
@@ -384,6 +451,7 @@ class Learner:
 
     def actor_update(self, obs):
         J, g = actor_loss_and_grads(self.actor, self.critic, self.actor_dims, self.critic_dims, obs)
+        g, self.actor_grad_norm = clip_grad_norm(g, self.max_grad_norm)
         self.a_t += 1
         self.actor, self.a_m, self.a_v = adam_step(self.actor, g, self.a_m, self.a_v, self.a_t,
                                                    self.lr, self.beta1, self.beta2, self.eps)
