@@ -90,8 +90,12 @@ typedef struct { float *obs, *act, *rew, *next_obs, *done; } pql_replay_storage;
  * boot[B] (gamma^n times the product of (1 - d) over the window). */
 typedef struct { int64_t *idx; float *obs, *act, *ret, *next_obs, *boot; } pql_batch;
 
-/* Adam hyper-parameters (Table B.1 names the optimiser and the learning rate). */
-typedef struct { float lr, beta1, beta2, eps; } pql_adam;
+/* Optimiser step: Adam hyper-parameters (Table B.1 names the optimiser and the learning rate)
+ * and the gradient clipping bound (Table B.1 "Gradient Clipping 0.5"; the kind is not stated there:
+ * here the whole gradient of one step is scaled by max_grad_norm / ||g||_2 when its Euclidean norm
+ * exceeds max_grad_norm, both critics of the V-learner step counting as one gradient).
+ * max_grad_norm = 0 switches clipping off. */
+typedef struct { float lr, beta1, beta2, eps, max_grad_norm; } pql_adam;
 
 /* ---- context and host-side queries (no device work) ------------------------------------ */
 
@@ -155,7 +159,9 @@ int32_t pql_actor_act(pql_ctx* ctx, const float* actor_params, const float* obs,
 /* y = ret + boot * min_i Q'_i(next_obs, pi^v(next_obs));  L_i = mean_b (Q_i(obs, act) - y)^2;
  * gradient of L_1 + L_2 w.r.t. critic_params (y is a constant) is written to grads_out, then
  * one Adam step (bias-corrected, eps outside the root) updates critic_params, adam_m, adam_v
- * in place.  loss_out[2] ([device]) receives L_1, L_2 evaluated before the step.
+ * in place.  loss_out[3] ([device]) receives L_1, L_2 evaluated before the step and, when
+ * opt.max_grad_norm > 0, the gradient norm before clipping (0 otherwise); with clipping on,
+ * grads_out holds the clipped gradient, the one the step used.
  * critic_params / critic_target_params / adam_m / adam_v / grads_out: twin-critic vectors
  * (2 * pql_critic_param_count floats); actor_target_params: the lagged policy pi^v.
  * Advances the critic Adam step counter. */
@@ -169,7 +175,9 @@ int32_t pql_critic_update(pql_ctx* ctx, float* critic_params, const float* criti
 /* J = -mean_b min(Q_1, Q_2)(obs_b, pi(obs_b)); the gradient w.r.t. actor_params flows through
  * the action input of whichever critic is smaller per row (ties: Q_1); critics are read-only.
  * Writes grads_out (actor layout), performs one Adam step on actor_params/adam_m/adam_v,
- * stores J (before the step) in loss_out[1] ([device]).  Advances the actor Adam counter. */
+ * stores J (before the step) in loss_out[0] and the gradient norm before clipping in loss_out[1]
+ * (0 when opt.max_grad_norm == 0); loss_out is float[2] [device].  With clipping on, grads_out holds
+ * the clipped gradient.  Advances the actor Adam counter. */
 int32_t pql_actor_update(pql_ctx* ctx, float* actor_params, const float* critic_params, float* adam_m,
                          float* adam_v, float* grads_out, const float* obs, int32_t batch_size, pql_adam opt,
                          float* loss_out, void* workspace, void* stream);
@@ -180,9 +188,32 @@ int32_t pql_actor_update(pql_ctx* ctx, float* actor_params, const float* critic_
  * square root) on a flat vector with a caller-given gradient; the same kernel performs the fused
  * step inside pql_critic_update / pql_actor_update.  params/grads/adam_m/adam_v: [device],
  * `count` floats each (count < 2^31); `t` >= 1 is the step number used for the bias correction.
- * Context counters are not touched. */
+ * opt.max_grad_norm must be 0 (this call has no scratch for the norm).  Context counters are not
+ * touched. */
 int32_t pql_adam_step(pql_ctx* ctx, float* params, const float* grads, float* adam_m, float* adam_v,
                       int64_t count, pql_adam opt, int64_t t, void* stream);
+
+/* ---- observation standardisation (Table B.1 "Normalized Observations: True"; the mechanism is
+ *      not described there) ---------------------------------------------------------------- */
+
+/* Running per-dimension statistics of every observation s_t pushed so far: count, mean and
+ * sum of squared deviations in double precision (merged batch by batch with the pairwise update
+ * of Chan, Golub and LeVeque), population variance = m2 / count.  Before the first push the mean
+ * is 0 and the variance 1.  The statistics live in a caller-owned [device] block of
+ * pql_obs_norm_bytes(cfg) bytes, 256-byte aligned, laid out as
+ *     double count, reserved, mean[o], m2[o];  float mean32[o], rstd32[o];  scratch,
+ * rstd32 = 1 / sqrt(var + eps).  While a block is attached:
+ *   - pql_replay_push merges its obs[N][o] argument into the statistics (after the copy; the ring
+ *     keeps raw observations);
+ *   - pql_sample_nstep / pql_gather_nstep write out.obs and out.next_obs standardised,
+ *     (x - mean32) * rstd32, with the statistics current on the stream at that point;
+ *   - pql_actor_act standardises its obs argument the same way before the policy.
+ * pql_obs_norm_attach(ctx, NULL, 0) detaches.  Attach does no device work; pql_obs_norm_reset
+ * enqueues the initialisation of the attached block (count 0) and must precede its first use.
+ * Errors: PQL_ERR_ALIGNMENT, PQL_ERR_INVALID_ARG (eps < 0), PQL_ERR_NULL (reset with no block). */
+int64_t pql_obs_norm_bytes(const pql_config* cfg);
+int32_t pql_obs_norm_attach(pql_ctx* ctx, void* stats, float eps);
+int32_t pql_obs_norm_reset(pql_ctx* ctx, void* stream);
 
 /* ---- target tracking (Table B.1 target update rate; Section 3.2 hard policy sync) -------- */
 

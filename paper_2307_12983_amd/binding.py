@@ -22,7 +22,8 @@ ERRORS = {0: "PQL_OK", -1: "PQL_ERR_INVALID_ARG", -2: "PQL_ERR_NULL", -3: "PQL_E
 EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_count", "pql_critic_param_count",
            "pql_workspace_bytes", "pql_last_error", "pql_get_state", "pql_set_state", "pql_replay_push",
            "pql_sample_nstep", "pql_gather_nstep", "pql_actor_act", "pql_critic_update", "pql_actor_update",
-           "pql_soft_update", "pql_adam_step", "pql_profile_begin", "pql_profile_end"]
+           "pql_soft_update", "pql_adam_step", "pql_profile_begin", "pql_profile_end",
+           "pql_obs_norm_bytes", "pql_obs_norm_attach", "pql_obs_norm_reset"]
 
 
 class PqlConfig(C.Structure):
@@ -40,7 +41,8 @@ class PqlBatch(C.Structure):
 
 
 class PqlAdam(C.Structure):
-    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("max_grad_norm", C.c_float)]
 
 
 class PqlKernelStat(C.Structure):
@@ -91,6 +93,9 @@ def load_library() -> C.CDLL:
         "pql_adam_step": (I32, [P, P, P, P, P, I64, PqlAdam, I64, P]),
         "pql_profile_begin": (I32, [P, I32]),
         "pql_profile_end": (I32, [P, C.POINTER(PqlKernelStat), I32, C.POINTER(I32)]),
+        "pql_obs_norm_bytes": (I64, [cfgp]),
+        "pql_obs_norm_attach": (I32, [P, P, F]),
+        "pql_obs_norm_reset": (I32, [P, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -194,6 +199,9 @@ class Context:
     def workspace_bytes(self) -> int:
         return self.lib.pql_workspace_bytes(C.byref(self.cfg))
 
+    def obs_norm_bytes(self) -> int:
+        return self.lib.pql_obs_norm_bytes(C.byref(self.cfg))
+
     def last_error(self) -> str:
         return (self.lib.pql_last_error(self.h) or b"").decode()
 
@@ -250,3 +258,9 @@ class Context:
 
     def pql_soft_update(self, src, dst, count, tau, stream=None):
         self._check(self.lib.pql_soft_update(self.h, _ptr(src), _ptr(dst), count, tau, _stream(stream)))
+
+    def pql_obs_norm_attach(self, stats, eps):
+        self._check(self.lib.pql_obs_norm_attach(self.h, _ptr(stats), eps))
+
+    def pql_obs_norm_reset(self, stream=None):
+        self._check(self.lib.pql_obs_norm_reset(self.h, _stream(stream)))

@@ -45,6 +45,10 @@ const char* kernel_name(int kid) {
         case KID_FUSED_POLICY: return "fused_policy_kernel";
         case KID_FUSED_ACT: return "fused_act_kernel";
         case KID_TRANSPOSE: return "transpose_kernel";
+        case KID_ADAM_CLIP: return "adam_clip_kernel";
+        case KID_OBS_STATS: return "obs_stats_chunk_kernel";
+        case KID_OBS_MERGE: return "obs_stats_merge_kernel";
+        case KID_NORMALIZE: return "normalize_rows_kernel";
         default: return "?";
     }
 }
@@ -73,6 +77,8 @@ struct pql_ctx {
     // parameter offsets (floats) inside one actor / one critic vector: W then b per layer
     int64_t a_w[PQL_MAX_HIDDEN + 1], a_b[PQL_MAX_HIDDEN + 1], a_total;
     int64_t c_w[PQL_MAX_HIDDEN + 1], c_b[PQL_MAX_HIDDEN + 1], c_total;
+    void* obs_norm;              // caller-owned device block of running observation statistics, or NULL
+    float obs_eps;
     std::string err;
 };
 
@@ -151,6 +157,8 @@ struct Layout {
     size_t w1aT[2];                                                   // transposed action rows of the critics' first layer
     size_t waT[PQL_MAX_HIDDEN + 1];                                   // transposed policy weights, layer l = 1..L
     size_t splitk;
+    size_t sqp;                                                       // per-workgroup sums of squared gradients
+    size_t xn;                                                        // standardised Actor observations
     size_t total;
 };
 
@@ -265,6 +273,11 @@ void make_layout(const pql_config* c, Layout& w) {
     }
     for (int l = 1; l <= L; ++l) w.waT[l] = take((size_t)c->hidden[l - 1] * (l < L ? c->hidden[l] : c->act_dim));
     w.splitk = take(splitk_floats(c, (int)B));
+    {
+        const size_t pa = (size_t)pql_actor_param_count(c), pc = 2 * (size_t)pql_critic_param_count(c);
+        w.sqp = take(adam_reduce_blocks_bound(pa > pc ? pa : pc, RED_MAX_TENSORS));
+    }
+    w.xn = fused_ok(c) ? off : take(B * (size_t)c->obs_dim);
     w.total = off;
 }
 
@@ -354,7 +367,8 @@ void red(AdamArgs& ad, int64_t offset, const float* partial, int count, int npar
 }
 
 bool adam_ok(const pql_adam& o) {
-    return o.lr >= 0.f && o.beta1 >= 0.f && o.beta1 < 1.f && o.beta2 >= 0.f && o.beta2 < 1.f && o.eps >= 0.f;
+    return o.lr >= 0.f && o.beta1 >= 0.f && o.beta1 < 1.f && o.beta2 >= 0.f && o.beta2 < 1.f && o.eps >= 0.f &&
+           o.max_grad_norm >= 0.f && o.max_grad_norm <= 3.0e38f;
 }
 
 void fill_adam(AdamArgs& ad, const pql_adam& o, int64_t t) {
@@ -388,6 +402,8 @@ int32_t pql_create(const pql_config* cfg, pql_ctx** out) {
     c->L = cfg->n_hidden;
     c->T = cfg->capacity / cfg->num_envs;
     c->head = c->count = c->pushes = c->samples = c->acts = c->critic_t = c->actor_t = 0;
+    c->obs_norm = nullptr;
+    c->obs_eps = 0.f;
     c->a_total = net_params(cfg->obs_dim, cfg, cfg->act_dim, c->a_w, c->a_b);
     c->c_total = net_params(cfg->obs_dim + cfg->act_dim, cfg, 1, c->c_w, c->c_b);
     *out = c;
@@ -458,8 +474,12 @@ int32_t pql_replay_push(pql_ctx* c, pql_replay_storage st, const float* obs, con
     p.src[2] = rew;      p.dst[2] = st.rew + base;           p.count[2] = N;
     p.src[3] = next_obs; p.dst[3] = st.next_obs + base * o;  p.count[3] = N * o;
     p.src[4] = done;     p.dst[4] = st.done + base;          p.count[4] = N;
-    const hipError_t e = push_launch(p, (hipStream_t)stream);
+    hipError_t e = push_launch(p, (hipStream_t)stream);
     if (e != hipSuccess) return E.hip(e, "pql_replay_push");
+    if (c->obs_norm) {
+        e = obs_stats_update_launch(obs_stats_view(c->obs_norm, (int)o), obs, (int)N, (int)o, c->obs_eps, (hipStream_t)stream);
+        if (e != hipSuccess) return E.hip(e, "pql_replay_push");
+    }
     c->head = (c->head + 1) % c->T;
     c->count = c->count + 1 < c->T ? c->count + 1 : c->T;
     c->pushes += 1;
@@ -481,6 +501,11 @@ static int32_t sample_common(pql_ctx* c, pql_replay_storage st, const int64_t* i
     a.nstep = c->cfg.nstep; a.head = (int)c->head; a.count = (int)c->count; a.gamma = c->cfg.gamma;
     a.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); a.key1 = (uint32_t)(c->cfg.seed >> 32);
     a.ctr2 = (uint32_t)((uint64_t)c->samples & 0xffffffffu); a.ctr3 = (uint32_t)((uint64_t)c->samples >> 32);
+    a.nmean = a.nrstd = nullptr;
+    if (c->obs_norm) {
+        const ObsStatsView ov = obs_stats_view(c->obs_norm, c->cfg.obs_dim);
+        a.nmean = ov.mean_f; a.nrstd = ov.rstd_f;
+    }
     const hipError_t e = sample_launch(a, (hipStream_t)stream);
     if (e != hipSuccess) return E.hip(e, who);
     return PQL_OK;
@@ -554,6 +579,10 @@ int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, i
         for (int l = 0; l < c->L; ++l) fa.H[l] = c->cfg.hidden[l];
         for (int l = 0; l <= c->L; ++l) { fa.pi.w[l] = actor_params + c->a_w[l]; fa.pi.b[l] = actor_params + c->a_b[l]; }
         fa.obs = obs; fa.act_out = act_out;
+        if (c->obs_norm) {
+            const ObsStatsView ov = obs_stats_view(c->obs_norm, c->cfg.obs_dim);
+            fa.nmean = ov.mean_f; fa.nrstd = ov.rstd_f;
+        }
         fa.noise.act_dim = c->cfg.act_dim; fa.noise.sigma_rows = num; fa.noise.sigma_min = sigma_min; fa.noise.sigma_max = sigma_max;
         fa.noise.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); fa.noise.key1 = (uint32_t)(c->cfg.seed >> 32);
         fa.noise.ctr2 = (uint32_t)((uint64_t)c->acts & 0xffffffffu); fa.noise.ctr3 = (uint32_t)((uint64_t)c->acts >> 32);
@@ -562,7 +591,14 @@ int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, i
         c->acts += 1;
         return PQL_OK;
     }
-    hipError_t e = actor_hidden_forward(c, actor_params, obs, num, ws, w, st);
+    hipError_t e;
+    if (c->obs_norm) {
+        const ObsStatsView ov = obs_stats_view(c->obs_norm, c->cfg.obs_dim);
+        e = normalize_rows_launch(obs, ov.mean_f, ov.rstd_f, ws + w.xn, num, c->cfg.obs_dim, st);
+        if (e != hipSuccess) return E.hip(e, "pql_actor_act");
+        obs = ws + w.xn;
+    }
+    e = actor_hidden_forward(c, actor_params, obs, num, ws, w, st);
     if (e != hipSuccess) return E.hip(e, "pql_actor_act");
     const int L = c->L, HL = c->cfg.hidden[L - 1], ad = c->cfg.act_dim;
     std::vector<GemmProb> ps;
@@ -736,6 +772,7 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
     adm.nloss = 2; adm.loss_parts = head_parts; adm.loss_scale = 1.f / (float)B;
     adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
     adm.theta = critic_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
+    adm.max_norm = opt.max_grad_norm; adm.sq_partial = ws + w.sqp; adm.norm_out = loss_out + 2;
     fill_adam(adm, opt, c->critic_t + 1);
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
     c->critic_t += 1;
@@ -886,6 +923,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     adm.nloss = 1; adm.loss_parts = loss_parts; adm.loss_scale = -1.f / (float)B;
     adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
     adm.theta = actor_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
+    adm.max_norm = opt.max_grad_norm; adm.sq_partial = ws + w.sqp; adm.norm_out = loss_out + 1;
     fill_adam(adm, opt, c->actor_t + 1);
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
     c->actor_t += 1;
@@ -947,12 +985,38 @@ int32_t pql_profile_end(pql_ctx* c, pql_kernel_stat* out, int32_t max_out, int32
 }
 
 // ---------------------------------------------------------------------------------------------
+int64_t pql_obs_norm_bytes(const pql_config* cfg) {
+    const int rc = validate_cfg(cfg);
+    return rc != PQL_OK ? rc : (int64_t)obs_stats_bytes(cfg->obs_dim, cfg->num_envs);
+}
+
+int32_t pql_obs_norm_attach(pql_ctx* c, void* stats, float eps) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (stats && (((uintptr_t)stats) & 255)) return E.fail(PQL_ERR_ALIGNMENT, "pql_obs_norm_attach: block not 256-byte aligned");
+    if (stats && !(eps >= 0.f && eps <= 3.0e38f)) return E.fail(PQL_ERR_INVALID_ARG, "pql_obs_norm_attach: bad eps");
+    c->obs_norm = stats;
+    c->obs_eps = stats ? eps : 0.f;
+    return PQL_OK;
+}
+
+int32_t pql_obs_norm_reset(pql_ctx* c, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!c->obs_norm) return E.fail(PQL_ERR_NULL, "pql_obs_norm_reset: no statistics block attached");
+    const hipError_t e = obs_stats_reset_launch(obs_stats_view(c->obs_norm, c->cfg.obs_dim), c->cfg.obs_dim, c->obs_eps,
+                                                (hipStream_t)stream);
+    if (e != hipSuccess) return E.hip(e, "pql_obs_norm_reset");
+    return PQL_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 int32_t pql_adam_step(pql_ctx* c, float* params, const float* grads, float* adam_m, float* adam_v, int64_t count,
                       pql_adam opt, int64_t t, void* stream) {
     if (!c) return PQL_ERR_NULL;
     Err E{c};
     if (!params || !grads || !adam_m || !adam_v) return E.fail(PQL_ERR_NULL, "pql_adam_step: null pointer");
-    if (count < 0 || count > 0x7fffffffLL || t < 1 || !adam_ok(opt))
+    if (count < 0 || count > 0x7fffffffLL || t < 1 || !adam_ok(opt) || opt.max_grad_norm != 0.f)
         return E.fail(PQL_ERR_INVALID_ARG, "pql_adam_step: bad count, step number or Adam constants");
     if (count == 0) return PQL_OK;
     AdamArgs adm;

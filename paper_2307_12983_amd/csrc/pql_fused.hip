@@ -676,6 +676,17 @@ __global__ __launch_bounds__(FT) void fused_act_kernel(const FusedActArgs A) {
     const TileMem m = carve(o, a, A.hmax);
     const int r0 = blockIdx.x * BMF;
     load_rows(T, m.XA, m.SXA, A.obs, o, r0, B);
+    if (A.nmean != nullptr) {
+        // standardise the rows just loaded (each thread revisits exactly the elements it wrote)
+        const int kp = (o + 7) & ~7;
+        for (int i = T.tid; i < BMF * kp; i += FT) {
+            const int row = i / kp, col = i - row * kp;
+            if (col < o && r0 + row < B) {
+                const int at = m.XA + row * m.SXA + col;
+                smem[at] = (smem[at] - A.nmean[col]) * A.nrstd[col];
+            }
+        }
+    }
     __syncthreads();
     const FusedNet* const nets[1] = {&A.pi};
     float* const* const hg[1] = {nullptr};

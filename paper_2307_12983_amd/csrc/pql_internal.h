@@ -16,7 +16,8 @@ namespace pql {
 enum KernelId : int {
     KID_GEMM = 0, KID_PUSH = 15, KID_SAMPLE = 16, KID_HEAD_CRITIC = 17, KID_HEAD_POLICY = 18,
     KID_ADAM = 19, KID_SOFT_UPDATE = 20, KID_COPY = 21, KID_FUSED_CRITIC = 22, KID_FUSED_POLICY = 23,
-    KID_FUSED_ACT = 24, KID_TRANSPOSE = 25, KID_COUNT = 26
+    KID_FUSED_ACT = 24, KID_TRANSPOSE = 25, KID_ADAM_CLIP = 26, KID_OBS_STATS = 27, KID_OBS_MERGE = 28,
+    KID_NORMALIZE = 29, KID_COUNT = 30
 };
 const char* kernel_name(int kid);
 bool prof_active();
@@ -130,10 +131,17 @@ struct AdamArgs {
     float* loss_out;
     float* theta; float* m; float* v; float* g;
     float lr, beta1, beta2, eps, inv_bc1, inv_bc2;
+    // Clipping by global norm (max_norm > 0): the reduction writes the gradient to g and one
+    // sum of squares per workgroup to sq_partial; a second kernel rescales and steps.
+    float max_norm;
+    float* sq_partial;      // at least adam_reduce_blocks(a) floats
+    float* norm_out;        // receives the norm before clipping
     RedTensor t[RED_MAX_TENSORS];
 };
 
 hipError_t adam_reduce_launch(const AdamArgs& a, hipStream_t stream);
+// Upper bound of the reduction's workgroup count for `params` elements in `ntensors` tensors.
+size_t adam_reduce_blocks_bound(size_t params, int ntensors);
 
 // ---- output heads -----------------------------------------------------------------------
 struct HeadArgs {
@@ -170,10 +178,29 @@ struct SampleArgs {
     int head, count;
     float gamma;
     uint32_t key0, key1, ctr2, ctr3;
+    const float* nmean;     // optional standardisation of s and s': (x - nmean[c]) * nrstd[c]
+    const float* nrstd;
 };
 hipError_t sample_launch(const SampleArgs& a, hipStream_t stream);
 
 hipError_t soft_update_launch(const float* src, float* dst, int64_t count, float tau, hipStream_t stream);
+
+// ---- running observation statistics --------------------------------------------------------
+// Device block handed over by the caller (all offsets in bytes from its 256-byte aligned start):
+//   double count, pad, mean[o], m2[o];  float mean_f[o], rstd_f[o];  then per-chunk partials.
+constexpr int OBS_CHUNK_ROWS = 64;
+struct ObsStatsView {
+    double* stat;           // count, pad, mean[o], m2[o]
+    float* mean_f;          // [o]
+    float* rstd_f;          // [o]
+    double* part;           // [nchunk][2][o]: chunk mean, chunk sum of squared deviations
+};
+size_t obs_stats_bytes(int o, int max_rows);
+ObsStatsView obs_stats_view(void* base, int o);
+hipError_t obs_stats_reset_launch(const ObsStatsView& v, int o, float eps, hipStream_t stream);
+hipError_t obs_stats_update_launch(const ObsStatsView& v, const float* obs, int rows, int o, float eps, hipStream_t stream);
+hipError_t normalize_rows_launch(const float* x, const float* mean_f, const float* rstd_f, float* out, int rows, int o,
+                                 hipStream_t stream);
 
 // ---- row-tile fused kernels (layers at most FUSED_MAXW wide) ------------------------------
 constexpr int FUSED_BM = 32;        // batch rows per workgroup
@@ -226,6 +253,8 @@ struct FusedActArgs {
     int H[PQL_MAX_HIDDEN];
     FusedNet pi;
     const float* obs;
+    const float* nmean;             // optional standardisation of obs
+    const float* nrstd;
     float* act_out;
     GemmNoise noise;
 };

@@ -63,6 +63,25 @@ __device__ inline void copy_row(float* __restrict__ dst, const float* __restrict
     }
 }
 
+// Row copy with the standardisation (x - mu[c]) * rs[c] applied on the way (Table B.1
+// "Normalized Observations": the ring keeps raw observations, batches are standardised with the
+// statistics current at sampling time).
+template <int G, bool VEC>
+__device__ inline void copy_row_std(float* __restrict__ dst, const float* __restrict__ src, int n, int gl,
+                                    const float* __restrict__ mu, const float* __restrict__ rs) {
+    if (VEC) {
+        const int n4 = n >> 2;
+        for (int c = gl; c < n4; c += G) {
+            float4 v = reinterpret_cast<const float4*>(src)[c];
+            const float4 m = reinterpret_cast<const float4*>(mu)[c], r = reinterpret_cast<const float4*>(rs)[c];
+            v.x = (v.x - m.x) * r.x; v.y = (v.y - m.y) * r.y; v.z = (v.z - m.z) * r.z; v.w = (v.w - m.w) * r.w;
+            reinterpret_cast<float4*>(dst)[c] = v;
+        }
+    } else {
+        for (int c = gl; c < n; c += G) dst[c] = (src[c] - mu[c]) * rs[c];
+    }
+}
+
 // G lanes cooperate on one sample; the rows of s, a, s' are copied with coalesced accesses.
 template <int G, bool VEC_O, bool VEC_A>
 __global__ __launch_bounds__(256) void sample_kernel(const SampleArgs a) {
@@ -104,9 +123,15 @@ __global__ __launch_bounds__(256) void sample_kernel(const SampleArgs a) {
         a.out.ret[k] = ret;
         a.out.boot[k] = g * alive;
     }
-    copy_row<G, VEC_O>(a.out.obs + (size_t)k * a.o, a.st.obs + (size_t)slot * a.o, a.o, gl);
     copy_row<G, VEC_A>(a.out.act + (size_t)k * a.a, a.st.act + (size_t)slot * a.a, a.a, gl);
-    copy_row<G, VEC_O>(a.out.next_obs + (size_t)k * a.o, a.st.next_obs + (size_t)last * a.o, a.o, gl);
+    if (a.nmean != nullptr) {
+        copy_row_std<G, VEC_O>(a.out.obs + (size_t)k * a.o, a.st.obs + (size_t)slot * a.o, a.o, gl, a.nmean, a.nrstd);
+        copy_row_std<G, VEC_O>(a.out.next_obs + (size_t)k * a.o, a.st.next_obs + (size_t)last * a.o, a.o, gl, a.nmean,
+                               a.nrstd);
+    } else {
+        copy_row<G, VEC_O>(a.out.obs + (size_t)k * a.o, a.st.obs + (size_t)slot * a.o, a.o, gl);
+        copy_row<G, VEC_O>(a.out.next_obs + (size_t)k * a.o, a.st.next_obs + (size_t)last * a.o, a.o, gl);
+    }
 }
 
 template <int G>
@@ -122,7 +147,8 @@ static inline bool al16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 
 hipError_t sample_launch(const SampleArgs& a, hipStream_t stream) {
     if (a.batch <= 0) return hipSuccess;
-    const bool vo = (a.o % 4 == 0) && al16(a.st.obs) && al16(a.st.next_obs) && al16(a.out.obs) && al16(a.out.next_obs);
+    const bool vo = (a.o % 4 == 0) && al16(a.st.obs) && al16(a.st.next_obs) && al16(a.out.obs) && al16(a.out.next_obs) &&
+                    al16(a.nmean) && al16(a.nrstd);
     const bool va = (a.a % 4 == 0) && al16(a.st.act) && al16(a.out.act);
     const int per_row = vo ? a.o / 4 : a.o;
     // per sample: read s, a, s' and n (r, d) pairs; write s, a, s', ret, boot and the index
@@ -341,7 +367,18 @@ __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
         if (q == 0)
             for (int k = 1; k < Q; ++k) g += sm[k * E + e];
     }
-    if (live && q == 0) {
+    const bool clip = a.max_norm > 0.f;
+    if (clip) {
+        // Clipping needs the norm of the whole gradient first: store g and this workgroup's sum
+        // of squares; adam_clip_kernel finishes the step.
+        const bool own = live && q == 0;
+        if (own) a.g[T.offset + i] = g;
+        const float sq = wave_sum(own ? g * g : 0.f);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = sq;
+        __syncthreads();
+        if (threadIdx.x == 0) a.sq_partial[b] = (sm[0] + sm[1]) + (sm[2] + sm[3]);
+    } else if (live && q == 0) {
         const int64_t k = T.offset + i;
         const float m = a.beta1 * a.m[k] + (1.f - a.beta1) * g;
         const float v = a.beta2 * a.v[k] + (1.f - a.beta2) * g * g;
@@ -360,6 +397,45 @@ __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
             s = wave_sum(s);
             if (lane == 0) a.loss_out[wave] = s * a.loss_scale;
         }
+        if (!clip && threadIdx.x == 0 && a.norm_out != nullptr) *a.norm_out = 0.f;   // norm not computed
+    }
+}
+
+// Second half of a clipped step (Table B.1 "Gradient Clipping"): every workgroup adds the
+// per-workgroup sums of squares in the same fixed order, rescales its share of the stored
+// gradient when the norm exceeds the bound, and applies Adam.
+struct AdamClipArgs {
+    float* theta; float* m; float* v; float* g;
+    const float* sq_partial; float* norm_out;
+    int64_t n; int nparts;
+    float lr, beta1, beta2, eps, inv_bc1, inv_bc2, max_norm;
+};
+
+__global__ __launch_bounds__(256) void adam_clip_kernel(const AdamClipArgs a) {
+    __shared__ double smd[256];
+    double s = 0.0;
+    for (int j = threadIdx.x; j < a.nparts; j += 256) s += (double)a.sq_partial[j];
+    smd[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) smd[threadIdx.x] += smd[threadIdx.x + w];
+        __syncthreads();
+    }
+    const float norm = (float)sqrt(smd[0]);
+    const float scale = norm > a.max_norm ? a.max_norm / norm : 1.f;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.norm_out = norm;
+    const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t k = base + 256 * j;
+        if (k >= a.n) break;
+        const float g = a.g[k] * scale;
+        const float m = a.beta1 * a.m[k] + (1.f - a.beta1) * g;
+        const float v = a.beta2 * a.v[k] + (1.f - a.beta2) * g * g;
+        a.theta[k] = a.theta[k] - a.lr * (m * a.inv_bc1) / (sqrtf(v * a.inv_bc2) + a.eps);
+        a.m[k] = m;
+        a.v[k] = v;
+        a.g[k] = g;
     }
 }
 
@@ -386,8 +462,24 @@ hipError_t adam_reduce_launch(const AdamArgs& args, hipStream_t stream) {
     const ProfSlot ps = prof_slot();
     PQL_LAUNCH(ps, adam_reduce_kernel, grid, block, 0, stream, a);
     prof_commit(ps, KID_ADAM, 0.0, ps.on ? adam_bytes(a) : 0.0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !(a.max_norm > 0.f)) return e;
+    AdamClipArgs c;
+    c.theta = a.theta; c.m = a.m; c.v = a.v; c.g = a.g; c.sq_partial = a.sq_partial; c.norm_out = a.norm_out;
+    c.n = 0;
+    for (int i = 0; i < a.ntensors; ++i)
+        if (a.t[i].offset + a.t[i].count > c.n) c.n = a.t[i].offset + a.t[i].count;
+    c.nparts = blocks;
+    c.lr = a.lr; c.beta1 = a.beta1; c.beta2 = a.beta2; c.eps = a.eps; c.inv_bc1 = a.inv_bc1; c.inv_bc2 = a.inv_bc2;
+    c.max_norm = a.max_norm;
+    const ProfSlot pc = prof_slot();
+    PQL_LAUNCH(pc, adam_clip_kernel, dim3((unsigned)((c.n + 1023) / 1024)), block, 0, stream, c);
+    prof_commit(pc, KID_ADAM_CLIP, 0.0, 32.0 * (double)c.n);   // theta, m, v, g read and written
     return hipGetLastError();
 }
+
+// The reduction handles at least 16 elements per workgroup and rounds every tensor up.
+size_t adam_reduce_blocks_bound(size_t params, int ntensors) { return params / 16 + (size_t)ntensors + 1; }
 
 // =============================================================================================
 // Polyak target update (Table B.1 target update rate tau; tau = 1 is the hard policy sync of
@@ -428,6 +520,137 @@ hipError_t soft_update_launch(const float* src, float* dst, int64_t count, float
     if (tau == 1.f) PQL_LAUNCH(ps, copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count, vec);
     else PQL_LAUNCH(ps, soft_update_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, count, tau, vec);
     prof_commit(ps, tau == 1.f ? KID_COPY : KID_SOFT_UPDATE, 0.0, (tau == 1.f ? 8.0 : 12.0) * (double)count);
+    return hipGetLastError();
+}
+
+// =============================================================================================
+// Running observation statistics (Table B.1 "Normalized Observations").  Per dimension the
+// count, mean and sum of squared deviations of every observation pushed so far are kept in
+// double; a new Actor step of N observations is merged in two launches: per chunk of rows the
+// chunk mean and its sum of squared deviations (two passes over the chunk), then one workgroup
+// merges the chunks into the running values in a fixed order with the pairwise update of Chan,
+// Golub and LeVeque, and refreshes the fp32 mean and 1 / sqrt(var + eps) that consumers read.
+// =============================================================================================
+size_t obs_stats_bytes(int o, int max_rows) {
+    const size_t nchunk = ((size_t)max_rows + OBS_CHUNK_ROWS - 1) / OBS_CHUNK_ROWS;
+    size_t head = sizeof(double) * (2 * (size_t)o + 2) + sizeof(float) * 2 * (size_t)o;
+    head = (head + 255) / 256 * 256;
+    return head + sizeof(double) * nchunk * 2 * (size_t)o;
+}
+
+ObsStatsView obs_stats_view(void* base, int o) {
+    ObsStatsView v;
+    v.stat = (double*)base;
+    v.mean_f = (float*)(v.stat + 2 * (size_t)o + 2);
+    v.rstd_f = v.mean_f + o;
+    size_t head = sizeof(double) * (2 * (size_t)o + 2) + sizeof(float) * 2 * (size_t)o;
+    head = (head + 255) / 256 * 256;
+    v.part = (double*)((char*)base + head);
+    return v;
+}
+
+__global__ __launch_bounds__(256) void obs_stats_reset_kernel(ObsStatsView v, int o, float eps) {
+    for (int c = threadIdx.x; c < o; c += 256) {
+        v.stat[2 + c] = 0.0;
+        v.stat[2 + o + c] = 0.0;
+        v.mean_f[c] = 0.f;
+        v.rstd_f[c] = (float)(1.0 / sqrt(1.0 + (double)eps));   // no data yet: mean 0, variance 1
+    }
+    if (threadIdx.x == 0) { v.stat[0] = 0.0; v.stat[1] = 0.0; }
+}
+
+__global__ __launch_bounds__(256) void obs_stats_chunk_kernel(ObsStatsView v, const float* __restrict__ x, int rows, int o) {
+    __shared__ double sm[4][64];
+    const int lane = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int r0 = blockIdx.x * OBS_CHUNK_ROWS;
+    const int nr = rows - r0 < OBS_CHUNK_ROWS ? rows - r0 : OBS_CHUNK_ROWS;
+    double* __restrict__ out = v.part + (size_t)blockIdx.x * 2 * o;
+    for (int c0 = 0; c0 < o; c0 += 64) {
+        const int c = c0 + lane;
+        double s = 0.0;
+        if (c < o)
+            for (int r = rg; r < nr; r += 4) s += (double)x[(size_t)(r0 + r) * o + c];
+        sm[rg][lane] = s;
+        __syncthreads();
+        const double mean = ((sm[0][lane] + sm[1][lane]) + (sm[2][lane] + sm[3][lane])) / (double)nr;
+        __syncthreads();
+        double q = 0.0;
+        if (c < o)
+            for (int r = rg; r < nr; r += 4) {
+                const double d = (double)x[(size_t)(r0 + r) * o + c] - mean;
+                q += d * d;
+            }
+        sm[rg][lane] = q;
+        __syncthreads();
+        if (rg == 0 && c < o) {
+            out[c] = mean;
+            out[o + c] = (sm[0][lane] + sm[1][lane]) + (sm[2][lane] + sm[3][lane]);
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void obs_stats_merge_kernel(ObsStatsView v, int rows, int o, float eps) {
+    const double n0 = v.stat[0];
+    const int nchunk = (rows + OBS_CHUNK_ROWS - 1) / OBS_CHUNK_ROWS;
+    for (int c = threadIdx.x; c < o; c += 256) {
+        double n = n0, mean = v.stat[2 + c], m2 = v.stat[2 + o + c];
+        for (int k = 0; k < nchunk; ++k) {
+            const int left = rows - k * OBS_CHUNK_ROWS;
+            const double nb = (double)(left < OBS_CHUNK_ROWS ? left : OBS_CHUNK_ROWS);
+            const double mb = v.part[(size_t)k * 2 * o + c], qb = v.part[(size_t)k * 2 * o + o + c];
+            const double tot = n + nb, delta = mb - mean;
+            mean += delta * (nb / tot);
+            m2 += qb + delta * delta * (n * nb / tot);
+            n = tot;
+        }
+        v.stat[2 + c] = mean;
+        v.stat[2 + o + c] = m2;
+        v.mean_f[c] = (float)mean;
+        v.rstd_f[c] = (float)(1.0 / sqrt(m2 / n + (double)eps));
+    }
+    __syncthreads();                                   // every thread has read the old count
+    if (threadIdx.x == 0) v.stat[0] = n0 + (double)rows;
+}
+
+hipError_t obs_stats_reset_launch(const ObsStatsView& v, int o, float eps, hipStream_t stream) {
+    hipLaunchKernelGGL(obs_stats_reset_kernel, dim3(1), dim3(256), 0, stream, v, o, eps);
+    return hipGetLastError();
+}
+
+hipError_t obs_stats_update_launch(const ObsStatsView& v, const float* obs, int rows, int o, float eps, hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    const int nchunk = (rows + OBS_CHUNK_ROWS - 1) / OBS_CHUNK_ROWS;
+    const ProfSlot p1 = prof_slot();
+    PQL_LAUNCH(p1, obs_stats_chunk_kernel, dim3(nchunk), dim3(256), 0, stream, v, obs, rows, o);
+    prof_commit(p1, KID_OBS_STATS, 0.0, 4.0 * (double)rows * o);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const ProfSlot p2 = prof_slot();
+    PQL_LAUNCH(p2, obs_stats_merge_kernel, dim3(1), dim3(256), 0, stream, v, rows, o, eps);
+    prof_commit(p2, KID_OBS_MERGE, 0.0, 16.0 * (double)nchunk * o);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void normalize_rows_kernel(const float* __restrict__ x, const float* __restrict__ mu,
+                                                             const float* __restrict__ rs, float* __restrict__ out,
+                                                             int64_t n, int o) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const int c = (int)(i % o);
+        out[i] = (x[i] - mu[c]) * rs[c];
+    }
+}
+
+hipError_t normalize_rows_launch(const float* x, const float* mean_f, const float* rstd_f, float* out, int rows, int o,
+                                 hipStream_t stream) {
+    const int64_t n = (int64_t)rows * o;
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, normalize_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, x, mean_f, rstd_f, out, n, o);
+    prof_commit(ps, KID_NORMALIZE, 0.0, 8.0 * (double)n);
     return hipGetLastError();
 }
 

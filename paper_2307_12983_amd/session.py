@@ -35,12 +35,26 @@ class LearnerSession:
         z = lambda n: torch.zeros(n, dtype=torch.float32, device=device)
         self.c_m, self.c_v, self.c_g = z(critic.size), z(critic.size), z(critic.size)
         self.a_m, self.a_v, self.a_g = z(actor.size), z(actor.size), z(actor.size)
-        self.critic_loss = z(2)
-        self.actor_loss = z(1)
+        self.critic_out, self.actor_out = z(3), z(2)      # losses, then the gradient norm before clipping
+        self.critic_loss, self.critic_grad_norm = self.critic_out[:2], self.critic_out[2:]
+        self.actor_loss, self.actor_grad_norm = self.actor_out[:1], self.actor_out[1:]
         self.workspace = torch.zeros(self.ctx.workspace_bytes() // 4 + 64, dtype=torch.float32, device=device)
         assert self.workspace.data_ptr() % 256 == 0
         self.act_out = torch.zeros((self.max_batch, w.act_dim), dtype=torch.float32, device=device)
-        self.opt = B.PqlAdam(w.lr, w.beta1, w.beta2, w.eps)
+        self.opt = B.PqlAdam(w.lr, w.beta1, w.beta2, w.eps, w.max_grad_norm)
+        self.obs_stats = None
+        if w.obs_norm:
+            self.obs_stats = torch.zeros(self.ctx.obs_norm_bytes() // 8 + 32, dtype=torch.float64, device=device)
+            assert self.obs_stats.data_ptr() % 256 == 0
+            self.ctx.pql_obs_norm_attach(self.obs_stats, w.obs_norm_eps)
+            self.ctx.pql_obs_norm_reset()
+
+    def obs_statistics(self):
+        """(count, mean[o], m2[o]) in float64 and (mean32[o], rstd32[o]) as stored on the device."""
+        o = self.w.obs_dim
+        d = self.obs_stats.cpu().numpy()
+        f = d[2 + 2 * o: 2 + 3 * o].view(np.float32)
+        return d[0], d[2:2 + o].copy(), d[2 + o:2 + 2 * o].copy(), f[:o].copy(), f[o:2 * o].copy()
 
     # ---- steps, one C call each ----------------------------------------------------------
     def to_device(self, row):

@@ -52,6 +52,11 @@ class Workload:
     critic_updates: int = 100
     actor_updates: int = 0
     index: int = 0
+    max_grad_norm: float = 0.0     # Table B.1 gradient clipping (0.5 there); 0 = off
+    obs_norm: bool = False         # Table B.1 normalized observations
+    obs_norm_eps: float = _f32(1e-5)
+    obs_loc: float = 0.0           # synthetic observations are obs_loc + obs_scale * N(0, 1)
+    obs_scale: float = 1.0
 
     @property
     def rows(self) -> int:
@@ -117,15 +122,24 @@ def transition_rows(w: Workload, rng: np.random.Generator, rows: int = 1):
 
     Order of draws per row (fixed, so any consumer regenerates the same data):
     obs ~ N(0,1) [N,o]; act ~ U[-1,1) [N,a]; rew ~ N(0,1) [N]; next_obs ~ N(0,1) [N,o];
-    done ~ Bernoulli(done_p) as 0.0/1.0 [N].  All fp32.
+    done ~ Bernoulli(done_p) as 0.0/1.0 [N].  All fp32.  With a non-default obs_loc / obs_scale,
+    dimension c of both observation fields becomes obs_loc * ((c mod 3) - 1) +
+    obs_scale * (1 + c mod 4) * z (unequal units per dimension, as simulator observations have).
     """
     out = []
     N, o, a = w.num_envs, w.obs_dim, w.act_dim
+    units = w.obs_loc != 0.0 or w.obs_scale != 1.0
+    c = np.arange(o)
+    loc = (w.obs_loc * ((c % 3) - 1)).astype(np.float32)
+    scale = (w.obs_scale * (1 + c % 4)).astype(np.float32)
     for _ in range(rows):
         obs = rng.standard_normal((N, o), dtype=np.float32)
         act = rng.uniform(-1.0, 1.0, size=(N, a)).astype(np.float32)
         rew = rng.standard_normal((N,), dtype=np.float32)
         nxt = rng.standard_normal((N, o), dtype=np.float32)
+        if units:
+            obs = loc + scale * obs
+            nxt = loc + scale * nxt
         done = (rng.random((N,)) < w.done_p).astype(np.float32)
         out.append(dict(obs=obs, act=act, rew=rew, next_obs=nxt, done=done))
     return out

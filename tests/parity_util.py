@@ -79,16 +79,29 @@ def oracle_ring(w: W.Workload):
 
 
 def oracle_learner(w: W.Workload, actor, critic):
-    return O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps)
+    return O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps,
+                     max_grad_norm=(w.max_grad_norm if w.max_grad_norm > 0 else None))
 
 
-def fill_both(sess, ring, w: W.Workload, rows: int, rng=None):
-    """Pushes the same `rows` synthetic Actor steps into the device ring and the oracle ring."""
+def oracle_normalizer(w: W.Workload):
+    return O.ObsNormalizer(w.obs_dim, w.obs_norm_eps) if w.obs_norm else None
+
+
+def fill_both(sess, ring, w: W.Workload, rows: int, rng=None, normalizer=None):
+    """Pushes the same `rows` synthetic Actor steps into the device ring and the oracle ring (and
+    the pushed observations into the oracle's running statistics, when given)."""
     rng = rng or W.data_rng(w)
     for row in W.transition_rows(w, rng, rows):
         sess.push(row)
         ring.push(row["obs"], row["act"], row["rew"], row["next_obs"], row["done"])
+        if normalizer is not None:
+            normalizer.update(row["obs"])
     return rng
+
+
+def oracle_batch(ring, w: W.Workload, batch_size, call, normalizer=None):
+    b = O.gather_nstep(ring, O.sample_indices(ring, w.nstep, batch_size, w.rng_seed, call), w.nstep, w.gamma)
+    return b if normalizer is None else O.normalize_batch(b, normalizer)
 
 
 def batch_to_numpy(batch, B):
@@ -97,9 +110,14 @@ def batch_to_numpy(batch, B):
                 boot=batch.boot[:B].cpu().numpy())
 
 
-def assert_batch_matches(got, ref):
+def assert_batch_matches(got, ref, normalized=False):
+    """Copies are bit-exact; standardised observations (normalized=True) are fp32 arithmetic on
+    one subtraction and one product per element: 1e-6 of the tensor's largest value."""
     assert np.array_equal(got["idx"], ref["idx"]), "sampled indices differ"
     for k in ("obs", "act", "next_obs"):
+        if normalized and k != "act":
+            assert rel_err(got[k], ref[k]) <= 1e-6, "standardised %s: rel err %.2e" % (k, rel_err(got[k], ref[k]))
+            continue
         assert np.array_equal(got[k], ref[k]), "gathered %s differs (must be bit-exact)" % k
     assert rel_err(got["ret"], ref["ret"]) <= 1e-6
     assert rel_err(got["boot"], ref["boot"]) <= 1e-6

@@ -26,7 +26,7 @@ def cfg_of(w, max_batch=None):
 def test_library_exports_every_declared_symbol():
     lib = B.load_library()
     names = header_functions()
-    assert len(names) == 19 and sorted(B.EXPORTS) == names
+    assert len(names) == 22 and sorted(B.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -113,3 +113,36 @@ def test_state_roundtrip_and_validation():
     with pytest.raises(B.PqlError):
         ctx.set_state([0, 0, -1, 0, 0, 0, 0, 0])
     assert ctx.get_state() == [3, 10, 99, 7, 5, 4, 2, 0]
+
+
+def test_obs_norm_host_side():
+    lib = B.load_library()
+    w = W.WORKLOADS["tiny"]
+    ctx = B.Context(cfg_of(w))
+    n = ctx.obs_norm_bytes()
+    # count, reserved, mean, m2 in double; mean32, rstd32 in float; one (mean, m2) pair per 64-row chunk
+    assert n >= 8 * (2 * w.obs_dim + 2) + 8 * w.obs_dim + 16 * w.obs_dim * ((w.num_envs + 63) // 64)
+    bad = cfg_of(w)
+    bad.obs_dim = 0
+    assert lib.pql_obs_norm_bytes(C.byref(bad)) == -1
+    assert lib.pql_obs_norm_attach(ctx.h, C.c_void_p(0x1000 + 8), 1e-5) == -6         # misaligned
+    assert lib.pql_obs_norm_attach(ctx.h, C.c_void_p(0x1000), -1.0) == -1             # negative eps
+    assert lib.pql_obs_norm_reset(ctx.h, None) == -2                                   # nothing attached
+    assert "no statistics block" in ctx.last_error()
+    assert lib.pql_obs_norm_attach(ctx.h, None, 0.0) == 0                              # detach is always fine
+    ctx.close()
+
+
+def test_clipping_bound_is_validated_on_the_host():
+    lib = B.load_library()
+    w = W.WORKLOADS["tiny"]
+    ctx = B.Context(cfg_of(w))
+    p = C.c_void_p(0x1000)
+    bad = B.PqlAdam(1e-3, 0.9, 0.999, 1e-8, -0.5)
+    batch = B.PqlBatch(p, p, p, p, p, p)
+    assert lib.pql_critic_update(ctx.h, p, p, p, p, p, p, batch, 8, bad, p, p, None) == -1
+    assert lib.pql_actor_update(ctx.h, p, p, p, p, p, p, 8, bad, p, p, None) == -1
+    clip = B.PqlAdam(1e-3, 0.9, 0.999, 1e-8, 0.5)
+    assert lib.pql_adam_step(ctx.h, p, p, p, p, 16, clip, 1, None) == -1               # no scratch for the norm here
+    assert ctx.get_state() == [0] * 8
+    ctx.close()

@@ -11,7 +11,8 @@ from oracle import pql_oracle as O
 from paper_2307_12983_amd import workloads as W
 
 from parity_util import (TOL_100_STEPS, TOL_ONE_STEP, assert_batch_matches, assert_first_step_params,
-                         assert_params_close, batch_to_numpy, fill_both, oracle_learner, oracle_ring, rel_err)
+                         assert_params_close, batch_to_numpy, fill_both, oracle_batch, oracle_learner,
+                         oracle_normalizer, oracle_ring, rel_err)
 
 pytestmark = pytest.mark.gpu
 
@@ -186,18 +187,26 @@ def test_actor_act_matches_oracle(torch_cuda, case):
 
 # ---------------------------------------------------------------------------------------------
 def one_step(torch, w, rows, check_all=True):
-    s, ring = make_session(w), oracle_ring(w)
-    fill_both(s, ring, w, rows)
+    """One sample + critic update + Polyak + policy update + sync on both sides.  The workload's
+    switches decide whether batches are standardised and gradients clipped (Table B.1)."""
+    s, ring, nz = make_session(w), oracle_ring(w), oracle_normalizer(w)
+    fill_both(s, ring, w, rows, normalizer=nz)
     L = oracle_learner(w, s.actor_init, s.critic_init)
     Bsz = w.batch
     s.sample(Bsz)
-    batch = O.gather_nstep(ring, O.sample_indices(ring, w.nstep, Bsz, w.rng_seed, 0), w.nstep, w.gamma)
-    assert_batch_matches(batch_to_numpy(s.batch, Bsz), batch)
+    batch = oracle_batch(ring, w, Bsz, 0, nz)
+    assert_batch_matches(batch_to_numpy(s.batch, Bsz), batch, normalized=nz is not None)
     # critic update
     s.critic_update(Bsz)
     losses, g = L.critic_update(batch)
     res = {}
     res["loss"] = rel_err(s.critic_loss.cpu().numpy(), losses)
+    if w.max_grad_norm > 0:
+        res["c_norm"] = abs(float(s.critic_grad_norm.cpu()[0]) - L.critic_grad_norm) / L.critic_grad_norm
+        res["c_clipped"] = L.critic_grad_norm > w.max_grad_norm
+        assert res["c_norm"] <= 1e-5
+    else:
+        assert float(s.critic_grad_norm.cpu()[0]) == 0.0
     res["grad"] = assert_params_close(s.c_g.cpu().numpy(), g, w.critic_dims(), 2, TOL_ONE_STEP, "critic grad")
     res["theta"] = assert_first_step_params(s.critic.cpu().numpy(), L.critic, s.c_g.cpu().numpy(), g, w.critic_dims(), 2,
                                             w.lr, w.eps, TOL_ONE_STEP, "critic params")
@@ -213,6 +222,12 @@ def one_step(torch, w, rows, check_all=True):
     s.actor_update(None, Bsz)
     J, ga = L.actor_update(batch["obs"])
     res["J"] = abs(float(s.actor_loss.cpu().numpy()[0]) - J) / max(abs(J), 1e-30)
+    if w.max_grad_norm > 0:
+        res["a_norm"] = abs(float(s.actor_grad_norm.cpu()[0]) - L.actor_grad_norm) / L.actor_grad_norm
+        res["a_clipped"] = L.actor_grad_norm > w.max_grad_norm
+        assert res["a_norm"] <= 1e-5
+    else:
+        assert float(s.actor_grad_norm.cpu()[0]) == 0.0
     res["a_grad"] = assert_params_close(s.a_g.cpu().numpy(), ga, w.actor_dims(), 1, TOL_ONE_STEP, "actor grad")
     res["a_theta"] = assert_first_step_params(s.actor.cpu().numpy(), L.actor, s.a_g.cpu().numpy(), ga, w.actor_dims(), 1,
                                               w.lr, w.eps, TOL_ONE_STEP, "actor params")
@@ -244,8 +259,8 @@ def test_one_update_full_size(torch_cuda, name):
 
 # ---------------------------------------------------------------------------------------------
 def many_steps(torch, w, rows, steps, actor_every=0):
-    s, ring = make_session(w), oracle_ring(w)
-    fill_both(s, ring, w, rows)
+    s, ring, nz = make_session(w), oracle_ring(w), oracle_normalizer(w)
+    fill_both(s, ring, w, rows, normalizer=nz)
     L = oracle_learner(w, s.actor_init, s.critic_init)
     Bsz = w.batch
     worst_loss = 0.0
@@ -253,7 +268,7 @@ def many_steps(torch, w, rows, steps, actor_every=0):
         s.sample(Bsz)
         s.critic_update(Bsz)
         s.soft_update_targets()
-        batch = O.gather_nstep(ring, O.sample_indices(ring, w.nstep, Bsz, w.rng_seed, it), w.nstep, w.gamma)
+        batch = oracle_batch(ring, w, Bsz, it, nz)
         losses, _ = L.critic_update(batch)
         L.soft_update_targets()
         if actor_every and (it + 1) % actor_every == 0:
@@ -293,6 +308,88 @@ def test_100_updates_reduced_batch(torch_cuda, name):
     w = W.WORKLOADS[name].replace(num_envs=256, capacity=256 * 16, batch=1024)
     res = many_steps(torch_cuda, w, w.rows, 100, actor_every=0)
     say(name, "100 steps", res)
+
+
+# ---------------------------------------------------------------------------------------------
+# Table B.1 defaults left off in the five workloads: observation standardisation and gradient clipping
+def paper_defaults(w, bound=0.5):
+    return w.replace(max_grad_norm=float(np.float32(bound)), obs_norm=True, obs_loc=3.0, obs_scale=2.0)
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged", "fused_l3", "shadow_s"])
+def test_running_observation_statistics(torch_cuda, case):
+    """Count exact; mean and sum of squared deviations are double-precision sums in a different
+    association than the oracle's (chunks of 64 rows): 1e-12 / 1e-10; the fp32 mean and
+    1/sqrt(var + eps) that the kernels read: fp32 rounding of the oracle's values."""
+    w = paper_defaults(SMALL[case])
+    s, ring, nz = make_session(w), oracle_ring(w), oracle_normalizer(w)
+    cnt, mean, m2, mean32, rstd32 = s.obs_statistics()
+    assert cnt == 0 and not mean.any() and not m2.any() and not mean32.any()
+    assert np.allclose(rstd32, 1.0 / np.sqrt(1.0 + w.obs_norm_eps), rtol=1e-7)
+    rng = None
+    for rows in (1, 2, w.rows + 3):                     # statistics keep growing after the ring wraps
+        rng = fill_both(s, ring, w, rows, rng=rng, normalizer=nz)
+        cnt, mean, m2, mean32, rstd32 = s.obs_statistics()
+        assert cnt == nz.count
+        e_mean, e_m2 = rel_err(mean, nz.mean), rel_err(m2, nz.m2)
+        e32 = max(rel_err(mean32, nz.mean), rel_err(rstd32, 1.0 / np.sqrt(nz.var + nz.eps)))
+        say(case, "rows", nz.count // w.num_envs, "mean %.1e m2 %.1e fp32 %.1e" % (e_mean, e_m2, e32))
+        assert e_mean <= 1e-12 and e_m2 <= 1e-10 and e32 <= 1e-7
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged", "ant_s", "fused_l1", "scale_s"])
+def test_standardised_sampling_and_actor_step(torch_cuda, case):
+    torch = torch_cuda
+    w = paper_defaults(SMALL[case])
+    s, ring, nz = make_session(w), oracle_ring(w), oracle_normalizer(w)
+    fill_both(s, ring, w, w.nstep + 3, normalizer=nz)
+    for call in range(2):
+        Bsz = w.batch if call == 0 else 7
+        s.sample(Bsz)
+        assert_batch_matches(batch_to_numpy(s.batch, Bsz), oracle_batch(ring, w, Bsz, call, nz), normalized=True)
+    idx = np.arange(w.num_envs, dtype=np.int64)
+    s.gather(torch.from_numpy(idx).cuda())
+    got = batch_to_numpy(s.batch, idx.size)
+    got["idx"] = idx
+    assert_batch_matches(got, O.normalize_batch(O.gather_nstep(ring, idx, w.nstep, w.gamma), nz), normalized=True)
+    assert np.array_equal(s.storage.obs.cpu().numpy(), ring.obs)          # the ring keeps raw observations
+    row = W.transition_rows(w, np.random.default_rng(3), 1)[0]
+    for call, num in enumerate((w.num_envs, 5)):
+        obs = row["obs"][:num]
+        got = s.act(torch.from_numpy(obs).cuda(), 0.05, 0.8).cpu().numpy()
+        ref = O.actor_act(s.actor_init, w.actor_dims(), nz.normalize(obs), float(np.float32(0.05)),
+                          float(np.float32(0.8)), w.rng_seed, call)
+        e = rel_err(got, ref)
+        say(case, "standardised act, num", num, "rel err %.2e" % e)
+        assert e <= TOL_ONE_STEP
+    # detaching restores the raw path bit for bit
+    s.ctx.pql_obs_norm_attach(None, 0.0)
+    s.sample(w.batch)
+    assert_batch_matches(batch_to_numpy(s.batch, w.batch), oracle_batch(ring, w, w.batch, 2, None))
+
+
+@pytest.mark.parametrize("case,bound", [("tiny", 0.5), ("ragged", 0.5), ("ant_s", 0.5), ("fused_l3", 0.01),
+                                        ("humanoid_s", 0.01), ("tiny", 1e6)])
+def test_one_update_with_clipping_and_standardisation(torch_cuda, case, bound):
+    """bound 0.5: the critic gradient is clipped, the policy gradient is inside the ball;
+    0.01: both are clipped; 1e6: neither (the two-kernel clipped step must then equal the plain one)."""
+    w = paper_defaults(SMALL[case], bound)
+    res = one_step(torch_cuda, w, min(w.rows, w.nstep + 4))
+    say(case, bound, res)
+    assert res["c_clipped"] == (bound < 1.0) and res["a_clipped"] == (bound < 0.02)
+
+
+@pytest.mark.parametrize("case", ["tiny", "ant_s"])
+def test_100_updates_with_clipping_and_standardisation(torch_cuda, case):
+    w = paper_defaults(SMALL[case])
+    res = many_steps(torch_cuda, w, w.rows, 100, actor_every=2)
+    say(case, "100 clipped steps", res)
+
+
+def test_ant_full_batch_paper_defaults(torch_cuda):
+    w = paper_defaults(W.WORKLOADS["ant"])
+    res = one_step(torch_cuda, w, w.nstep + 8)
+    say("ant, clipping + standardisation", res)
 
 
 # ---------------------------------------------------------------------------------------------
