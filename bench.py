@@ -81,10 +81,14 @@ def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0):
     except Exception:
         threads = len(os.sched_getaffinity(0))
     ring = O.ReplayRing(w.rows, w.num_envs, w.obs_dim, w.act_dim)
+    nz = O.ObsNormalizer(w.obs_dim, w.obs_norm_eps) if w.obs_norm else None
     for row in fill_rows:
         ring.push(row["obs"], row["act"], row["rew"], row["next_obs"], row["done"])
+        if nz is not None:
+            nz.update(row["obs"])
     actor, critic = W.init_networks(w)
-    L = O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps)
+    L = O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps,
+                  max_grad_norm=(w.max_grad_norm if w.max_grad_norm > 0 else None))
     done_steps, tick, acts = 0, 0, 0
     t0 = time.perf_counter()
     while True:
@@ -92,10 +96,15 @@ def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0):
         if i % ACTOR_EVERY == 0:
             row = env_rows_host[tick % len(env_rows_host)]
             tick += 1
-            a = O.actor_act(L.actor, w.actor_dims(), row["obs"], w.sigma_min, w.sigma_max, w.rng_seed, acts)
+            seen = row["obs"] if nz is None else nz.normalize(row["obs"])
+            a = O.actor_act(L.actor, w.actor_dims(), seen, w.sigma_min, w.sigma_max, w.rng_seed, acts)
             acts += 1
             ring.push(row["obs"], a.astype(np.float32), row["rew"], row["next_obs"], row["done"])
+            if nz is not None:
+                nz.update(row["obs"])
         batch = O.gather_nstep(ring, O.sample_indices(ring, w.nstep, w.batch, w.rng_seed, i), w.nstep, w.gamma)
+        if nz is not None:
+            batch = O.normalize_batch(batch, nz)
         L.critic_update(batch)
         L.soft_update_targets()
         if i % POLICY_EVERY == POLICY_EVERY - 1:
@@ -118,6 +127,9 @@ def main():
     ap.add_argument("--fill-rows", type=int, default=0, help="ring rows to fill before timing (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=48)
+    ap.add_argument("--paper-defaults", action="store_true",
+                    help="switch on the two Table B.1 defaults that the five workloads leave off: observation "
+                         "standardisation and gradient clipping at 0.5")
     ap.add_argument("--isolated", action="store_true",
                     help="also time a critic-only loop and a policy-update-only loop (changes the launch mix "
                          "that a profiler sees)")
@@ -133,6 +145,8 @@ def main():
         sys.exit(1)
 
     w = W.WORKLOADS[args.workload]
+    if args.paper_defaults:
+        w = w.replace(max_grad_norm=0.5, obs_norm=True)
     sess = LearnerSession(w)
     rng = W.data_rng(w)
     n_fill = args.fill_rows or w.rows
@@ -214,8 +228,10 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s-shaped: obs %d, act %d, %d envs, replay %d, batch %d, n=%d, MLP %s ELU fp32; "
                                "per critic update: sample + update + Polyak, policy update every %d, "
-                               "Actor step + push every %d" % (w.name, w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.batch,
-                                                              w.nstep, list(w.hidden), POLICY_EVERY, ACTOR_EVERY),
+                               "Actor step + push every %d%s" % (w.name, w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.batch,
+                                                                w.nstep, list(w.hidden), POLICY_EVERY, ACTOR_EVERY,
+                                                                "; observation standardisation and gradient clipping 0.5 on"
+                                                                if args.paper_defaults else ""),
                    "rows_filled": n_fill},
         "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,

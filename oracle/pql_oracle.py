@@ -33,6 +33,7 @@ MASK64 = 0xFFFFFFFFFFFFFFFF
 
 STREAM_SAMPLE = 1   # index sampling draws
 STREAM_ACT = 2      # exploration-noise draws
+STREAM_STATE = 3    # the P-learner's draws of states
 
 
 # --------------------------------------------------------------------------------------
@@ -115,7 +116,7 @@ class ReplayRing:
         return (self.head - self.count + j) % self.T
 
 
-def sample_indices(ring: ReplayRing, nstep: int, batch: int, seed: int, call: int):
+def sample_indices(ring: ReplayRing, nstep: int, batch: int, seed: int, call: int, stream: int = STREAM_SAMPLE):
     """I.i.d. uniform start slots, with replacement (Section 3.1: the V-learner samples
     "a batch of I.I.D. training data"; Algorithm 3).
 
@@ -127,7 +128,7 @@ def sample_indices(ring: ReplayRing, nstep: int, batch: int, seed: int, call: in
     if ring.count < nstep:
         raise ValueError("not enough rows pushed for an n-step window")
     V = (ring.count - nstep + 1) * ring.N
-    w0, w1, _, _ = rng_words(seed, STREAM_SAMPLE, call, np.arange(batch, dtype=np.uint64))
+    w0, w1, _, _ = rng_words(seed, stream, call, np.arange(batch, dtype=np.uint64))
     idx = np.empty(batch, dtype=np.int64)
     for k in range(batch):                      # exact big-integer arithmetic
         u = (int(w1[k]) << 32) | int(w0[k])
@@ -166,6 +167,14 @@ def gather_nstep(ring: ReplayRing, idx, nstep: int, gamma: float):
     boot = g * alive
     return dict(idx=idx, obs=ring.obs[idx].copy(), act=ring.act[idx].copy(), ret=ret,
                 next_obs=ring.next_obs[last].copy(), boot=boot)
+
+
+def sample_states(ring: ReplayRing, batch: int, seed: int, call: int):
+    """The P-learner's batch (Algorithm 2: "sample a batch of {s_t}"): i.i.d. uniform slots,
+    with replacement, among all count * N stored transitions (a window of one row), drawn on
+    a generator stream of their own; only the states are used.  Returns (slots, states)."""
+    idx = sample_indices(ring, 1, batch, seed, call, stream=STREAM_STATE)
+    return idx, ring.obs[idx].copy()
 
 
 # --------------------------------------------------------------------------------------
@@ -459,3 +468,91 @@ class Learner:
 
     def sync_lagged_policy(self):
         self.actor_lag = soft_update(self.actor, self.actor_lag, 1.0)
+
+
+# --------------------------------------------------------------------------------------
+# The parallel scheme (Section 3.1, Section 3.2, Algorithms 1-3) as a deterministic schedule
+# --------------------------------------------------------------------------------------
+class ParallelScheme:
+    """Actor, V-learner and P-learner with their local copies (pi^a, pi^v, Q^p), exchanging
+    data and networks once per Actor iteration, as Algorithms 1-3 route every transfer
+    through the Actor's loop.
+
+    The paper's processes run asynchronously and are throttled by sleeping so that the
+    update frequencies keep the ratios beta_a:v and beta_p:v (Section 3.2).  Here the same
+    ratios are kept exactly: one *period* is one Actor iteration of ``horizon`` environment
+    steps, ``v_updates`` critic updates and ``p_updates`` policy updates (1 : 8 and 1 : 2 by
+    default give 1 step, 8 and 4).  Within a period the three parts only touch their local
+    copies, so they are independent of each other and may run in any order or at the same
+    time; at the period boundary
+        * the V-learner receives the transitions the Actor produced during the period and
+          the P-learner's policy (-> pi^v, the lagged target policy of Section 3.2);
+        * the P-learner receives those states (here: it samples states from the same
+          store, which then contains them) and the V-learner's critics (-> Q^p);
+        * the Actor receives the P-learner's policy (-> pi^a).
+    ``env_step(period, step, actions)`` plays the simulator: it returns the transition rows
+    (obs, rew, next_obs, done) of that step; obs must not depend on the actions (synthetic
+    data), the actions are stored with the transition.
+    """
+
+    def __init__(self, learner: Learner, ring: ReplayRing, nstep: int, batch: int, seed: int,
+                 sigma_min: float, sigma_max: float, normalizer: ObsNormalizer = None,
+                 horizon: int = 1, v_updates: int = 8, p_updates: int = 4):
+        self.L, self.ring, self.nstep, self.batch, self.seed = learner, ring, nstep, batch, seed
+        self.sigma_min, self.sigma_max, self.nz = sigma_min, sigma_max, normalizer
+        self.horizon, self.v_updates, self.p_updates = horizon, v_updates, p_updates
+        self.pi_a = learner.actor.copy()              # the Actor's local policy
+        self.q_p = learner.critic.copy()              # the P-learner's local critics
+        learner.actor_lag = learner.actor.copy()      # pi^v
+        self.sample_calls = self.state_calls = self.act_calls = 0
+        self.period = 0
+        self.trace = []                               # per period: what each part used
+
+    def run_period(self, env_step, obs_rows):
+        """obs_rows[t]: the observations s_t the Actor sees at step t of this period."""
+        L = self.L
+        rec = dict(pi_a=self.pi_a.copy(), pi_v=L.actor_lag.copy(), q_p=self.q_p.copy(), rows=self.ring.count)
+        # ---- Actor (Algorithm 1): roll out pi^a; the transitions are delivered at the boundary
+        produced = []
+        for t in range(self.horizon):
+            s = obs_rows[t]
+            seen = s if self.nz is None else self.nz.normalize(s)
+            a = actor_act(self.pi_a, L.actor_dims, seen, self.sigma_min, self.sigma_max, self.seed, self.act_calls)
+            self.act_calls += 1
+            row = env_step(self.period, t, a)
+            produced.append(dict(row, act=a.astype(np.float32)))
+        # ---- V-learner (Algorithm 3): critic updates with the lagged policy pi^v
+        v_losses = []
+        for _ in range(self.v_updates):
+            b = gather_nstep(self.ring, sample_indices(self.ring, self.nstep, self.batch, self.seed, self.sample_calls),
+                             self.nstep, L.gamma)
+            self.sample_calls += 1
+            if self.nz is not None:
+                b = normalize_batch(b, self.nz)
+            losses, _ = L.critic_update(b)
+            L.soft_update_targets()
+            v_losses.append(losses)
+        # ---- P-learner (Algorithm 2): policy updates against its local critics Q^p
+        q_v = L.critic
+        L.critic = self.q_p
+        p_losses = []
+        for _ in range(self.p_updates):
+            _, states = sample_states(self.ring, self.batch, self.seed, self.state_calls)
+            self.state_calls += 1
+            if self.nz is not None:
+                states = self.nz.normalize(states)
+            J, _ = L.actor_update(states)
+            p_losses.append(J)
+        L.critic = q_v
+        # ---- period boundary: data and network transfer
+        for row in produced:
+            self.ring.push(row["obs"], row["act"], row["rew"], row["next_obs"], row["done"])
+            if self.nz is not None:
+                self.nz.update(row["obs"])
+        L.sync_lagged_policy()                        # pi^v <- pi^p
+        self.pi_a = L.actor.copy()                    # pi^a <- pi^p
+        self.q_p = L.critic.copy()                    # Q^p  <- Q^v
+        rec.update(v_losses=v_losses, p_losses=p_losses, actions=[r["act"] for r in produced])
+        self.trace.append(rec)
+        self.period += 1
+        return rec

@@ -590,26 +590,46 @@ __global__ __launch_bounds__(256) void obs_stats_chunk_kernel(ObsStatsView v, co
     }
 }
 
+// Merge of (n, mean, m2) with (nb, mb, qb): pairwise update of Chan, Golub and LeVeque.
+__device__ inline void stats_merge(double& n, double& mean, double& m2, double nb, double mb, double qb) {
+    if (nb <= 0.0) return;
+    const double tot = n + nb, delta = mb - mean, f = nb / tot;
+    mean += delta * f;
+    m2 += qb + delta * delta * (n * f);
+    n = tot;
+}
+
+// One workgroup; lane = column (in tiles of 64), the four wavefronts each fold a contiguous
+// quarter of the chunks, then wavefront 0 folds the running values and the four quarters in order.
 __global__ __launch_bounds__(256) void obs_stats_merge_kernel(ObsStatsView v, int rows, int o, float eps) {
+    __shared__ double sn[4][64], smean[4][64], sm2[4][64];
+    const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
     const double n0 = v.stat[0];
     const int nchunk = (rows + OBS_CHUNK_ROWS - 1) / OBS_CHUNK_ROWS;
-    for (int c = threadIdx.x; c < o; c += 256) {
-        double n = n0, mean = v.stat[2 + c], m2 = v.stat[2 + o + c];
-        for (int k = 0; k < nchunk; ++k) {
-            const int left = rows - k * OBS_CHUNK_ROWS;
-            const double nb = (double)(left < OBS_CHUNK_ROWS ? left : OBS_CHUNK_ROWS);
-            const double mb = v.part[(size_t)k * 2 * o + c], qb = v.part[(size_t)k * 2 * o + o + c];
-            const double tot = n + nb, delta = mb - mean;
-            mean += delta * (nb / tot);
-            m2 += qb + delta * delta * (n * nb / tot);
-            n = tot;
+    const int per = (nchunk + 3) / 4;
+    const int k0 = grp * per, k1 = (k0 + per < nchunk) ? k0 + per : nchunk;
+    for (int c0 = 0; c0 < o; c0 += 64) {
+        const int c = c0 + lane;
+        double n = 0.0, mean = 0.0, m2 = 0.0;
+        if (c < o)
+            for (int k = k0; k < k1; ++k) {
+                const int left = rows - k * OBS_CHUNK_ROWS;
+                const double nb = (double)(left < OBS_CHUNK_ROWS ? left : OBS_CHUNK_ROWS);
+                stats_merge(n, mean, m2, nb, v.part[(size_t)k * 2 * o + c], v.part[(size_t)k * 2 * o + o + c]);
+            }
+        sn[grp][lane] = n; smean[grp][lane] = mean; sm2[grp][lane] = m2;
+        __syncthreads();
+        if (grp == 0 && c < o) {
+            n = n0; mean = v.stat[2 + c]; m2 = v.stat[2 + o + c];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) stats_merge(n, mean, m2, sn[g][lane], smean[g][lane], sm2[g][lane]);
+            v.stat[2 + c] = mean;
+            v.stat[2 + o + c] = m2;
+            v.mean_f[c] = (float)mean;
+            v.rstd_f[c] = (float)(1.0 / sqrt(m2 / n + (double)eps));
         }
-        v.stat[2 + c] = mean;
-        v.stat[2 + o + c] = m2;
-        v.mean_f[c] = (float)mean;
-        v.rstd_f[c] = (float)(1.0 / sqrt(m2 / n + (double)eps));
+        __syncthreads();                               // every thread has read the old count; LDS reusable
     }
-    __syncthreads();                                   // every thread has read the old count
     if (threadIdx.x == 0) v.stat[0] = n0 + (double)rows;
 }
 
