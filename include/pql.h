@@ -44,9 +44,9 @@
  *                  done[T*N] (0.0 / 1.0), all row-major fp32.
  *   Random draws   Philox-4x32-10 (Salmon et al., SC'11) with key = the two halves of
  *                  cfg.seed and counter = (element, stream id, call number low, call number
- *                  high); stream id 1 = index sampling, 2 = exploration noise.  The call number
- *                  is the context's sample / act counter, so a run is reproducible from
- *                  (seed, state).
+ *                  high); stream id 1 = index sampling, 2 = exploration noise, 3 = the
+ *                  P-learner's state sampling.  The call number is the context's counter for
+ *                  that kind of draw, so a run is reproducible from (seed, state).
  */
 #ifndef PQL_H
 #define PQL_H
@@ -113,7 +113,7 @@ int64_t pql_workspace_bytes(const pql_config* cfg);    /* bytes of scratch for m
 const char* pql_last_error(const pql_ctx* ctx);
 
 /* Host state: [0] head row, [1] valid rows, [2] pushes so far, [3] sample calls so far,
- * [4] act calls so far, [5] critic Adam steps, [6] actor Adam steps, [7] reserved (0).
+ * [4] act calls so far, [5] critic Adam steps, [6] actor Adam steps, [7] state-sample calls.
  * Setting it resumes a run bit-exactly on the same device buffers. */
 int32_t pql_get_state(const pql_ctx* ctx, int64_t out[8]);
 int32_t pql_set_state(pql_ctx* ctx, const int64_t in[8]);
@@ -136,6 +136,16 @@ int32_t pql_replay_push(pql_ctx* ctx, pql_replay_storage storage, const float* o
  * Advances the sample counter.  Errors: PQL_ERR_NOT_ENOUGH_DATA if count < n,
  * PQL_ERR_BATCH_TOO_LARGE, PQL_ERR_NULL. */
 int32_t pql_sample_nstep(pql_ctx* ctx, pql_replay_storage storage, int32_t batch, pql_batch out, void* stream);
+
+/* The P-learner's batch (Algorithm 2 "sample a batch of {s_t}"; Section 3.1: the Actor sends it the
+ * states only): `batch` i.i.d. uniform slots, with replacement, among all count * N stored
+ * transitions (position floor(u * count * N / 2^64), drawn like pql_sample_nstep's but on generator
+ * stream 3 with a counter of its own), written to idx_out[batch] ([device] int64) together with their
+ * states obs_out[batch][o] ([device]; standardised while a statistics block is attached).  Only
+ * storage.obs is read.  Errors: PQL_ERR_NOT_ENOUGH_DATA if nothing has been pushed,
+ * PQL_ERR_BATCH_TOO_LARGE, PQL_ERR_NULL. */
+int32_t pql_sample_states(pql_ctx* ctx, pql_replay_storage storage, int32_t batch, int64_t* idx_out,
+                          float* obs_out, void* stream);
 
 /* Same assembly for caller-given start slots idx[batch] ([device], each slot must start a
  * window inside the valid rows; the caller guarantees it).  out.idx is not written.  Does not

@@ -527,6 +527,7 @@ class ParallelScheme:
             b = gather_nstep(self.ring, sample_indices(self.ring, self.nstep, self.batch, self.seed, self.sample_calls),
                              self.nstep, L.gamma)
             self.sample_calls += 1
+            rec["v_idx"] = b["idx"]                    # slots of the last batch, for inspection
             if self.nz is not None:
                 b = normalize_batch(b, self.nz)
             losses, _ = L.critic_update(b)
@@ -537,7 +538,7 @@ class ParallelScheme:
         L.critic = self.q_p
         p_losses = []
         for _ in range(self.p_updates):
-            _, states = sample_states(self.ring, self.batch, self.seed, self.state_calls)
+            rec["p_idx"], states = sample_states(self.ring, self.batch, self.seed, self.state_calls)
             self.state_calls += 1
             if self.nz is not None:
                 states = self.nz.normalize(states)

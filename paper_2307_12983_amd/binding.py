@@ -23,7 +23,7 @@ EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_coun
            "pql_workspace_bytes", "pql_last_error", "pql_get_state", "pql_set_state", "pql_replay_push",
            "pql_sample_nstep", "pql_gather_nstep", "pql_actor_act", "pql_critic_update", "pql_actor_update",
            "pql_soft_update", "pql_adam_step", "pql_profile_begin", "pql_profile_end",
-           "pql_obs_norm_bytes", "pql_obs_norm_attach", "pql_obs_norm_reset"]
+           "pql_obs_norm_bytes", "pql_obs_norm_attach", "pql_obs_norm_reset", "pql_sample_states"]
 
 
 class PqlConfig(C.Structure):
@@ -86,6 +86,7 @@ def load_library() -> C.CDLL:
         "pql_replay_push": (I32, [P, PqlStorage, P, P, P, P, P, P]),
         "pql_sample_nstep": (I32, [P, PqlStorage, I32, PqlBatch, P]),
         "pql_gather_nstep": (I32, [P, PqlStorage, P, I32, PqlBatch, P]),
+        "pql_sample_states": (I32, [P, PqlStorage, I32, P, P, P]),
         "pql_actor_act": (I32, [P, P, P, I32, F, F, P, P, P]),
         "pql_critic_update": (I32, [P, P, P, P, P, P, P, PqlBatch, I32, PqlAdam, P, P, P]),
         "pql_actor_update": (I32, [P, P, P, P, P, P, P, I32, PqlAdam, P, P, P]),
@@ -221,6 +222,10 @@ class Context:
 
     def pql_sample_nstep(self, storage, batch_size, out, stream=None):
         self._check(self.lib.pql_sample_nstep(self.h, storage.c(), batch_size, out.c(), _stream(stream)))
+
+    def pql_sample_states(self, storage, batch_size, idx_out, obs_out, stream=None):
+        self._check(self.lib.pql_sample_states(self.h, storage.c(), batch_size, _ptr(idx_out), _ptr(obs_out),
+                                               _stream(stream)))
 
     def pql_gather_nstep(self, storage, idx, batch_size, out, stream=None):
         self._check(self.lib.pql_gather_nstep(self.h, storage.c(), _ptr(idx), batch_size, out.c(), _stream(stream)))

@@ -73,7 +73,7 @@ struct pql_ctx {
     pql_config cfg;
     int L;                       // hidden layers
     int64_t T;                   // ring rows
-    int64_t head, count, pushes, samples, acts, critic_t, actor_t;
+    int64_t head, count, pushes, samples, acts, critic_t, actor_t, state_samples;
     // parameter offsets (floats) inside one actor / one critic vector: W then b per layer
     int64_t a_w[PQL_MAX_HIDDEN + 1], a_b[PQL_MAX_HIDDEN + 1], a_total;
     int64_t c_w[PQL_MAX_HIDDEN + 1], c_b[PQL_MAX_HIDDEN + 1], c_total;
@@ -401,7 +401,7 @@ int32_t pql_create(const pql_config* cfg, pql_ctx** out) {
     c->cfg = *cfg;
     c->L = cfg->n_hidden;
     c->T = cfg->capacity / cfg->num_envs;
-    c->head = c->count = c->pushes = c->samples = c->acts = c->critic_t = c->actor_t = 0;
+    c->head = c->count = c->pushes = c->samples = c->acts = c->critic_t = c->actor_t = c->state_samples = 0;
     c->obs_norm = nullptr;
     c->obs_eps = 0.f;
     c->a_total = net_params(cfg->obs_dim, cfg, cfg->act_dim, c->a_w, c->a_b);
@@ -444,7 +444,7 @@ const char* pql_last_error(const pql_ctx* ctx) { return ctx ? ctx->err.c_str() :
 int32_t pql_get_state(const pql_ctx* c, int64_t out[8]) {
     if (!c || !out) return PQL_ERR_NULL;
     out[0] = c->head; out[1] = c->count; out[2] = c->pushes; out[3] = c->samples;
-    out[4] = c->acts; out[5] = c->critic_t; out[6] = c->actor_t; out[7] = 0;
+    out[4] = c->acts; out[5] = c->critic_t; out[6] = c->actor_t; out[7] = c->state_samples;
     return PQL_OK;
 }
 
@@ -452,10 +452,10 @@ int32_t pql_set_state(pql_ctx* c, const int64_t in[8]) {
     if (!c || !in) return PQL_ERR_NULL;
     Err E{c};
     if (in[0] < 0 || in[0] >= c->T || in[1] < 0 || in[1] > c->T) return E.fail(PQL_ERR_INVALID_ARG, "ring cursor out of range");
-    for (int i = 2; i < 7; ++i)
+    for (int i = 2; i < 8; ++i)
         if (in[i] < 0) return E.fail(PQL_ERR_INVALID_ARG, "negative counter");
     c->head = in[0]; c->count = in[1]; c->pushes = in[2]; c->samples = in[3];
-    c->acts = in[4]; c->critic_t = in[5]; c->actor_t = in[6];
+    c->acts = in[4]; c->critic_t = in[5]; c->actor_t = in[6]; c->state_samples = in[7];
     return PQL_OK;
 }
 
@@ -501,6 +501,7 @@ static int32_t sample_common(pql_ctx* c, pql_replay_storage st, const int64_t* i
     a.nstep = c->cfg.nstep; a.head = (int)c->head; a.count = (int)c->count; a.gamma = c->cfg.gamma;
     a.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); a.key1 = (uint32_t)(c->cfg.seed >> 32);
     a.ctr2 = (uint32_t)((uint64_t)c->samples & 0xffffffffu); a.ctr3 = (uint32_t)((uint64_t)c->samples >> 32);
+    a.stream_id = 1u; a.only_obs = 0;
     a.nmean = a.nrstd = nullptr;
     if (c->obs_norm) {
         const ObsStatsView ov = obs_stats_view(c->obs_norm, c->cfg.obs_dim);
@@ -516,6 +517,33 @@ int32_t pql_sample_nstep(pql_ctx* c, pql_replay_storage st, int32_t batch, pql_b
     const int32_t rc = sample_common(c, st, nullptr, batch, out, stream, "pql_sample_nstep");
     if (rc == PQL_OK) c->samples += 1;
     return rc;
+}
+
+int32_t pql_sample_states(pql_ctx* c, pql_replay_storage st, int32_t batch, int64_t* idx_out, float* obs_out,
+                          void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    const char* who = "pql_sample_states";
+    if (!st.obs || !idx_out || !obs_out) return E.fail(PQL_ERR_NULL, who);
+    if (batch < 0) return E.fail(PQL_ERR_INVALID_ARG, who);
+    if (batch > c->cfg.max_batch) return E.fail(PQL_ERR_BATCH_TOO_LARGE, who);
+    if (c->count < 1) return E.fail(PQL_ERR_NOT_ENOUGH_DATA, who);
+    SampleArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.st = st; a.out.idx = idx_out; a.out.obs = obs_out;
+    a.batch = batch; a.o = c->cfg.obs_dim; a.a = c->cfg.act_dim; a.N = c->cfg.num_envs; a.T = (int)c->T;
+    a.nstep = 1; a.head = (int)c->head; a.count = (int)c->count; a.gamma = c->cfg.gamma;
+    a.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); a.key1 = (uint32_t)(c->cfg.seed >> 32);
+    a.ctr2 = (uint32_t)((uint64_t)c->state_samples & 0xffffffffu); a.ctr3 = (uint32_t)((uint64_t)c->state_samples >> 32);
+    a.stream_id = 3u; a.only_obs = 1;
+    if (c->obs_norm) {
+        const ObsStatsView ov = obs_stats_view(c->obs_norm, c->cfg.obs_dim);
+        a.nmean = ov.mean_f; a.nrstd = ov.rstd_f;
+    }
+    const hipError_t e = sample_launch(a, (hipStream_t)stream);
+    if (e != hipSuccess) return E.hip(e, who);
+    c->state_samples += 1;
+    return PQL_OK;
 }
 
 int32_t pql_gather_nstep(pql_ctx* c, pql_replay_storage st, const int64_t* idx, int32_t batch, pql_batch out,

@@ -180,6 +180,8 @@ struct SampleArgs {
     uint32_t key0, key1, ctr2, ctr3;
     const float* nmean;     // optional standardisation of s and s': (x - nmean[c]) * nrstd[c]
     const float* nrstd;
+    uint32_t stream_id;     // generator stream of the draw: 1 = transitions, 3 = the P-learner's states
+    int only_obs;           // 1: windows of one row, write idx and obs only
 };
 hipError_t sample_launch(const SampleArgs& a, hipStream_t stream);
 

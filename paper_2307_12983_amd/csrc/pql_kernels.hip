@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void sample_kernel(const SampleArgs a) {
         slot = a.idx_in[k];
     } else {
         uint32_t w0, w1;
-        philox4x32_10_w01((uint32_t)k, 1u, a.ctr2, a.ctr3, a.key0, a.key1, w0, w1);
+        philox4x32_10_w01((uint32_t)k, a.stream_id, a.ctr2, a.ctr3, a.key0, a.key1, w0, w1);
         const uint64_t u = ((uint64_t)w1 << 32) | (uint64_t)w0;
         const uint64_t V = (uint64_t)(a.count - a.nstep + 1) * (uint64_t)a.N;
         const uint64_t p = __umul64hi(u, V);
@@ -103,6 +103,13 @@ __global__ __launch_bounds__(256) void sample_kernel(const SampleArgs a) {
         const int64_t row = ((int64_t)a.head - (int64_t)a.count + (int64_t)j + (int64_t)a.T) % (int64_t)a.T;
         slot = row * (int64_t)a.N + (int64_t)e;
         if (gl == 0) a.out.idx[k] = slot;
+    }
+    if (a.only_obs) {       // Algorithm 2: the P-learner's batch is states only
+        if (a.nmean != nullptr)
+            copy_row_std<G, VEC_O>(a.out.obs + (size_t)k * a.o, a.st.obs + (size_t)slot * a.o, a.o, gl, a.nmean, a.nrstd);
+        else
+            copy_row<G, VEC_O>(a.out.obs + (size_t)k * a.o, a.st.obs + (size_t)slot * a.o, a.o, gl);
+        return;
     }
     const int64_t row0 = slot / a.N;
     const int64_t env = slot - row0 * a.N;
@@ -147,12 +154,13 @@ static inline bool al16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 
 hipError_t sample_launch(const SampleArgs& a, hipStream_t stream) {
     if (a.batch <= 0) return hipSuccess;
-    const bool vo = (a.o % 4 == 0) && al16(a.st.obs) && al16(a.st.next_obs) && al16(a.out.obs) && al16(a.out.next_obs) &&
-                    al16(a.nmean) && al16(a.nrstd);
-    const bool va = (a.a % 4 == 0) && al16(a.st.act) && al16(a.out.act);
+    const bool vo = (a.o % 4 == 0) && al16(a.st.obs) && al16(a.out.obs) && al16(a.nmean) && al16(a.nrstd) &&
+                    (a.only_obs || (al16(a.st.next_obs) && al16(a.out.next_obs)));
+    const bool va = a.only_obs || ((a.a % 4 == 0) && al16(a.st.act) && al16(a.out.act));
     const int per_row = vo ? a.o / 4 : a.o;
     // per sample: read s, a, s' and n (r, d) pairs; write s, a, s', ret, boot and the index
-    const double bytes = (double)a.batch * (4.0 * (2 * a.o + a.a + 2 * a.nstep) + 4.0 * (2 * a.o + a.a + 2) + 8.0);
+    const double bytes = a.only_obs ? (double)a.batch * (8.0 * a.o + 8.0)
+                                    : (double)a.batch * (4.0 * (2 * a.o + a.a + 2 * a.nstep) + 4.0 * (2 * a.o + a.a + 2) + 8.0);
     const ProfSlot ps = prof_slot();
     if (per_row <= 32) sample_dispatch<16>(a, vo, va, ps, stream);
     else               sample_dispatch<64>(a, vo, va, ps, stream);
