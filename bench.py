@@ -72,7 +72,7 @@ class Schedule:
             s.sync_lagged_policy()
 
 
-def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0):
+def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0, parallel=False):
     """The float64 oracle on the host, same schedule, on a bounded number of steps."""
     from oracle import pql_oracle as O
     try:
@@ -91,6 +91,17 @@ def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0):
                   max_grad_norm=(w.max_grad_norm if w.max_grad_norm > 0 else None))
     done_steps, tick, acts = 0, 0, 0
     t0 = time.perf_counter()
+    if parallel:
+        S = O.ParallelScheme(L, ring, w.nstep, w.batch, w.rng_seed, w.sigma_min, w.sigma_max, normalizer=nz)
+        while True:
+            row = env_rows_host[S.period % len(env_rows_host)]
+            S.run_period(lambda period, t, a: row, [row["obs"]])
+            done_steps += S.v_updates
+            el = time.perf_counter() - t0
+            if el >= budget_s or done_steps >= 64:
+                break
+        return dict(value=done_steps / el, unit="updates/s", cores=int(threads), kind="oracle",
+                    sample="%d periods of the same schedule at batch %d (numpy float64, %.1f s)" % (S.period, w.batch, el))
     while True:
         i = done_steps
         if i % ACTOR_EVERY == 0:
@@ -130,6 +141,11 @@ def main():
     ap.add_argument("--paper-defaults", action="store_true",
                     help="switch on the two Table B.1 defaults that the five workloads leave off: observation "
                          "standardisation and gradient clipping at 0.5")
+    ap.add_argument("--schedule", default="serial", choices=["serial", "parallel", "parallel-1stream"],
+                    help="serial: every call on one stream, networks shared by all parts (default).  parallel: the "
+                         "Actor, V-learner and P-learner on three streams with local network copies exchanged once "
+                         "per Actor step (Section 3.1 / 3.2), same 1 : 8 : 4 rates.  parallel-1stream: that schedule "
+                         "enqueued on one stream")
     ap.add_argument("--isolated", action="store_true",
                     help="also time a critic-only loop and a policy-update-only loop (changes the launch mix "
                          "that a profiler sees)")
@@ -170,14 +186,32 @@ def main():
     del cal_src, cal_dst
 
     sched = Schedule(sess, env_dev)
-    for i in range(args.warmup):
-        sched.step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.warmup, args.warmup + args.steps):
-        sched.step(i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if args.schedule == "serial":
+        for i in range(args.warmup):
+            sched.step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.warmup, args.warmup + args.steps):
+            sched.step(i)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    else:
+        from paper_2307_12983_amd.scheme import ParallelSchemeSession
+        if args.steps % ACTOR_EVERY or args.warmup % ACTOR_EVERY:
+            print("--steps and --warmup must be multiples of %d for the parallel schedule" % ACTOR_EVERY, file=sys.stderr)
+            sys.exit(2)
+        ps = ParallelSchemeSession(sess, env_dev, horizon=1, v_updates=ACTOR_EVERY, p_updates=ACTOR_EVERY // POLICY_EVERY,
+                                   concurrent=args.schedule == "parallel")
+        for _ in range(args.warmup // ACTOR_EVERY):
+            ps.run_period()
+        ps.finish()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps // ACTOR_EVERY):
+            ps.run_period()
+        ps.finish()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     ms_per_step = 1e3 * dt / args.steps
     value = args.steps / dt
 
@@ -232,7 +266,7 @@ def main():
                                                                 w.nstep, list(w.hidden), POLICY_EVERY, ACTOR_EVERY,
                                                                 "; observation standardisation and gradient clipping 0.5 on"
                                                                 if args.paper_defaults else ""),
-                   "rows_filled": n_fill},
+                   "rows_filled": n_fill, "schedule": args.schedule},
         "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
                      "avg_launch_us": 1e3 * dom["total_ms"] / dom["launches"], "launches": dom["launches"],
@@ -247,7 +281,7 @@ def main():
         out["critic_only_mfma_util_pct"] = 100.0 * w.batch * fl["critic_update"] / t_critic / (PEAK_FP32_MFMA_TFLOPS * 1e12)
         out["actor_update_per_s"] = 1.0 / t_actor_upd
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, keep, env_host)
+        out["cpu_baseline"] = cpu_baseline(w, keep, env_host, parallel=args.schedule != "serial")
     print(json.dumps(out))
 
 
