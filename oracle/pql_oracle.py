@@ -362,6 +362,108 @@ def actor_loss_and_grads(actor_params, critic_params, actor_dims, critic_dims, o
 
 
 # --------------------------------------------------------------------------------------
+# PQL-D: distributional critics (Section 3: distributional RL added to PQL; Appendix
+# "Distributional critic update": categorical parameterisation over l = 51 fixed atoms on
+# (-10, 10), categorical projection, cross-entropy; Bellemare, Dabney, Munos 2017)
+# --------------------------------------------------------------------------------------
+def atom_values(num_atoms: int, v_min: float, v_max: float):
+    """z_j = v_min + j * (v_max - v_min) / (l - 1), j = 0..l-1."""
+    return v_min + np.arange(num_atoms, dtype=np.float64) * ((v_max - v_min) / (num_atoms - 1))
+
+
+def log_softmax(logits):
+    x = np.asarray(logits, np.float64)
+    x = x - x.max(axis=-1, keepdims=True)
+    return x - np.log(np.exp(x).sum(axis=-1, keepdims=True))
+
+
+def dist_critic_forward(critic_params, critic_dims, obs, act):
+    """Logits over the atoms, [B, l]; the critic's last layer has l outputs."""
+    x = np.concatenate([np.asarray(obs, np.float64), np.asarray(act, np.float64)], axis=1)
+    zs, hs = mlp_forward(unpack(critic_params, critic_dims), x)
+    return hs[-1]
+
+
+def categorical_projection(p_next, ret, boot, z, v_min, v_max):
+    """Projection of the shifted and shrunk distribution onto the fixed support
+    (Bellemare et al. 2017, Eq. 7), with the n-step quantities of this path in place of
+    (r, gamma): atom z_j of the next-state distribution moves to
+    T z_j = clip(ret + boot * z_j, v_min, v_max) and its mass p_j is shared between the two
+    neighbouring atoms in proportion to proximity:
+        m_k = sum_j [1 - |T z_j - z_k| / dz]_0^1 * p_j."""
+    p_next = np.asarray(p_next, np.float64)
+    dz = (v_max - v_min) / (z.shape[0] - 1)
+    tz = np.clip(np.asarray(ret, np.float64)[:, None] + np.asarray(boot, np.float64)[:, None] * z[None, :], v_min, v_max)
+    w = np.clip(1.0 - np.abs(tz[:, :, None] - z[None, None, :]) / dz, 0.0, 1.0)        # [B, j, k]
+    return np.einsum("bj,bjk->bk", p_next, w)
+
+
+def dist_td_target(batch, actor_target_params, critic_target_params, actor_dims, critic_dims, v_min, v_max):
+    """Target distribution m [B, l]: next action from the lagged policy pi^v (Section 3.2);
+    of the twin target critics the one with the smaller expected value at (s', a') supplies
+    the next-state distribution (the distributional form of min_i Q'_i; ties: Q'_1), which is
+    then projected."""
+    l = critic_dims[-1][1]
+    z = atom_values(l, v_min, v_max)
+    a_next = actor_forward(actor_target_params, actor_dims, batch["next_obs"])
+    t1, t2 = split_twin(critic_target_params)
+    p1 = np.exp(log_softmax(dist_critic_forward(t1, critic_dims, batch["next_obs"], a_next)))
+    p2 = np.exp(log_softmax(dist_critic_forward(t2, critic_dims, batch["next_obs"], a_next)))
+    pick1 = (p1 @ z) <= (p2 @ z)
+    p_next = np.where(pick1[:, None], p1, p2)
+    return categorical_projection(p_next, batch["ret"], batch["boot"], z, v_min, v_max)
+
+
+def dist_critic_loss_and_grads(critic_params, critic_dims, batch, m):
+    """Cross-entropy of each critic's distribution at (s, a) against the projected target:
+    L_i = -mean_b sum_k m_bk log p_i,bk; optimised loss L_1 + L_2; m is a constant.
+    Returns ([L_1, L_2], flat gradient)."""
+    x = np.concatenate([np.asarray(batch["obs"], np.float64), np.asarray(batch["act"], np.float64)], axis=1)
+    B = x.shape[0]
+    losses, flat = [], []
+    for p in split_twin(critic_params):
+        layers = unpack(p, critic_dims)
+        zs, hs = mlp_forward(layers, x)
+        logp = log_softmax(hs[-1])
+        losses.append(float(-np.mean(np.sum(m * logp, axis=1))))
+        d_logits = (np.exp(logp) * m.sum(axis=1, keepdims=True) - m) / B      # d/dlogits of -sum_k m_k log p_k
+        grads, _ = mlp_backward(layers, zs, hs, d_logits)
+        flat.append(pack(grads))
+    return np.array(losses), np.concatenate(flat)
+
+
+def dist_actor_loss_and_grads(actor_params, critic_params, actor_dims, critic_dims, obs, v_min, v_max):
+    """Policy objective with distributional critics: Q_i = sum_k p_i,k z_k (the mean of the
+    distribution) takes the place of the scalar critic in J = -mean_b min_i Q_i(s, pi(s));
+    ties go to Q_1; critics constant."""
+    obs = np.asarray(obs, np.float64)
+    B = obs.shape[0]
+    z = atom_values(critic_dims[-1][1], v_min, v_max)
+    a_layers = unpack(actor_params, actor_dims)
+    a_zs, a_hs = mlp_forward(a_layers, obs)
+    a_pi = np.tanh(a_hs[-1])
+    x = np.concatenate([obs, a_pi], axis=1)
+    qs, caches = [], []
+    for p in split_twin(critic_params):
+        layers = unpack(p, critic_dims)
+        zs, hs = mlp_forward(layers, x)
+        prob = np.exp(log_softmax(hs[-1]))
+        qs.append(prob @ z)
+        caches.append((layers, zs, hs, prob))
+    pick1 = qs[0] <= qs[1]
+    J = -float(np.mean(np.where(pick1, qs[0], qs[1])))
+    d_act = np.zeros_like(a_pi)
+    for sel, q, (layers, zs, hs, prob) in zip((pick1, ~pick1), qs, caches):
+        d_q = np.where(sel, -1.0 / B, 0.0)[:, None]
+        d_logits = d_q * prob * (z[None, :] - q[:, None])       # dQ/dlogit_k = p_k (z_k - Q)
+        _, d_x = mlp_backward(layers, zs, hs, d_logits)
+        d_act += d_x[:, obs.shape[1]:]
+    d_pre = d_act * (1.0 - a_pi * a_pi)
+    grads, _ = mlp_backward(a_layers, a_zs, a_hs, d_pre)
+    return J, pack(grads)
+
+
+# --------------------------------------------------------------------------------------
 # Optimiser and target tracking (Table B.1: Adam, learning rate 5e-4, target update rate
 # tau = 5e-2)
 # --------------------------------------------------------------------------------------
@@ -433,8 +535,9 @@ class Learner:
     the paper's loops do.  Parameters enter as fp32 arrays and are promoted."""
 
     def __init__(self, actor_dims, critic_dims, actor_params, critic_params, lr, gamma, tau,
-                 beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=None):
+                 beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=None, v_min=None, v_max=None):
         self.actor_dims, self.critic_dims = actor_dims, critic_dims
+        self.v_min, self.v_max = v_min, v_max         # set: PQL-D (critic outputs are logits over atoms)
         self.max_grad_norm = max_grad_norm            # None: no clipping
         self.critic_grad_norm = self.actor_grad_norm = 0.0
         self.actor = np.asarray(actor_params, np.float64).copy()
@@ -447,8 +550,13 @@ class Learner:
         self.beta1, self.beta2, self.eps = beta1, beta2, eps
 
     def critic_update(self, batch):
-        y = td_target(batch, self.actor_lag, self.critic_target, self.actor_dims, self.critic_dims)
-        losses, g = critic_loss_and_grads(self.critic, self.critic_dims, batch, y)
+        if self.v_min is not None:
+            m = dist_td_target(batch, self.actor_lag, self.critic_target, self.actor_dims, self.critic_dims,
+                               self.v_min, self.v_max)
+            losses, g = dist_critic_loss_and_grads(self.critic, self.critic_dims, batch, m)
+        else:
+            y = td_target(batch, self.actor_lag, self.critic_target, self.actor_dims, self.critic_dims)
+            losses, g = critic_loss_and_grads(self.critic, self.critic_dims, batch, y)
         g, self.critic_grad_norm = clip_grad_norm(g, self.max_grad_norm)   # both critics: one step, one norm
         self.c_t += 1
         self.critic, self.c_m, self.c_v = adam_step(self.critic, g, self.c_m, self.c_v, self.c_t,
@@ -459,7 +567,11 @@ class Learner:
         self.critic_target = soft_update(self.critic, self.critic_target, self.tau)
 
     def actor_update(self, obs):
-        J, g = actor_loss_and_grads(self.actor, self.critic, self.actor_dims, self.critic_dims, obs)
+        if self.v_min is not None:
+            J, g = dist_actor_loss_and_grads(self.actor, self.critic, self.actor_dims, self.critic_dims, obs,
+                                             self.v_min, self.v_max)
+        else:
+            J, g = actor_loss_and_grads(self.actor, self.critic, self.actor_dims, self.critic_dims, obs)
         g, self.actor_grad_norm = clip_grad_norm(g, self.max_grad_norm)
         self.a_t += 1
         self.actor, self.a_m, self.a_v = adam_step(self.actor, g, self.a_m, self.a_v, self.a_t,
