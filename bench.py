@@ -88,7 +88,8 @@ def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0, paralle
             nz.update(row["obs"])
     actor, critic = W.init_networks(w)
     L = O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps,
-                  max_grad_norm=(w.max_grad_norm if w.max_grad_norm > 0 else None))
+                  max_grad_norm=(w.max_grad_norm if w.max_grad_norm > 0 else None),
+                  v_min=(w.v_min if w.num_atoms >= 2 else None), v_max=(w.v_max if w.num_atoms >= 2 else None))
     done_steps, tick, acts = 0, 0, 0
     t0 = time.perf_counter()
     if parallel:
@@ -141,6 +142,8 @@ def main():
     ap.add_argument("--paper-defaults", action="store_true",
                     help="switch on the two Table B.1 defaults that the five workloads leave off: observation "
                          "standardisation and gradient clipping at 0.5")
+    ap.add_argument("--atoms", type=int, default=0,
+                    help="distributional critics (PQL-D) with this many atoms on (-10, 10); the paper uses 51")
     ap.add_argument("--schedule", default="serial", choices=["serial", "parallel", "parallel-1stream"],
                     help="serial: every call on one stream, networks shared by all parts (default).  parallel: the "
                          "Actor, V-learner and P-learner on three streams with local network copies exchanged once "
@@ -163,6 +166,8 @@ def main():
     w = W.WORKLOADS[args.workload]
     if args.paper_defaults:
         w = w.replace(max_grad_norm=0.5, obs_norm=True)
+    if args.atoms >= 2:
+        w = w.replace(num_atoms=args.atoms)
     sess = LearnerSession(w)
     rng = W.data_rng(w)
     n_fill = args.fill_rows or w.rows
@@ -265,7 +270,9 @@ def main():
                                "Actor step + push every %d%s" % (w.name, w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.batch,
                                                                 w.nstep, list(w.hidden), POLICY_EVERY, ACTOR_EVERY,
                                                                 "; observation standardisation and gradient clipping 0.5 on"
-                                                                if args.paper_defaults else ""),
+                                                                if args.paper_defaults else "")
+                               + ("; distributional critics, %d atoms on (%g, %g)" % (w.num_atoms, w.v_min, w.v_max)
+                                  if w.num_atoms >= 2 else ""),
                    "rows_filled": n_fill, "schedule": args.schedule},
         "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,

@@ -35,7 +35,8 @@
  *                  W[in][out] row-major (y = x W + b), then the bias b[out].  Hidden layers use
  *                  ELU (alpha = 1).  Actor: in = obs_dim, hidden..., out = act_dim, then tanh.
  *                  Critic: in = obs_dim + act_dim (s and a concatenated), hidden..., out = 1,
- *                  linear.  "Twin critics" = the vector of Q_1 immediately followed by that of
+ *                  linear (num_atoms outputs, read as logits over the atoms, when the critics
+ *                  are distributional).  "Twin critics" = the vector of Q_1 immediately followed by that of
  *                  Q_2.  Gradients and Adam moments use the same layout.  The caller initialises
  *                  parameters.
  *   Replay layout  The ring has T = capacity / num_envs rows; a row is one Actor step of all N
@@ -80,6 +81,10 @@ typedef struct {
     int32_t  hidden[PQL_MAX_HIDDEN];  /* widths, each >= 1                                       */
     int32_t  max_batch;               /* largest batch_size / num_envs any call will use         */
     uint64_t seed;                    /* key of the counter-based generator                      */
+    int32_t  num_atoms;               /* 0 or 1: scalar critics.  2..64: distributional critics  */
+                                      /* (PQL-D; the paper's appendix uses 51) with that many     */
+                                      /* atoms                                                    */
+    float    v_min, v_max;            /* support of the atoms, v_max > v_min (paper: -10, 10)     */
 } pql_config;
 
 /* [device] replay storage, sizes as under "Replay layout". */
@@ -166,7 +171,17 @@ int32_t pql_actor_act(pql_ctx* ctx, const float* actor_params, const float* obs,
 /* ---- V-learner step (Algorithm 3 "update Q_1, Q_2 by minimizing the mean-squared Bellman
  *      error (with Double Q-learning)"; Section 3.2 for the lagged target policy) ----------- */
 
-/* y = ret + boot * min_i Q'_i(next_obs, pi^v(next_obs));  L_i = mean_b (Q_i(obs, act) - y)^2;
+/* Distributional critics (cfg.num_atoms = l >= 2; Section 3 "PQL-D", appendix paragraph "Distributional
+ * critic update": categorical distribution over l fixed atoms z_k = v_min + k (v_max - v_min)/(l - 1),
+ * categorical projection, cross-entropy [Bellemare et al. 2017]): p_i = softmax of critic i's l outputs.
+ * The target critic with the smaller mean sum_k p'_ik z_k at (next_obs, pi^v(next_obs)) supplies the
+ * next-state distribution p' (ties: the first); its atoms move to T z_j = clip(ret + boot z_j, v_min,
+ * v_max) and are projected back: m_k = sum_j [1 - |T z_j - z_k| / dz]_0^1 p'_j;  L_i = -mean_b sum_k m_k
+ * log p_ik(obs, act).  pql_actor_update then uses Q_i = sum_k p_ik z_k in place of the scalar critic.
+ * Everything else below is unchanged.
+ *
+ * Scalar critics:
+ * y = ret + boot * min_i Q'_i(next_obs, pi^v(next_obs));  L_i = mean_b (Q_i(obs, act) - y)^2;
  * gradient of L_1 + L_2 w.r.t. critic_params (y is a constant) is written to grads_out, then
  * one Adam step (bias-corrected, eps outside the root) updates critic_params, adam_m, adam_v
  * in place.  loss_out[3] ([device]) receives L_1, L_2 evaluated before the step and, when

@@ -29,7 +29,8 @@ EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_coun
 class PqlConfig(C.Structure):
     _fields_ = [("obs_dim", C.c_int32), ("act_dim", C.c_int32), ("num_envs", C.c_int32), ("capacity", C.c_int64),
                 ("nstep", C.c_int32), ("gamma", C.c_float), ("n_hidden", C.c_int32),
-                ("hidden", C.c_int32 * PQL_MAX_HIDDEN), ("max_batch", C.c_int32), ("seed", C.c_uint64)]
+                ("hidden", C.c_int32 * PQL_MAX_HIDDEN), ("max_batch", C.c_int32), ("seed", C.c_uint64),
+                ("num_atoms", C.c_int32), ("v_min", C.c_float), ("v_max", C.c_float)]
 
 
 class PqlStorage(C.Structure):
@@ -105,12 +106,14 @@ def load_library() -> C.CDLL:
     return lib
 
 
-def make_config(obs_dim, act_dim, num_envs, capacity, nstep, gamma, hidden: Sequence[int], max_batch, seed) -> PqlConfig:
+def make_config(obs_dim, act_dim, num_envs, capacity, nstep, gamma, hidden: Sequence[int], max_batch, seed,
+                num_atoms=0, v_min=0.0, v_max=0.0) -> PqlConfig:
     cfg = PqlConfig()
     cfg.obs_dim, cfg.act_dim, cfg.num_envs, cfg.capacity = obs_dim, act_dim, num_envs, capacity
     cfg.nstep, cfg.gamma, cfg.n_hidden, cfg.max_batch, cfg.seed = nstep, gamma, len(hidden), max_batch, seed
     for i, h in enumerate(hidden[:PQL_MAX_HIDDEN]):
         cfg.hidden[i] = int(h)
+    cfg.num_atoms, cfg.v_min, cfg.v_max = int(num_atoms), float(v_min), float(v_max)
     return cfg
 
 

@@ -49,6 +49,8 @@ const char* kernel_name(int kid) {
         case KID_OBS_STATS: return "obs_stats_chunk_kernel";
         case KID_OBS_MERGE: return "obs_stats_merge_kernel";
         case KID_NORMALIZE: return "normalize_rows_kernel";
+        case KID_DIST_CRITIC: return "dist_head_kernel_critic";
+        case KID_DIST_POLICY: return "dist_head_kernel_policy";
         default: return "?";
     }
 }
@@ -99,8 +101,14 @@ int validate_cfg(const pql_config* c) {
     if (c->capacity < (int64_t)c->num_envs * c->nstep) return PQL_ERR_INVALID_ARG;
     if (c->capacity / c->num_envs > 0x7fffffffLL) return PQL_ERR_INVALID_ARG;
     if ((int64_t)c->max_batch * c->act_dim > 0xffffffffLL) return PQL_ERR_INVALID_ARG;   // 32-bit element counter
+    if (c->num_atoms < 0 || c->num_atoms > DIST_MAX_ATOMS) return PQL_ERR_INVALID_ARG;
+    if (c->num_atoms >= 2 && !(c->v_max > c->v_min)) return PQL_ERR_INVALID_ARG;
     return PQL_OK;
 }
+
+// Outputs of one critic: 1 (scalar Q) or the number of atoms of a distributional critic.
+inline int critic_out(const pql_config* c) { return c->num_atoms >= 2 ? c->num_atoms : 1; }
+inline bool distributional(const pql_config* c) { return c->num_atoms >= 2; }
 
 int64_t net_params(int in, const pql_config* c, int out, int64_t* w, int64_t* b) {
     int64_t off = 0;
@@ -157,6 +165,7 @@ struct Layout {
     size_t w1aT[2];                                                   // transposed action rows of the critics' first layer
     size_t waT[PQL_MAX_HIDDEN + 1];                                   // transposed policy weights, layer l = 1..L
     size_t splitk;
+    size_t lgT[2], lgQ[2], p_dbo[2];                                  // distributional critics: logits, output-bias partials
     size_t sqp;                                                       // per-workgroup sums of squared gradients
     size_t xn;                                                        // standardised Actor observations
     size_t total;
@@ -165,6 +174,7 @@ struct Layout {
 // The row-tile fused kernels apply when every hidden layer is a multiple of 32 and at most
 // FUSED_MAXW wide, the action vector fits one MFMA tile and the tile's LDS footprint fits a CU.
 bool fused_ok(const pql_config* c) {
+    if (distributional(c)) return false;          // logits layer and projection run on the layered path
     int hmax = 0;
     for (int l = 0; l < c->n_hidden; ++l) {
         if (c->hidden[l] % 32 != 0 || c->hidden[l] > FUSED_MAXW) return false;
@@ -226,6 +236,7 @@ size_t splitk_floats(const pql_config* c, int B) {
         critic.push_back({c->obs_dim, c->hidden[0]});
         critic.push_back({c->act_dim, c->hidden[0]});
         for (int l = 1; l < L; ++l) critic.push_back({c->hidden[l - 1], c->hidden[l]});
+        if (distributional(c)) critic.push_back({c->hidden[L - 1], c->num_atoms});
     }
     actor.push_back({c->obs_dim, c->hidden[0]});
     for (int l = 1; l < L; ++l) actor.push_back({c->hidden[l - 1], c->hidden[l]});
@@ -243,6 +254,7 @@ void make_layout(const pql_config* c, Layout& w) {
     const size_t crow = B / 32 + 8;                 // rows of a column-sum partial buffer
     size_t nwg = (size_t)head_workgroups((int)B);
     if (nwg < (B + FUSED_BM - 1) / FUSED_BM) nwg = (B + FUSED_BM - 1) / FUSED_BM;   // one partial row per row tile
+    if (distributional(c) && nwg < (size_t)dist_head_workgroups((int)B)) nwg = (size_t)dist_head_workgroups((int)B);
     for (int l = 1; l <= L; ++l) {
         const size_t h = (size_t)c->hidden[l - 1];
         w.hA[l] = take(B * h);
@@ -278,6 +290,12 @@ void make_layout(const pql_config* c, Layout& w) {
         w.sqp = take(adam_reduce_blocks_bound(pa > pc ? pa : pc, RED_MAX_TENSORS));
     }
     w.xn = fused_ok(c) ? off : take(B * (size_t)c->obs_dim);
+    if (distributional(c))
+        for (int i = 0; i < 2; ++i) {
+            w.lgT[i] = take(B * (size_t)c->num_atoms);
+            w.lgQ[i] = take(B * (size_t)c->num_atoms);
+            w.p_dbo[i] = take(nwg * (size_t)c->num_atoms);
+        }
     w.total = off;
 }
 
@@ -405,7 +423,7 @@ int32_t pql_create(const pql_config* cfg, pql_ctx** out) {
     c->obs_norm = nullptr;
     c->obs_eps = 0.f;
     c->a_total = net_params(cfg->obs_dim, cfg, cfg->act_dim, c->a_w, c->a_b);
-    c->c_total = net_params(cfg->obs_dim + cfg->act_dim, cfg, 1, c->c_w, c->c_b);
+    c->c_total = net_params(cfg->obs_dim + cfg->act_dim, cfg, critic_out(cfg), c->c_w, c->c_b);
     *out = c;
     return PQL_OK;
 }
@@ -428,7 +446,7 @@ int64_t pql_actor_param_count(const pql_config* cfg) {
 
 int64_t pql_critic_param_count(const pql_config* cfg) {
     const int rc = validate_cfg(cfg);
-    return rc != PQL_OK ? rc : net_params(cfg->obs_dim + cfg->act_dim, cfg, 1, nullptr, nullptr);
+    return rc != PQL_OK ? rc : net_params(cfg->obs_dim + cfg->act_dim, cfg, critic_out(cfg), nullptr, nullptr);
 }
 
 int64_t pql_workspace_bytes(const pql_config* cfg) {
@@ -668,6 +686,7 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
     AdamArgs adm;
     std::memset(&adm, 0, sizeof(adm));
     int head_parts = 0;
+    const bool dist = distributional(&c->cfg);
     if (fused_ok(&c->cfg)) {
         // One launch per row tile: target path, forward, heads and backward data path.
         TransposeArgs tr;
@@ -736,19 +755,56 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
                                           l > 1 ? ws + w.hT[i][l - 1] : nullptr, ws + w.hT[i][l], B));
             if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
         }
-        // 4. heads: y, losses, output deltas, delta of the last hidden layer
-        HeadArgs h;
-        std::memset(&h, 0, sizeof(h));
-        h.B = B; h.H = HL; h.nwg = head_workgroups(B);
-        for (int i = 0; i < 2; ++i) {
-            h.hT[i] = ws + w.hT[i][L]; h.wT[i] = critic_target_params + i * Pc + c->c_w[L]; h.bT[i] = critic_target_params + i * Pc + c->c_b[L];
-            h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L];        h.bQ[i] = critic_params + i * Pc + c->c_b[L];
-            h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
-            h.p_dw[i] = ws + w.p_dw[i]; h.p_dbh[i] = ws + w.p_dbh[i]; h.p_db[i] = ws + w.p_db[i];
+        if (dist) {
+            // 4. logits of the four critics, then target distribution, projection, cross-entropy, dLoss/dlogits
+            const int la = c->cfg.num_atoms;
+            std::vector<GemmProb> ps;
+            for (int i = 0; i < 2; ++i) {
+                GemmProb pt = prob(B, la, ws + w.lgT[i], la, EPI_BIAS);
+                add_seg(pt, ws + w.hT[i][L], HL, critic_target_params + i * Pc + c->c_w[L], la, HL);
+                pt.bias = critic_target_params + i * Pc + c->c_b[L];
+                ps.push_back(pt);
+                GemmProb pq = prob(B, la, ws + w.lgQ[i], la, EPI_BIAS);
+                add_seg(pq, ws + w.hQ[i][L], HL, critic_params + i * Pc + c->c_w[L], la, HL);
+                pq.bias = critic_params + i * Pc + c->c_b[L];
+                ps.push_back(pq);
+            }
+            if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
+            DistHeadArgs h;
+            std::memset(&h, 0, sizeof(h));
+            h.B = B; h.atoms = la; h.nwg = dist_head_workgroups(B); h.v_min = c->cfg.v_min; h.v_max = c->cfg.v_max;
+            for (int i = 0; i < 2; ++i) { h.logitsT[i] = ws + w.lgT[i]; h.logitsQ[i] = ws + w.lgQ[i]; h.p_db[i] = ws + w.p_dbo[i]; }
+            h.ret = batch.ret; h.boot = batch.boot; h.p_loss = ws + w.p_loss;
+            if ((e = dist_critic_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
+            head_parts = h.nwg;
+            // delta of the last hidden layer through the logits layer; its column sums are that layer's bias gradient
+            std::vector<GemmProb> pb;
+            for (int i = 0; i < 2; ++i) {
+                GemmProb p = prob(B, HL, ws + w.dQ[i][L], HL, EPI_MUL_DELU);
+                add_seg(p, ws + w.lgQ[i], la, critic_params + i * Pc + c->c_w[L], la, la);
+                p.aux = ws + w.hQ[i][L]; p.ldaux = HL;
+                p.colsum = ws + w.colQ[i][L];
+                pb.push_back(p);
+            }
+            const int tile = choose_tile(GEMM_NT, pb);
+            if ((e = run(GEMM_NT, tile, pb, nullptr, st)) != hipSuccess) return E.hip(e, who);
+            for (int i = 0; i < 2; ++i)
+                red(adm, i * Pc + c->c_b[L - 1], ws + w.colQ[i][L], HL, colsum_rows(tile, B), HL);
+        } else {
+            // 4. heads: y, losses, output deltas, delta of the last hidden layer
+            HeadArgs h;
+            std::memset(&h, 0, sizeof(h));
+            h.B = B; h.H = HL; h.nwg = head_workgroups(B);
+            for (int i = 0; i < 2; ++i) {
+                h.hT[i] = ws + w.hT[i][L]; h.wT[i] = critic_target_params + i * Pc + c->c_w[L]; h.bT[i] = critic_target_params + i * Pc + c->c_b[L];
+                h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L];        h.bQ[i] = critic_params + i * Pc + c->c_b[L];
+                h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
+                h.p_dw[i] = ws + w.p_dw[i]; h.p_dbh[i] = ws + w.p_dbh[i]; h.p_db[i] = ws + w.p_db[i];
+            }
+            h.ret = batch.ret; h.boot = batch.boot; h.y = ws + w.y; h.p_loss = ws + w.p_loss;
+            if ((e = critic_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
+            head_parts = h.nwg;
         }
-        h.ret = batch.ret; h.boot = batch.boot; h.y = ws + w.y; h.p_loss = ws + w.p_loss;
-        if ((e = critic_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
-        head_parts = h.nwg;
 
         // 5. backward data path: delta_{l-1} = (delta_l W_l^T) * ELU'(z_{l-1}), bias grads as column sums
         for (int l = L; l >= 2; --l) {
@@ -788,11 +844,21 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
                     ps.push_back(p); offs.push_back(i * Pc + c->c_w[l - 1]);
                 }
             }
+            if (dist) {
+                const int la = c->cfg.num_atoms;
+                GemmProb p = prob(HL, la, nullptr, la, EPI_STORE);
+                add_seg(p, ws + w.hQ[i][L], HL, ws + w.lgQ[i], la, B);
+                ps.push_back(p); offs.push_back(i * Pc + c->c_w[L]);
+            }
         }
         if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st)) != hipSuccess) return E.hip(e, who);
     }
     // 7. remaining reductions (last hidden bias, output layer) + Adam + loss scalars
     for (int i = 0; i < 2; ++i) {
+        if (dist) {
+            red(adm, i * Pc + c->c_b[L], ws + w.p_dbo[i], c->cfg.num_atoms, head_parts, c->cfg.num_atoms);
+            continue;
+        }
         red(adm, i * Pc + c->c_b[L - 1], ws + w.p_dbh[i], HL, head_parts, HL);
         red(adm, i * Pc + c->c_w[L], ws + w.p_dw[i], HL, head_parts, HL);
         red(adm, i * Pc + c->c_b[L], ws + w.p_db[i], 1, head_parts, 1);
@@ -886,17 +952,45 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
                                           l > 1 ? ws + w.hQ[i][l - 1] : nullptr, ws + w.hQ[i][l], B));
             if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
         }
-        // 3. heads: J partials and the delta entering the smaller critic
-        HeadArgs h;
-        std::memset(&h, 0, sizeof(h));
-        h.B = B; h.H = HL; h.nwg = head_workgroups(B);
-        for (int i = 0; i < 2; ++i) {
-            h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L]; h.bQ[i] = critic_params + i * Pc + c->c_b[L];
-            h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
+        if (distributional(&c->cfg)) {
+            // 3. logits, J partials from the distribution means, dJ/dlogits, delta of the last hidden layer
+            const int la = c->cfg.num_atoms;
+            std::vector<GemmProb> ps;
+            for (int i = 0; i < 2; ++i) {
+                GemmProb pq = prob(B, la, ws + w.lgQ[i], la, EPI_BIAS);
+                add_seg(pq, ws + w.hQ[i][L], HL, critic_params + i * Pc + c->c_w[L], la, HL);
+                pq.bias = critic_params + i * Pc + c->c_b[L];
+                ps.push_back(pq);
+            }
+            if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
+            DistHeadArgs h;
+            std::memset(&h, 0, sizeof(h));
+            h.B = B; h.atoms = la; h.nwg = dist_head_workgroups(B); h.v_min = c->cfg.v_min; h.v_max = c->cfg.v_max;
+            for (int i = 0; i < 2; ++i) h.logitsQ[i] = ws + w.lgQ[i];
+            h.p_loss = ws + w.p_loss;
+            if ((e = dist_policy_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
+            loss_parts = h.nwg;
+            std::vector<GemmProb> pb;
+            for (int i = 0; i < 2; ++i) {
+                GemmProb p = prob(B, HL, ws + w.dQ[i][L], HL, EPI_MUL_DELU);
+                add_seg(p, ws + w.lgQ[i], la, critic_params + i * Pc + c->c_w[L], la, la);
+                p.aux = ws + w.hQ[i][L]; p.ldaux = HL;
+                pb.push_back(p);
+            }
+            if ((e = run_auto(GEMM_NT, pb, st)) != hipSuccess) return E.hip(e, who);
+        } else {
+            // 3. heads: J partials and the delta entering the smaller critic
+            HeadArgs h;
+            std::memset(&h, 0, sizeof(h));
+            h.B = B; h.H = HL; h.nwg = head_workgroups(B);
+            for (int i = 0; i < 2; ++i) {
+                h.hQ[i] = ws + w.hQ[i][L]; h.wQ[i] = critic_params + i * Pc + c->c_w[L]; h.bQ[i] = critic_params + i * Pc + c->c_b[L];
+                h.dQ[i] = ws + w.dQ[i][L]; h.q[i] = ws + w.q[i];
+            }
+            h.p_loss = ws + w.p_loss;
+            if ((e = policy_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
+            loss_parts = h.nwg;
         }
-        h.p_loss = ws + w.p_loss;
-        if ((e = policy_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
-        loss_parts = h.nwg;
         // 4. critic backward data path down to layer 1
         for (int l = L; l >= 2; --l) {
             std::vector<GemmProb> ps;

@@ -274,7 +274,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
         const int n = n0 + (wn * TN + j) * 32 + l32;
         const bool n_ok = n < N;
         float bias = 0.f;
-        if (n_ok && (epi == EPI_BIAS_ELU || epi == EPI_BIAS_TANH || epi == EPI_BIAS_TANH_NOISE)) bias = P.bias[n];
+        if (n_ok && (epi == EPI_BIAS_ELU || epi == EPI_BIAS_TANH || epi == EPI_BIAS_TANH_NOISE || epi == EPI_BIAS)) bias = P.bias[n];
         float csum = 0.f;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -288,6 +288,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
                     // rounding of the accumulation that produced x
                     case EPI_BIAS_ELU: x += bias; x = x > 0.f ? x : __expf(x) - 1.f; break;
                     case EPI_BIAS_TANH: x = tanhf(x + bias); break;
+                    case EPI_BIAS: x += bias; break;
                     case EPI_BIAS_TANH_NOISE:
                         x = tanhf(x + bias);
                         if (NOISE) x = fminf(fmaxf(x + exploration_noise(g.noise, m, n), -1.f), 1.f);

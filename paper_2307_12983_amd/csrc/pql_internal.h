@@ -17,7 +17,7 @@ enum KernelId : int {
     KID_GEMM = 0, KID_PUSH = 15, KID_SAMPLE = 16, KID_HEAD_CRITIC = 17, KID_HEAD_POLICY = 18,
     KID_ADAM = 19, KID_SOFT_UPDATE = 20, KID_COPY = 21, KID_FUSED_CRITIC = 22, KID_FUSED_POLICY = 23,
     KID_FUSED_ACT = 24, KID_TRANSPOSE = 25, KID_ADAM_CLIP = 26, KID_OBS_STATS = 27, KID_OBS_MERGE = 28,
-    KID_NORMALIZE = 29, KID_COUNT = 30
+    KID_NORMALIZE = 29, KID_DIST_CRITIC = 30, KID_DIST_POLICY = 31, KID_COUNT = 32
 };
 const char* kernel_name(int kid);
 bool prof_active();
@@ -55,7 +55,8 @@ enum GemmEpilogue : int {
     EPI_BIAS_TANH = 2,      // C = tanh(acc + bias[n])
     EPI_BIAS_TANH_NOISE = 3,// C = clip(tanh(acc + bias[n]) + sigma_m * eps, -1, 1)
     EPI_MUL_DELU = 4,       // C = acc * ELU'(z) with ELU'(z) recovered from aux = ELU(z)
-    EPI_MUL_DTANH = 5       // C = acc * (1 - aux^2), aux = tanh(z)
+    EPI_MUL_DTANH = 5,      // C = acc * (1 - aux^2), aux = tanh(z)
+    EPI_BIAS = 6            // C = acc + bias[n]  (logits of a distributional critic)
 };
 
 struct GemmSeg {
@@ -160,9 +161,24 @@ struct HeadArgs {
     float* p_loss;          // [2][nwg] (critic) or [1][nwg] (policy)
 };
 
+// Heads of the distributional critics (PQL-D): one wavefront per row, lane = atom.
+constexpr int DIST_MAX_ATOMS = 64;
+struct DistHeadArgs {
+    int B, atoms, nwg;
+    float v_min, v_max;
+    const float* logitsT[2];    // [B][atoms] target critics at (s', pi^v(s'))   (critic update only)
+    float* logitsQ[2];          // [B][atoms] online critics; overwritten with dLoss/dlogits
+    const float* ret; const float* boot;
+    float* p_db[2];             // [nwg][atoms] partial sums of the output-bias gradient (critic update only)
+    float* p_loss;              // [2][nwg] (critic) or [1][nwg] (policy)
+};
+hipError_t dist_critic_head_launch(const DistHeadArgs& a, hipStream_t stream);
+hipError_t dist_policy_head_launch(const DistHeadArgs& a, hipStream_t stream);
+
 hipError_t critic_head_launch(const HeadArgs& a, hipStream_t stream);
 hipError_t policy_head_launch(const HeadArgs& a, hipStream_t stream);
 int head_workgroups(int B);
+int dist_head_workgroups(int B);
 
 // ---- replay + elementwise ---------------------------------------------------------------
 struct PushArgs {

@@ -309,6 +309,125 @@ __global__ __launch_bounds__(64 * HEAD_WAVES) void head_kernel(const HeadArgs a)
     }
 }
 
+// =============================================================================================
+// Heads of the distributional critics (PQL-D: categorical distribution over fixed atoms z_k on
+// [v_min, v_max], categorical projection of the n-step target, cross-entropy).  One wavefront per
+// row, lane k holds atom k.
+// =============================================================================================
+__device__ inline float wave_max(float x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+
+// Softmax over the lanes < atoms: returns p_k, and log p_k through `logp` (0 / -inf-free for idle lanes).
+__device__ inline float lane_softmax(float logit, bool live, float& logp) {
+    const float mx = wave_max(live ? logit : -3.0e38f);
+    const float e = live ? expf(logit - mx) : 0.f;
+    const float s = wave_sum(e);
+    logp = live ? (logit - mx) - logf(s) : 0.f;
+    return e / s;
+}
+
+template <bool POLICY>
+__global__ __launch_bounds__(64 * HEAD_WAVES) void dist_head_kernel(const DistHeadArgs a) {
+    __shared__ float lds[HEAD_WAVES][2][64];
+    __shared__ float lds_loss[HEAD_WAVES][2];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l = a.atoms, B = a.B;
+    const bool live = lane < l;
+    const int gw = blockIdx.x * HEAD_WAVES + wave, nw = gridDim.x * HEAD_WAVES;
+    const float dz = (a.v_max - a.v_min) / (float)(l - 1);
+    const float z = a.v_min + (float)lane * dz;
+    const float invB = 1.f / (float)B;
+    float loss0 = 0.f, loss1 = 0.f, db0 = 0.f, db1 = 0.f;
+
+    for (int row = gw; row < B; row += nw) {
+        const size_t at = (size_t)row * l + lane;
+        float lp0, lp1;
+        const float p0 = lane_softmax(live ? a.logitsQ[0][at] : 0.f, live, lp0);
+        const float p1 = lane_softmax(live ? a.logitsQ[1][at] : 0.f, live, lp1);
+        float d0, d1;
+        if (POLICY) {
+            // Q_i = sum_k p_ik z_k; maximise min(Q_1, Q_2): dJ/dlogit_k = -(1/B) p_k (z_k - Q) for
+            // the smaller critic (ties: Q_1), 0 for the other
+            const float q0 = wave_sum(p0 * z), q1 = wave_sum(p1 * z);
+            const bool pick0 = q0 <= q1;
+            loss0 += pick0 ? q0 : q1;
+            d0 = pick0 ? -invB * p0 * (z - q0) : 0.f;
+            d1 = pick0 ? 0.f : -invB * p1 * (z - q1);
+        } else {
+            float unused;
+            const float t0 = lane_softmax(live ? a.logitsT[0][at] : 0.f, live, unused);
+            const float t1 = lane_softmax(live ? a.logitsT[1][at] : 0.f, live, unused);
+            const float qt0 = wave_sum(t0 * z), qt1 = wave_sum(t1 * z);
+            const float pn = qt0 <= qt1 ? t0 : t1;           // next-state distribution: the smaller mean
+            // atom j moves to clip(ret + boot z_j); position in units of the atom spacing
+            const float tz = fminf(fmaxf(a.ret[row] + a.boot[row] * z, a.v_min), a.v_max);
+            const float pos = (tz - a.v_min) / dz;
+            float m = 0.f;
+            for (int j = 0; j < l; ++j) {               // j is wave-uniform: lane j's values come as scalars
+                const float pos_j = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pos), j));
+                const float pn_j = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pn), j));
+                const float wgt = 1.f - fabsf(pos_j - (float)lane);
+                m += pn_j * fminf(fmaxf(wgt, 0.f), 1.f);
+            }
+            if (!live) m = 0.f;
+            const float S = wave_sum(m);
+            loss0 -= wave_sum(m * lp0);
+            loss1 -= wave_sum(m * lp1);
+            d0 = (p0 * S - m) * invB;
+            d1 = (p1 * S - m) * invB;
+            db0 += d0;
+            db1 += d1;
+        }
+        if (live) {
+            a.logitsQ[0][at] = d0;
+            a.logitsQ[1][at] = d1;
+        }
+    }
+    const int wg = blockIdx.x, nwg = gridDim.x;
+    lds[wave][0][lane] = db0;
+    lds[wave][1][lane] = db1;
+    if (lane == 0) { lds_loss[wave][0] = loss0; lds_loss[wave][1] = loss1; }
+    __syncthreads();
+    if (!POLICY && threadIdx.x < 128) {
+        const int i = threadIdx.x >> 6;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < HEAD_WAVES; ++w) sum += lds[w][i][lane];
+        if (live) a.p_db[i][(size_t)wg * l + lane] = sum;
+    }
+    if (threadIdx.x < 2) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < HEAD_WAVES; ++w) sum += lds_loss[w][threadIdx.x];
+        if (threadIdx.x == 0) a.p_loss[wg] = sum;
+        else if (!POLICY) a.p_loss[nwg + wg] = sum;
+    }
+}
+
+hipError_t dist_critic_head_launch(const DistHeadArgs& a, hipStream_t stream) {
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, dist_head_kernel<false>, dim3(a.nwg), dim3(64 * HEAD_WAVES), 0, stream, a);
+    prof_commit(ps, KID_DIST_CRITIC, 0.0, 24.0 * (double)a.B * a.atoms);    // 4 logit rows read, 2 written
+    return hipGetLastError();
+}
+
+hipError_t dist_policy_head_launch(const DistHeadArgs& a, hipStream_t stream) {
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, dist_head_kernel<true>, dim3(a.nwg), dim3(64 * HEAD_WAVES), 0, stream, a);
+    prof_commit(ps, KID_DIST_POLICY, 0.0, 16.0 * (double)a.B * a.atoms);
+    return hipGetLastError();
+}
+
+int dist_head_workgroups(int B) {
+    int n = (B + HEAD_WAVES * 2 - 1) / (HEAD_WAVES * 2);   // about 2 rows per wavefront
+    if (n < 1) n = 1;
+    if (n > 1024) n = 1024;
+    return n;
+}
+
 int head_workgroups(int B) {
     int n = (B + HEAD_WAVES * 8 - 1) / (HEAD_WAVES * 8);   // about 8 rows per wavefront
     if (n < 1) n = 1;

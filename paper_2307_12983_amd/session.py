@@ -20,7 +20,7 @@ class LearnerSession:
         self.device = device
         self.max_batch = int(max_batch or max(w.batch, w.num_envs))
         self.cfg = B.make_config(w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.nstep, w.gamma, w.hidden,
-                                 self.max_batch, w.rng_seed if seed is None else seed)
+                                 self.max_batch, w.rng_seed if seed is None else seed, w.num_atoms, w.v_min, w.v_max)
         self.ctx = B.Context(self.cfg)
         self.rows = self.ctx.replay_rows()
         self.storage = B.Storage(self.rows, w.num_envs, w.obs_dim, w.act_dim, device)

@@ -57,6 +57,9 @@ class Workload:
     obs_norm_eps: float = _f32(1e-5)
     obs_loc: float = 0.0           # synthetic observations are obs_loc + obs_scale * N(0, 1)
     obs_scale: float = 1.0
+    num_atoms: int = 0             # PQL-D: 51 atoms on (-10, 10); 0 = scalar critics
+    v_min: float = -10.0
+    v_max: float = 10.0
 
     @property
     def rows(self) -> int:
@@ -80,7 +83,7 @@ class Workload:
         return layer_dims(self.obs_dim, self.hidden, self.act_dim)
 
     def critic_dims(self) -> List[Tuple[int, int]]:
-        return layer_dims(self.obs_dim + self.act_dim, self.hidden, 1)
+        return layer_dims(self.obs_dim + self.act_dim, self.hidden, self.num_atoms if self.num_atoms >= 2 else 1)
 
     def replace(self, **kw) -> "Workload":
         d = dict(self.__dict__)

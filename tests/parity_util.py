@@ -80,7 +80,8 @@ def oracle_ring(w: W.Workload):
 
 def oracle_learner(w: W.Workload, actor, critic):
     return O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps,
-                     max_grad_norm=(w.max_grad_norm if w.max_grad_norm > 0 else None))
+                     max_grad_norm=(w.max_grad_norm if w.max_grad_norm > 0 else None),
+                     v_min=(w.v_min if w.num_atoms >= 2 else None), v_max=(w.v_max if w.num_atoms >= 2 else None))
 
 
 def oracle_normalizer(w: W.Workload):

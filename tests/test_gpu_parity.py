@@ -393,6 +393,50 @@ def test_ant_full_batch_paper_defaults(torch_cuda):
 
 
 # ---------------------------------------------------------------------------------------------
+# PQL-D: distributional critics (51 atoms on (-10, 10) in the paper's appendix)
+def distributional(w, atoms=51, v_min=-10.0, v_max=10.0):
+    return w.replace(num_atoms=atoms, v_min=float(np.float32(v_min)), v_max=float(np.float32(v_max)))
+
+
+DIST_CASES = {
+    "tiny_d": (SMALL["tiny"], 51, -10.0, 10.0),
+    "ragged_d": (SMALL["ragged"], 11, -4.0, 4.0),          # few atoms on a narrow support: much clipping at the bounds
+    "ant_s_d": (SMALL["ant_s"], 51, -10.0, 10.0),
+    "shadow_s_d": (SMALL["shadow_s"], 64, -10.0, 10.0),    # the largest supported atom count
+    "fused_l3_d": (SMALL["fused_l3"], 2, -1.0, 1.0),       # the smallest
+}
+
+
+@pytest.mark.parametrize("case", list(DIST_CASES))
+def test_one_update_distributional(torch_cuda, case):
+    base, atoms, lo, hi = DIST_CASES[case]
+    w = distributional(base, atoms, lo, hi)
+    say("case", case, "atoms", atoms, "critic dims", w.critic_dims())
+    res = one_step(torch_cuda, w, min(w.rows, w.nstep + 4))
+    say(case, res)
+
+
+def test_one_update_distributional_with_paper_defaults(torch_cuda):
+    w = paper_defaults(distributional(SMALL["ant_s"]))
+    res = one_step(torch_cuda, w, w.nstep + 4)
+    say("ant_s, 51 atoms, clipping + standardisation", res)
+
+
+@pytest.mark.parametrize("case", ["tiny_d", "ant_s_d"])
+def test_100_updates_distributional(torch_cuda, case):
+    base, atoms, lo, hi = DIST_CASES[case]
+    w = distributional(base, atoms, lo, hi)
+    res = many_steps(torch_cuda, w, w.rows, 100, actor_every=2)
+    say(case, "100 steps", res)
+
+
+def test_distributional_full_batch_ant(torch_cuda):
+    w = distributional(W.WORKLOADS["ant"])
+    res = one_step(torch_cuda, w, w.nstep + 8)
+    say("ant, 51 atoms, batch 8192", res)
+
+
+# ---------------------------------------------------------------------------------------------
 def test_ant_full_ring_as_benchmarked(torch_cuda):
     """The benchmark's launch configuration: ant-shaped workload with the whole ring filled and
     wrapped (T = 244 rows of 4096 environments), batch 8192: sampled indices and gathered rows

@@ -39,6 +39,8 @@ def cases():
         "ant_s": Wk["ant"].replace(name="ant_s", num_envs=96, capacity=96 * 13, batch=1000),
         "tiny_defaults": Wk["tiny"].replace(name="tiny_defaults", max_grad_norm=0.5, obs_norm=True, obs_loc=3.0,
                                             obs_scale=2.0, index=13),
+        "ragged_dist": Wk["tiny"].replace(name="ragged_dist", obs_dim=13, act_dim=3, num_envs=50, capacity=50 * 11,
+                                          batch=333, hidden=(96, 40), index=14, num_atoms=51),
     }
 
 
@@ -56,7 +58,7 @@ def build(torch, w, concurrent, horizon=1):
     return s, ps, ring, nz, env_host
 
 
-@pytest.mark.parametrize("case,horizon", [("tiny", 1), ("ragged", 2), ("ant_s", 1), ("tiny_defaults", 1)])
+@pytest.mark.parametrize("case,horizon", [("tiny", 1), ("ragged", 2), ("ant_s", 1), ("tiny_defaults", 1), ("ragged_dist", 1)])
 def test_scheme_matches_oracle(torch_cuda, case, horizon):
     torch = torch_cuda
     w = CASES[case]
