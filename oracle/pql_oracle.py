@@ -34,6 +34,8 @@ MASK64 = 0xFFFFFFFFFFFFFFFF
 STREAM_SAMPLE = 1   # index sampling draws
 STREAM_ACT = 2      # exploration-noise draws
 STREAM_STATE = 3    # the P-learner's draws of states
+STREAM_SAC_TARGET = 4   # PQL + SAC: action noise of the V-learner's target sample a' ~ pi^v(.|s')
+STREAM_SAC_POLICY = 5   # PQL + SAC: action noise of the P-learner's reparameterised sample
 
 
 # --------------------------------------------------------------------------------------
@@ -508,10 +510,10 @@ def exploration_sigma(num_envs: int, sigma_min: float, sigma_max: float):
     return sigma_min + (i / (num_envs - 1)) * (sigma_max - sigma_min)
 
 
-def gaussian_noise(seed: int, call: int, count: int):
+def gaussian_noise(seed: int, call: int, count: int, stream: int = STREAM_ACT):
     """Standard normal draws, one per element index 0..count-1: Box-Muller on two 24-bit
     uniforms u = ((word >> 8) + 0.5) / 2^24 taken from generator words 0 and 1."""
-    w0, w1, _, _ = rng_words(seed, STREAM_ACT, call, np.arange(count, dtype=np.uint64))
+    w0, w1, _, _ = rng_words(seed, stream, call, np.arange(count, dtype=np.uint64))
     u1 = ((w0 >> np.uint64(8)).astype(np.float64) + 0.5) * 2.0 ** -24
     u2 = ((w1 >> np.uint64(8)).astype(np.float64) + 0.5) * 2.0 ** -24
     return np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
@@ -528,6 +530,89 @@ def actor_act(actor_params, actor_dims, obs, sigma_min, sigma_max, seed, call):
 
 
 # --------------------------------------------------------------------------------------
+# PQL + SAC (Section 3: the scheme extends to SAC; appendix paragraph "PQL for SAC";
+# Table B.1: learnable entropy coefficient).  The paper gives no formulas: the definitions
+# are those of Haarnoja et al. 2018 (soft actor-critic with automatic temperature), written
+# out for a tanh-squashed diagonal Gaussian policy.
+# --------------------------------------------------------------------------------------
+LOG_STD_MIN, LOG_STD_MAX = -5.0, 2.0
+
+
+def sac_policy_sample(actor_params, actor_dims, obs, eps):
+    """Stochastic policy: the network's last layer has 2a outputs (mu, raw log sigma);
+    log sigma = clip(raw, -5, 2); u = mu + sigma * eps; a = tanh(u);
+    log pi(a|s) = sum_d [-eps_d^2 / 2 - log sigma_d - log(2 pi) / 2 - log(1 - tanh(u_d)^2)],
+    the last term evaluated as 2 (log 2 - u - softplus(-2u)).  Returns (a, log pi, cache)."""
+    layers = unpack(actor_params, actor_dims)
+    zs, hs = mlp_forward(layers, obs)
+    a_dim = hs[-1].shape[1] // 2
+    mu, raw = hs[-1][:, :a_dim], hs[-1][:, a_dim:]
+    log_std = np.clip(raw, LOG_STD_MIN, LOG_STD_MAX)
+    std = np.exp(log_std)
+    u = mu + std * eps
+    act = np.tanh(u)
+    log_det = 2.0 * (np.log(2.0) - u - np.logaddexp(0.0, -2.0 * u))          # log(1 - tanh(u)^2)
+    logp = np.sum(-0.5 * eps * eps - log_std - 0.5 * np.log(2.0 * np.pi) - log_det, axis=1)
+    return act, logp, (layers, zs, hs, raw, std, u, act)
+
+
+def sac_td_target(batch, actor_target_params, critic_target_params, actor_dims, critic_dims, log_alpha, eps):
+    """Soft target with n-step quantities: a' ~ pi^v(.|s') (the V-learner's lagged policy,
+    Section 3.2), y = ret + boot * (min_i Q'_i(s', a') - alpha log pi^v(a'|s'))."""
+    a_next, logp, _ = sac_policy_sample(actor_target_params, actor_dims, batch["next_obs"], eps)
+    t1, t2 = split_twin(critic_target_params)
+    q = np.minimum(critic_forward(t1, critic_dims, batch["next_obs"], a_next),
+                   critic_forward(t2, critic_dims, batch["next_obs"], a_next))
+    return np.asarray(batch["ret"], np.float64) + np.asarray(batch["boot"], np.float64) * (q - np.exp(log_alpha) * logp)
+
+
+def sac_actor_loss_and_grads(actor_params, critic_params, actor_dims, critic_dims, obs, log_alpha, eps):
+    """J = mean_b [alpha log pi(a_b|s_b) - min_i Q_i(s_b, a_b)] with the reparameterised
+    sample a_b = tanh(mu + sigma eps_b); alpha and the critics are constants; ties in the
+    min go to Q_1; the clip of log sigma passes no gradient outside (-5, 2).
+    Returns ((Q term, entropy term) of J, flat gradient, mean log pi)."""
+    obs = np.asarray(obs, np.float64)
+    B = obs.shape[0]
+    alpha = np.exp(log_alpha)
+    act, logp, (a_layers, a_zs, a_hs, raw, std, u, _) = sac_policy_sample(actor_params, actor_dims, obs, eps)
+    x = np.concatenate([obs, act], axis=1)
+    qs, caches = [], []
+    for p in split_twin(critic_params):
+        layers = unpack(p, critic_dims)
+        zs, hs = mlp_forward(layers, x)
+        qs.append(hs[-1][:, 0])
+        caches.append((layers, zs, hs))
+    pick1 = qs[0] <= qs[1]
+    q_term = -float(np.mean(np.where(pick1, qs[0], qs[1])))
+    ent_term = float(alpha * np.mean(logp))
+    d_act = np.zeros_like(act)
+    for sel, (layers, zs, hs) in zip((pick1, ~pick1), caches):
+        _, d_x = mlp_backward(layers, zs, hs, np.where(sel, -1.0 / B, 0.0)[:, None])
+        d_act += d_x[:, obs.shape[1]:]
+    d_u = d_act * (1.0 - act * act) + (alpha / B) * 2.0 * act       # d log pi / du = 2 tanh(u)
+    d_mu = d_u
+    inside = (raw > LOG_STD_MIN) & (raw < LOG_STD_MAX)
+    d_raw = np.where(inside, d_u * std * eps - alpha / B, 0.0)      # d log pi / d log sigma = -1 + 2 a sigma eps
+    grads, _ = mlp_backward(a_layers, a_zs, a_hs, np.concatenate([d_mu, d_raw], axis=1))
+    return (q_term, ent_term), pack(grads), float(np.mean(logp))
+
+
+def sac_actor_act(actor_params, actor_dims, obs, seed, call):
+    """The SAC Actor's step: a sample of the stochastic policy (its only exploration), noise
+    element index = env * act_dim + dim on the exploration-noise stream."""
+    N = np.asarray(obs).shape[0]
+    a_dim = actor_dims[-1][1] // 2
+    eps = gaussian_noise(seed, call, N * a_dim, STREAM_ACT).reshape(N, a_dim)
+    return sac_policy_sample(actor_params, actor_dims, obs, eps)[0]
+
+
+def sac_alpha_grad(log_alpha, mean_logp, target_entropy):
+    """Temperature objective J(alpha) = -alpha * mean_b (log pi + H_target), alpha = exp(log alpha)
+    optimised in log alpha: dJ / d log alpha = -alpha (mean log pi + H_target)."""
+    return -np.exp(log_alpha) * (mean_logp + target_entropy)
+
+
+# --------------------------------------------------------------------------------------
 # A whole learner, for multi-step parity runs
 # --------------------------------------------------------------------------------------
 class Learner:
@@ -535,9 +620,14 @@ class Learner:
     the paper's loops do.  Parameters enter as fp32 arrays and are promoted."""
 
     def __init__(self, actor_dims, critic_dims, actor_params, critic_params, lr, gamma, tau,
-                 beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=None, v_min=None, v_max=None):
+                 beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=None, v_min=None, v_max=None,
+                 sac=False, log_alpha=0.0, target_entropy=None, seed=0):
         self.actor_dims, self.critic_dims = actor_dims, critic_dims
         self.v_min, self.v_max = v_min, v_max         # set: PQL-D (critic outputs are logits over atoms)
+        self.sac, self.seed = sac, seed               # PQL + SAC: stochastic policy, learnable temperature
+        self.log_alpha, self.al_m, self.al_v = float(log_alpha), 0.0, 0.0
+        self.target_entropy = target_entropy
+        self.mean_logp = 0.0
         self.max_grad_norm = max_grad_norm            # None: no clipping
         self.critic_grad_norm = self.actor_grad_norm = 0.0
         self.actor = np.asarray(actor_params, np.float64).copy()
@@ -550,7 +640,14 @@ class Learner:
         self.beta1, self.beta2, self.eps = beta1, beta2, eps
 
     def critic_update(self, batch):
-        if self.v_min is not None:
+        if self.sac:
+            a_dim = self.actor_dims[-1][1] // 2
+            B = np.asarray(batch["ret"]).shape[0]
+            eps_n = gaussian_noise(self.seed, self.c_t, B * a_dim, STREAM_SAC_TARGET).reshape(B, a_dim)
+            y = sac_td_target(batch, self.actor_lag, self.critic_target, self.actor_dims, self.critic_dims,
+                              self.log_alpha, eps_n)
+            losses, g = critic_loss_and_grads(self.critic, self.critic_dims, batch, y)
+        elif self.v_min is not None:
             m = dist_td_target(batch, self.actor_lag, self.critic_target, self.actor_dims, self.critic_dims,
                                self.v_min, self.v_max)
             losses, g = dist_critic_loss_and_grads(self.critic, self.critic_dims, batch, m)
@@ -567,7 +664,13 @@ class Learner:
         self.critic_target = soft_update(self.critic, self.critic_target, self.tau)
 
     def actor_update(self, obs):
-        if self.v_min is not None:
+        if self.sac:
+            a_dim = self.actor_dims[-1][1] // 2
+            B = np.asarray(obs).shape[0]
+            eps_n = gaussian_noise(self.seed, self.a_t, B * a_dim, STREAM_SAC_POLICY).reshape(B, a_dim)
+            J, g, self.mean_logp = sac_actor_loss_and_grads(self.actor, self.critic, self.actor_dims, self.critic_dims,
+                                                            obs, self.log_alpha, eps_n)
+        elif self.v_min is not None:
             J, g = dist_actor_loss_and_grads(self.actor, self.critic, self.actor_dims, self.critic_dims, obs,
                                              self.v_min, self.v_max)
         else:
@@ -576,6 +679,10 @@ class Learner:
         self.a_t += 1
         self.actor, self.a_m, self.a_v = adam_step(self.actor, g, self.a_m, self.a_v, self.a_t,
                                                    self.lr, self.beta1, self.beta2, self.eps)
+        if self.sac:    # temperature step on the same batch, with the log-probabilities of the sampled actions
+            ga = sac_alpha_grad(self.log_alpha, self.mean_logp, self.target_entropy)
+            self.log_alpha, self.al_m, self.al_v = (float(x) for x in adam_step(
+                self.log_alpha, ga, self.al_m, self.al_v, self.a_t, self.lr, self.beta1, self.beta2, self.eps))
         return J, g
 
     def sync_lagged_policy(self):
