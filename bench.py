@@ -89,7 +89,9 @@ def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0, paralle
     actor, critic = W.init_networks(w)
     L = O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps,
                   max_grad_norm=(w.max_grad_norm if w.max_grad_norm > 0 else None),
-                  v_min=(w.v_min if w.num_atoms >= 2 else None), v_max=(w.v_max if w.num_atoms >= 2 else None))
+                  v_min=(w.v_min if w.num_atoms >= 2 else None), v_max=(w.v_max if w.num_atoms >= 2 else None),
+                  sac=w.sac, log_alpha=float(np.log(np.float64(w.init_alpha))), target_entropy=w.target_entropy,
+                  seed=w.rng_seed)
     done_steps, tick, acts = 0, 0, 0
     t0 = time.perf_counter()
     if parallel:
@@ -109,7 +111,10 @@ def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0, paralle
             row = env_rows_host[tick % len(env_rows_host)]
             tick += 1
             seen = row["obs"] if nz is None else nz.normalize(row["obs"])
-            a = O.actor_act(L.actor, w.actor_dims(), seen, w.sigma_min, w.sigma_max, w.rng_seed, acts)
+            if w.sac:
+                a = O.sac_actor_act(L.actor, w.actor_dims(), seen, w.rng_seed, acts)
+            else:
+                a = O.actor_act(L.actor, w.actor_dims(), seen, w.sigma_min, w.sigma_max, w.rng_seed, acts)
             acts += 1
             ring.push(row["obs"], a.astype(np.float32), row["rew"], row["next_obs"], row["done"])
             if nz is not None:
@@ -144,6 +149,8 @@ def main():
                          "standardisation and gradient clipping at 0.5")
     ap.add_argument("--atoms", type=int, default=0,
                     help="distributional critics (PQL-D) with this many atoms on (-10, 10); the paper uses 51")
+    ap.add_argument("--sac", action="store_true",
+                    help="PQL + SAC: tanh-Gaussian policy, soft target, learnable temperature")
     ap.add_argument("--schedule", default="serial", choices=["serial", "parallel", "parallel-1stream"],
                     help="serial: every call on one stream, networks shared by all parts (default).  parallel: the "
                          "Actor, V-learner and P-learner on three streams with local network copies exchanged once "
@@ -168,6 +175,8 @@ def main():
         w = w.replace(max_grad_norm=0.5, obs_norm=True)
     if args.atoms >= 2:
         w = w.replace(num_atoms=args.atoms)
+    if args.sac:
+        w = w.replace(sac=True)
     sess = LearnerSession(w)
     rng = W.data_rng(w)
     n_fill = args.fill_rows or w.rows
@@ -272,7 +281,8 @@ def main():
                                                                 "; observation standardisation and gradient clipping 0.5 on"
                                                                 if args.paper_defaults else "")
                                + ("; distributional critics, %d atoms on (%g, %g)" % (w.num_atoms, w.v_min, w.v_max)
-                                  if w.num_atoms >= 2 else ""),
+                                  if w.num_atoms >= 2 else "")
+                               + ("; SAC variant (stochastic policy, learnable temperature)" if w.sac else ""),
                    "rows_filled": n_fill, "schedule": args.schedule},
         "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,

@@ -85,6 +85,9 @@ typedef struct {
                                       /* (PQL-D; the paper's appendix uses 51) with that many     */
                                       /* atoms                                                    */
     float    v_min, v_max;            /* support of the atoms, v_max > v_min (paper: -10, 10)     */
+    int32_t  stochastic_policy;       /* 0: deterministic policy with exploration noise (PQL).    */
+                                      /* 1: tanh-squashed Gaussian policy with a learnable        */
+                                      /* temperature (PQL + SAC); scalar critics, act_dim <= 31   */
 } pql_config;
 
 /* [device] replay storage, sizes as under "Replay layout". */
@@ -217,6 +220,32 @@ int32_t pql_actor_update(pql_ctx* ctx, float* actor_params, const float* critic_
  * touched. */
 int32_t pql_adam_step(pql_ctx* ctx, float* params, const float* grads, float* adam_m, float* adam_v,
                       int64_t count, pql_adam opt, int64_t t, void* stream);
+
+/* ---- PQL + SAC (Section 3: the scheme extends to SAC; appendix paragraph "PQL for SAC"; Table B.1
+ *      "Learnable Entropy Coefficient").  The paper gives no formulas; these are the definitions of
+ *      Haarnoja et al. 2018 with automatic temperature. ------------------------------------------ */
+
+/* With cfg.stochastic_policy = 1 the policy network has 2a outputs (mu, raw): log sigma = clip(raw, -5, 2),
+ * a = tanh(u), u = mu + sigma eps, eps ~ N(0, 1) per (row, action dimension) (element row * a + dim;
+ * generator stream 2 in pql_actor_act, 4 in pql_critic_update, 5 in pql_actor_update, call number = that
+ * call's counter), log pi(a|s) = sum_d [-eps^2/2 - log sigma - log(2 pi)/2 - log(1 - a^2)].
+ *   pql_actor_act     a sample of the policy; sigma_min / sigma_max are ignored.
+ *   pql_critic_update y = ret + boot * (min_i Q'_i(next_obs, a') - alpha log pi^v(a'|next_obs)), a' ~ pi^v.
+ *   pql_actor_update  J = mean_b [alpha log pi(a_b|obs_b) - min_i Q_i(obs_b, a_b)] with the reparameterised
+ *                     sample; the clip passes no gradient outside (-5, 2); then one Adam step (same
+ *                     constants, step number of this call) on log alpha for
+ *                     J(alpha) = -alpha mean_b (log pi(a_b|obs_b) + target_entropy).
+ *                     loss_out is float[4]: [0] = -mean_b min_i Q_i, [1] = gradient norm (as above),
+ *                     [2] = alpha mean_b log pi, [3] = mean_b log pi; J = [0] + [2].
+ * alpha = exp(temperature[0]); `temperature` is a caller-owned, caller-initialised [device] float[4]
+ * {log alpha, Adam m, Adam v, unused}, 16-byte aligned, that must be attached before the first update
+ * (PQL_ERR_NULL otherwise).  Errors: PQL_ERR_INVALID_ARG for a context with a deterministic policy. */
+int32_t pql_sac_attach(pql_ctx* ctx, float* temperature, float target_entropy);
+
+/* The V-learner's copy of the temperature (Section 3.1: each part works on local copies): while set,
+ * pql_critic_update reads log alpha from log_alpha[0] ([device]) instead of temperature[0].  NULL (and every
+ * pql_sac_attach) goes back to the attached block.  Host-side only. */
+int32_t pql_sac_attach_lagged(pql_ctx* ctx, const float* log_alpha);
 
 /* ---- observation standardisation (Table B.1 "Normalized Observations: True"; the mechanism is
  *      not described there) ---------------------------------------------------------------- */

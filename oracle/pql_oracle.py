@@ -722,6 +722,7 @@ class ParallelScheme:
         self.horizon, self.v_updates, self.p_updates = horizon, v_updates, p_updates
         self.pi_a = learner.actor.copy()              # the Actor's local policy
         self.q_p = learner.critic.copy()              # the P-learner's local critics
+        self.log_alpha_v = learner.log_alpha          # SAC variant: the V-learner's copy of the temperature
         learner.actor_lag = learner.actor.copy()      # pi^v
         self.sample_calls = self.state_calls = self.act_calls = 0
         self.period = 0
@@ -730,18 +731,24 @@ class ParallelScheme:
     def run_period(self, env_step, obs_rows):
         """obs_rows[t]: the observations s_t the Actor sees at step t of this period."""
         L = self.L
-        rec = dict(pi_a=self.pi_a.copy(), pi_v=L.actor_lag.copy(), q_p=self.q_p.copy(), rows=self.ring.count)
+        rec = dict(pi_a=self.pi_a.copy(), pi_v=L.actor_lag.copy(), q_p=self.q_p.copy(), rows=self.ring.count,
+                   log_alpha_v=self.log_alpha_v)
         # ---- Actor (Algorithm 1): roll out pi^a; the transitions are delivered at the boundary
         produced = []
         for t in range(self.horizon):
             s = obs_rows[t]
             seen = s if self.nz is None else self.nz.normalize(s)
-            a = actor_act(self.pi_a, L.actor_dims, seen, self.sigma_min, self.sigma_max, self.seed, self.act_calls)
+            if L.sac:
+                a = sac_actor_act(self.pi_a, L.actor_dims, seen, self.seed, self.act_calls)
+            else:
+                a = actor_act(self.pi_a, L.actor_dims, seen, self.sigma_min, self.sigma_max, self.seed, self.act_calls)
             self.act_calls += 1
             row = env_step(self.period, t, a)
             produced.append(dict(row, act=a.astype(np.float32)))
-        # ---- V-learner (Algorithm 3): critic updates with the lagged policy pi^v
+        # ---- V-learner (Algorithm 3): critic updates with the lagged policy pi^v (and its copy of the temperature)
         v_losses = []
+        log_alpha_p = L.log_alpha
+        L.log_alpha = self.log_alpha_v
         for _ in range(self.v_updates):
             b = gather_nstep(self.ring, sample_indices(self.ring, self.nstep, self.batch, self.seed, self.sample_calls),
                              self.nstep, L.gamma)
@@ -752,6 +759,7 @@ class ParallelScheme:
             losses, _ = L.critic_update(b)
             L.soft_update_targets()
             v_losses.append(losses)
+        L.log_alpha = log_alpha_p
         # ---- P-learner (Algorithm 2): policy updates against its local critics Q^p
         q_v = L.critic
         L.critic = self.q_p
@@ -772,6 +780,7 @@ class ParallelScheme:
         L.sync_lagged_policy()                        # pi^v <- pi^p
         self.pi_a = L.actor.copy()                    # pi^a <- pi^p
         self.q_p = L.critic.copy()                    # Q^p  <- Q^v
+        self.log_alpha_v = L.log_alpha
         rec.update(v_losses=v_losses, p_losses=p_losses, actions=[r["act"] for r in produced])
         self.trace.append(rec)
         self.period += 1

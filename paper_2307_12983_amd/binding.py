@@ -23,14 +23,15 @@ EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_coun
            "pql_workspace_bytes", "pql_last_error", "pql_get_state", "pql_set_state", "pql_replay_push",
            "pql_sample_nstep", "pql_gather_nstep", "pql_actor_act", "pql_critic_update", "pql_actor_update",
            "pql_soft_update", "pql_adam_step", "pql_profile_begin", "pql_profile_end",
-           "pql_obs_norm_bytes", "pql_obs_norm_attach", "pql_obs_norm_reset", "pql_sample_states"]
+           "pql_obs_norm_bytes", "pql_obs_norm_attach", "pql_obs_norm_reset", "pql_sample_states", "pql_sac_attach",
+           "pql_sac_attach_lagged"]
 
 
 class PqlConfig(C.Structure):
     _fields_ = [("obs_dim", C.c_int32), ("act_dim", C.c_int32), ("num_envs", C.c_int32), ("capacity", C.c_int64),
                 ("nstep", C.c_int32), ("gamma", C.c_float), ("n_hidden", C.c_int32),
                 ("hidden", C.c_int32 * PQL_MAX_HIDDEN), ("max_batch", C.c_int32), ("seed", C.c_uint64),
-                ("num_atoms", C.c_int32), ("v_min", C.c_float), ("v_max", C.c_float)]
+                ("num_atoms", C.c_int32), ("v_min", C.c_float), ("v_max", C.c_float), ("stochastic_policy", C.c_int32)]
 
 
 class PqlStorage(C.Structure):
@@ -98,6 +99,8 @@ def load_library() -> C.CDLL:
         "pql_obs_norm_bytes": (I64, [cfgp]),
         "pql_obs_norm_attach": (I32, [P, P, F]),
         "pql_obs_norm_reset": (I32, [P, P]),
+        "pql_sac_attach": (I32, [P, P, F]),
+        "pql_sac_attach_lagged": (I32, [P, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -107,13 +110,14 @@ def load_library() -> C.CDLL:
 
 
 def make_config(obs_dim, act_dim, num_envs, capacity, nstep, gamma, hidden: Sequence[int], max_batch, seed,
-                num_atoms=0, v_min=0.0, v_max=0.0) -> PqlConfig:
+                num_atoms=0, v_min=0.0, v_max=0.0, stochastic_policy=0) -> PqlConfig:
     cfg = PqlConfig()
     cfg.obs_dim, cfg.act_dim, cfg.num_envs, cfg.capacity = obs_dim, act_dim, num_envs, capacity
     cfg.nstep, cfg.gamma, cfg.n_hidden, cfg.max_batch, cfg.seed = nstep, gamma, len(hidden), max_batch, seed
     for i, h in enumerate(hidden[:PQL_MAX_HIDDEN]):
         cfg.hidden[i] = int(h)
     cfg.num_atoms, cfg.v_min, cfg.v_max = int(num_atoms), float(v_min), float(v_max)
+    cfg.stochastic_policy = int(stochastic_policy)
     return cfg
 
 
@@ -272,3 +276,9 @@ class Context:
 
     def pql_obs_norm_reset(self, stream=None):
         self._check(self.lib.pql_obs_norm_reset(self.h, _stream(stream)))
+
+    def pql_sac_attach(self, temperature, target_entropy):
+        self._check(self.lib.pql_sac_attach(self.h, _ptr(temperature), target_entropy))
+
+    def pql_sac_attach_lagged(self, log_alpha):
+        self._check(self.lib.pql_sac_attach_lagged(self.h, _ptr(log_alpha)))

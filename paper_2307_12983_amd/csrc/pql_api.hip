@@ -51,6 +51,9 @@ const char* kernel_name(int kid) {
         case KID_NORMALIZE: return "normalize_rows_kernel";
         case KID_DIST_CRITIC: return "dist_head_kernel_critic";
         case KID_DIST_POLICY: return "dist_head_kernel_policy";
+        case KID_SAC_SAMPLE: return "sac_sample_kernel";
+        case KID_SAC_GRAD: return "sac_grad_kernel";
+        case KID_SAC_ALPHA: return "sac_alpha_kernel";
         default: return "?";
     }
 }
@@ -81,6 +84,9 @@ struct pql_ctx {
     int64_t c_w[PQL_MAX_HIDDEN + 1], c_b[PQL_MAX_HIDDEN + 1], c_total;
     void* obs_norm;              // caller-owned device block of running observation statistics, or NULL
     float obs_eps;
+    float* temperature;          // caller-owned device floats {log alpha, Adam m, Adam v, -} of the SAC variant, or NULL
+    const float* temperature_v;  // the V-learner's copy of log alpha (defaults to the one above)
+    float target_entropy;
     std::string err;
 };
 
@@ -103,12 +109,17 @@ int validate_cfg(const pql_config* c) {
     if ((int64_t)c->max_batch * c->act_dim > 0xffffffffLL) return PQL_ERR_INVALID_ARG;   // 32-bit element counter
     if (c->num_atoms < 0 || c->num_atoms > DIST_MAX_ATOMS) return PQL_ERR_INVALID_ARG;
     if (c->num_atoms >= 2 && !(c->v_max > c->v_min)) return PQL_ERR_INVALID_ARG;
+    if (c->stochastic_policy != 0 && c->stochastic_policy != 1) return PQL_ERR_INVALID_ARG;
+    // the stochastic policy is built for scalar critics; its gradient kernel keeps 2a + 1 columns of 256 rows in LDS
+    if (c->stochastic_policy && (c->num_atoms >= 2 || c->act_dim > 31)) return PQL_ERR_INVALID_ARG;
     return PQL_OK;
 }
 
 // Outputs of one critic: 1 (scalar Q) or the number of atoms of a distributional critic.
 inline int critic_out(const pql_config* c) { return c->num_atoms >= 2 ? c->num_atoms : 1; }
 inline bool distributional(const pql_config* c) { return c->num_atoms >= 2; }
+// Outputs of the policy network: a (deterministic) or 2a (mean and log standard deviation).
+inline int actor_out(const pql_config* c) { return c->stochastic_policy ? 2 * c->act_dim : c->act_dim; }
 
 int64_t net_params(int in, const pql_config* c, int out, int64_t* w, int64_t* b) {
     int64_t off = 0;
@@ -166,6 +177,7 @@ struct Layout {
     size_t waT[PQL_MAX_HIDDEN + 1];                                   // transposed policy weights, layer l = 1..L
     size_t splitk;
     size_t lgT[2], lgQ[2], p_dbo[2];                                  // distributional critics: logits, output-bias partials
+    size_t mu2a, logp, epsb, dOut, p_sc, p_lp;                        // stochastic policy: outputs, log pi, draws, gradient, partials
     size_t sqp;                                                       // per-workgroup sums of squared gradients
     size_t xn;                                                        // standardised Actor observations
     size_t total;
@@ -175,6 +187,7 @@ struct Layout {
 // FUSED_MAXW wide, the action vector fits one MFMA tile and the tile's LDS footprint fits a CU.
 bool fused_ok(const pql_config* c) {
     if (distributional(c)) return false;          // logits layer and projection run on the layered path
+    if (c->stochastic_policy) return false;       // so do sampling and the log-density terms
     int hmax = 0;
     for (int l = 0; l < c->n_hidden; ++l) {
         if (c->hidden[l] % 32 != 0 || c->hidden[l] > FUSED_MAXW) return false;
@@ -240,7 +253,7 @@ size_t splitk_floats(const pql_config* c, int B) {
     }
     actor.push_back({c->obs_dim, c->hidden[0]});
     for (int l = 1; l < L; ++l) actor.push_back({c->hidden[l - 1], c->hidden[l]});
-    actor.push_back({c->hidden[L - 1], c->act_dim});
+    actor.push_back({c->hidden[L - 1], actor_out(c)});
     const size_t sc = dw_slab_bound(critic, B), sa = dw_slab_bound(actor, B);
     return sc > sa ? sc : sa;
 }
@@ -290,6 +303,15 @@ void make_layout(const pql_config* c, Layout& w) {
         w.sqp = take(adam_reduce_blocks_bound(pa > pc ? pa : pc, RED_MAX_TENSORS));
     }
     w.xn = fused_ok(c) ? off : take(B * (size_t)c->obs_dim);
+    if (c->stochastic_policy) {
+        const size_t a2 = 2 * (size_t)c->act_dim, nblk = (B + SAC_ROWS - 1) / SAC_ROWS;
+        w.mu2a = take(B * a2);
+        w.logp = take(B);
+        w.epsb = take(B * c->act_dim);
+        w.dOut = take(B * a2);
+        w.p_sc = take(nblk * a2);
+        w.p_lp = take(nblk);
+    }
     if (distributional(c))
         for (int i = 0; i < 2; ++i) {
             w.lgT[i] = take(B * (size_t)c->num_atoms);
@@ -422,7 +444,10 @@ int32_t pql_create(const pql_config* cfg, pql_ctx** out) {
     c->head = c->count = c->pushes = c->samples = c->acts = c->critic_t = c->actor_t = c->state_samples = 0;
     c->obs_norm = nullptr;
     c->obs_eps = 0.f;
-    c->a_total = net_params(cfg->obs_dim, cfg, cfg->act_dim, c->a_w, c->a_b);
+    c->a_total = net_params(cfg->obs_dim, cfg, actor_out(cfg), c->a_w, c->a_b);
+    c->temperature = nullptr;
+    c->temperature_v = nullptr;
+    c->target_entropy = 0.f;
     c->c_total = net_params(cfg->obs_dim + cfg->act_dim, cfg, critic_out(cfg), c->c_w, c->c_b);
     *out = c;
     return PQL_OK;
@@ -441,7 +466,7 @@ int64_t pql_replay_rows(const pql_config* cfg) {
 
 int64_t pql_actor_param_count(const pql_config* cfg) {
     const int rc = validate_cfg(cfg);
-    return rc != PQL_OK ? rc : net_params(cfg->obs_dim, cfg, cfg->act_dim, nullptr, nullptr);
+    return rc != PQL_OK ? rc : net_params(cfg->obs_dim, cfg, actor_out(cfg), nullptr, nullptr);
 }
 
 int64_t pql_critic_param_count(const pql_config* cfg) {
@@ -590,6 +615,25 @@ static hipError_t actor_hidden_forward(pql_ctx* c, const float* params, const fl
     return hipSuccess;
 }
 
+// Output layer of the stochastic policy (mu, raw log sigma) on top of hA[L], then one sample per row.
+static hipError_t stochastic_policy_sample(pql_ctx* c, const float* params, int B, float* ws, const Layout& w, float* act,
+                                           float* logp, float* eps, uint32_t stream_id, int64_t call, hipStream_t st) {
+    const int L = c->L, HL = c->cfg.hidden[L - 1], ad = c->cfg.act_dim;
+    std::vector<GemmProb> ps;
+    GemmProb p = prob(B, 2 * ad, ws + w.mu2a, 2 * ad, EPI_BIAS);
+    add_seg(p, ws + w.hA[L], HL, params + c->a_w[L], 2 * ad, HL);
+    p.bias = params + c->a_b[L];
+    ps.push_back(p);
+    hipError_t e = run_auto(GEMM_NN, ps, st);
+    if (e != hipSuccess) return e;
+    SacSampleArgs sa;
+    sa.B = B; sa.a = ad; sa.out2a = ws + w.mu2a; sa.act = act; sa.logp = logp; sa.eps = eps;
+    sa.stream_id = stream_id;
+    sa.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); sa.key1 = (uint32_t)(c->cfg.seed >> 32);
+    sa.ctr2 = (uint32_t)((uint64_t)call & 0xffffffffu); sa.ctr3 = (uint32_t)((uint64_t)call >> 32);
+    return sac_sample_launch(sa, st);
+}
+
 // One hidden layer of a critic as a forward problem.
 static GemmProb critic_layer(pql_ctx* c, const float* params, int l, const float* s, const float* a, int lda_a,
                              const float* h_prev, float* h_out, int B) {
@@ -646,6 +690,12 @@ int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, i
     }
     e = actor_hidden_forward(c, actor_params, obs, num, ws, w, st);
     if (e != hipSuccess) return E.hip(e, "pql_actor_act");
+    if (c->cfg.stochastic_policy) {     // exploration is the policy's own randomness; the sigma schedule does not apply
+        e = stochastic_policy_sample(c, actor_params, num, ws, w, act_out, nullptr, nullptr, 2u, c->acts, st);
+        if (e != hipSuccess) return E.hip(e, "pql_actor_act");
+        c->acts += 1;
+        return PQL_OK;
+    }
     const int L = c->L, HL = c->cfg.hidden[L - 1], ad = c->cfg.act_dim;
     std::vector<GemmProb> ps;
     GemmProb p = prob(num, ad, act_out, ad, EPI_BIAS_TANH_NOISE);
@@ -672,6 +722,7 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
         !batch.obs || !batch.act || !batch.ret || !batch.next_obs || !batch.boot || !loss_out || !workspace)
         return E.fail(PQL_ERR_NULL, "pql_critic_update: null pointer");
     if (B < 1 || !adam_ok(opt)) return E.fail(PQL_ERR_INVALID_ARG, "pql_critic_update: bad batch size or Adam constants");
+    if (c->cfg.stochastic_policy && !c->temperature) return E.fail(PQL_ERR_NULL, "pql_critic_update: no temperature attached");
     if (B > c->cfg.max_batch) return E.fail(PQL_ERR_BATCH_TOO_LARGE, "pql_critic_update: batch > max_batch");
     if (((uintptr_t)workspace) & 255) return E.fail(PQL_ERR_ALIGNMENT, "pql_critic_update: workspace not 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
@@ -738,8 +789,12 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
                                           l > 1 ? ws + w.hQ[i][l - 1] : nullptr, ws + w.hQ[i][l], B));
             if ((e = run_auto(GEMM_NN, ps, st)) != hipSuccess) return E.hip(e, who);
         }
-        // 2. a' = tanh(output layer of pi^v)
-        {
+        // 2. a' = tanh(output layer of pi^v), or a sample a' ~ pi^v(.|s') with its log-density
+        if (c->cfg.stochastic_policy) {
+            if ((e = stochastic_policy_sample(c, actor_target_params, B, ws, w, ws + w.aOut, ws + w.logp, nullptr, 4u,
+                                              c->critic_t, st)) != hipSuccess)
+                return E.hip(e, who);
+        } else {
             std::vector<GemmProb> ps;
             GemmProb p = prob(B, ad, ws + w.aOut, ad, EPI_BIAS_TANH);
             add_seg(p, ws + w.hA[L], HL, actor_target_params + c->a_w[L], ad, HL);
@@ -802,6 +857,7 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
                 h.p_dw[i] = ws + w.p_dw[i]; h.p_dbh[i] = ws + w.p_dbh[i]; h.p_db[i] = ws + w.p_db[i];
             }
             h.ret = batch.ret; h.boot = batch.boot; h.y = ws + w.y; h.p_loss = ws + w.p_loss;
+            if (c->cfg.stochastic_policy) { h.logp_next = ws + w.logp; h.log_alpha = c->temperature_v; }
             if ((e = critic_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
             head_parts = h.nwg;
         }
@@ -882,6 +938,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     if (!actor_params || !critic_params || !adam_m || !adam_v || !grads_out || !obs || !loss_out || !workspace)
         return E.fail(PQL_ERR_NULL, "pql_actor_update: null pointer");
     if (B < 1 || !adam_ok(opt)) return E.fail(PQL_ERR_INVALID_ARG, "pql_actor_update: bad batch size or Adam constants");
+    if (c->cfg.stochastic_policy && !c->temperature) return E.fail(PQL_ERR_NULL, "pql_actor_update: no temperature attached");
     if (B > c->cfg.max_batch) return E.fail(PQL_ERR_BATCH_TOO_LARGE, "pql_actor_update: batch > max_batch");
     if (((uintptr_t)workspace) & 255) return E.fail(PQL_ERR_ALIGNMENT, "pql_actor_update: workspace not 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
@@ -896,6 +953,9 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     AdamArgs adm;
     std::memset(&adm, 0, sizeof(adm));
     int loss_parts = 0;
+    const bool sac = c->cfg.stochastic_policy != 0;
+    const int aw = actor_out(&c->cfg);                          // width of the policy's output layer
+    const float* d_top = sac ? ws + w.dOut : ws + w.dPre;       // gradient at that layer
     if (fused_ok(&c->cfg)) {
         TransposeArgs tr;
         tr.n = 0;
@@ -934,9 +994,13 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
         red(adm, c->a_b[L], ws + w.colA[L + 1], ad, fa.nwg, ad);
         for (int l = 1; l <= L; ++l) red(adm, c->a_b[l - 1], ws + w.colA[l], c->cfg.hidden[l - 1], fa.nwg, c->cfg.hidden[l - 1]);
     } else {
-        // 1. a = pi(s)
+        // 1. a = pi(s), or the reparameterised sample a = tanh(mu + sigma eps)
         if ((e = actor_hidden_forward(c, actor_params, obs, B, ws, w, st)) != hipSuccess) return E.hip(e, who);
-        {
+        if (sac) {
+            if ((e = stochastic_policy_sample(c, actor_params, B, ws, w, ws + w.aOut, ws + w.logp, ws + w.epsb, 5u,
+                                              c->actor_t, st)) != hipSuccess)
+                return E.hip(e, who);
+        } else {
             std::vector<GemmProb> ps;
             GemmProb p = prob(B, ad, ws + w.aOut, ad, EPI_BIAS_TANH);
             add_seg(p, ws + w.hA[L], HL, actor_params + c->a_w[L], ad, HL);
@@ -1010,17 +1074,25 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
             for (int i = 0; i < 2; ++i)
                 add_seg(p, ws + w.dQ[i][1], H1, critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, H1, H1);
             p.aux = ws + w.aOut; p.ldaux = ad;
-            p.colsum = ws + w.colA[L + 1];
+            if (!sac) p.colsum = ws + w.colA[L + 1];
             ps.push_back(p);
             if ((e = run(GEMM_NT, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
-            red(adm, c->a_b[L], ws + w.colA[L + 1], ad, colsum_rows(TILE_128x32, B), ad);
+            if (!sac) red(adm, c->a_b[L], ws + w.colA[L + 1], ad, colsum_rows(TILE_128x32, B), ad);
+        }
+        if (sac) {      // add the log-density terms and split into the gradients of mu and raw log sigma
+            SacGradArgs ga;
+            ga.B = B; ga.a = ad; ga.d_u = ws + w.dPre; ga.act = ws + w.aOut; ga.eps = ws + w.epsb; ga.out2a = ws + w.mu2a;
+            ga.logp = ws + w.logp; ga.log_alpha = c->temperature;
+            ga.d_out = ws + w.dOut; ga.p_cols = ws + w.p_sc; ga.p_logp = ws + w.p_lp;
+            if ((e = sac_grad_launch(ga, st)) != hipSuccess) return E.hip(e, who);
+            red(adm, c->a_b[L], ws + w.p_sc, aw, (B + SAC_ROWS - 1) / SAC_ROWS, aw);
         }
         // 6. policy backward data path
         for (int l = L + 1; l >= 2; --l) {
             std::vector<GemmProb> ps;
-            const int Hl = (l == L + 1) ? ad : c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
+            const int Hl = (l == L + 1) ? aw : c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
             GemmProb p = prob(B, Hp, ws + w.dA[l - 1], Hp, EPI_MUL_DELU);
-            add_seg(p, (l == L + 1) ? ws + w.dPre : ws + w.dA[l], Hl, actor_params + c->a_w[l - 1], Hl, Hl);
+            add_seg(p, (l == L + 1) ? d_top : ws + w.dA[l], Hl, actor_params + c->a_w[l - 1], Hl, Hl);
             p.aux = ws + w.hA[l - 1]; p.ldaux = Hp;
             p.colsum = ws + w.colA[l - 1];
             ps.push_back(p);
@@ -1034,10 +1106,10 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
         std::vector<GemmProb> ps;
         std::vector<int64_t> offs;
         for (int l = 1; l <= L + 1; ++l) {
-            const int Hl = (l == L + 1) ? ad : c->cfg.hidden[l - 1];
+            const int Hl = (l == L + 1) ? aw : c->cfg.hidden[l - 1];
             const int Hp = (l == 1) ? o : c->cfg.hidden[l - 2];
             GemmProb p = prob(Hp, Hl, nullptr, Hl, EPI_STORE);
-            add_seg(p, (l == 1) ? obs : ws + w.hA[l - 1], Hp, (l == L + 1) ? ws + w.dPre : ws + w.dA[l], Hl, B);
+            add_seg(p, (l == 1) ? obs : ws + w.hA[l - 1], Hp, (l == L + 1) ? d_top : ws + w.dA[l], Hl, B);
             ps.push_back(p); offs.push_back(c->a_w[l - 1]);
         }
         if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st)) != hipSuccess) return E.hip(e, who);
@@ -1048,6 +1120,13 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     adm.max_norm = opt.max_grad_norm; adm.sq_partial = ws + w.sqp; adm.norm_out = loss_out + 1;
     fill_adam(adm, opt, c->actor_t + 1);
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
+    if (sac) {      // temperature step on the log-densities of this batch
+        SacAlphaArgs al;
+        al.B = B; al.nparts = (B + SAC_ROWS - 1) / SAC_ROWS; al.p_logp = ws + w.p_lp; al.temperature = c->temperature;
+        al.loss_out = loss_out; al.target_entropy = c->target_entropy;
+        al.lr = adm.lr; al.beta1 = adm.beta1; al.beta2 = adm.beta2; al.eps = adm.eps; al.inv_bc1 = adm.inv_bc1; al.inv_bc2 = adm.inv_bc2;
+        if ((e = sac_alpha_launch(al, st)) != hipSuccess) return E.hip(e, who);
+    }
     c->actor_t += 1;
     return PQL_OK;
 }
@@ -1104,6 +1183,26 @@ int32_t pql_profile_end(pql_ctx* c, pql_kernel_stat* out, int32_t max_out, int32
     }
     *n_out = n;
     return rc;
+}
+
+// ---------------------------------------------------------------------------------------------
+int32_t pql_sac_attach(pql_ctx* c, float* temperature, float target_entropy) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!c->cfg.stochastic_policy) return E.fail(PQL_ERR_INVALID_ARG, "pql_sac_attach: the policy of this context is deterministic");
+    if (temperature && (((uintptr_t)temperature) & 15)) return E.fail(PQL_ERR_ALIGNMENT, "pql_sac_attach: not 16-byte aligned");
+    c->temperature = temperature;
+    c->temperature_v = temperature;
+    c->target_entropy = target_entropy;
+    return PQL_OK;
+}
+
+int32_t pql_sac_attach_lagged(pql_ctx* c, const float* log_alpha) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!c->cfg.stochastic_policy) return E.fail(PQL_ERR_INVALID_ARG, "pql_sac_attach_lagged: the policy of this context is deterministic");
+    c->temperature_v = log_alpha ? log_alpha : c->temperature;
+    return PQL_OK;
 }
 
 // ---------------------------------------------------------------------------------------------

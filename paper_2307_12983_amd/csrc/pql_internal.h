@@ -17,7 +17,8 @@ enum KernelId : int {
     KID_GEMM = 0, KID_PUSH = 15, KID_SAMPLE = 16, KID_HEAD_CRITIC = 17, KID_HEAD_POLICY = 18,
     KID_ADAM = 19, KID_SOFT_UPDATE = 20, KID_COPY = 21, KID_FUSED_CRITIC = 22, KID_FUSED_POLICY = 23,
     KID_FUSED_ACT = 24, KID_TRANSPOSE = 25, KID_ADAM_CLIP = 26, KID_OBS_STATS = 27, KID_OBS_MERGE = 28,
-    KID_NORMALIZE = 29, KID_DIST_CRITIC = 30, KID_DIST_POLICY = 31, KID_COUNT = 32
+    KID_NORMALIZE = 29, KID_DIST_CRITIC = 30, KID_DIST_POLICY = 31, KID_SAC_SAMPLE = 32, KID_SAC_GRAD = 33,
+    KID_SAC_ALPHA = 34, KID_COUNT = 35
 };
 const char* kernel_name(int kid);
 bool prof_active();
@@ -159,7 +160,42 @@ struct HeadArgs {
     float* p_dbh[2];        // [nwg][H]  partial column sums of dQ (bias grad of last hidden)
     float* p_db[2];         // [nwg]     partial sums of dL/db_out
     float* p_loss;          // [2][nwg] (critic) or [1][nwg] (policy)
+    // soft target of the stochastic-policy variant: y = ret + boot * (min Q' - exp(*log_alpha) * logp_next)
+    const float* logp_next; const float* log_alpha;
 };
+
+// ---- stochastic (tanh-Gaussian) policy of the SAC variant -----------------------------------
+constexpr float SAC_LOG_STD_MIN = -5.f, SAC_LOG_STD_MAX = 2.f;
+constexpr int SAC_ROWS = 256;           // rows per workgroup of the policy-gradient kernel
+struct SacSampleArgs {
+    int B, a;
+    const float* out2a;     // [B][2a]: mu, raw log sigma
+    float* act;             // [B][a]  tanh(mu + sigma eps)
+    float* logp;            // [B] log pi(a|s), or NULL
+    float* eps;             // [B][a] the draws, kept for the backward pass, or NULL
+    uint32_t stream_id, key0, key1, ctr2, ctr3;
+};
+hipError_t sac_sample_launch(const SacSampleArgs& a, hipStream_t stream);
+
+struct SacGradArgs {
+    int B, a;
+    const float* d_u;       // [B][a]: dJ/da * (1 - a^2) from the critics
+    const float* act; const float* eps; const float* out2a; const float* logp;
+    const float* log_alpha;
+    float* d_out;           // [B][2a]: gradient at the policy's output layer
+    float* p_cols;          // [nblk][2a] partial column sums of d_out (output-bias gradient)
+    float* p_logp;          // [nblk] partial sums of log pi
+};
+hipError_t sac_grad_launch(const SacGradArgs& a, hipStream_t stream);
+
+struct SacAlphaArgs {
+    int B, nparts;
+    const float* p_logp;
+    float* temperature;     // log alpha, Adam m, Adam v
+    float* loss_out;        // [2] <- alpha * mean log pi, [3] <- mean log pi
+    float target_entropy, lr, beta1, beta2, eps, inv_bc1, inv_bc2;
+};
+hipError_t sac_alpha_launch(const SacAlphaArgs& a, hipStream_t stream);
 
 // Heads of the distributional critics (PQL-D): one wavefront per row, lane = atom.
 constexpr int DIST_MAX_ATOMS = 64;

@@ -224,6 +224,7 @@ __global__ __launch_bounds__(64 * HEAD_WAVES) void head_kernel(const HeadArgs a)
     const float bq0 = a.bQ[0][0], bq1 = a.bQ[1][0];
     const float bt0 = POLICY ? 0.f : a.bT[0][0], bt1 = POLICY ? 0.f : a.bT[1][0];
     const float invB = 1.f / (float)B;
+    const float alpha = (!POLICY && a.logp_next != nullptr) ? expf(a.log_alpha[0]) : 0.f;
     float loss0 = 0.f, loss1 = 0.f, db0 = 0.f, db1 = 0.f;
 
     for (int row = gw; row < B; row += nw) {
@@ -255,7 +256,9 @@ __global__ __launch_bounds__(64 * HEAD_WAVES) void head_kernel(const HeadArgs a)
         } else {
             t0 = wave_sum(t0) + bt0;
             t1 = wave_sum(t1) + bt1;
-            const float y = a.ret[row] + a.boot[row] * fminf(t0, t1);
+            float tq = fminf(t0, t1);
+            if (a.logp_next != nullptr) tq -= alpha * a.logp_next[row];      // soft value of the SAC variant
+            const float y = a.ret[row] + a.boot[row] * tq;
             const float e0 = q0 - y, e1 = q1 - y;
             loss0 += e0 * e0;
             loss1 += e1 * e1;
@@ -798,6 +801,118 @@ hipError_t normalize_rows_launch(const float* x, const float* mean_f, const floa
     const ProfSlot ps = prof_slot();
     PQL_LAUNCH(ps, normalize_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, x, mean_f, rstd_f, out, n, o);
     prof_commit(ps, KID_NORMALIZE, 0.0, 8.0 * (double)n);
+    return hipGetLastError();
+}
+
+// =============================================================================================
+// Stochastic policy of the SAC variant (Section 3 / appendix "PQL for SAC"; Haarnoja et al. 2018):
+// a = tanh(mu + sigma eps), log sigma = clip(raw, -5, 2),
+// log pi = sum_d [-eps^2/2 - log sigma - log(2 pi)/2 - log(1 - a^2)], the last term evaluated as
+// 2 (log 2 - u - softplus(-2u)).  One thread per row.
+// =============================================================================================
+__device__ inline float std_normal_draw(uint32_t element, uint32_t stream_id, uint32_t ctr2, uint32_t ctr3, uint32_t k0,
+                                        uint32_t k1) {
+    uint32_t w0, w1;
+    philox4x32_10_w01(element, stream_id, ctr2, ctr3, k0, k1, w0, w1);
+    // double precision: (w >> 8) + 0.5 needs 25 significant bits
+    const double u1 = ((double)(w0 >> 8) + 0.5) * 0x1p-24;
+    const double u2 = ((double)(w1 >> 8) + 0.5) * 0x1p-24;
+    return (float)(sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2));
+}
+
+__global__ __launch_bounds__(256) void sac_sample_kernel(const SacSampleArgs a) {
+    const int row = blockIdx.x * 256 + threadIdx.x;
+    if (row >= a.B) return;
+    const float* __restrict__ o2 = a.out2a + (size_t)row * 2 * a.a;
+    float lp = 0.f;
+    for (int d = 0; d < a.a; ++d) {
+        const float e = std_normal_draw((uint32_t)(row * a.a + d), a.stream_id, a.ctr2, a.ctr3, a.key0, a.key1);
+        const float ls = fminf(fmaxf(o2[a.a + d], SAC_LOG_STD_MIN), SAC_LOG_STD_MAX);
+        const float u = o2[d] + expf(ls) * e;
+        const float x = -2.f * u;
+        const float softplus = fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
+        lp += -0.5f * e * e - ls - 0.91893853320467274178f - 2.f * (0.69314718055994530942f - u - softplus);
+        a.act[(size_t)row * a.a + d] = tanhf(u);
+        if (a.eps != nullptr) a.eps[(size_t)row * a.a + d] = e;
+    }
+    if (a.logp != nullptr) a.logp[row] = lp;
+}
+
+hipError_t sac_sample_launch(const SacSampleArgs& a, hipStream_t stream) {
+    if (a.B <= 0) return hipSuccess;
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, sac_sample_kernel, dim3((a.B + 255) / 256), dim3(256), 0, stream, a);
+    prof_commit(ps, KID_SAC_SAMPLE, 0.0, 4.0 * (double)a.B * (4.0 * a.a + 1.0));
+    return hipGetLastError();
+}
+
+// Gradient at the policy's output layer: J = mean_b [alpha log pi - min Q], u = mu + sigma eps,
+//   dJ/dmu = dJ/du = d_u + (alpha / B) 2 a            (d log pi / du = 2 tanh(u))
+//   dJ/draw = dJ/du sigma eps - alpha / B              inside the clip, 0 outside
+// plus the per-workgroup column sums of both (the output-bias gradient) and of log pi.
+__global__ __launch_bounds__(SAC_ROWS) void sac_grad_kernel(const SacGradArgs a) {
+    extern __shared__ float tile[];                     // [SAC_ROWS][2a + 1]
+    const int row = blockIdx.x * SAC_ROWS + threadIdx.x;
+    const int w2 = 2 * a.a, ld = w2 + 1;
+    const float alpha = expf(a.log_alpha[0]), ab = alpha / (float)a.B;
+    const bool live = row < a.B;
+    for (int d = 0; d < a.a; ++d) {
+        float dmu = 0.f, draw = 0.f;
+        if (live) {
+            const size_t at = (size_t)row * a.a + d;
+            const float raw = a.out2a[(size_t)row * w2 + a.a + d];
+            const float ls = fminf(fmaxf(raw, SAC_LOG_STD_MIN), SAC_LOG_STD_MAX);
+            dmu = a.d_u[at] + ab * 2.f * a.act[at];
+            if (raw > SAC_LOG_STD_MIN && raw < SAC_LOG_STD_MAX) draw = dmu * expf(ls) * a.eps[at] - ab;
+            a.d_out[(size_t)row * w2 + d] = dmu;
+            a.d_out[(size_t)row * w2 + a.a + d] = draw;
+        }
+        tile[threadIdx.x * ld + d] = dmu;
+        tile[threadIdx.x * ld + a.a + d] = draw;
+    }
+    tile[threadIdx.x * ld + w2] = live ? a.logp[row] : 0.f;
+    __syncthreads();
+    for (int c = threadIdx.x; c <= w2; c += SAC_ROWS) {
+        float s = 0.f;
+        for (int r = 0; r < SAC_ROWS; ++r) s += tile[r * ld + c];
+        if (c < w2) a.p_cols[(size_t)blockIdx.x * w2 + c] = s;
+        else a.p_logp[blockIdx.x] = s;
+    }
+}
+
+hipError_t sac_grad_launch(const SacGradArgs& a, hipStream_t stream) {
+    if (a.B <= 0) return hipSuccess;
+    const size_t lds = (size_t)SAC_ROWS * (2 * a.a + 1) * sizeof(float);
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, sac_grad_kernel, dim3((a.B + SAC_ROWS - 1) / SAC_ROWS), dim3(SAC_ROWS), lds, stream, a);
+    prof_commit(ps, KID_SAC_GRAD, 0.0, 4.0 * (double)a.B * (7.0 * a.a + 1.0));
+    return hipGetLastError();
+}
+
+// Temperature step (Table B.1 "Learnable Entropy Coefficient"): J(alpha) = -alpha mean(log pi + H),
+// optimised in log alpha with Adam; also reports the entropy term of the policy objective.
+__global__ __launch_bounds__(64) void sac_alpha_kernel(const SacAlphaArgs a) {
+    float s = 0.f;
+    for (int j = threadIdx.x; j < a.nparts; j += 64) s += a.p_logp[j];
+    s = wave_sum(s);
+    if (threadIdx.x == 0) {
+        const float mean_logp = s / (float)a.B;
+        const float la = a.temperature[0], alpha = expf(la);
+        a.loss_out[2] = alpha * mean_logp;
+        a.loss_out[3] = mean_logp;
+        const float g = -alpha * (mean_logp + a.target_entropy);
+        const float m = a.beta1 * a.temperature[1] + (1.f - a.beta1) * g;
+        const float v = a.beta2 * a.temperature[2] + (1.f - a.beta2) * g * g;
+        a.temperature[0] = la - a.lr * (m * a.inv_bc1) / (sqrtf(v * a.inv_bc2) + a.eps);
+        a.temperature[1] = m;
+        a.temperature[2] = v;
+    }
+}
+
+hipError_t sac_alpha_launch(const SacAlphaArgs& a, hipStream_t stream) {
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, sac_alpha_kernel, dim3(1), dim3(64), 0, stream, a);
+    prof_commit(ps, KID_SAC_ALPHA, 0.0, 4.0 * (double)a.nparts);
     return hipGetLastError();
 }
 

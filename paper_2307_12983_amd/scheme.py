@@ -44,6 +44,8 @@ class ParallelSchemeSession:
         w = self.w
         self.pi_snap = [sess.actor.clone(), sess.actor.clone()]       # pi^a = pi^v: the P-learner's last hand-over
         self.q_snap = [sess.critic.clone(), sess.critic.clone()]      # Q^p: the V-learner's last hand-over
+        # SAC variant: the temperature is learned by the P-learner and handed to the V-learner like the policy
+        self.alpha_snap = None if sess.temperature is None else [sess.temperature.clone(), sess.temperature.clone()]
         nws = sess.workspace.numel()
         self.ws_p = torch.zeros(nws, dtype=torch.float32, device=dev)
         self.ws_a = torch.zeros(nws, dtype=torch.float32, device=dev)
@@ -103,6 +105,8 @@ class ParallelSchemeSession:
         # ---- V-learner (Algorithm 3) and P-learner (Algorithm 2), enqueued interleaved so that
         #      neither stream runs dry while the host is busy with the other
         st_p.wait_event(ev_pushed)                # ring holds the new states; Q snapshot of the last period is complete
+        if self.alpha_snap is not None:
+            c.pql_sac_attach_lagged(self.alpha_snap[prev])
         done_p = 0
         for k in range(self.v_updates):
             c.pql_sample_nstep(s.storage, w.batch, s.batch, st_v)
@@ -119,6 +123,8 @@ class ParallelSchemeSession:
         # ---- hand-overs for the next period
         c.pql_soft_update(s.critic, self.q_snap[cur], s.critic.numel(), 1.0, st_v)
         c.pql_soft_update(s.actor, self.pi_snap[cur], s.actor.numel(), 1.0, st_p)
+        if self.alpha_snap is not None:
+            c.pql_soft_update(s.temperature, self.alpha_snap[cur], 4, 1.0, st_p)
         self.ev_a, self.ev_p = ev_a, self._event(st_p)
         self.period += 1
 

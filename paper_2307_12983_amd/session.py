@@ -20,7 +20,8 @@ class LearnerSession:
         self.device = device
         self.max_batch = int(max_batch or max(w.batch, w.num_envs))
         self.cfg = B.make_config(w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.nstep, w.gamma, w.hidden,
-                                 self.max_batch, w.rng_seed if seed is None else seed, w.num_atoms, w.v_min, w.v_max)
+                                 self.max_batch, w.rng_seed if seed is None else seed, w.num_atoms, w.v_min, w.v_max,
+                                 1 if w.sac else 0)
         self.ctx = B.Context(self.cfg)
         self.rows = self.ctx.replay_rows()
         self.storage = B.Storage(self.rows, w.num_envs, w.obs_dim, w.act_dim, device)
@@ -35,13 +36,18 @@ class LearnerSession:
         z = lambda n: torch.zeros(n, dtype=torch.float32, device=device)
         self.c_m, self.c_v, self.c_g = z(critic.size), z(critic.size), z(critic.size)
         self.a_m, self.a_v, self.a_g = z(actor.size), z(actor.size), z(actor.size)
-        self.critic_out, self.actor_out = z(3), z(2)      # losses, then the gradient norm before clipping
+        self.critic_out, self.actor_out = z(3), z(4)      # losses, then the gradient norm before clipping (SAC: two more)
         self.critic_loss, self.critic_grad_norm = self.critic_out[:2], self.critic_out[2:]
         self.actor_loss, self.actor_grad_norm = self.actor_out[:1], self.actor_out[1:]
         self.workspace = torch.zeros(self.ctx.workspace_bytes() // 4 + 64, dtype=torch.float32, device=device)
         assert self.workspace.data_ptr() % 256 == 0
         self.act_out = torch.zeros((self.max_batch, w.act_dim), dtype=torch.float32, device=device)
         self.opt = B.PqlAdam(w.lr, w.beta1, w.beta2, w.eps, w.max_grad_norm)
+        self.temperature = None
+        if w.sac:
+            self.temperature = torch.tensor([float(np.log(np.float64(w.init_alpha))), 0.0, 0.0, 0.0], dtype=torch.float32,
+                                            device=device)
+            self.ctx.pql_sac_attach(self.temperature, w.target_entropy)
         self.obs_stats = None
         if w.obs_norm:
             self.obs_stats = torch.zeros(self.ctx.obs_norm_bytes() // 8 + 32, dtype=torch.float64, device=device)

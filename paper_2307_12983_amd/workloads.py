@@ -60,6 +60,8 @@ class Workload:
     num_atoms: int = 0             # PQL-D: 51 atoms on (-10, 10); 0 = scalar critics
     v_min: float = -10.0
     v_max: float = 10.0
+    sac: bool = False              # PQL + SAC: tanh-Gaussian policy, learnable temperature
+    init_alpha: float = _f32(0.2)  # initial entropy coefficient (not given in the paper)
 
     @property
     def rows(self) -> int:
@@ -79,8 +81,12 @@ class Workload:
         """Seed of the counter-based generator used for index sampling / exploration."""
         return 0x5EED0000 + self.index
 
+    @property
+    def target_entropy(self) -> float:
+        return -float(self.act_dim)
+
     def actor_dims(self) -> List[Tuple[int, int]]:
-        return layer_dims(self.obs_dim, self.hidden, self.act_dim)
+        return layer_dims(self.obs_dim, self.hidden, 2 * self.act_dim if self.sac else self.act_dim)
 
     def critic_dims(self) -> List[Tuple[int, int]]:
         return layer_dims(self.obs_dim + self.act_dim, self.hidden, self.num_atoms if self.num_atoms >= 2 else 1)

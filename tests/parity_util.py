@@ -81,7 +81,9 @@ def oracle_ring(w: W.Workload):
 def oracle_learner(w: W.Workload, actor, critic):
     return O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, w.lr, w.gamma, w.tau, w.beta1, w.beta2, w.eps,
                      max_grad_norm=(w.max_grad_norm if w.max_grad_norm > 0 else None),
-                     v_min=(w.v_min if w.num_atoms >= 2 else None), v_max=(w.v_max if w.num_atoms >= 2 else None))
+                     v_min=(w.v_min if w.num_atoms >= 2 else None), v_max=(w.v_max if w.num_atoms >= 2 else None),
+                     sac=w.sac, log_alpha=float(np.float32(np.log(np.float64(w.init_alpha)))),
+                     target_entropy=w.target_entropy, seed=w.rng_seed)
 
 
 def oracle_normalizer(w: W.Workload):

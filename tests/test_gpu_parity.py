@@ -221,7 +221,14 @@ def one_step(torch, w, rows, check_all=True):
     # policy update on the sampled states, then hard sync of the lagged policy
     s.actor_update(None, Bsz)
     J, ga = L.actor_update(batch["obs"])
-    res["J"] = abs(float(s.actor_loss.cpu().numpy()[0]) - J) / max(abs(J), 1e-30)
+    if w.sac:       # J = Q term + entropy term, reported separately; then the temperature step
+        out = s.actor_out.cpu().numpy().astype(np.float64)
+        res["J"] = max(abs(out[0] - J[0]) / abs(J[0]), abs(out[2] - J[1]) / abs(J[1]), abs(out[3] - L.mean_logp) / abs(L.mean_logp))
+        res["log_alpha"] = abs(float(s.temperature.cpu()[0]) - L.log_alpha)
+        assert res["log_alpha"] <= TOL_ONE_STEP * abs(L.log_alpha)
+        assert abs(float(s.temperature.cpu()[1]) - L.al_m) <= TOL_ONE_STEP * abs(L.al_m)
+    else:
+        res["J"] = abs(float(s.actor_loss.cpu().numpy()[0]) - J) / max(abs(J), 1e-30)
     if w.max_grad_norm > 0:
         res["a_norm"] = abs(float(s.actor_grad_norm.cpu()[0]) - L.actor_grad_norm) / L.actor_grad_norm
         res["a_clipped"] = L.actor_grad_norm > w.max_grad_norm
@@ -286,6 +293,9 @@ def many_steps(torch, w, rows, steps, actor_every=0):
     res["target"] = assert_params_close(s.critic_target.cpu().numpy(), L.critic_target, w.critic_dims(), 2, TOL_100_STEPS, "critic target")
     res["actor"] = assert_params_close(s.actor.cpu().numpy(), L.actor, w.actor_dims(), 1, TOL_100_STEPS, "actor params")
     assert worst_loss <= TOL_100_STEPS
+    if w.sac:
+        res["log_alpha"] = abs(float(s.temperature.cpu()[0]) - L.log_alpha) / abs(L.log_alpha)
+        assert res["log_alpha"] <= TOL_100_STEPS
     return res
 
 
@@ -434,6 +444,54 @@ def test_distributional_full_batch_ant(torch_cuda):
     w = distributional(W.WORKLOADS["ant"])
     res = one_step(torch_cuda, w, w.nstep + 8)
     say("ant, 51 atoms, batch 8192", res)
+
+
+# ---------------------------------------------------------------------------------------------
+# PQL + SAC: tanh-Gaussian policy, soft target, learnable temperature
+def with_sac(w):
+    return w.replace(sac=True)
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged", "ant_s", "humanoid_s", "fused_l1"])
+def test_sac_actor_step_is_a_policy_sample(torch_cuda, case):
+    torch = torch_cuda
+    w = with_sac(SMALL[case])
+    s = make_session(w)
+    rng = np.random.default_rng(7)
+    for call, num in enumerate((w.num_envs, 1, min(s.max_batch, 333))):
+        obs = rng.standard_normal((num, w.obs_dim), dtype=np.float32)
+        got = s.act(torch.from_numpy(obs).cuda()).cpu().numpy()
+        ref = O.sac_actor_act(s.actor_init, w.actor_dims(), obs, w.rng_seed, call)
+        e = rel_err(got, ref)
+        say(case, "SAC act call", call, "num", num, "rel err %.2e" % e)
+        assert e <= TOL_ONE_STEP and np.abs(got).max() <= 1.0
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged", "ant_s", "humanoid_s", "fused_l3"])
+def test_one_update_sac(torch_cuda, case):
+    w = with_sac(SMALL[case])
+    say("case", case, "actor dims", w.actor_dims())
+    res = one_step(torch_cuda, w, min(w.rows, w.nstep + 4))
+    say(case, res)
+
+
+def test_one_update_sac_with_paper_defaults(torch_cuda):
+    w = paper_defaults(with_sac(SMALL["ant_s"]))
+    res = one_step(torch_cuda, w, w.nstep + 4)
+    say("ant_s SAC, clipping + standardisation", res)
+
+
+@pytest.mark.parametrize("case", ["tiny", "ant_s"])
+def test_100_updates_sac(torch_cuda, case):
+    w = with_sac(SMALL[case])
+    s_res = many_steps(torch_cuda, w, w.rows, 100, actor_every=2)
+    say(case, "100 SAC steps", s_res)
+
+
+def test_sac_full_batch_ant(torch_cuda):
+    w = with_sac(W.WORKLOADS["ant"])
+    res = one_step(torch_cuda, w, w.nstep + 8)
+    say("ant SAC, batch 8192", res)
 
 
 # ---------------------------------------------------------------------------------------------

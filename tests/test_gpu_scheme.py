@@ -41,6 +41,8 @@ def cases():
                                             obs_scale=2.0, index=13),
         "ragged_dist": Wk["tiny"].replace(name="ragged_dist", obs_dim=13, act_dim=3, num_envs=50, capacity=50 * 11,
                                           batch=333, hidden=(96, 40), index=14, num_atoms=51),
+        "ragged_sac": Wk["tiny"].replace(name="ragged_sac", obs_dim=13, act_dim=3, num_envs=50, capacity=50 * 11,
+                                         batch=333, hidden=(96, 40), index=15, sac=True),
     }
 
 
@@ -58,7 +60,7 @@ def build(torch, w, concurrent, horizon=1):
     return s, ps, ring, nz, env_host
 
 
-@pytest.mark.parametrize("case,horizon", [("tiny", 1), ("ragged", 2), ("ant_s", 1), ("tiny_defaults", 1), ("ragged_dist", 1)])
+@pytest.mark.parametrize("case,horizon", [("tiny", 1), ("ragged", 2), ("ant_s", 1), ("tiny_defaults", 1), ("ragged_dist", 1), ("ragged_sac", 1)])
 def test_scheme_matches_oracle(torch_cuda, case, horizon):
     torch = torch_cuda
     w = CASES[case]
@@ -82,7 +84,11 @@ def test_scheme_matches_oracle(torch_cuda, case, horizon):
         assert np.array_equal(s.batch.idx[:w.batch].cpu().numpy(), rec["v_idx"])
         assert np.array_equal(ps.p_idx[:w.batch].cpu().numpy(), rec["p_idx"])
         e_loss = rel_err(s.critic_loss.cpu().numpy(), rec["v_losses"][-1])
-        e_J = abs(float(s.actor_loss.cpu()[0]) - rec["p_losses"][-1]) / abs(rec["p_losses"][-1])
+        if w.sac:
+            out, Jr = s.actor_out.cpu().numpy(), rec["p_losses"][-1]
+            e_J = max(abs(out[0] - Jr[0]) / abs(Jr[0]), abs(out[2] - Jr[1]) / abs(Jr[1]))
+        else:
+            e_J = abs(float(s.actor_loss.cpu()[0]) - rec["p_losses"][-1]) / abs(rec["p_losses"][-1])
         say("  last losses: critic %.2e policy %.2e" % (e_loss, e_J))
         assert e_loss <= TOL_100_STEPS and e_J <= TOL_100_STEPS
     st = s.ctx.get_state()
@@ -95,10 +101,13 @@ def test_scheme_matches_oracle(torch_cuda, case, horizon):
         actor=assert_params_close(s.actor.cpu().numpy(), L.actor, w.actor_dims(), 1, TOL_100_STEPS, "actor"),
         pi_a=assert_params_close(ps.pi_snap[(periods - 1) % 2].cpu().numpy(), S.pi_a, w.actor_dims(), 1, TOL_100_STEPS, "pi^a"),
         q_p=assert_params_close(ps.q_snap[(periods - 1) % 2].cpu().numpy(), S.q_p, w.critic_dims(), 2, TOL_100_STEPS, "Q^p"))
+    if w.sac:
+        assert abs(float(s.temperature.cpu()[0]) - L.log_alpha) <= TOL_100_STEPS * abs(L.log_alpha)
+        assert abs(float(ps.alpha_snap[(periods - 1) % 2].cpu()[0]) - S.log_alpha_v) <= TOL_100_STEPS * abs(S.log_alpha_v)
     say(case, res)
 
 
-@pytest.mark.parametrize("case", ["ragged", "ant_s", "tiny_defaults"])
+@pytest.mark.parametrize("case", ["ragged", "ant_s", "tiny_defaults", "ragged_sac"])
 def test_three_streams_equal_one_stream_bit_for_bit(torch_cuda, case):
     torch = torch_cuda
     w = CASES[case]

@@ -160,3 +160,25 @@ def test_policy_part_alone_is_the_plain_policy_loop_on_sampled_states():
     assert np.array_equal(L.actor, ref_L.actor)
     assert np.array_equal(L.critic, ref_L.critic)            # untouched
     assert np.array_equal(ring.act, ref_ring.act)
+
+
+def test_sac_variant_hands_the_temperature_over_like_the_policy():
+    w = SMALL.replace(sac=True)
+    rng = W.data_rng(w)
+    ring = O.ReplayRing(w.rows, w.num_envs, w.obs_dim, w.act_dim)
+    for row in W.transition_rows(w, rng, w.nstep + 1):
+        ring.push(row["obs"], row["act"], row["rew"], row["next_obs"], row["done"])
+    actor, critic = W.init_networks(w)
+    L = O.Learner(w.actor_dims(), w.critic_dims(), actor, critic, 5e-3, w.gamma, w.tau, sac=True,
+                  log_alpha=np.log(0.2), target_entropy=-3.0, seed=w.rng_seed)
+    S = O.ParallelScheme(L, ring, w.nstep, w.batch, w.rng_seed, 0.05, 0.8)
+    env_rows = W.transition_rows(w, rng, 8)
+    alphas = [L.log_alpha]
+    for p in range(3):
+        rec = S.run_period(lambda period, t, a: env_rows[period], [env_rows[p]["obs"]])
+        alphas.append(L.log_alpha)
+        assert rec["log_alpha_v"] == alphas[p]                 # the V-learner's copy: the value at the last boundary
+        # the Actor's exploration is a sample of its policy copy
+        ref = O.sac_actor_act(rec["pi_a"], w.actor_dims(), env_rows[p]["obs"], w.rng_seed, p)
+        assert np.array_equal(rec["actions"][0], ref.astype(np.float32))
+    assert len(set(alphas)) == 4                               # the P-learner moved it in every period
