@@ -193,9 +193,10 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
         else      rb.load(S.B, S.ldb, k0, n0, S.kend, N, S.vb, tid);
     };
 
-    auto kgroup = [&](const float* __restrict__ Asm, const float* __restrict__ Bsm, int kg) {
+    // Operand fragments of one group of 8 k-values: lane-half h holds k = 4h + u, u = 0..3.
+    auto load_frag = [&](const float* __restrict__ Asm, const float* __restrict__ Bsm, int kg, float (&a)[TM][4],
+                         float (&b)[TN][4]) {
         const int kk = kg * 8 + 4 * half;
-        float a[TM][4], b[TN][4];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int m = (wm * TM + i) * 32 + l32;
@@ -218,6 +219,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
                 for (int u = 0; u < 4; ++u) b[j][u] = Bsm[(kk + u) * SB + n];
             }
         }
+    };
+    auto mfma_group = [&](const float (&a)[TM][4], const float (&b)[TN][4]) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -231,12 +234,34 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
         const float* Asm = As[t & 1];
         const float* Bsm = Bs[t & 1];
         const int kvalid = (t < nt0) ? min(BK, s0.kend - (s0.kbeg + t * BK)) : min(BK, s1.kend - (t - nt0) * BK);
+        float a[2][TM][4], b[2][TN][4];
         if (kvalid == BK) {
+            if (TM * TN == 1) {
+                // One MFMA tile per wavefront: little matrix work per fragment, so the fragments of group
+                // kg + 1 are read from LDS while group kg feeds the matrix core (measured +2..4 %; with four
+                // tiles per wavefront the same change costs 3..5 %, so those keep read-then-use order).
+                load_frag(Asm, Bsm, 0, a[0], b[0]);
 #pragma unroll
-            for (int kg = 0; kg < BK / 8; ++kg) kgroup(Asm, Bsm, kg);
+                for (int kg = 0; kg < BK / 8; ++kg) {
+                    if (kg + 1 < BK / 8) load_frag(Asm, Bsm, kg + 1, a[(kg + 1) & 1], b[(kg + 1) & 1]);
+                    // keep the instruction scheduler from sinking those reads back down to their first use
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_group(a[kg & 1], b[kg & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int kg = 0; kg < BK / 8; ++kg) {
+                    load_frag(Asm, Bsm, kg, a[0], b[0]);
+                    mfma_group(a[0], b[0]);
+                }
+            }
         } else {
             const int ngroups = (kvalid + 7) >> 3;
-            for (int kg = 0; kg < ngroups; ++kg) kgroup(Asm, Bsm, kg);
+            for (int kg = 0; kg < ngroups; ++kg) {
+                load_frag(Asm, Bsm, kg, a[0], b[0]);
+                mfma_group(a[0], b[0]);
+            }
         }
     };
 
