@@ -156,9 +156,9 @@ def main():
                          "Actor, V-learner and P-learner on three streams with local network copies exchanged once "
                          "per Actor step (Section 3.1 / 3.2), same 1 : 8 : 4 rates.  parallel-1stream: that schedule "
                          "enqueued on one stream")
-    ap.add_argument("--isolated", action="store_true",
-                    help="also time a critic-only loop and a policy-update-only loop (changes the launch mix "
-                         "that a profiler sees)")
+    ap.add_argument("--no-isolated", dest="isolated", action="store_false",
+                    help="skip the extra loops that time the V-learner alone (sample + critic update + Polyak) and "
+                         "the policy update alone")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -198,6 +198,20 @@ def main():
     sess.ctx.pql_soft_update(cal_src, cal_dst, cal_src.numel(), 1.0)
     torch.cuda.synchronize()
     del cal_src, cal_dst
+
+    # The matrix cores' sustained rate on register operands (no memory): the achievable ceiling next
+    # to the nominal peak.  Outside the timed region.
+    probe_blocks, probe_iters = 256 * 8, 4096
+    probe_out = torch.empty(probe_blocks * 256, dtype=torch.float32, device="cuda")
+    sess.ctx.pql_probe_mfma(probe_out, probe_blocks, 64)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    sess.ctx.pql_probe_mfma(probe_out, probe_blocks, probe_iters)
+    ev1.record()
+    torch.cuda.synchronize()
+    mfma_ceiling = probe_blocks * 4 * 4 * probe_iters * 4096.0 / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
+    del probe_out
 
     sched = Schedule(sess, env_dev)
     if args.schedule == "serial":
@@ -287,6 +301,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
                      "avg_launch_us": 1e3 * dom["total_ms"] / dom["launches"], "launches": dom["launches"],
+                     "achievable_peak": mfma_ceiling, "frac_of_achievable": achieved / mfma_ceiling,
                      "all_gemm_tflops": tot_gemm_flops / (tot_gemm_ms * 1e-3) / 1e12},
         "mfma_util_pct": 100.0 * flops_step * value / (PEAK_FP32_MFMA_TFLOPS * 1e12),
         "actor_actions_per_s": w.num_envs / t_act,

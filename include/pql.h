@@ -295,6 +295,14 @@ typedef struct {
     double  bytes;
 } pql_kernel_stat;
 
+/* Achievable matrix-core rate: `blocks` workgroups of 4 wavefronts each issue 4 * iters independent
+ * v_mfma_f32_32x32x2_f32 on register operands (no memory traffic) and store one float per thread to
+ * out[blocks * 256] ([device]).  Work = blocks * 4 * 4 * iters * 4096 FLOP; time it with events or
+ * through pql_profile_begin / pql_profile_end (kernel "mfma_probe_kernel").  This is the ceiling the
+ * matrix pipelines sustain at the clock the chip holds under that load, for comparison with the
+ * nominal peak. */
+int32_t pql_probe_mfma(pql_ctx* ctx, float* out, int32_t blocks, int32_t iters, void* stream);
+
 int32_t pql_profile_begin(pql_ctx* ctx, int32_t max_launches);
 int32_t pql_profile_end(pql_ctx* ctx, pql_kernel_stat* out, int32_t max_out, int32_t* n_out);
 

@@ -24,7 +24,7 @@ EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_coun
            "pql_sample_nstep", "pql_gather_nstep", "pql_actor_act", "pql_critic_update", "pql_actor_update",
            "pql_soft_update", "pql_adam_step", "pql_profile_begin", "pql_profile_end",
            "pql_obs_norm_bytes", "pql_obs_norm_attach", "pql_obs_norm_reset", "pql_sample_states", "pql_sac_attach",
-           "pql_sac_attach_lagged"]
+           "pql_sac_attach_lagged", "pql_probe_mfma"]
 
 
 class PqlConfig(C.Structure):
@@ -101,6 +101,7 @@ def load_library() -> C.CDLL:
         "pql_obs_norm_reset": (I32, [P, P]),
         "pql_sac_attach": (I32, [P, P, F]),
         "pql_sac_attach_lagged": (I32, [P, P]),
+        "pql_probe_mfma": (I32, [P, P, I32, I32, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -282,3 +283,6 @@ class Context:
 
     def pql_sac_attach_lagged(self, log_alpha):
         self._check(self.lib.pql_sac_attach_lagged(self.h, _ptr(log_alpha)))
+
+    def pql_probe_mfma(self, out, blocks, iters, stream=None):
+        self._check(self.lib.pql_probe_mfma(self.h, _ptr(out), blocks, iters, _stream(stream)))

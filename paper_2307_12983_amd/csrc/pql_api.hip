@@ -54,6 +54,7 @@ const char* kernel_name(int kid) {
         case KID_SAC_SAMPLE: return "sac_sample_kernel";
         case KID_SAC_GRAD: return "sac_grad_kernel";
         case KID_SAC_ALPHA: return "sac_alpha_kernel";
+        case KID_MFMA_PROBE: return "mfma_probe_kernel";
         default: return "?";
     }
 }
@@ -1183,6 +1184,17 @@ int32_t pql_profile_end(pql_ctx* c, pql_kernel_stat* out, int32_t max_out, int32
     }
     *n_out = n;
     return rc;
+}
+
+// ---------------------------------------------------------------------------------------------
+int32_t pql_probe_mfma(pql_ctx* c, float* out, int32_t blocks, int32_t iters, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!out) return E.fail(PQL_ERR_NULL, "pql_probe_mfma: null pointer");
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1 || iters > (1 << 24)) return E.fail(PQL_ERR_INVALID_ARG, "pql_probe_mfma: bad size");
+    const hipError_t e = mfma_probe_launch(out, blocks, iters, (hipStream_t)stream);
+    if (e != hipSuccess) return E.hip(e, "pql_probe_mfma");
+    return PQL_OK;
 }
 
 // ---------------------------------------------------------------------------------------------

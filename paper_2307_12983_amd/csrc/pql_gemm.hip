@@ -394,4 +394,32 @@ hipError_t gemm_launch(int mode, int tile, GemmGroup& g, hipStream_t stream) {
     return e;
 }
 
+// ---- achievable matrix-core rate ---------------------------------------------------------------
+// Every wavefront issues `iters` rounds of four independent v_mfma_f32_32x32x2_f32 on register
+// operands (no memory, no LDS): the rate the matrix cores sustain at the clock the chip holds
+// under that load.  Results are stored so that the work cannot be optimised away.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* __restrict__ out, int iters) {
+    floatx16 c0, c1, c2, c3;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { c0[r] = 0.f; c1[r] = 0.f; c2[r] = 0.f; c3[r] = 0.f; }
+    float a = 1e-3f * (float)(threadIdx.x & 7), b = 1e-3f * (float)(blockIdx.x & 3);
+    for (int i = 0; i < iters; ++i) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(b, a, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, a, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x2f32(b, b, c3, 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += c0[r] + c1[r] + c2[r] + c3[r];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+hipError_t mfma_probe_launch(float* out, int blocks, int iters, hipStream_t stream) {
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, mfma_probe_kernel, dim3(blocks), dim3(256), 0, stream, out, iters);
+    prof_commit(ps, KID_MFMA_PROBE, 2.0 * 32 * 32 * 2 * 4.0 * (double)iters * 4.0 * (double)blocks, 0.0);
+    return hipGetLastError();
+}
+
 }  // namespace pql

@@ -18,7 +18,7 @@ enum KernelId : int {
     KID_ADAM = 19, KID_SOFT_UPDATE = 20, KID_COPY = 21, KID_FUSED_CRITIC = 22, KID_FUSED_POLICY = 23,
     KID_FUSED_ACT = 24, KID_TRANSPOSE = 25, KID_ADAM_CLIP = 26, KID_OBS_STATS = 27, KID_OBS_MERGE = 28,
     KID_NORMALIZE = 29, KID_DIST_CRITIC = 30, KID_DIST_POLICY = 31, KID_SAC_SAMPLE = 32, KID_SAC_GRAD = 33,
-    KID_SAC_ALPHA = 34, KID_COUNT = 35
+    KID_SAC_ALPHA = 34, KID_MFMA_PROBE = 35, KID_COUNT = 36
 };
 const char* kernel_name(int kid);
 bool prof_active();
@@ -110,6 +110,7 @@ int gemm_tile_n(int tile);
 int gemm_waves_m(int tile);
 // Fills tiles_m/tiles_n/tile_begin/total_tiles from M, N, splits; returns hipError.
 hipError_t gemm_launch(int mode, int tile, GemmGroup& g, hipStream_t stream);
+hipError_t mfma_probe_launch(float* out, int blocks, int iters, hipStream_t stream);
 
 // ---- reduction + Adam -------------------------------------------------------------------
 struct RedTensor {

@@ -26,7 +26,7 @@ def cfg_of(w, max_batch=None):
 def test_library_exports_every_declared_symbol():
     lib = B.load_library()
     names = header_functions()
-    assert len(names) == 25 and sorted(B.EXPORTS) == names
+    assert len(names) == 26 and sorted(B.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
 
