@@ -56,8 +56,8 @@ def stats_summary(stats_csv, bench_json, out, title):
     with open(out, "w") as f:
         f.write("# %s\n\n" % title)
         f.write("Command (from the repository root, on one MI355X):\n\n")
-        f.write("    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof_bench -o bench -- python3 bench.py\n")
-        f.write("    python -m paper_2307_12983_amd.profile_tools stats gpurun_out/prof_bench/bench_kernel_stats.csv <bench line> <this file> <title>\n\n")
+        f.write("    rocprofv3 --kernel-trace --stats --output-format csv -d <out>/prof_bench -o bench -- python3 bench.py\n")
+        f.write("    python -m paper_2307_12983_amd.profile_tools stats <out>/prof_bench/bench_kernel_stats.csv <bench line> <this file> <title>\n\n")
         f.write("Kernel summary (`bench_kernel_stats.csv`), all launches of the process (ring fill, calibration copy, "
                 "warm-up, timed steps, Actor loop, event pass):\n\n")
         f.write("| kernel (name in bench.py) | calls | avg us | min us | max us | % of GPU time |\n|---|---|---|---|---|---|\n")
@@ -97,9 +97,9 @@ def traffic_summary(fetch_csv, write_csv, kernel, out):
     with open(out, "w") as f:
         f.write("# HBM traffic per launch of %s (bench.py, default workload)\n" % kernel)
         f.write("# Commands (two counter passes, each its own run; from the repository root on one MI355X):\n")
-        f.write("#   rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch -o b -- python3 bench.py --steps 96 --warmup 16 --no-cpu-baseline\n")
-        f.write("#   rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_write -o b -- python3 bench.py --steps 96 --warmup 16 --no-cpu-baseline\n")
-        f.write("#   python -m paper_2307_12983_amd.profile_tools traffic gpurun_out/pmc_fetch/b_counter_collection.csv gpurun_out/pmc_write/b_counter_collection.csv %s <this file>\n" % kernel)
+        f.write("#   rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out>/pmc_fetch -o b -- python3 bench.py --steps 96 --warmup 16 --no-cpu-baseline\n")
+        f.write("#   rocprofv3 --pmc WRITE_SIZE --output-format csv -d <out>/pmc_write -o b -- python3 bench.py --steps 96 --warmup 16 --no-cpu-baseline\n")
+        f.write("#   python -m paper_2307_12983_amd.profile_tools traffic <out>/pmc_fetch/b_counter_collection.csv <out>/pmc_write/b_counter_collection.csv %s <this file>\n" % kernel)
         f.write("# Each counter (KiB per dispatch) is scaled by what it reads for the calibration copy of %d floats\n" % CAL_COPY_FLOATS)
         f.write("# (%d bytes read, as many written).\n" % (CAL_COPY_FLOATS * 4))
         f.write("kernel=%s\n" % kernel)
