@@ -146,3 +146,51 @@ def test_clipping_bound_is_validated_on_the_host():
     assert lib.pql_adam_step(ctx.h, p, p, p, p, 16, clip, 1, None) == -1               # no scratch for the norm here
     assert ctx.get_state() == [0] * 8
     ctx.close()
+
+
+def test_variant_switches_are_validated_on_the_host():
+    lib = B.load_library()
+    w = W.WORKLOADS["tiny"]
+    h = C.c_void_p()
+
+    def cfg(**kw):
+        return B.make_config(w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.nstep, w.gamma, w.hidden, 256, w.rng_seed, **kw)
+
+    for bad in (dict(num_atoms=-1), dict(num_atoms=65), dict(num_atoms=51, v_min=1.0, v_max=1.0),
+                dict(stochastic_policy=2), dict(stochastic_policy=1, num_atoms=51, v_min=-10.0, v_max=10.0)):
+        assert lib.pql_create(C.byref(cfg(**bad)), C.byref(h)) == -1, bad
+    # output widths follow the switches
+    base = B.Context(cfg())
+    dist = B.Context(cfg(num_atoms=51, v_min=-10.0, v_max=10.0))
+    sac = B.Context(cfg(stochastic_policy=1))
+    hl = w.hidden[-1]
+    assert dist.critic_param_count() - base.critic_param_count() == 50 * (hl + 1)
+    assert sac.actor_param_count() - base.actor_param_count() == w.act_dim * (hl + 1)
+    assert dist.actor_param_count() == base.actor_param_count() and sac.critic_param_count() == base.critic_param_count()
+    # the temperature belongs to the stochastic policy only, and updates refuse to run without it
+    p = C.c_void_p(0x1000)
+    assert lib.pql_sac_attach(base.h, p, -2.0) == -1
+    assert lib.pql_sac_attach(sac.h, C.c_void_p(0x1004), -2.0) == -6
+    opt = B.PqlAdam(1e-3, 0.9, 0.999, 1e-8, 0.0)
+    batch = B.PqlBatch(p, p, p, p, p, p)
+    assert lib.pql_critic_update(sac.h, p, p, p, p, p, p, batch, 8, opt, p, p, None) == -2
+    assert lib.pql_actor_update(sac.h, p, p, p, p, p, p, 8, opt, p, p, None) == -2
+    assert "temperature" in sac.last_error()
+    for c in (base, dist, sac):
+        c.close()
+
+
+def test_state_sampling_and_probe_argument_errors():
+    lib = B.load_library()
+    w = W.WORKLOADS["tiny"]
+    ctx = B.Context(cfg_of(w))
+    p = C.c_void_p(0x1000)
+    st = B.PqlStorage(p, p, p, p, p)
+    assert lib.pql_sample_states(ctx.h, st, 16, p, p, None) == -3            # nothing pushed yet
+    assert lib.pql_sample_states(ctx.h, st, 16, None, p, None) == -2
+    assert lib.pql_sample_states(ctx.h, st, -1, p, p, None) == -1
+    assert lib.pql_sample_states(ctx.h, st, max(w.batch, w.num_envs) + 1, p, p, None) == -4
+    assert lib.pql_probe_mfma(ctx.h, None, 8, 8, None) == -2
+    assert lib.pql_probe_mfma(ctx.h, p, 0, 8, None) == -1
+    assert ctx.get_state() == [0] * 8
+    ctx.close()
