@@ -188,14 +188,14 @@ struct Layout {
 // FUSED_MAXW wide, the action vector fits one MFMA tile and the tile's LDS footprint fits a CU.
 bool fused_ok(const pql_config* c) {
     if (distributional(c)) return false;          // logits layer and projection run on the layered path
-    if (c->stochastic_policy) return false;       // so do sampling and the log-density terms
     int hmax = 0;
     for (int l = 0; l < c->n_hidden; ++l) {
         if (c->hidden[l] % 32 != 0 || c->hidden[l] > FUSED_MAXW) return false;
         hmax = c->hidden[l] > hmax ? c->hidden[l] : hmax;
     }
-    if (c->act_dim > FUSED_MAX_ACT || c->obs_dim > 1024) return false;
-    return fused_lds_bytes(c->obs_dim, c->act_dim, hmax) <= 160 * 1024;
+    const int aw = actor_out(c);                  // the policy's output columns share one 32-column tile
+    if (aw > FUSED_MAX_ACT || c->obs_dim > 1024) return false;
+    return fused_lds_bytes(c->obs_dim, aw, hmax) <= 160 * 1024;
 }
 int max_hidden(const pql_config* c) {
     int hmax = 0;
@@ -281,9 +281,9 @@ void make_layout(const pql_config* c, Layout& w) {
             w.colQ[i][l] = take(crow * h);
         }
     }
-    w.colA[L + 1] = take(crow * (size_t)c->act_dim);
+    w.colA[L + 1] = take(crow * (size_t)actor_out(c));
     w.aOut = take(B * c->act_dim);
-    w.dPre = take(B * c->act_dim);
+    w.dPre = take(B * (size_t)actor_out(c));
     w.y = take(B);
     const size_t hl = (size_t)c->hidden[L - 1];
     for (int i = 0; i < 2; ++i) {
@@ -297,7 +297,7 @@ void make_layout(const pql_config* c, Layout& w) {
         for (int l = 1; l < L; ++l) w.wT[i][l] = take((size_t)c->hidden[l - 1] * c->hidden[l]);
         w.w1aT[i] = take((size_t)c->act_dim * c->hidden[0]);
     }
-    for (int l = 1; l <= L; ++l) w.waT[l] = take((size_t)c->hidden[l - 1] * (l < L ? c->hidden[l] : c->act_dim));
+    for (int l = 1; l <= L; ++l) w.waT[l] = take((size_t)c->hidden[l - 1] * (l < L ? c->hidden[l] : actor_out(c)));
     w.splitk = take(splitk_floats(c, (int)B));
     {
         const size_t pa = (size_t)pql_actor_param_count(c), pc = 2 * (size_t)pql_critic_param_count(c);
@@ -311,7 +311,7 @@ void make_layout(const pql_config* c, Layout& w) {
         w.epsb = take(B * c->act_dim);
         w.dOut = take(B * a2);
         w.p_sc = take(nblk * a2);
-        w.p_lp = take(nblk);
+        w.p_lp = take(nblk > nwg ? nblk : nwg);       // one partial per workgroup of whichever kernel writes them
     }
     if (distributional(c))
         for (int i = 0; i < 2; ++i) {
@@ -616,6 +616,18 @@ static hipError_t actor_hidden_forward(pql_ctx* c, const float* params, const fl
     return hipSuccess;
 }
 
+// Draw selection of the stochastic policy inside the row-tile kernels (off for a deterministic policy).
+static FusedSac fused_sac(const pql_ctx* c, uint32_t stream_id, int64_t call, const float* log_alpha) {
+    FusedSac f;
+    std::memset(&f, 0, sizeof(f));
+    f.on = c->cfg.stochastic_policy ? 1 : 0;
+    f.stream_id = stream_id;
+    f.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); f.key1 = (uint32_t)(c->cfg.seed >> 32);
+    f.ctr2 = (uint32_t)((uint64_t)call & 0xffffffffu); f.ctr3 = (uint32_t)((uint64_t)call >> 32);
+    f.log_alpha = log_alpha;
+    return f;
+}
+
 // Output layer of the stochastic policy (mu, raw log sigma) on top of hA[L], then one sample per row.
 static hipError_t stochastic_policy_sample(pql_ctx* c, const float* params, int B, float* ws, const Layout& w, float* act,
                                            float* logp, float* eps, uint32_t stream_id, int64_t call, hipStream_t st) {
@@ -677,6 +689,7 @@ int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, i
         fa.noise.act_dim = c->cfg.act_dim; fa.noise.sigma_rows = num; fa.noise.sigma_min = sigma_min; fa.noise.sigma_max = sigma_max;
         fa.noise.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); fa.noise.key1 = (uint32_t)(c->cfg.seed >> 32);
         fa.noise.ctr2 = (uint32_t)((uint64_t)c->acts & 0xffffffffu); fa.noise.ctr3 = (uint32_t)((uint64_t)c->acts >> 32);
+        fa.sac = fused_sac(c, 2u, c->acts, nullptr);
         const hipError_t fe = fused_act_launch(fa, st);
         if (fe != hipSuccess) return E.hip(fe, "pql_actor_act");
         c->acts += 1;
@@ -769,6 +782,7 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
         }
         fa.obs = batch.obs; fa.act = batch.act; fa.ret = batch.ret; fa.next_obs = batch.next_obs; fa.boot = batch.boot;
         fa.y = ws + w.y; fa.p_loss = ws + w.p_loss;
+        fa.sac = fused_sac(c, 4u, c->critic_t, c->temperature_v);
         if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
         if ((e = fused_critic_launch(fa, st)) != hipSuccess) return E.hip(e, who);
         head_parts = fa.nwg;
@@ -957,6 +971,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     const bool sac = c->cfg.stochastic_policy != 0;
     const int aw = actor_out(&c->cfg);                          // width of the policy's output layer
     const float* d_top = sac ? ws + w.dOut : ws + w.dPre;       // gradient at that layer
+    int logp_parts = (B + SAC_ROWS - 1) / SAC_ROWS;             // partial sums of log pi (stochastic policy)
     if (fused_ok(&c->cfg)) {
         TransposeArgs tr;
         tr.n = 0;
@@ -983,16 +998,19 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
             fa.q_out[i] = ws + w.q[i];
         }
         for (int l = 1; l <= L; ++l) {
-            add_tr(actor_params + c->a_w[l], ws + w.waT[l], c->cfg.hidden[l - 1], l < L ? c->cfg.hidden[l] : ad);
+            add_tr(actor_params + c->a_w[l], ws + w.waT[l], c->cfg.hidden[l - 1], l < L ? c->cfg.hidden[l] : aw);
             fa.waT[l] = ws + w.waT[l];
             fa.hA[l] = ws + w.hA[l]; fa.dA[l] = ws + w.dA[l]; fa.colA[l] = ws + w.colA[l];
         }
         fa.colA[L + 1] = ws + w.colA[L + 1];
-        fa.obs = obs; fa.dPre = ws + w.dPre; fa.p_loss = ws + w.p_loss;
+        fa.obs = obs; fa.dPre = const_cast<float*>(d_top); fa.p_loss = ws + w.p_loss;
+        fa.sac = fused_sac(c, 5u, c->actor_t, c->temperature);
+        fa.p_logp = sac ? ws + w.p_lp : nullptr;
         if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
         if ((e = fused_policy_launch(fa, st)) != hipSuccess) return E.hip(e, who);
         loss_parts = fa.nwg;
-        red(adm, c->a_b[L], ws + w.colA[L + 1], ad, fa.nwg, ad);
+        logp_parts = fa.nwg;
+        red(adm, c->a_b[L], ws + w.colA[L + 1], aw, fa.nwg, aw);
         for (int l = 1; l <= L; ++l) red(adm, c->a_b[l - 1], ws + w.colA[l], c->cfg.hidden[l - 1], fa.nwg, c->cfg.hidden[l - 1]);
     } else {
         // 1. a = pi(s), or the reparameterised sample a = tanh(mu + sigma eps)
@@ -1123,7 +1141,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
     if (sac) {      // temperature step on the log-densities of this batch
         SacAlphaArgs al;
-        al.B = B; al.nparts = (B + SAC_ROWS - 1) / SAC_ROWS; al.p_logp = ws + w.p_lp; al.temperature = c->temperature;
+        al.B = B; al.nparts = logp_parts; al.p_logp = ws + w.p_lp; al.temperature = c->temperature;
         al.loss_out = loss_out; al.target_entropy = c->target_entropy;
         al.lr = adm.lr; al.beta1 = adm.beta1; al.beta2 = adm.beta2; al.eps = adm.eps; al.inv_bc1 = adm.inv_bc1; al.inv_bc2 = adm.inv_bc2;
         if ((e = sac_alpha_launch(al, st)) != hipSuccess) return E.hip(e, who);

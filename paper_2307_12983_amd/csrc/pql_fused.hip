@@ -240,7 +240,7 @@ struct TileMem {
 __host__ __device__ inline int tile_floats(int o, int a, int hmax, bool with_small) {
     const int sxa = ((o + 7) & ~7) + 4, sxb = ((a + 7) & ~7) + 4, sh = hmax + 4;
     const int scratch = (2 * BMF * sh >= SCRATCH_F) ? 0 : SCRATCH_F;
-    return BMF * (sxa + sxb + 4 * sh) + scratch + (with_small ? 16 * BMF : 0);
+    return BMF * (sxa + sxb + 4 * sh) + scratch + (with_small ? 48 * BMF : 0);
 }
 
 __device__ inline TileMem carve(int o, int a, int hmax) {
@@ -297,6 +297,54 @@ __device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const Fus
     return cur;
 }
 
+// ---- stochastic policy on a tile (SAC variant) ------------------------------------------------
+__device__ inline void philox4x32_10_f(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                       uint32_t& o0, uint32_t& o1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    o0 = c0; o1 = c1;
+}
+
+__device__ inline float std_normal_f(uint32_t element, const FusedSac& sc) {
+    uint32_t w0, w1;
+    philox4x32_10_f(element, sc.stream_id, sc.ctr2, sc.ctr3, sc.key0, sc.key1, w0, w1);
+    // double precision: (w >> 8) + 0.5 needs 25 significant bits
+    const double u1 = ((double)(w0 >> 8) + 0.5) * 0x1p-24;
+    const double u2 = ((double)(w1 >> 8) + 0.5) * 0x1p-24;
+    return (float)(sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2));
+}
+
+// After small_partial() of the policy's 2a-column output layer: element e of the 32x32 result tile
+// that falls on column col < a draws eps, forms a = tanh(mu + sigma eps) and its share of log pi;
+// the shares of a row (32 consecutive lanes) are added, so every lane returns the row's log pi.
+// Outputs for col >= a are zero.
+__device__ inline float sac_tile_sample(int scratch, int e, int a, const float* __restrict__ bias, int r0, const FusedSac& sc,
+                                        int& row, int& col, float& act, float& eps, float& raw) {
+    const float s = small_sum(scratch, e, row, col);
+    float lp = 0.f;
+    act = 0.f; eps = 0.f; raw = 0.f;
+    if (col < a) {
+        int r2, c2;
+        const float mu = s + bias[col];
+        raw = small_sum(scratch, e + a, r2, c2) + bias[col + a];
+        eps = std_normal_f((uint32_t)((r0 + row) * a + col), sc);
+        const float ls = fminf(fmaxf(raw, SAC_LOG_STD_MIN), SAC_LOG_STD_MAX);
+        const float u = mu + expf(ls) * eps;
+        const float x = -2.f * u;
+        const float softplus = fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
+        lp = -0.5f * eps * eps - ls - 0.91893853320467274178f - 2.f * (0.69314718055994530942f - u - softplus);
+        act = tanhf(u);
+    }
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) lp += __shfl_xor(lp, o);
+    return lp;
+}
+
 // =============================================================================================
 // V-learner step on one row tile (Algorithm 3; Section 3.2 for the lagged target policy):
 // a' = pi^v(s'), t_i = Q'_i(s', a'), y = ret + boot * min(t_1, t_2); q_i = Q_i(s, a);
@@ -307,12 +355,14 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     Lanes T;
     T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
     const int o = A.o, a = A.a, L = A.L, B = A.B;
-    const TileMem m = carve(o, a, A.hmax);
+    const bool sac = A.sac.on != 0;
+    const TileMem m = carve(o, sac ? 2 * a : a, A.hmax);
     const int r0 = blockIdx.x * BMF;
     const int HL = A.H[L - 1];
     float* sm_ret = &smem[m.sm];           // [32]
     float* sm_boot = &smem[m.sm + 32];     // [32]
     float* sm_y = &smem[m.sm + 64];        // [32]
+    float* sm_logp = &smem[m.sm + 96];     // [32] log pi^v(a'|s') of the sampled target action
     float* sm_red = &smem[m.sm + 128];     // [FW][4]
 
     // ---- target path ------------------------------------------------------------------------
@@ -329,12 +379,20 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         float* const* const hg[1] = {nullptr};
         cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, hg, r0, B);
     }
-    small_partial(T, m.H[0][cur], m.SH, HL, A.pi.w[L], a, a, m.scratch);
+    const int aw = sac ? 2 * a : a;        // columns of the policy's output layer
+    small_partial(T, m.H[0][cur], m.SH, HL, A.pi.w[L], aw, aw, m.scratch);
     __syncthreads();
     for (int e = T.tid; e < 1024; e += FT) {
         int row, col;
-        const float s = small_sum(m.scratch, e, row, col);
-        if (col < m.SXB - 4) smem[m.XB + row * m.SXB + col] = col < a ? tanhf(s + A.pi.b[L][col]) : 0.f;
+        if (sac) {      // a' ~ pi^v(.|s') with its log-density (soft target of the SAC variant)
+            float act, eps, raw;
+            const float lp = sac_tile_sample(m.scratch, e, a, A.pi.b[L], r0, A.sac, row, col, act, eps, raw);
+            if (col < m.SXB - 4) smem[m.XB + row * m.SXB + col] = act;
+            if (col == 0) sm_logp[row] = lp;
+        } else {
+            const float s = small_sum(m.scratch, e, row, col);
+            if (col < m.SXB - 4) smem[m.XB + row * m.SXB + col] = col < a ? tanhf(s + A.pi.b[L][col]) : 0.f;
+        }
     }
     __syncthreads();
     {
@@ -351,6 +409,7 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
             wt1[j] = c < HL ? A.qt[1].w[L][c] : 0.f;
         }
         const float bt0 = A.qt[0].b[L][0], bt1 = A.qt[1].b[L][0];
+        const float alpha = sac ? expf(A.sac.log_alpha[0]) : 0.f;
         for (int rr = 0; rr < BMF / FW; ++rr) {
             const int row = T.wave * (BMF / FW) + rr;
             float s0 = 0.f, s1 = 0.f;
@@ -365,7 +424,9 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
             s0 = wsum(s0) + bt0;
             s1 = wsum(s1) + bt1;
             if (T.lane == 0) {
-                const float y = sm_ret[row] + sm_boot[row] * fminf(s0, s1);
+                float tq = fminf(s0, s1);
+                if (sac) tq -= alpha * sm_logp[row];
+                const float y = sm_ret[row] + sm_boot[row] * tq;
                 sm_y[row] = y;
                 if (r0 + row < B) A.y[r0 + row] = y;
             }
@@ -499,7 +560,9 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     Lanes T;
     T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
     const int o = A.o, a = A.a, L = A.L, B = A.B;
-    const TileMem m = carve(o, a, A.hmax);
+    const bool sac = A.sac.on != 0;
+    const int aw = sac ? 2 * a : a;        // columns of the policy's output layer
+    const TileMem m = carve(o, aw, A.hmax);
     const int r0 = blockIdx.x * BMF;
     const int HL = A.H[L - 1], H1 = A.H[0];
     float* sm_red = &smem[m.sm + 128];     // [FW]
@@ -513,12 +576,23 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
         float* const* const hg[1] = {A.hA};
         cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, hg, r0, B, true);
     }
-    small_partial(T, m.H[0][cur], m.SH, HL, A.pi.w[L], a, a, m.scratch);
+    small_partial(T, m.H[0][cur], m.SH, HL, A.pi.w[L], aw, aw, m.scratch);
     __syncthreads();
+    float* sm_eps = &smem[m.sm + 160];     // [32][16] draws of the reparameterised sample
+    float* sm_raw = &smem[m.sm + 672];     // [32][16] raw log sigma outputs
+    float logp_acc = 0.f;
     for (int e = T.tid; e < 1024; e += FT) {
         int row, col;
-        const float s = small_sum(m.scratch, e, row, col);
-        if (col < m.SXB - 4) smem[m.XB + row * m.SXB + col] = col < a ? tanhf(s + A.pi.b[L][col]) : 0.f;
+        if (sac) {      // a = tanh(mu + sigma eps); eps and raw are kept for the backward pass
+            float act, eps, raw;
+            const float lp = sac_tile_sample(m.scratch, e, a, A.pi.b[L], r0, A.sac, row, col, act, eps, raw);
+            if (col < m.SXB - 4) smem[m.XB + row * m.SXB + col] = act;
+            if (col < a) { sm_eps[row * 16 + col] = eps; sm_raw[row * 16 + col] = raw; }
+            if (col == 0 && r0 + row < B) logp_acc += lp;
+        } else {
+            const float s = small_sum(m.scratch, e, row, col);
+            if (col < m.SXB - 4) smem[m.XB + row * m.SXB + col] = col < a ? tanhf(s + A.pi.b[L][col]) : 0.f;
+        }
     }
     __syncthreads();
     {
@@ -604,21 +678,41 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
         for (int r = 0; r < 16; ++r) smem[m.scratch + T.wave * 1024 + r * 64 + T.lane] = acc0[0][r] + acc1[0][r];
     }
     __syncthreads();
+    const float ab = sac ? expf(A.sac.log_alpha[0]) / (float)B : 0.f;
     for (int e = T.tid; e < 1024; e += FT) {
         int row, col;
         const float s = small_sum(m.scratch, e, row, col);
-        if (col < m.SXB - 4) {
+        const bool rv = r0 + row < B;
+        if (!sac) {
+            if (col < m.SXB - 4) {
+                const float ap = smem[m.XB + row * m.SXB + col];
+                const float g = (col < a && rv) ? s * (1.f - ap * ap) : 0.f;
+                smem[m.XB + row * m.SXB + col] = g;
+                if (col < a && rv) A.dPre[(size_t)(r0 + row) * a + col] = g;
+            }
+        } else if (col < a) {
+            // J = mean(alpha log pi - min Q): dJ/dmu = dJ/du = g + (alpha/B) 2a; dJ/draw = dJ/du sigma eps - alpha/B
+            // inside the clip of log sigma, 0 outside.  This thread writes columns col (mu) and a + col (raw).
             const float ap = smem[m.XB + row * m.SXB + col];
-            const float g = (col < a && r0 + row < B) ? s * (1.f - ap * ap) : 0.f;
-            smem[m.XB + row * m.SXB + col] = g;
-            if (col < a && r0 + row < B) A.dPre[(size_t)(r0 + row) * a + col] = g;
+            const float raw = sm_raw[row * 16 + col];
+            const float ls = fminf(fmaxf(raw, SAC_LOG_STD_MIN), SAC_LOG_STD_MAX);
+            const float dmu = rv ? s * (1.f - ap * ap) + ab * 2.f * ap : 0.f;
+            const float draw = (rv && raw > SAC_LOG_STD_MIN && raw < SAC_LOG_STD_MAX) ? dmu * expf(ls) * sm_eps[row * 16 + col] - ab : 0.f;
+            smem[m.XB + row * m.SXB + col] = dmu;
+            smem[m.XB + row * m.SXB + a + col] = draw;
+            if (rv) {
+                A.dPre[(size_t)(r0 + row) * aw + col] = dmu;
+                A.dPre[(size_t)(r0 + row) * aw + a + col] = draw;
+            }
+        } else if (col >= aw && col < m.SXB - 4) {
+            smem[m.XB + row * m.SXB + col] = 0.f;
         }
     }
     __syncthreads();
-    if (T.tid < a) {       // bias gradient of the output layer: column sums of dPre over the tile
+    if (T.tid < aw) {      // bias gradient of the output layer: column sums of dPre over the tile
         float s = 0.f;
         for (int row = 0; row < BMF; ++row) s += smem[m.XB + row * m.SXB + T.tid];
-        A.colA[L + 1][(size_t)wg * a + T.tid] = s;
+        A.colA[L + 1][(size_t)wg * aw + T.tid] = s;
     }
     // policy backward data path: delta_L = (dPre W_out^T) * ELU'(z_L), then down the hidden layers
     int pc = 0;
@@ -626,7 +720,7 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     __syncthreads();
     {
         WideArgs<1> w;
-        w.in0[0] = m.XB; w.W0[0] = A.waT[L]; w.ld0 = m.SXB; w.K0 = a; w.in1[0] = 0; w.W1[0] = nullptr; w.ld1 = 0; w.K1 = 0;
+        w.in0[0] = m.XB; w.W0[0] = A.waT[L]; w.ld0 = m.SXB; w.K0 = aw; w.in1[0] = 0; w.W1[0] = nullptr; w.ld1 = 0; w.K1 = 0;
         w.ldw = HL; w.N = HL; w.bias[0] = nullptr; w.aux[0] = m.H[0][pc]; w.ldaux = m.SH; w.outL[0] = m.H[0][pc]; w.ldo = m.SH;
         w.outG[0] = A.dA[L]; w.ldg = HL; w.colsum[0] = A.colA[L] + (size_t)wg * HL; w.epi = WIDE_MUL_DELU;
         wide_linear<1>(T, w, r0, B);
@@ -644,36 +738,28 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
         pc ^= 1;
         __syncthreads();
     }
-    if (T.lane == 0) sm_red[T.wave] = loss_acc;
+    logp_acc = wsum(logp_acc);
+    if (T.lane == 0) { sm_red[T.wave] = loss_acc; sm_red[FW + T.wave] = logp_acc; }
     __syncthreads();
     if (T.tid == 0) {
-        float s = 0.f;
+        float s = 0.f, lp = 0.f;
 #pragma unroll
-        for (int w = 0; w < FW; ++w) s += sm_red[w];
+        for (int w = 0; w < FW; ++w) { s += sm_red[w]; lp += sm_red[FW + w]; }
         A.p_loss[wg] = s;
+        if (sac) A.p_logp[wg] = lp;
     }
 }
 
 // =============================================================================================
 // Actor step on one row tile (Section 3.3, Algorithm 1): a = clip(pi(s) + sigma_i * eps, -1, 1).
 // =============================================================================================
-__device__ inline void philox4x32_10_f(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
-                                       uint32_t& o0, uint32_t& o1) {
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
-        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
-    }
-    o0 = c0; o1 = c1;
-}
-
 __global__ __launch_bounds__(FT) void fused_act_kernel(const FusedActArgs A) {
     Lanes T;
     T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
     const int o = A.o, a = A.a, L = A.L, B = A.B;
-    const TileMem m = carve(o, a, A.hmax);
+    const bool sac = A.sac.on != 0;
+    const int aw = sac ? 2 * a : a;
+    const TileMem m = carve(o, aw, A.hmax);
     const int r0 = blockIdx.x * BMF;
     load_rows(T, m.XA, m.SXA, A.obs, o, r0, B);
     if (A.nmean != nullptr) {
@@ -691,11 +777,17 @@ __global__ __launch_bounds__(FT) void fused_act_kernel(const FusedActArgs A) {
     const FusedNet* const nets[1] = {&A.pi};
     float* const* const hg[1] = {nullptr};
     const int cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, hg, r0, B);
-    small_partial(T, m.H[0][cur], m.SH, A.H[L - 1], A.pi.w[L], a, a, m.scratch);
+    small_partial(T, m.H[0][cur], m.SH, A.H[L - 1], A.pi.w[L], aw, aw, m.scratch);
     __syncthreads();
     const GemmNoise& nz = A.noise;
     for (int e = T.tid; e < 1024; e += FT) {
         int row, col;
+        if (sac) {      // the Actor of the SAC variant samples its policy
+            float act, eps, raw;
+            (void)sac_tile_sample(m.scratch, e, a, A.pi.b[L], r0, A.sac, row, col, act, eps, raw);
+            if (col < a && r0 + row < B) A.act_out[(size_t)(r0 + row) * a + col] = act;
+            continue;
+        }
         const float s = small_sum(m.scratch, e, row, col);
         const int env = r0 + row;
         if (col < a && env < B) {
@@ -722,7 +814,7 @@ static hipError_t set_lds_limit(const void* fn, size_t lds, size_t& configured) 
 }
 
 hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream) {
-    const size_t lds = fused_lds_bytes(a.o, a.a, a.hmax);
+    const size_t lds = fused_lds_bytes(a.o, a.sac.on ? 2 * a.a : a.a, a.hmax);
     static size_t configured = 0;
     const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(fused_policy_kernel), lds, configured);
     if (e != hipSuccess) return e;
@@ -743,7 +835,7 @@ hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream) {
 }
 
 hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream) {
-    const size_t lds = fused_lds_bytes(a.o, a.a, a.hmax);
+    const size_t lds = fused_lds_bytes(a.o, a.sac.on ? 2 * a.a : a.a, a.hmax);
     static size_t configured = 0;
     const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(fused_act_kernel), lds, configured);
     if (e != hipSuccess) return e;
@@ -761,7 +853,7 @@ hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream) {
 }
 
 hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream) {
-    const size_t lds = fused_lds_bytes(a.o, a.a, a.hmax);
+    const size_t lds = fused_lds_bytes(a.o, a.sac.on ? 2 * a.a : a.a, a.hmax);
     static size_t configured = 0;
     if (lds > configured) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_critic_kernel),

@@ -262,6 +262,13 @@ constexpr int FUSED_BM = 32;        // batch rows per workgroup
 constexpr int FUSED_MAXW = 256;     // widest hidden layer
 constexpr int FUSED_MAX_ACT = 32;   // widest action vector
 
+// Stochastic (tanh-Gaussian) policy inside the row-tile kernels: which draw to use and where alpha lives.
+struct FusedSac {
+    int on;
+    uint32_t stream_id, key0, key1, ctr2, ctr3;
+    const float* log_alpha;
+};
+
 struct FusedNet {                   // per layer l = 0..L: weights W_l[in][out] and bias b_l[out]
     const float* w[PQL_MAX_HIDDEN + 1];
     const float* b[PQL_MAX_HIDDEN + 1];
@@ -280,6 +287,7 @@ struct FusedCriticArgs {
     float* colQ[2][PQL_MAX_HIDDEN + 1];        // [i][l], l = 1..L-1: bias-gradient partials [nwg][H_l]
     float* y; float* q_out[2];
     float* p_dw[2]; float* p_dbh[2]; float* p_db[2]; float* p_loss;
+    FusedSac sac;                   // on: a' is a sample of pi^v and y carries the entropy term
 };
 hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream);
 size_t fused_lds_bytes(int o, int a, int hmax);
@@ -297,9 +305,11 @@ struct FusedPolicyArgs {
     float* dA[PQL_MAX_HIDDEN + 1];             // [l], l = 1..L: policy deltas
     float* colA[PQL_MAX_HIDDEN + 2];           // [l], l = 1..L+1: bias-gradient partials [nwg][width]
     float* hQ[2][PQL_MAX_HIDDEN + 1];          // [i][l], l = 1..L-1: critic activations (scratch for L > 2)
-    float* dPre;                               // [B][a]: delta at the policy's pre-tanh output
+    float* dPre;                               // [B][a] (stochastic policy: [B][2a]): delta at the policy's output layer
     float* q_out[2];
     float* p_loss;                             // [nwg]
+    FusedSac sac;                              // on: reparameterised sample, log-density terms in the gradient
+    float* p_logp;                             // [nwg] partial sums of log pi (stochastic policy)
 };
 hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream);
 
@@ -312,6 +322,7 @@ struct FusedActArgs {
     const float* nrstd;
     float* act_out;
     GemmNoise noise;
+    FusedSac sac;                   // on: the action is a sample of the policy, `noise` is unused
 };
 hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream);
 
