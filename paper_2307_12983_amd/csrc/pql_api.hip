@@ -177,7 +177,7 @@ struct Layout {
     size_t w1aT[2];                                                   // transposed action rows of the critics' first layer
     size_t waT[PQL_MAX_HIDDEN + 1];                                   // transposed policy weights, layer l = 1..L
     size_t splitk;
-    size_t lgT[2], lgQ[2], p_dbo[2];                                  // distributional critics: logits, output-bias partials
+    size_t lgT[2], lgQ[2], p_dbo[2], woT[2];                          // distributional critics: logits, output-bias partials, W_out^T
     size_t mu2a, logp, epsb, dOut, p_sc, p_lp;                        // stochastic policy: outputs, log pi, draws, gradient, partials
     size_t sqp;                                                       // per-workgroup sums of squared gradients
     size_t xn;                                                        // standardised Actor observations
@@ -187,7 +187,6 @@ struct Layout {
 // The row-tile fused kernels apply when every hidden layer is a multiple of 32 and at most
 // FUSED_MAXW wide, the action vector fits one MFMA tile and the tile's LDS footprint fits a CU.
 bool fused_ok(const pql_config* c) {
-    if (distributional(c)) return false;          // logits layer and projection run on the layered path
     int hmax = 0;
     for (int l = 0; l < c->n_hidden; ++l) {
         if (c->hidden[l] % 32 != 0 || c->hidden[l] > FUSED_MAXW) return false;
@@ -195,6 +194,7 @@ bool fused_ok(const pql_config* c) {
     }
     const int aw = actor_out(c);                  // the policy's output columns share one 32-column tile
     if (aw > FUSED_MAX_ACT || c->obs_dim > 1024) return false;
+    if (distributional(c) && hmax < 64) return false;   // the dlogits of a row tile borrow 64 columns of an activation tile
     return fused_lds_bytes(c->obs_dim, aw, hmax) <= 160 * 1024;
 }
 int max_hidden(const pql_config* c) {
@@ -318,6 +318,7 @@ void make_layout(const pql_config* c, Layout& w) {
             w.lgT[i] = take(B * (size_t)c->num_atoms);
             w.lgQ[i] = take(B * (size_t)c->num_atoms);
             w.p_dbo[i] = take(nwg * (size_t)c->num_atoms);
+            w.woT[i] = take((size_t)c->num_atoms * c->hidden[L - 1]);
         }
     w.total = off;
 }
@@ -783,12 +784,22 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
         fa.obs = batch.obs; fa.act = batch.act; fa.ret = batch.ret; fa.next_obs = batch.next_obs; fa.boot = batch.boot;
         fa.y = ws + w.y; fa.p_loss = ws + w.p_loss;
         fa.sac = fused_sac(c, 4u, c->critic_t, c->temperature_v);
+        if (dist) {
+            fa.atoms = c->cfg.num_atoms; fa.v_min = c->cfg.v_min; fa.v_max = c->cfg.v_max;
+            for (int i = 0; i < 2; ++i) {
+                TransposeArgs::Mat& mt = tr.m[tr.n++];
+                mt.src = critic_params + i * Pc + c->c_w[L]; mt.dst = ws + w.woT[i]; mt.rows = HL; mt.cols = fa.atoms;
+                fa.woT[i] = ws + w.woT[i]; fa.dlg[i] = ws + w.lgQ[i]; fa.p_dbo[i] = ws + w.p_dbo[i];
+            }
+        }
         if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
         if ((e = fused_critic_launch(fa, st)) != hipSuccess) return E.hip(e, who);
         head_parts = fa.nwg;
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i) {
             for (int l = 1; l < L; ++l)
                 red(adm, i * Pc + c->c_b[l - 1], ws + w.colQ[i][l], c->cfg.hidden[l - 1], fa.nwg, c->cfg.hidden[l - 1]);
+            if (dist) red(adm, i * Pc + c->c_b[L - 1], ws + w.colQ[i][L], HL, fa.nwg, HL);
+        }
     } else {
         // 1. lagged policy pi^v on s' (hidden layers) together with the online critics on (s, a)
         for (int l = 1; l <= L; ++l) {
@@ -996,7 +1007,12 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
             fa.w1aT[i] = ws + w.w1aT[i];
             for (int l = 1; l <= L; ++l) fa.hQ[i][l] = ws + w.hQ[i][l];
             fa.q_out[i] = ws + w.q[i];
+            if (distributional(&c->cfg)) {
+                add_tr(critic_params + i * Pc + c->c_w[L], ws + w.woT[i], HL, c->cfg.num_atoms);
+                fa.woT[i] = ws + w.woT[i];
+            }
         }
+        if (distributional(&c->cfg)) { fa.atoms = c->cfg.num_atoms; fa.v_min = c->cfg.v_min; fa.v_max = c->cfg.v_max; }
         for (int l = 1; l <= L; ++l) {
             add_tr(actor_params + c->a_w[l], ws + w.waT[l], c->cfg.hidden[l - 1], l < L ? c->cfg.hidden[l] : aw);
             fa.waT[l] = ws + w.waT[l];

@@ -345,12 +345,58 @@ __device__ inline float sac_tile_sample(int scratch, int e, int a, const float* 
     return lp;
 }
 
+// ---- distributional critics on a tile (PQL-D) -------------------------------------------------
+__device__ inline float wmax(float x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+
+// Softmax over the lanes < atoms (lane = atom): returns p and, through logp, log p (0 for idle lanes).
+__device__ inline float lane_softmax_f(float logit, bool live, float& logp) {
+    const float mx = wmax(live ? logit : -3.0e38f);
+    const float e = live ? expf(logit - mx) : 0.f;
+    const float s = wsum(e);
+    logp = live ? (logit - mx) - logf(s) : 0.f;
+    return e / s;
+}
+
+// Logits of two critics (atoms <= 64 columns each) from their last hidden tiles: wavefront w takes
+// network (w >> 1) & 1, 32-column tile w & 1 and every second chunk of the contraction starting at
+// w >> 2; the eight partial 32x32 tiles go to `scratch` (accumulator layout).  The scratch region may
+// alias one of the input tiles, hence the barrier between reading and writing.
+__device__ inline void dist_logit_partial(const Lanes& T, const int (&in)[2], int ld, int K, const float* const (&W)[2],
+                                          int atoms, int scratch) {
+    floatx16 acc0[1], acc1[1];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc0[0][r] = 0.f; acc1[0][r] = 0.f; }
+    const int net = (T.wave >> 1) & 1, tile = T.wave & 1, kh = T.wave >> 2;
+    const int n = tile * 32 + T.l32;
+    const int ncol = n < atoms ? n : atoms - 1;
+    const int ins[1] = {net ? in[1] : in[0]};
+    const float* const ws[1] = {net ? W[1] : W[0]};
+    if (tile * 32 < atoms) mac_segment<1>(acc0, acc1, ins, ld, K, ws, atoms, ncol, T, kh, 2);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) smem[scratch + T.wave * 1024 + r * 64 + T.lane] = acc0[0][r] + acc1[0][r];
+}
+
+// Logit (before the bias) of network `net` at tile row `row`, atom k < 64, from those partial tiles.
+__device__ inline float dist_logit(int scratch, int net, int row, int k) {
+    const int tile = k >> 5, col = k & 31;
+    const int rr = ((row >> 3) << 2) | (row & 3), half = (row >> 2) & 1;    // inverse of acc_row()
+    const int e = rr * 64 + half * 32 + col;
+    const int w0 = net * 2 + tile;
+    return smem[scratch + w0 * 1024 + e] + smem[scratch + (w0 + 4) * 1024 + e];
+}
+
 // =============================================================================================
 // V-learner step on one row tile (Algorithm 3; Section 3.2 for the lagged target policy):
 // a' = pi^v(s'), t_i = Q'_i(s', a'), y = ret + boot * min(t_1, t_2); q_i = Q_i(s, a);
 // loss partials, output deltas, and the deltas of every hidden layer of both critics.  The twin
 // critics always run as a pair: each wavefront carries one 32-column tile of both.
 // =============================================================================================
+template <bool DIST>
 __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs A) {
     Lanes T;
     T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
@@ -400,35 +446,68 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         float* const* const hg[2] = {nullptr, nullptr};
         cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B);
     }
-    {   // scalar heads of the target critics, min, TD target: one wavefront per row
-        float wt0[4], wt1[4];
+    float m_reg[BMF / FW];      // distributional critics: the projected target distribution of this wavefront's rows (lane = atom)
+    const int atoms = DIST ? A.atoms : 1;
+    const bool live = T.lane < atoms;
+    const float dz = DIST ? (A.v_max - A.v_min) / (float)(atoms - 1) : 0.f;
+    const float zk = A.v_min + (float)T.lane * dz;
+    if (DIST) {
+        // logits of the twin target critics, the smaller mean picks the next-state distribution, its atoms
+        // move to clip(ret + boot z) and are projected back onto the support (lane k gathers atom k's mass)
+        const int ins[2] = {m.H[0][cur], m.H[1][cur]};
+        const float* const wo[2] = {A.qt[0].w[L], A.qt[1].w[L]};
+        dist_logit_partial(T, ins, m.SH, HL, wo, atoms, m.scratch);
+        __syncthreads();
+        const float bt0 = live ? A.qt[0].b[L][T.lane] : 0.f, bt1 = live ? A.qt[1].b[L][T.lane] : 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = T.lane + 64 * j;
-            wt0[j] = c < HL ? A.qt[0].w[L][c] : 0.f;
-            wt1[j] = c < HL ? A.qt[1].w[L][c] : 0.f;
-        }
-        const float bt0 = A.qt[0].b[L][0], bt1 = A.qt[1].b[L][0];
-        const float alpha = sac ? expf(A.sac.log_alpha[0]) : 0.f;
         for (int rr = 0; rr < BMF / FW; ++rr) {
             const int row = T.wave * (BMF / FW) + rr;
-            float s0 = 0.f, s1 = 0.f;
-#pragma unroll
+            float unused;
+            const float t0 = lane_softmax_f(dist_logit(m.scratch, 0, row, T.lane) + bt0, live, unused);
+            const float t1 = lane_softmax_f(dist_logit(m.scratch, 1, row, T.lane) + bt1, live, unused);
+            const float q0 = wsum(t0 * zk), q1 = wsum(t1 * zk);
+            const float pn = q0 <= q1 ? t0 : t1;
+            const float tz = fminf(fmaxf(sm_ret[row] + sm_boot[row] * zk, A.v_min), A.v_max);
+            const float pos = (tz - A.v_min) / dz;
+            float mm = 0.f;
+            for (int j = 0; j < atoms; ++j) {           // j is wave-uniform: lane j's values come as scalars
+                const float pos_j = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pos), j));
+                const float pn_j = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pn), j));
+                mm += pn_j * fminf(fmaxf(1.f - fabsf(pos_j - (float)T.lane), 0.f), 1.f);
+            }
+            m_reg[rr] = live ? mm : 0.f;
+        }
+    } else {
+        {   // scalar heads of the target critics, min, TD target: one wavefront per row
+            float wt0[4], wt1[4];
+    #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int c = T.lane + 64 * j;
-                if (c < HL) {
-                    s0 += smem[m.H[0][cur] + row * m.SH + c] * wt0[j];
-                    s1 += smem[m.H[1][cur] + row * m.SH + c] * wt1[j];
-                }
+                wt0[j] = c < HL ? A.qt[0].w[L][c] : 0.f;
+                wt1[j] = c < HL ? A.qt[1].w[L][c] : 0.f;
             }
-            s0 = wsum(s0) + bt0;
-            s1 = wsum(s1) + bt1;
-            if (T.lane == 0) {
-                float tq = fminf(s0, s1);
-                if (sac) tq -= alpha * sm_logp[row];
-                const float y = sm_ret[row] + sm_boot[row] * tq;
-                sm_y[row] = y;
-                if (r0 + row < B) A.y[r0 + row] = y;
+            const float bt0 = A.qt[0].b[L][0], bt1 = A.qt[1].b[L][0];
+            const float alpha = sac ? expf(A.sac.log_alpha[0]) : 0.f;
+            for (int rr = 0; rr < BMF / FW; ++rr) {
+                const int row = T.wave * (BMF / FW) + rr;
+                float s0 = 0.f, s1 = 0.f;
+    #pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int c = T.lane + 64 * j;
+                    if (c < HL) {
+                        s0 += smem[m.H[0][cur] + row * m.SH + c] * wt0[j];
+                        s1 += smem[m.H[1][cur] + row * m.SH + c] * wt1[j];
+                    }
+                }
+                s0 = wsum(s0) + bt0;
+                s1 = wsum(s1) + bt1;
+                if (T.lane == 0) {
+                    float tq = fminf(s0, s1);
+                    if (sac) tq -= alpha * sm_logp[row];
+                    const float y = sm_ret[row] + sm_boot[row] * tq;
+                    sm_y[row] = y;
+                    if (r0 + row < B) A.y[r0 + row] = y;
+                }
             }
         }
     }
@@ -440,12 +519,60 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     {
         const FusedNet* const nets[2] = {&A.q[0], &A.q[1]};
         float* const* const hg[2] = {A.hQ[0], A.hQ[1]};
-        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B);
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B, DIST);
     }
     const float invB = 1.f / (float)B;
     float loss_acc[2] = {0.f, 0.f}, db_acc[2] = {0.f, 0.f};
     float dw_acc[2][4], dbh_acc[2][4];
-    {   // heads: q, Bellman error, output delta; delta of the last hidden layer written in place
+    if (DIST) {
+        // logits of the online critics, cross-entropy against the projected target, dLoss/dlogits
+        const int ins[2] = {m.H[0][cur], m.H[1][cur]};
+        const float* const wo[2] = {A.q[0].w[L], A.q[1].w[L]};
+        dist_logit_partial(T, ins, m.SH, HL, wo, atoms, m.scratch);
+        __syncthreads();
+        float dl[2][BMF / FW];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const float bq = live ? A.q[i].b[L][T.lane] : 0.f;
+#pragma unroll
+            for (int rr = 0; rr < BMF / FW; ++rr) {
+                const int row = T.wave * (BMF / FW) + rr;
+                const bool rv = r0 + row < B;
+                float lp;
+                const float p = lane_softmax_f(dist_logit(m.scratch, i, row, T.lane) + bq, live, lp);
+                const float S = wsum(m_reg[rr]);
+                const float ce = wsum(m_reg[rr] * lp);
+                if (rv) loss_acc[i] -= ce;
+                const float d = (rv && live) ? (p * S - m_reg[rr]) * invB : 0.f;
+                dl[i][rr] = d;
+                db_acc[i] += d;                         // per lane: the output-bias gradient of atom `lane`
+                if (rv && live) A.dlg[i][(size_t)(r0 + row) * atoms + T.lane] = d;
+            }
+        }
+        __syncthreads();                                // the partial tiles in scratch have been read
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int rr = 0; rr < BMF / FW; ++rr)
+                smem[m.H[i][cur ^ 1] + (T.wave * (BMF / FW) + rr) * m.SH + T.lane] = dl[i][rr];
+        smem[m.sm + 160 + (0 * FW + T.wave) * 64 + T.lane] = db_acc[0];
+        smem[m.sm + 160 + (1 * FW + T.wave) * 64 + T.lane] = db_acc[1];
+        // the partial tiles may have overwritten the second critic's last hidden tile: bring it back
+        if (m.scratch == m.H[1][cur]) load_rows(T, m.H[1][cur], m.SH, A.hQ[1][L], HL, r0, B);
+        __syncthreads();
+        // delta of the last hidden layer: (dlogits W_out^T) * ELU'(h_L), in place over h_L
+        WideArgs<2> w;
+        w.ld0 = m.SH; w.K0 = atoms; w.ld1 = 0; w.K1 = 0; w.ldw = HL; w.N = HL; w.epi = WIDE_MUL_DELU;
+        w.ldaux = m.SH; w.ldo = m.SH; w.ldg = HL;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            w.in0[i] = m.H[i][cur ^ 1]; w.W0[i] = A.woT[i]; w.in1[i] = 0; w.W1[i] = nullptr;
+            w.bias[i] = nullptr; w.aux[i] = m.H[i][cur]; w.outL[i] = m.H[i][cur];
+            w.outG[i] = A.dQ[i][L];
+            w.colsum[i] = A.colQ[i][L] + (size_t)blockIdx.x * HL;
+        }
+        wide_linear<2>(T, w, r0, B);
+    } else {   // heads: q, Bellman error, output delta; delta of the last hidden layer written in place
         float wq[2][4], bq[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -494,7 +621,7 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     // backward data path: delta_{l-1} = (delta_l W_l^T) * ELU'(z_{l-1}), l = L..2 (layers from 1)
     for (int l = L; l >= 2; --l) {
         const int Hl = A.H[l - 1], Hp = A.H[l - 2];
-        if (l < L) {       // h_{l-1} is no longer on chip: bring it back from memory
+        if (l < L || DIST) {   // h_{l-1} is no longer on chip (the dlogits took its tile): bring it back from memory
             load_rows(T, m.H[0][cur ^ 1], m.SH, A.hQ[0][l - 1], Hp, r0, B);
             load_rows(T, m.H[1][cur ^ 1], m.SH, A.hQ[1][l - 1], Hp, r0, B);
             __syncthreads();
@@ -515,13 +642,15 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     }
     // ---- per-workgroup partial sums -----------------------------------------------------------
     // scratch[(arr * FW + wave) * 256 + c], arr = 0..3: dW_out(Q1), dW_out(Q2), db_L(Q1), db_L(Q2)
+    if (!DIST) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int c = T.lane + 64 * j;
-        smem[m.scratch + (0 * FW + T.wave) * 256 + c] = dw_acc[0][j];
-        smem[m.scratch + (1 * FW + T.wave) * 256 + c] = dw_acc[1][j];
-        smem[m.scratch + (2 * FW + T.wave) * 256 + c] = dbh_acc[0][j];
-        smem[m.scratch + (3 * FW + T.wave) * 256 + c] = dbh_acc[1][j];
+        for (int j = 0; j < 4; ++j) {
+            const int c = T.lane + 64 * j;
+            smem[m.scratch + (0 * FW + T.wave) * 256 + c] = dw_acc[0][j];
+            smem[m.scratch + (1 * FW + T.wave) * 256 + c] = dw_acc[1][j];
+            smem[m.scratch + (2 * FW + T.wave) * 256 + c] = dbh_acc[0][j];
+            smem[m.scratch + (3 * FW + T.wave) * 256 + c] = dbh_acc[1][j];
+        }
     }
     if (T.lane == 0) {
         sm_red[T.wave * 4 + 0] = loss_acc[0]; sm_red[T.wave * 4 + 1] = loss_acc[1];
@@ -529,14 +658,25 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     }
     __syncthreads();
     const int wg = blockIdx.x, nwg = gridDim.x;
-    for (int e = T.tid; e < 4 * 256; e += FT) {
-        const int arr = e >> 8, c = e & 255;
-        if (c < HL) {
+    if (DIST) {
+        // output-bias gradient per atom: the wavefronts' per-lane sums were left in the small region
+        if (T.tid < 128) {
+            const int i = T.tid >> 6, k = T.tid & 63;
             float s = 0.f;
 #pragma unroll
-            for (int w = 0; w < FW; ++w) s += smem[m.scratch + (arr * FW + w) * 256 + c];
-            float* dst = arr == 0 ? A.p_dw[0] : (arr == 1 ? A.p_dw[1] : (arr == 2 ? A.p_dbh[0] : A.p_dbh[1]));
-            dst[(size_t)wg * HL + c] = s;
+            for (int w = 0; w < FW; ++w) s += smem[m.sm + 160 + (i * FW + w) * 64 + k];
+            if (k < atoms) A.p_dbo[i][(size_t)wg * atoms + k] = s;
+        }
+    } else {
+        for (int e = T.tid; e < 4 * 256; e += FT) {
+            const int arr = e >> 8, c = e & 255;
+            if (c < HL) {
+                float s = 0.f;
+#pragma unroll
+                for (int w = 0; w < FW; ++w) s += smem[m.scratch + (arr * FW + w) * 256 + c];
+                float* dst = arr == 0 ? A.p_dw[0] : (arr == 1 ? A.p_dw[1] : (arr == 2 ? A.p_dbh[0] : A.p_dbh[1]));
+                dst[(size_t)wg * HL + c] = s;
+            }
         }
     }
     if (T.tid < 4) {
@@ -545,8 +685,8 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         for (int w = 0; w < FW; ++w) s += sm_red[w * 4 + T.tid];
         if (T.tid == 0) A.p_loss[wg] = s;
         if (T.tid == 1) A.p_loss[nwg + wg] = s;
-        if (T.tid == 2) A.p_db[0][wg] = s;
-        if (T.tid == 3) A.p_db[1][wg] = s;
+        if (!DIST && T.tid == 2) A.p_db[0][wg] = s;
+        if (!DIST && T.tid == 3) A.p_db[1][wg] = s;
     }
 }
 
@@ -556,6 +696,7 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
 // through tanh' and back through the policy.  Leaves the policy's activations and deltas in
 // memory for the weight-gradient GEMMs.
 // =============================================================================================
+template <bool DIST>
 __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs A) {
     Lanes T;
     T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
@@ -598,10 +739,54 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     {
         const FusedNet* const nets[2] = {&A.q[0], &A.q[1]};
         float* const* const hg[2] = {A.hQ[0], A.hQ[1]};
-        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B);
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B, DIST);
     }
     float loss_acc = 0.f;
-    {   // heads: q_1, q_2, the smaller one receives -1/B; delta of the last hidden layer in place
+    if (DIST) {
+        // Q_i = mean of critic i's distribution; the smaller one receives dJ/dlogit_k = -(1/B) p_k (z_k - Q)
+        const int atoms = A.atoms;
+        const bool live = T.lane < atoms;
+        const float zk = A.v_min + (float)T.lane * ((A.v_max - A.v_min) / (float)(atoms - 1));
+        const float invB = 1.f / (float)B;
+        const int ins[2] = {m.H[0][cur], m.H[1][cur]};
+        const float* const wo[2] = {A.q[0].w[L], A.q[1].w[L]};
+        dist_logit_partial(T, ins, m.SH, HL, wo, atoms, m.scratch);
+        __syncthreads();
+        const float bq0 = live ? A.q[0].b[L][T.lane] : 0.f, bq1 = live ? A.q[1].b[L][T.lane] : 0.f;
+        float dl[2][BMF / FW];
+#pragma unroll
+        for (int rr = 0; rr < BMF / FW; ++rr) {
+            const int row = T.wave * (BMF / FW) + rr;
+            const bool rv = r0 + row < B;
+            float unused;
+            const float p0 = lane_softmax_f(dist_logit(m.scratch, 0, row, T.lane) + bq0, live, unused);
+            const float p1 = lane_softmax_f(dist_logit(m.scratch, 1, row, T.lane) + bq1, live, unused);
+            const float q0 = wsum(p0 * zk), q1 = wsum(p1 * zk);
+            const bool pick0 = q0 <= q1;
+            if (rv) loss_acc += pick0 ? q0 : q1;
+            if (T.lane == 0 && rv) { A.q_out[0][r0 + row] = q0; A.q_out[1][r0 + row] = q1; }
+            dl[0][rr] = (rv && live && pick0) ? -invB * p0 * (zk - q0) : 0.f;
+            dl[1][rr] = (rv && live && !pick0) ? -invB * p1 * (zk - q1) : 0.f;
+        }
+        __syncthreads();                                // the partial tiles in scratch have been read
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int rr = 0; rr < BMF / FW; ++rr)
+                smem[m.H[i][cur ^ 1] + (T.wave * (BMF / FW) + rr) * m.SH + T.lane] = dl[i][rr];
+        if (m.scratch == m.H[1][cur]) load_rows(T, m.H[1][cur], m.SH, A.hQ[1][L], HL, r0, B);
+        __syncthreads();
+        WideArgs<2> w;
+        w.ld0 = m.SH; w.K0 = atoms; w.ld1 = 0; w.K1 = 0; w.ldw = HL; w.N = HL; w.epi = WIDE_MUL_DELU;
+        w.ldaux = m.SH; w.ldo = m.SH; w.ldg = HL;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            w.in0[i] = m.H[i][cur ^ 1]; w.W0[i] = A.woT[i]; w.in1[i] = 0; w.W1[i] = nullptr;
+            w.bias[i] = nullptr; w.aux[i] = m.H[i][cur]; w.outL[i] = m.H[i][cur];
+            w.outG[i] = nullptr; w.colsum[i] = nullptr;
+        }
+        wide_linear<2>(T, w, r0, B);
+    } else {   // heads: q_1, q_2, the smaller one receives -1/B; delta of the last hidden layer in place
         const float invB = 1.f / (float)B;
         float wq[2][4], bq[2];
 #pragma unroll
@@ -642,7 +827,7 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     // critic backward data path down to the first hidden layer (no parameter gradients here)
     for (int l = L; l >= 2; --l) {
         const int Hl = A.H[l - 1], Hp = A.H[l - 2];
-        if (l < L) {
+        if (l < L || DIST) {
             load_rows(T, m.H[0][cur ^ 1], m.SH, A.hQ[0][l - 1], Hp, r0, B);
             load_rows(T, m.H[1][cur ^ 1], m.SH, A.hQ[1][l - 1], Hp, r0, B);
             __syncthreads();
@@ -816,10 +1001,14 @@ static hipError_t set_lds_limit(const void* fn, size_t lds, size_t& configured) 
 hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream) {
     const size_t lds = fused_lds_bytes(a.o, a.sac.on ? 2 * a.a : a.a, a.hmax);
     static size_t configured = 0;
-    const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(fused_policy_kernel), lds, configured);
+    static size_t configured_d = 0;
+    const bool dist = a.atoms >= 2;
+    const hipError_t e = dist ? set_lds_limit(reinterpret_cast<const void*>(fused_policy_kernel<true>), lds, configured_d)
+                              : set_lds_limit(reinterpret_cast<const void*>(fused_policy_kernel<false>), lds, configured);
     if (e != hipSuccess) return e;
     const ProfSlot ps = prof_slot();
-    PQL_LAUNCH(ps, fused_policy_kernel, dim3(a.nwg), dim3(FT), lds, stream, a);
+    if (dist) PQL_LAUNCH(ps, fused_policy_kernel<true>, dim3(a.nwg), dim3(FT), lds, stream, a);
+    else      PQL_LAUNCH(ps, fused_policy_kernel<false>, dim3(a.nwg), dim3(FT), lds, stream, a);
     double flops = 0.0;
     if (ps.on) {
         double pa = (double)a.o * a.H[0], pc = (double)(a.o + a.a) * a.H[0], pb = (double)a.a * a.H[0], pab = 0.0;
@@ -827,7 +1016,8 @@ hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream) {
             const double w = (double)a.H[l - 1] * a.H[l];
             pa += w; pc += w; pb += w; pab += w;
         }
-        pa += (double)a.H[a.L - 1] * a.a; pab += (double)a.H[a.L - 1] * a.a; pc += a.H[a.L - 1]; pb += a.H[a.L - 1];
+        const double outs = a.atoms >= 2 ? (double)a.atoms : 1.0, aw = a.sac.on ? 2.0 * a.a : (double)a.a;   // critic / policy output widths
+        pa += (double)a.H[a.L - 1] * aw; pab += (double)a.H[a.L - 1] * aw; pc += a.H[a.L - 1] * outs; pb += a.H[a.L - 1] * outs;
         flops = 2.0 * a.B * (pa + 2.0 * pc + 2.0 * pb + pab);
     }
     prof_commit(ps, KID_FUSED_POLICY, flops, 0.0);
@@ -854,21 +1044,21 @@ hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream) {
 
 hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream) {
     const size_t lds = fused_lds_bytes(a.o, a.sac.on ? 2 * a.a : a.a, a.hmax);
-    static size_t configured = 0;
-    if (lds > configured) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_critic_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        configured = lds;
-    }
+    static size_t configured = 0, configured_d = 0;
+    const bool dist = a.atoms >= 2;
+    const hipError_t le = dist ? set_lds_limit(reinterpret_cast<const void*>(fused_critic_kernel<true>), lds, configured_d)
+                               : set_lds_limit(reinterpret_cast<const void*>(fused_critic_kernel<false>), lds, configured);
+    if (le != hipSuccess) return le;
     const ProfSlot ps = prof_slot();
-    PQL_LAUNCH(ps, fused_critic_kernel, dim3(a.nwg), dim3(FT), lds, stream, a);
+    if (dist) PQL_LAUNCH(ps, fused_critic_kernel<true>, dim3(a.nwg), dim3(FT), lds, stream, a);
+    else      PQL_LAUNCH(ps, fused_critic_kernel<false>, dim3(a.nwg), dim3(FT), lds, stream, a);
     // 2 flops per multiply-add of every layer the tile passes through (no weight gradients here)
     double flops = 0.0;
     if (ps.on) {
         double pa = (double)a.o * a.H[0], pc = (double)(a.o + a.a) * a.H[0], pb = 0.0;
         for (int l = 1; l < a.L; ++l) { pa += (double)a.H[l - 1] * a.H[l]; pc += (double)a.H[l - 1] * a.H[l]; pb += (double)a.H[l - 1] * a.H[l]; }
-        pa += (double)a.H[a.L - 1] * a.a; pc += a.H[a.L - 1]; pb += a.H[a.L - 1];
+        const double outs = a.atoms >= 2 ? (double)a.atoms : 1.0;
+        pa += (double)a.H[a.L - 1] * (a.sac.on ? 2.0 * a.a : (double)a.a); pc += a.H[a.L - 1] * outs; pb += a.H[a.L - 1] * outs;
         flops = 2.0 * a.B * (pa + 4.0 * pc + 2.0 * pb);
     }
     prof_commit(ps, KID_FUSED_CRITIC, flops, 0.0);

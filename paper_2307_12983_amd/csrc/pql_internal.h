@@ -288,6 +288,11 @@ struct FusedCriticArgs {
     float* y; float* q_out[2];
     float* p_dw[2]; float* p_dbh[2]; float* p_db[2]; float* p_loss;
     FusedSac sac;                   // on: a' is a sample of pi^v and y carries the entropy term
+    // distributional critics (atoms >= 2): the last layer has `atoms` outputs
+    int atoms; float v_min, v_max;
+    const float* woT[2];            // transpose of the online critics' output weights: [atoms][H_L]
+    float* dlg[2];                  // [B][atoms] dLoss/dlogits (for the weight-gradient GEMM)
+    float* p_dbo[2];                // [nwg][atoms] partial sums of the output-bias gradient
 };
 hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream);
 size_t fused_lds_bytes(int o, int a, int hmax);
@@ -310,6 +315,8 @@ struct FusedPolicyArgs {
     float* p_loss;                             // [nwg]
     FusedSac sac;                              // on: reparameterised sample, log-density terms in the gradient
     float* p_logp;                             // [nwg] partial sums of log pi (stochastic policy)
+    int atoms; float v_min, v_max;             // distributional critics (atoms >= 2)
+    const float* woT[2];                       // transpose of the critics' output weights: [atoms][H_L]
 };
 hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream);
 
