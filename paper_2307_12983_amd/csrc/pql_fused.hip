@@ -264,10 +264,14 @@ size_t fused_lds_bytes(int o, int a, int hmax) { return sizeof(float) * (size_t)
 // Hidden layers of NN equally shaped networks on the tile: layer 1 reads XA (and XB when
 // a_cols > 0), later layers ping-pong between the two tiles of each network.  Returns the index of
 // the tile holding the last hidden activations.  hG[n][l] (l = 1..L-1, may be null) receives h_l.
+// Rows to bring into XA / XB as soon as the first layer has consumed them (their load latency then
+// hides behind the remaining layers instead of standing alone before the next chain).
+struct NextInputs { const float* xa; int xa_cols; const float* xb; int xb_cols; };
+
 template <int NN>
 __device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const FusedNet* const (&nets)[NN], const int* Hw,
                                      int L, int o, int a_cols, float* const* const (&hG)[NN], int r0, int B,
-                                     bool store_last = false) {
+                                     bool store_last = false, const NextInputs* next = nullptr) {
     int cur = 0;
     for (int l = 0; l < L; ++l) {
         const int N = Hw[l];
@@ -293,6 +297,10 @@ __device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const Fus
         wide_linear<NN>(T, w, r0, B);
         cur = dst;
         __syncthreads();
+        if (l == 0 && next != nullptr) {
+            load_rows(T, m.XA, m.SXA, next->xa, next->xa_cols, r0, B);
+            if (next->xb != nullptr) load_rows(T, m.XB, m.SXB, next->xb, next->xb_cols, r0, B);
+        }
     }
     return cur;
 }
@@ -444,7 +452,8 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     {
         const FusedNet* const nets[2] = {&A.qt[0], &A.qt[1]};
         float* const* const hg[2] = {nullptr, nullptr};
-        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B);
+        const NextInputs nx = {A.obs, o, A.act, a};        // the online critics' inputs
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B, false, &nx);
     }
     float m_reg[BMF / FW];      // distributional critics: the projected target distribution of this wavefront's rows (lane = atom)
     const int atoms = DIST ? A.atoms : 1;
@@ -512,10 +521,7 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         }
     }
     __syncthreads();
-    // ---- online critics ---------------------------------------------------------------------
-    load_rows(T, m.XA, m.SXA, A.obs, o, r0, B);
-    load_rows(T, m.XB, m.SXB, A.act, a, r0, B);
-    __syncthreads();
+    // ---- online critics (their inputs were loaded behind the target critics' first layer) ---------
     {
         const FusedNet* const nets[2] = {&A.q[0], &A.q[1]};
         float* const* const hg[2] = {A.hQ[0], A.hQ[1]};
