@@ -1,7 +1,7 @@
 """Turns rocprofv3 CSV output of ``bench.py`` into the short text summaries kept under
 ``profiles/``.
 
-    python -m paper_2307_12983_amd.profile_tools stats   <kernel_stats.csv> <bench.json> <out.md> <title>
+    python -m paper_2307_12983_amd.profile_tools stats   <kernel_stats.csv> <bench.json> <out.md> <title> [bench.py arguments]
     python -m paper_2307_12983_amd.profile_tools traffic <fetch_counter_collection.csv> <write_counter_collection.csv> \
                                                          <kernel name> <out.txt>
 
@@ -39,7 +39,7 @@ def source_hash() -> str:
 
 def short_name(profiler_name: str) -> str:
     """Maps a demangled kernel name to the name bench.py / pql_profile_end use."""
-    m = re.search(r"gemm_grouped_kernel<(\d), (\d), (\d), (\d), (\d), (true|false)>", profiler_name)
+    m = re.search(r"gemm_grouped_kernel<(\d), (\d), (\d), (\d), (\d), (true|false)(?:, \d+)?>", profiler_name)
     if m:
         tile = GEMM_TILES.get(m.group(2, 3, 4, 5), "?")
         return "gemm_grouped_%s_%s%s" % (GEMM_MODES.get(m.group(1), "?"), tile, "_noise" if m.group(6) == "true" else "")
@@ -50,13 +50,13 @@ def short_name(profiler_name: str) -> str:
     return m.group(1) if m else profiler_name
 
 
-def stats_summary(stats_csv, bench_json, out, title):
+def stats_summary(stats_csv, bench_json, out, title, bench_args=""):
     st = list(csv.DictReader(open(stats_csv)))
     b = json.loads(open(bench_json).read().strip().splitlines()[-1])
     with open(out, "w") as f:
         f.write("# %s\n\n" % title)
         f.write("Command (from the repository root, on one MI355X):\n\n")
-        f.write("    rocprofv3 --kernel-trace --stats --output-format csv -d <out>/prof_bench -o bench -- python3 bench.py\n")
+        f.write("    rocprofv3 --kernel-trace --stats --output-format csv -d <out>/prof_bench -o bench -- python3 bench.py%s\n" % ((" " + bench_args) if bench_args else ""))
         f.write("    python -m paper_2307_12983_amd.profile_tools stats <out>/prof_bench/bench_kernel_stats.csv <bench line> <this file> <title>\n\n")
         f.write("Kernel summary (`bench_kernel_stats.csv`), all launches of the process (ring fill, calibration copy, "
                 "warm-up, timed steps, Actor loop, event pass):\n\n")
@@ -123,7 +123,7 @@ def stored_traffic(path, kernel):
 
 if __name__ == "__main__":
     if len(sys.argv) >= 6 and sys.argv[1] == "stats":
-        stats_summary(*sys.argv[2:6])
+        stats_summary(*sys.argv[2:7])
     elif len(sys.argv) >= 6 and sys.argv[1] == "traffic":
         traffic_summary(*sys.argv[2:6])
     else:
