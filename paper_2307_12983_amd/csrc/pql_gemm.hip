@@ -236,25 +236,26 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
         const int kvalid = (t < nt0) ? min(BK, s0.kend - (s0.kbeg + t * BK)) : min(BK, s1.kend - (t - nt0) * BK);
         float a[2][TM][4], b[2][TN][4];
         if (kvalid == BK) {
-            if (TM * TN == 1) {
-                // One MFMA tile per wavefront: little matrix work per fragment, so the fragments of group
-                // kg + 1 are read from LDS while group kg feeds the matrix core (measured +2..4 %; with four
-                // tiles per wavefront the same change costs 3..5 %, so those keep read-then-use order).
-                load_frag(Asm, Bsm, 0, a[0], b[0]);
+            // The fragments of group kg + 1 are read from LDS while group kg feeds the matrix core: the
+            // reads are spread between the MFMAs (one read after every few of them) instead of all being
+            // issued, and waited for, right before their first use.
+            constexpr int NMFMA = 4 * TM * TN;
+            constexpr int NREAD = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);
+            constexpr int PER = NMFMA / (NREAD + 1) > 0 ? NMFMA / (NREAD + 1) : 1;
+            load_frag(Asm, Bsm, 0, a[0], b[0]);
 #pragma unroll
-                for (int kg = 0; kg < BK / 8; ++kg) {
-                    if (kg + 1 < BK / 8) load_frag(Asm, Bsm, kg + 1, a[(kg + 1) & 1], b[(kg + 1) & 1]);
-                    // keep the instruction scheduler from sinking those reads back down to their first use
-                    __builtin_amdgcn_sched_barrier(0);
-                    mfma_group(a[kg & 1], b[kg & 1]);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            } else {
+            for (int kg = 0; kg < BK / 8; ++kg) {
+                if (kg + 1 < BK / 8) load_frag(Asm, Bsm, kg + 1, a[(kg + 1) & 1], b[(kg + 1) & 1]);
+                mfma_group(a[kg & 1], b[kg & 1]);
+                if (kg + 1 < BK / 8) {
 #pragma unroll
-                for (int kg = 0; kg < BK / 8; ++kg) {
-                    load_frag(Asm, Bsm, kg, a[0], b[0]);
-                    mfma_group(a[0], b[0]);
+                    for (int i = 0; i < NREAD; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);    // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // LDS read
+                    }
                 }
+                __builtin_amdgcn_sched_group_barrier(0x008, NMFMA, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         } else {
             const int ngroups = (kvalid + 7) >> 3;
@@ -265,8 +266,9 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
         }
     };
 
-    // Software pipeline: while tile t feeds the matrix cores from LDS stage t&1, tile t+1 moves
-    // from registers into the other stage and tile t+2 is in flight from memory.
+    // Software pipeline: while tile t feeds the matrix cores from LDS stage t&1, tile t+2 is requested
+    // from memory and tile t+1, requested one step earlier, moves from registers into the other stage
+    // after the matrix work (a load has two steps of matrix work to arrive before it is waited for).
     if (nt > 0) {
         fetch(0, ra0, rb0);
         if (nt > 1) fetch(1, ra1, rb1);
@@ -275,14 +277,14 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
         __syncthreads();
     }
     for (int t = 0; t < nt; t += 2) {
-        if (t + 1 < nt) { ra1.store(As[1], SA, tid); rb1.store(Bs[1], SB, tid); }
         if (t + 2 < nt) fetch(t + 2, ra0, rb0);
         compute(t);
+        if (t + 1 < nt) { ra1.store(As[1], SA, tid); rb1.store(Bs[1], SB, tid); }
         __syncthreads();
         if (t + 1 < nt) {
-            if (t + 2 < nt) { ra0.store(As[0], SA, tid); rb0.store(Bs[0], SB, tid); }
             if (t + 3 < nt) fetch(t + 3, ra1, rb1);
             compute(t + 1);
+            if (t + 2 < nt) { ra0.store(As[0], SA, tid); rb0.store(Bs[0], SB, tid); }
             __syncthreads();
         }
     }
