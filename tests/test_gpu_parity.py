@@ -495,6 +495,67 @@ def test_sac_full_batch_ant(torch_cuda):
 
 
 # ---------------------------------------------------------------------------------------------
+# degenerate and boundary sizes
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+@pytest.mark.parametrize("Bsz", [1, 33])
+def test_updates_on_one_row_and_on_one_row_more_than_a_tile(torch_cuda, case, Bsz):
+    """Batch 1 (every mean is over one sample) and batch 33 (a 32-row tile plus one row), through the
+    row-tile kernels (tiny) and the grouped GEMMs (ragged)."""
+    w = SMALL[case].replace(batch=Bsz)
+    res = one_step(torch_cuda, w, w.nstep + 2)
+    say(case, "batch", Bsz, res)
+
+
+def test_empty_batch_and_single_environment(torch_cuda):
+    torch = torch_cuda
+    w = SMALL["tiny"]
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, w.nstep + 1)
+    before = {k: getattr(s.batch, k).clone() for k in ("idx", "obs", "act", "ret", "next_obs", "boot")}
+    s.ctx.pql_sample_nstep(s.storage, 0, s.batch)      # nothing to draw: nothing is written, the draw is still counted
+    torch.cuda.synchronize()
+    for k, v in before.items():
+        assert torch.equal(getattr(s.batch, k), v), k
+    assert s.ctx.get_state()[3] == 1
+    s.sample(w.batch)                                  # the next draw is call number 1 on both sides
+    assert_batch_matches(batch_to_numpy(s.batch, w.batch), oracle_batch(ring, w, w.batch, 1))
+    # one environment: its noise scale is sigma_min (Section 3.3 with N = 1)
+    obs = np.random.default_rng(2).standard_normal((1, w.obs_dim), dtype=np.float32)
+    got = s.act(torch.from_numpy(obs).cuda(), 0.3, 0.9).cpu().numpy()
+    ref = O.actor_act(s.actor_init, w.actor_dims(), obs, float(np.float32(0.3)), float(np.float32(0.9)), w.rng_seed, 0)
+    assert rel_err(got, ref) <= TOL_ONE_STEP
+    mu = O.actor_forward(s.actor_init, w.actor_dims(), obs)
+    eps = O.gaussian_noise(w.rng_seed, 0, w.act_dim)
+    assert np.allclose(ref, np.clip(mu + float(np.float32(0.3)) * eps, -1, 1), rtol=1e-12)
+
+
+def test_every_transition_terminal(torch_cuda):
+    """done = 1 everywhere: boot = 0 for every window, the target is the first reward alone and the
+    target networks drop out of the update."""
+    torch = torch_cuda
+    w = SMALL["ant_s"].replace(done_p=1.0, batch=200)
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, w.nstep + 3)
+    s.sample(w.batch)
+    got = batch_to_numpy(s.batch, w.batch)
+    assert not got["boot"].any()
+    assert np.array_equal(got["ret"], ring.rew[got["idx"]])            # later rewards are masked out exactly
+    s.critic_update(w.batch)
+    loss_a = s.critic_loss.cpu().numpy().copy()
+    s2 = make_session(w)
+    fill_both(s2, oracle_ring(w), w, w.nstep + 3)
+    s2.critic_target.mul_(3.0)                                          # different target critics and lagged policy: no influence
+    s2.actor_lag.mul_(-2.0)
+    s2.sample(w.batch)
+    s2.critic_update(w.batch)
+    assert np.array_equal(s2.critic_loss.cpu().numpy(), loss_a)
+    assert torch.equal(s.critic, s2.critic)
+    L = oracle_learner(w, s.actor_init, s.critic_init)
+    losses, _ = L.critic_update(oracle_batch(ring, w, w.batch, 0))
+    assert rel_err(loss_a, losses) <= TOL_ONE_STEP
+
+
+# ---------------------------------------------------------------------------------------------
 def test_ant_full_ring_as_benchmarked(torch_cuda):
     """The benchmark's launch configuration: ant-shaped workload with the whole ring filled and
     wrapped (T = 244 rows of 4096 environments), batch 8192: sampled indices and gathered rows
