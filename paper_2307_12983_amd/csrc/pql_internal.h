@@ -336,7 +336,9 @@ hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream);
 struct TransposeArgs {
     struct Mat { const float* src; float* dst; int rows, cols, block_begin, pad_; };
     int n;
-    Mat m[24];
+    // most entries: policy step with PQL_MAX_HIDDEN layers and distributional critics:
+    // 2 * (L - 1 + 1 + 1) critic matrices + L policy matrices = 26
+    Mat m[2 * (PQL_MAX_HIDDEN + 1) + PQL_MAX_HIDDEN];
 };
 hipError_t transpose_launch(TransposeArgs& a, hipStream_t stream);
 

@@ -506,6 +506,20 @@ def test_updates_on_one_row_and_on_one_row_more_than_a_tile(torch_cuda, case, Bs
     say(case, "batch", Bsz, res)
 
 
+@pytest.mark.parametrize("variant", ["scalar", "dist", "sac"])
+@pytest.mark.parametrize("widths", [(64,) * 8, (96, 40, 96, 40, 96, 40, 96, 40)])
+def test_deepest_network(torch_cuda, widths, variant):
+    """Eight hidden layers (the most the interface takes): the row-tile kernels (widths 64) and the grouped
+    GEMMs (widths 96 / 40), with every variant of critic and policy."""
+    w = SMALL["ragged"].replace(hidden=widths, batch=150, index=30)
+    if variant == "dist":
+        w = distributional(w)
+    if variant == "sac":
+        w = with_sac(w)
+    res = one_step(torch_cuda, w, w.nstep + 2)
+    say("8 layers", widths[:2], variant, res)
+
+
 def test_empty_batch_and_single_environment(torch_cuda):
     torch = torch_cuda
     w = SMALL["tiny"]
