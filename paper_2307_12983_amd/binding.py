@@ -263,11 +263,11 @@ class Context:
         self._check(self.lib.pql_profile_begin(self.h, max_launches))
 
     def pql_profile_end(self):
-        arr = (PqlKernelStat * 32)()
+        arr = (PqlKernelStat * 64)()
         n = C.c_int32(0)
-        self._check(self.lib.pql_profile_end(self.h, arr, 32, C.byref(n)))
+        self._check(self.lib.pql_profile_end(self.h, arr, 64, C.byref(n)))
         return [dict(name=arr[i].name.decode(), launches=arr[i].launches, total_ms=arr[i].total_ms,
-                     flops=arr[i].flops, bytes=arr[i].bytes) for i in range(min(n.value, 32))]
+                     flops=arr[i].flops, bytes=arr[i].bytes) for i in range(min(n.value, 64))]
 
     def pql_soft_update(self, src, dst, count, tau, stream=None):
         self._check(self.lib.pql_soft_update(self.h, _ptr(src), _ptr(dst), count, tau, _stream(stream)))

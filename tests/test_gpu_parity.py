@@ -520,6 +520,28 @@ def test_deepest_network(torch_cuda, widths, variant):
     say("8 layers", widths[:2], variant, res)
 
 
+@pytest.mark.parametrize("variant", ["scalar", "dist64", "sac31"])
+def test_widest_inputs_and_outputs(torch_cuda, variant):
+    """Wide observation and action vectors (more than one 32-column tile of actions), the most atoms with a
+    last hidden layer too narrow for the row-tile path, the widest stochastic policy (31 actions)."""
+    base = SMALL["ragged"].replace(obs_dim=300, act_dim=40, hidden=(128, 64), batch=200, num_envs=37, capacity=37 * 8, index=31)
+    if variant == "dist64":
+        w = distributional(base.replace(hidden=(128, 32)), 64)
+    elif variant == "sac31":
+        w = with_sac(base.replace(act_dim=31))
+    else:
+        w = base
+    res = one_step(torch_cuda, w, w.nstep + 2)
+    say("wide", variant, res)
+    torch = torch_cuda
+    s = make_session(w)
+    obs = np.random.default_rng(5).standard_normal((w.num_envs, w.obs_dim), dtype=np.float32)
+    got = s.act(torch.from_numpy(obs).cuda(), 0.05, 0.8).cpu().numpy()
+    ref = (O.sac_actor_act(s.actor_init, w.actor_dims(), obs, w.rng_seed, 0) if w.sac else
+           O.actor_act(s.actor_init, w.actor_dims(), obs, float(np.float32(0.05)), float(np.float32(0.8)), w.rng_seed, 0))
+    assert rel_err(got, ref) <= TOL_ONE_STEP
+
+
 def test_empty_batch_and_single_environment(torch_cuda):
     torch = torch_cuda
     w = SMALL["tiny"]
