@@ -217,15 +217,51 @@ __device__ inline float small_sum(int scratch, int e, int& row, int& col) {
 }
 
 // Copies rows r0..r0+31 of a row-major [B][ncols] array into an LDS tile, zero-filling rows
-// beyond B and the columns up to the next multiple of 8.
+// beyond B and the columns up to the next multiple of 8.  Four loads per thread are issued before
+// the first LDS store, so a tile costs one or two memory round trips instead of one per element;
+// 16-byte accesses when the row length and the base address allow it.
 __device__ inline void load_rows(const Lanes& T, int dst, int stride, const float* __restrict__ src, int ncols,
                                  int r0, int B) {
     const int kp = (ncols + 7) & ~7;
-    for (int i = T.tid; i < BMF * kp; i += FT) {
-        const int row = i / kp, col = i - row * kp;
-        float v = 0.f;
-        if (col < ncols && r0 + row < B) v = src[(size_t)(r0 + row) * (size_t)ncols + col];
-        smem[dst + row * stride + col] = v;
+    if ((ncols & 3) == 0 && (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
+        const int g = kp >> 2, gv = ncols >> 2;      // 16-byte granules per tile row / of them holding data
+        const int total = BMF * g;
+        float4* const smem4w = reinterpret_cast<float4*>(smem);
+        for (int base = 0; base < total; base += 4 * FT) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * FT + T.tid;
+                const int row = i / g, c4 = i - row * g;
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i < total && c4 < gv && r0 + row < B)
+                    v[u] = *reinterpret_cast<const float4*>(src + (size_t)(r0 + row) * (size_t)ncols + 4 * c4);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * FT + T.tid;
+                const int row = i / g, c4 = i - row * g;
+                if (i < total) smem4w[((dst + row * stride) >> 2) + c4] = v[u];
+            }
+        }
+        return;
+    }
+    const int total = BMF * kp;
+    for (int base = 0; base < total; base += 4 * FT) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = base + u * FT + T.tid;
+            const int row = i / kp, col = i - row * kp;
+            v[u] = 0.f;
+            if (i < total && col < ncols && r0 + row < B) v[u] = src[(size_t)(r0 + row) * (size_t)ncols + col];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = base + u * FT + T.tid;
+            const int row = i / kp, col = i - row * kp;
+            if (i < total) smem[dst + row * stride + col] = v[u];
+        }
     }
 }
 
@@ -233,8 +269,11 @@ __device__ inline void load_rows(const Lanes& T, int dst, int stride, const floa
 // tiles for each of two networks, scratch for split contractions (aliased onto the second
 // network's tiles when those are large enough), small per-row arrays.
 struct TileMem {
-    int XA, XB, H[2][2], scratch, sm;     // offsets into smem, in floats
+    int XA, XB, H0, scratch, sm;          // offsets into smem, in floats
     int SXA, SXB, SH;
+    // ping-pong tile k of network n; computed, not tabulated: a table indexed at run time would
+    // live in private memory
+    __device__ int Ht(int n, int k) const { return H0 + (2 * n + k) * (BMF * SH); }
 };
 
 __host__ __device__ inline int tile_floats(int o, int a, int hmax, bool with_small) {
@@ -250,10 +289,9 @@ __device__ inline TileMem carve(int o, int a, int hmax) {
     m.SH = hmax + 4;
     m.XA = 0;
     m.XB = m.XA + BMF * m.SXA;
-    int p = m.XB + BMF * m.SXB;
-    for (int n = 0; n < 2; ++n)
-        for (int k = 0; k < 2; ++k) { m.H[n][k] = p; p += BMF * m.SH; }
-    if (2 * BMF * m.SH >= SCRATCH_F) m.scratch = m.H[1][0];
+    m.H0 = m.XB + BMF * m.SXB;
+    int p = m.H0 + 4 * BMF * m.SH;
+    if (2 * BMF * m.SH >= SCRATCH_F) m.scratch = m.Ht(1, 0);
     else { m.scratch = p; p += SCRATCH_F; }
     m.sm = p;
     return m;
@@ -263,15 +301,17 @@ size_t fused_lds_bytes(int o, int a, int hmax) { return sizeof(float) * (size_t)
 
 // Hidden layers of NN equally shaped networks on the tile: layer 1 reads XA (and XB when
 // a_cols > 0), later layers ping-pong between the two tiles of each network.  Returns the index of
-// the tile holding the last hidden activations.  hG[n][l] (l = 1..L-1, may be null) receives h_l.
+// the tile holding the last hidden activations.  With keep_hidden, hG[n][l] (l = 1..L-1, and L with
+// store_last) receives h_l; the flag is separate from the pointers so that no address derived from
+// the kernel's argument block is ever compared (that would force a private copy of the block).
 // Rows to bring into XA / XB as soon as the first layer has consumed them (their load latency then
 // hides behind the remaining layers instead of standing alone before the next chain).
 struct NextInputs { const float* xa; int xa_cols; const float* xb; int xb_cols; };
 
 template <int NN>
 __device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const FusedNet* const (&nets)[NN], const int* Hw,
-                                     int L, int o, int a_cols, float* const* const (&hG)[NN], int r0, int B,
-                                     bool store_last = false, const NextInputs* next = nullptr) {
+                                     int L, int o, int a_cols, bool keep_hidden, float* const* const (&hG)[NN], int r0,
+                                     int B, bool store_last = false, const NextInputs* next = nullptr) {
     int cur = 0;
     for (int l = 0; l < L; ++l) {
         const int N = Hw[l];
@@ -284,12 +324,12 @@ __device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const Fus
                 w.in0[n] = m.XA; w.W0[n] = nets[n]->w[0];
                 w.in1[n] = m.XB; w.W1[n] = nets[n]->w[0] + (size_t)o * N;
             } else {
-                w.in0[n] = m.H[n][cur]; w.W0[n] = nets[n]->w[l];
+                w.in0[n] = m.Ht(n, cur); w.W0[n] = nets[n]->w[l];
                 w.in1[n] = 0; w.W1[n] = nullptr;
             }
             w.bias[n] = nets[n]->b[l]; w.aux[n] = 0;
-            w.outL[n] = m.H[n][dst];
-            w.outG[n] = (hG[n] && (l < L - 1 || store_last)) ? hG[n][l + 1] : nullptr;
+            w.outL[n] = m.Ht(n, dst);
+            w.outG[n] = (keep_hidden && (l < L - 1 || store_last)) ? hG[n][l + 1] : nullptr;
             w.colsum[n] = nullptr;
         }
         if (l == 0) { w.ld0 = m.SXA; w.K0 = o; w.ld1 = m.SXB; w.K1 = a_cols; }
@@ -431,10 +471,10 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     {
         const FusedNet* const nets[1] = {&A.pi};
         float* const* const hg[1] = {nullptr};
-        cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, hg, r0, B);
+        cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, false, hg, r0, B);
     }
     const int aw = sac ? 2 * a : a;        // columns of the policy's output layer
-    small_partial(T, m.H[0][cur], m.SH, HL, A.pi.w[L], aw, aw, m.scratch);
+    small_partial(T, m.Ht(0, cur), m.SH, HL, A.pi.w[L], aw, aw, m.scratch);
     __syncthreads();
     for (int e = T.tid; e < 1024; e += FT) {
         int row, col;
@@ -453,7 +493,7 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         const FusedNet* const nets[2] = {&A.qt[0], &A.qt[1]};
         float* const* const hg[2] = {nullptr, nullptr};
         const NextInputs nx = {A.obs, o, A.act, a};        // the online critics' inputs
-        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B, false, &nx);
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, false, hg, r0, B, false, &nx);
     }
     float m_reg[BMF / FW];      // distributional critics: the projected target distribution of this wavefront's rows (lane = atom)
     const int atoms = DIST ? A.atoms : 1;
@@ -463,7 +503,7 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     if (DIST) {
         // logits of the twin target critics, the smaller mean picks the next-state distribution, its atoms
         // move to clip(ret + boot z) and are projected back onto the support (lane k gathers atom k's mass)
-        const int ins[2] = {m.H[0][cur], m.H[1][cur]};
+        const int ins[2] = {m.Ht(0, cur), m.Ht(1, cur)};
         const float* const wo[2] = {A.qt[0].w[L], A.qt[1].w[L]};
         dist_logit_partial(T, ins, m.SH, HL, wo, atoms, m.scratch);
         __syncthreads();
@@ -504,8 +544,8 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
                 for (int j = 0; j < 4; ++j) {
                     const int c = T.lane + 64 * j;
                     if (c < HL) {
-                        s0 += smem[m.H[0][cur] + row * m.SH + c] * wt0[j];
-                        s1 += smem[m.H[1][cur] + row * m.SH + c] * wt1[j];
+                        s0 += smem[m.Ht(0, cur) + row * m.SH + c] * wt0[j];
+                        s1 += smem[m.Ht(1, cur) + row * m.SH + c] * wt1[j];
                     }
                 }
                 s0 = wsum(s0) + bt0;
@@ -525,14 +565,14 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     {
         const FusedNet* const nets[2] = {&A.q[0], &A.q[1]};
         float* const* const hg[2] = {A.hQ[0], A.hQ[1]};
-        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B, DIST);
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, true, hg, r0, B, DIST);
     }
     const float invB = 1.f / (float)B;
     float loss_acc[2] = {0.f, 0.f}, db_acc[2] = {0.f, 0.f};
     float dw_acc[2][4], dbh_acc[2][4];
     if (DIST) {
         // logits of the online critics, cross-entropy against the projected target, dLoss/dlogits
-        const int ins[2] = {m.H[0][cur], m.H[1][cur]};
+        const int ins[2] = {m.Ht(0, cur), m.Ht(1, cur)};
         const float* const wo[2] = {A.q[0].w[L], A.q[1].w[L]};
         dist_logit_partial(T, ins, m.SH, HL, wo, atoms, m.scratch);
         __syncthreads();
@@ -560,11 +600,11 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int rr = 0; rr < BMF / FW; ++rr)
-                smem[m.H[i][cur ^ 1] + (T.wave * (BMF / FW) + rr) * m.SH + T.lane] = dl[i][rr];
+                smem[m.Ht(i, cur ^ 1) + (T.wave * (BMF / FW) + rr) * m.SH + T.lane] = dl[i][rr];
         smem[m.sm + 160 + (0 * FW + T.wave) * 64 + T.lane] = db_acc[0];
         smem[m.sm + 160 + (1 * FW + T.wave) * 64 + T.lane] = db_acc[1];
         // the partial tiles may have overwritten the second critic's last hidden tile: bring it back
-        if (m.scratch == m.H[1][cur]) load_rows(T, m.H[1][cur], m.SH, A.hQ[1][L], HL, r0, B);
+        if (m.scratch == m.Ht(1, cur)) load_rows(T, m.Ht(1, cur), m.SH, A.hQ[1][L], HL, r0, B);
         __syncthreads();
         // delta of the last hidden layer: (dlogits W_out^T) * ELU'(h_L), in place over h_L
         WideArgs<2> w;
@@ -572,8 +612,8 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         w.ldaux = m.SH; w.ldo = m.SH; w.ldg = HL;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            w.in0[i] = m.H[i][cur ^ 1]; w.W0[i] = A.woT[i]; w.in1[i] = 0; w.W1[i] = nullptr;
-            w.bias[i] = nullptr; w.aux[i] = m.H[i][cur]; w.outL[i] = m.H[i][cur];
+            w.in0[i] = m.Ht(i, cur ^ 1); w.W0[i] = A.woT[i]; w.in1[i] = 0; w.W1[i] = nullptr;
+            w.bias[i] = nullptr; w.aux[i] = m.Ht(i, cur); w.outL[i] = m.Ht(i, cur);
             w.outG[i] = A.dQ[i][L];
             w.colsum[i] = A.colQ[i][L] + (size_t)blockIdx.x * HL;
         }
@@ -594,7 +634,7 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
             const bool rv = r0 + row < B;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                float* hrow = &smem[m.H[i][cur] + row * m.SH];
+                float* hrow = &smem[m.Ht(i, cur) + row * m.SH];
                 float h[4];
                 float s = 0.f;
 #pragma unroll
@@ -628,8 +668,8 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
     for (int l = L; l >= 2; --l) {
         const int Hl = A.H[l - 1], Hp = A.H[l - 2];
         if (l < L || DIST) {   // h_{l-1} is no longer on chip (the dlogits took its tile): bring it back from memory
-            load_rows(T, m.H[0][cur ^ 1], m.SH, A.hQ[0][l - 1], Hp, r0, B);
-            load_rows(T, m.H[1][cur ^ 1], m.SH, A.hQ[1][l - 1], Hp, r0, B);
+            load_rows(T, m.Ht(0, cur ^ 1), m.SH, A.hQ[0][l - 1], Hp, r0, B);
+            load_rows(T, m.Ht(1, cur ^ 1), m.SH, A.hQ[1][l - 1], Hp, r0, B);
             __syncthreads();
         }
         WideArgs<2> w;
@@ -637,8 +677,8 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         w.ldaux = m.SH; w.ldo = m.SH; w.ldg = Hp;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            w.in0[i] = m.H[i][cur]; w.W0[i] = A.wT[i][l - 1]; w.in1[i] = 0; w.W1[i] = nullptr;
-            w.bias[i] = nullptr; w.aux[i] = m.H[i][cur ^ 1]; w.outL[i] = m.H[i][cur ^ 1];
+            w.in0[i] = m.Ht(i, cur); w.W0[i] = A.wT[i][l - 1]; w.in1[i] = 0; w.W1[i] = nullptr;
+            w.bias[i] = nullptr; w.aux[i] = m.Ht(i, cur ^ 1); w.outL[i] = m.Ht(i, cur ^ 1);
             w.outG[i] = A.dQ[i][l - 1];
             w.colsum[i] = A.colQ[i][l - 1] + (size_t)blockIdx.x * Hp;
         }
@@ -721,9 +761,9 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     {
         const FusedNet* const nets[1] = {&A.pi};
         float* const* const hg[1] = {A.hA};
-        cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, hg, r0, B, true);
+        cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, true, hg, r0, B, true);
     }
-    small_partial(T, m.H[0][cur], m.SH, HL, A.pi.w[L], aw, aw, m.scratch);
+    small_partial(T, m.Ht(0, cur), m.SH, HL, A.pi.w[L], aw, aw, m.scratch);
     __syncthreads();
     float* sm_eps = &smem[m.sm + 160];     // [32][16] draws of the reparameterised sample
     float* sm_raw = &smem[m.sm + 672];     // [32][16] raw log sigma outputs
@@ -745,7 +785,7 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     {
         const FusedNet* const nets[2] = {&A.q[0], &A.q[1]};
         float* const* const hg[2] = {A.hQ[0], A.hQ[1]};
-        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, hg, r0, B, DIST);
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, true, hg, r0, B, DIST);
     }
     float loss_acc = 0.f;
     if (DIST) {
@@ -754,7 +794,7 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
         const bool live = T.lane < atoms;
         const float zk = A.v_min + (float)T.lane * ((A.v_max - A.v_min) / (float)(atoms - 1));
         const float invB = 1.f / (float)B;
-        const int ins[2] = {m.H[0][cur], m.H[1][cur]};
+        const int ins[2] = {m.Ht(0, cur), m.Ht(1, cur)};
         const float* const wo[2] = {A.q[0].w[L], A.q[1].w[L]};
         dist_logit_partial(T, ins, m.SH, HL, wo, atoms, m.scratch);
         __syncthreads();
@@ -779,16 +819,16 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int rr = 0; rr < BMF / FW; ++rr)
-                smem[m.H[i][cur ^ 1] + (T.wave * (BMF / FW) + rr) * m.SH + T.lane] = dl[i][rr];
-        if (m.scratch == m.H[1][cur]) load_rows(T, m.H[1][cur], m.SH, A.hQ[1][L], HL, r0, B);
+                smem[m.Ht(i, cur ^ 1) + (T.wave * (BMF / FW) + rr) * m.SH + T.lane] = dl[i][rr];
+        if (m.scratch == m.Ht(1, cur)) load_rows(T, m.Ht(1, cur), m.SH, A.hQ[1][L], HL, r0, B);
         __syncthreads();
         WideArgs<2> w;
         w.ld0 = m.SH; w.K0 = atoms; w.ld1 = 0; w.K1 = 0; w.ldw = HL; w.N = HL; w.epi = WIDE_MUL_DELU;
         w.ldaux = m.SH; w.ldo = m.SH; w.ldg = HL;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            w.in0[i] = m.H[i][cur ^ 1]; w.W0[i] = A.woT[i]; w.in1[i] = 0; w.W1[i] = nullptr;
-            w.bias[i] = nullptr; w.aux[i] = m.H[i][cur]; w.outL[i] = m.H[i][cur];
+            w.in0[i] = m.Ht(i, cur ^ 1); w.W0[i] = A.woT[i]; w.in1[i] = 0; w.W1[i] = nullptr;
+            w.bias[i] = nullptr; w.aux[i] = m.Ht(i, cur); w.outL[i] = m.Ht(i, cur);
             w.outG[i] = nullptr; w.colsum[i] = nullptr;
         }
         wide_linear<2>(T, w, r0, B);
@@ -811,7 +851,7 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int c = T.lane + 64 * j;
-                    h[i][j] = c < HL ? smem[m.H[i][cur] + row * m.SH + c] : 0.f;
+                    h[i][j] = c < HL ? smem[m.Ht(i, cur) + row * m.SH + c] : 0.f;
                     s += h[i][j] * wq[i][j];
                 }
                 q[i] = wsum(s) + bq[i];
@@ -825,7 +865,7 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int c = T.lane + 64 * j;
-                    if (c < HL) smem[m.H[i][cur] + row * m.SH + c] = d[i] * wq[i][j] * delu_h(h[i][j]);
+                    if (c < HL) smem[m.Ht(i, cur) + row * m.SH + c] = d[i] * wq[i][j] * delu_h(h[i][j]);
                 }
         }
     }
@@ -834,8 +874,8 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     for (int l = L; l >= 2; --l) {
         const int Hl = A.H[l - 1], Hp = A.H[l - 2];
         if (l < L || DIST) {
-            load_rows(T, m.H[0][cur ^ 1], m.SH, A.hQ[0][l - 1], Hp, r0, B);
-            load_rows(T, m.H[1][cur ^ 1], m.SH, A.hQ[1][l - 1], Hp, r0, B);
+            load_rows(T, m.Ht(0, cur ^ 1), m.SH, A.hQ[0][l - 1], Hp, r0, B);
+            load_rows(T, m.Ht(1, cur ^ 1), m.SH, A.hQ[1][l - 1], Hp, r0, B);
             __syncthreads();
         }
         WideArgs<2> w;
@@ -843,8 +883,8 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
         w.ldaux = m.SH; w.ldo = m.SH; w.ldg = Hp;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            w.in0[i] = m.H[i][cur]; w.W0[i] = A.wT[i][l - 1]; w.in1[i] = 0; w.W1[i] = nullptr;
-            w.bias[i] = nullptr; w.aux[i] = m.H[i][cur ^ 1]; w.outL[i] = m.H[i][cur ^ 1];
+            w.in0[i] = m.Ht(i, cur); w.W0[i] = A.wT[i][l - 1]; w.in1[i] = 0; w.W1[i] = nullptr;
+            w.bias[i] = nullptr; w.aux[i] = m.Ht(i, cur ^ 1); w.outL[i] = m.Ht(i, cur ^ 1);
             w.outG[i] = nullptr; w.colsum[i] = nullptr;
         }
         wide_linear<2>(T, w, r0, B);
@@ -859,7 +899,7 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
         const int ncol = T.l32 < a ? T.l32 : a - 1;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int ins[1] = {m.H[i][cur]};
+            const int ins[1] = {m.Ht(i, cur)};
             const float* const ws[1] = {A.w1aT[i]};
             mac_segment<1>(acc0, acc1, ins, m.SH, H1, ws, a, ncol, T, T.wave, FW);
         }
@@ -907,23 +947,23 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     }
     // policy backward data path: delta_L = (dPre W_out^T) * ELU'(z_L), then down the hidden layers
     int pc = 0;
-    load_rows(T, m.H[0][pc], m.SH, A.hA[L], HL, r0, B);
+    load_rows(T, m.Ht(0, pc), m.SH, A.hA[L], HL, r0, B);
     __syncthreads();
     {
         WideArgs<1> w;
         w.in0[0] = m.XB; w.W0[0] = A.waT[L]; w.ld0 = m.SXB; w.K0 = aw; w.in1[0] = 0; w.W1[0] = nullptr; w.ld1 = 0; w.K1 = 0;
-        w.ldw = HL; w.N = HL; w.bias[0] = nullptr; w.aux[0] = m.H[0][pc]; w.ldaux = m.SH; w.outL[0] = m.H[0][pc]; w.ldo = m.SH;
+        w.ldw = HL; w.N = HL; w.bias[0] = nullptr; w.aux[0] = m.Ht(0, pc); w.ldaux = m.SH; w.outL[0] = m.Ht(0, pc); w.ldo = m.SH;
         w.outG[0] = A.dA[L]; w.ldg = HL; w.colsum[0] = A.colA[L] + (size_t)wg * HL; w.epi = WIDE_MUL_DELU;
         wide_linear<1>(T, w, r0, B);
     }
     __syncthreads();
     for (int l = L; l >= 2; --l) {
         const int Hl = A.H[l - 1], Hp = A.H[l - 2];
-        load_rows(T, m.H[0][pc ^ 1], m.SH, A.hA[l - 1], Hp, r0, B);
+        load_rows(T, m.Ht(0, pc ^ 1), m.SH, A.hA[l - 1], Hp, r0, B);
         __syncthreads();
         WideArgs<1> w;
-        w.in0[0] = m.H[0][pc]; w.W0[0] = A.waT[l - 1]; w.ld0 = m.SH; w.K0 = Hl; w.in1[0] = 0; w.W1[0] = nullptr; w.ld1 = 0; w.K1 = 0;
-        w.ldw = Hp; w.N = Hp; w.bias[0] = nullptr; w.aux[0] = m.H[0][pc ^ 1]; w.ldaux = m.SH; w.outL[0] = m.H[0][pc ^ 1]; w.ldo = m.SH;
+        w.in0[0] = m.Ht(0, pc); w.W0[0] = A.waT[l - 1]; w.ld0 = m.SH; w.K0 = Hl; w.in1[0] = 0; w.W1[0] = nullptr; w.ld1 = 0; w.K1 = 0;
+        w.ldw = Hp; w.N = Hp; w.bias[0] = nullptr; w.aux[0] = m.Ht(0, pc ^ 1); w.ldaux = m.SH; w.outL[0] = m.Ht(0, pc ^ 1); w.ldo = m.SH;
         w.outG[0] = A.dA[l - 1]; w.ldg = Hp; w.colsum[0] = A.colA[l - 1] + (size_t)wg * Hp; w.epi = WIDE_MUL_DELU;
         wide_linear<1>(T, w, r0, B);
         pc ^= 1;
@@ -954,7 +994,8 @@ __global__ __launch_bounds__(FT) void fused_act_kernel(const FusedActArgs A) {
     const int r0 = blockIdx.x * BMF;
     load_rows(T, m.XA, m.SXA, A.obs, o, r0, B);
     if (A.nmean != nullptr) {
-        // standardise the rows just loaded (each thread revisits exactly the elements it wrote)
+        // standardise the rows just loaded (by other threads: wait for them)
+        __syncthreads();
         const int kp = (o + 7) & ~7;
         for (int i = T.tid; i < BMF * kp; i += FT) {
             const int row = i / kp, col = i - row * kp;
@@ -967,8 +1008,8 @@ __global__ __launch_bounds__(FT) void fused_act_kernel(const FusedActArgs A) {
     __syncthreads();
     const FusedNet* const nets[1] = {&A.pi};
     float* const* const hg[1] = {nullptr};
-    const int cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, hg, r0, B);
-    small_partial(T, m.H[0][cur], m.SH, A.H[L - 1], A.pi.w[L], aw, aw, m.scratch);
+    const int cur = hidden_forward<1>(T, m, nets, A.H, L, o, 0, false, hg, r0, B);
+    small_partial(T, m.Ht(0, cur), m.SH, A.H[L - 1], A.pi.w[L], aw, aw, m.scratch);
     __syncthreads();
     const GemmNoise& nz = A.noise;
     for (int e = T.tid; e < 1024; e += FT) {
