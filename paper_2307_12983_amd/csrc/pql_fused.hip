@@ -39,87 +39,215 @@ __device__ inline float wsum(float x) {
 }
 __device__ inline int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
+// Where a lane finds its B fragments (weights) of one contraction segment: W are row-major in
+// memory with leading dimension ldw and K rows, the lane owns output column ncol.  The contraction
+// runs in chunks of 32 k-values: nfull whole ones and, when K is no multiple of 32, a shorter tail.
+// A wavefront that takes every c_step-th chunk starting at c_begin (c_step > 1 splits the
+// contraction across wavefronts) first does the tail, if it is among its chunks, and then its whole
+// chunks in one branch-free loop.  Every workgroup of the launch streams the same weight matrix;
+// starting each workgroup at a different whole chunk (rot) spreads the simultaneous requests over
+// the L2 channels instead of piling all compute units onto the same few cache lines.
+// The weights are read through buffer descriptors: one vector register holds the lane's byte offset
+// for every load of the segment, the row comes as a scalar offset (plain pointers cost a 64-bit
+// vector address per load in flight, 60 registers for two networks), and a read outside the
+// matrix returns zero instead of faulting.
+template <int NN>
+struct ChunkSrc {
+    __amdgpu_buffer_rsrc_t r[NN];
+    int K, ldw, ncol, nch, nfull, rot;
+    int half4;              // 4 * (lane >> 5): the lane's first row inside a group of 8
+    unsigned voff;          // byte offset of (row half4, column ncol)
+    bool tail_mine;         // the short last chunk belongs to this wavefront
+    int n_mine;             // whole chunks of this wavefront
+};
+
+template <int NN>
+__device__ inline ChunkSrc<NN> chunk_src(const float* const (&W)[NN], int K, int ldw, int ncol, const Lanes& T,
+                                         int c_begin, int c_step) {
+    ChunkSrc<NN> s;
+#pragma unroll
+    for (int n = 0; n < NN; ++n)
+        s.r[n] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(W[n]), 0, K * ldw * (int)sizeof(float), 0x00020000);
+    s.K = K; s.ldw = ldw; s.ncol = ncol;
+    s.nch = (K + 31) >> 5;
+    s.nfull = K >> 5;
+    s.rot = s.nfull > 0 ? (int)(blockIdx.x % (unsigned)s.nfull) : 0;
+    s.half4 = 4 * T.half;
+    s.voff = (unsigned)(s.half4 * ldw + ncol) * (unsigned)sizeof(float);
+    s.tail_mine = s.nch > s.nfull && s.nch - 1 >= c_begin && (s.nch - 1 - c_begin) % c_step == 0;
+    s.n_mine = s.nfull > c_begin ? (s.nfull - c_begin + c_step - 1) / c_step : 0;
+    return s;
+}
+
+__device__ inline float buf_load(__amdgpu_buffer_rsrc_t r, unsigned voff, int soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, soff, 0));
+}
+
+// The memory chunk behind whole chunk number ci of the wavefront's order.
+template <int NN>
+__device__ inline int rotated(const ChunkSrc<NN>& s, int ci) {
+    const int cc = ci + s.rot;
+    return cc >= s.nfull ? cc - s.nfull : cc;
+}
+
+// Weights of whole chunk ci (clamped to a valid one) into b: 16 loads per network, always.
+template <int NN>
+__device__ inline void load_full(const ChunkSrc<NN>& s, int ci, float (&b)[NN][16]) {
+    const int cc = rotated(s, ci < s.nfull ? ci : 0);
+    const int row_bytes = s.ldw * (int)sizeof(float);
+    const int base = cc * 32 * row_bytes;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int n = 0; n < NN; ++n) b[n][g * 4 + u] = buf_load(s.r[n], s.voff, base + (g * 8 + u) * row_bytes);
+}
+
+// Weights of the short last chunk: row indices are clamped to K - 1 (clamped rows meet zero columns
+// of the input tile, whose width is padded with zeros to a multiple of 8).
+template <int NN>
+__device__ inline void load_tail(const ChunkSrc<NN>& s, float (&b)[NN][16]) {
+    const int kbase = s.nfull * 32;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int k = kbase + g * 8 + s.half4 + u;
+            k = k < s.K ? k : s.K - 1;
+            const unsigned off = (unsigned)(k * s.ldw + s.ncol) * (unsigned)sizeof(float);
+#pragma unroll
+            for (int n = 0; n < NN; ++n) b[n][g * 4 + u] = buf_load(s.r[n], off, 0);
+        }
+}
+
+// acc[n] += in[n][32 rows x memory chunk cc] * b[n]: 16 MFMAs per network, no branches.  `in` are
+// LDS tiles with row stride ld.  A operand: one 16-byte LDS read per group of 8 k-values (tile
+// offsets and strides are multiples of 4 floats; indexing the array as float4 lets the compiler
+// prove the alignment and emit ds_read_b128, which the stride-(width + 4) layout serves without
+// bank conflicts).
+template <int NN>
+__device__ inline void mac_full(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], const int (&in)[NN], int ld,
+                                const Lanes& T, int cc, const float (&b)[NN][16]) {
+    const float4* smem4 = reinterpret_cast<const float4*>(smem);
+    const int a_off4 = T.l32 * (ld >> 2) + T.half + cc * 8;
+    float4 a[4][NN];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int n = 0; n < NN; ++n) a[g][n] = smem4[(in[n] >> 2) + a_off4 + g * 2];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int n = 0; n < NN; ++n) {
+            acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].x, b[n][g * 4 + 0], acc0[n], 0, 0, 0);
+            acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].y, b[n][g * 4 + 1], acc1[n], 0, 0, 0);
+            acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].z, b[n][g * 4 + 2], acc0[n], 0, 0, 0);
+            acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].w, b[n][g * 4 + 3], acc1[n], 0, 0, 0);
+        }
+    // Issue order: two LDS reads ahead, then four MFMAs per read (0x100 = LDS read, 0x008 = MFMA).
+    // Left alone, the scheduler places every read directly before its first use.
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+    for (int i = 0; i < 4 * NN - 2; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+}
+
+// The short last chunk: only the groups of 8 k-values that exist.
+template <int NN>
+__device__ inline void mac_tail(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], const int (&in)[NN], int ld,
+                                const ChunkSrc<NN>& s, const Lanes& T, const float (&b)[NN][16]) {
+    const float4* smem4 = reinterpret_cast<const float4*>(smem);
+    const int a_off4 = T.l32 * (ld >> 2) + T.half + s.nfull * 8;
+    const int ng = (s.K - s.nfull * 32 + 7) >> 3;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        if (g < ng) {
+#pragma unroll
+            for (int n = 0; n < NN; ++n) {
+                const float4 a = smem4[(in[n] >> 2) + a_off4 + g * 2];
+                acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b[n][g * 4 + 0], acc0[n], 0, 0, 0);
+                acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b[n][g * 4 + 1], acc1[n], 0, 0, 0);
+                acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b[n][g * 4 + 2], acc0[n], 0, 0, 0);
+                acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b[n][g * 4 + 3], acc1[n], 0, 0, 0);
+            }
+        }
+    }
+}
+
+// Requests the first chunk a later mac_segment() call with the same (W, K, ldw, ncol, c_begin,
+// c_step) and use_pre = true consumes: the tail if it is the wavefront's, else its first whole chunk.
+template <int NN>
+__device__ inline void prefetch_first_chunk(float (&pre)[NN][16], const float* const (&W)[NN], int K, int ldw, int ncol,
+                                            const Lanes& T, int c_begin, int c_step) {
+    const ChunkSrc<NN> s = chunk_src<NN>(W, K, ldw, ncol, T, c_begin, c_step);
+    if (s.tail_mine) load_tail<NN>(s, pre);
+    else if (s.n_mine > 0) load_full<NN>(s, c_begin, pre);
+}
+
 // acc[n] += in[n][32 x K] * W[n][K x .] for NN networks at once, for the output column `ncol`
-// of this lane.  `in` are LDS tiles with row stride ld whose columns are zero up to the next
-// multiple of 8; W are row-major in memory with leading dimension ldw.  The contraction runs in
-// chunks of 32 k-values (16 MFMAs per network); chunks are taken with stride c_step starting at
-// c_begin (c_step > 1 splits the contraction across wavefronts).  The weights of the next chunk
-// are loaded (unconditionally, with a clamped chunk index, so the number of loads in flight is
-// the same on every path) while the current chunk feeds the matrix core.
+// of this lane.  The weights of the next chunk are loaded while the current one feeds the matrix
+// core.  With use_pre, `pre` holds the first chunk already (prefetch_first_chunk(): its latency is
+// then not paid here); a flag and a reference rather than a nullable pointer, which would keep the
+// buffer in private memory.
+template <int NN>
+__device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], const int (&in)[NN], int ld,
+                                   int K, const float* const (&W)[NN], int ldw, int ncol, const Lanes& T, int c_begin,
+                                   int c_step, bool use_pre, const float (&pre)[NN][16]) {
+    const ChunkSrc<NN> s = chunk_src<NN>(W, K, ldw, ncol, T, c_begin, c_step);
+    if (!s.tail_mine && s.n_mine == 0) return;
+    float b0[NN][16], b1[NN][16];
+    if (use_pre) {
+#pragma unroll
+        for (int n = 0; n < NN; ++n)
+#pragma unroll
+            for (int u = 0; u < 16; ++u) b0[n][u] = pre[n][u];
+    } else if (s.tail_mine) {
+        load_tail<NN>(s, b0);
+    } else {
+        load_full<NN>(s, c_begin, b0);
+    }
+    if (s.tail_mine) {
+        if (s.n_mine > 0) load_full<NN>(s, c_begin, b1);
+        mac_tail<NN>(acc0, acc1, in, ld, s, T, b0);
+        if (s.n_mine == 0) return;
+#pragma unroll
+        for (int n = 0; n < NN; ++n)
+#pragma unroll
+            for (int u = 0; u < 16; ++u) b0[n][u] = b1[n][u];
+    }
+    int c = c_begin, left = s.n_mine;
+    // The fences keep the requests for the next chunk ahead of the MFMAs of the current one (the
+    // scheduler otherwise sinks them to their first use to save registers, exposing their latency).
+    while (true) {                       // b0 holds whole chunk c
+        load_full<NN>(s, left > 1 ? c + c_step : c, b1);       // (a repeat at the end keeps the counters uniform)
+        __builtin_amdgcn_sched_barrier(0);
+        mac_full<NN>(acc0, acc1, in, ld, T, rotated(s, c), b0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (--left == 0) break;
+        c += c_step;
+        load_full<NN>(s, left > 1 ? c + c_step : c, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mac_full<NN>(acc0, acc1, in, ld, T, rotated(s, c), b1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (--left == 0) break;
+        c += c_step;
+    }
+}
+
 template <int NN>
 __device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], const int (&in)[NN], int ld,
                                    int K, const float* const (&W)[NN], int ldw, int ncol, const Lanes& T, int c_begin,
                                    int c_step) {
-    const int nch = (K + 31) >> 5;
-    int c = c_begin;
-    if (c >= nch) return;
-    // A operand: one 16-byte LDS read per group (tile offsets and strides are multiples of 4 floats;
-    // indexing the array as float4 lets the compiler prove the alignment and emit ds_read_b128, which
-    // the stride-(width + 4) layout serves without bank conflicts)
-    const int a_off4 = T.l32 * (ld >> 2) + T.half;
-    const float4* smem4 = reinterpret_cast<const float4*>(smem);
-    // Every workgroup of the launch streams the same weight matrix.  Starting each workgroup at a
-    // different chunk spreads the simultaneous requests over the L2 channels instead of piling
-    // all compute units onto the same few cache lines.
-    const int rot = (int)(blockIdx.x % (unsigned)nch);
-    const int lane_off = 4 * T.half * ldw + ncol;     // this lane's fixed offset inside a group of rows
-    float b0[NN][16], b1[NN][16];
-    auto loadc = [&](int ci, float (&b)[NN][16]) {
-        int cc = ci + rot;
-        cc = cc >= nch ? cc - nch : cc;
-        const int kbase = cc * 32;
-        if (kbase + 32 <= K) {
-            // full chunk: uniform row base + per-lane constant offset (scalar address arithmetic)
+    float none[NN][16];
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
+    for (int n = 0; n < NN; ++n)
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int n = 0; n < NN; ++n)
-                        b[n][g * 4 + u] = (W[n] + (size_t)(kbase + g * 8 + u) * (size_t)ldw)[lane_off];
-        } else {
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    int k = kbase + g * 8 + 4 * T.half + u;
-                    k = k < K ? k : K - 1;                // clamped rows meet zero columns of `in`
-#pragma unroll
-                    for (int n = 0; n < NN; ++n) b[n][g * 4 + u] = W[n][(size_t)k * (size_t)ldw + ncol];
-                }
-        }
-    };
-    auto compute = [&](int ci, const float (&b)[NN][16]) {
-        int cr = ci + rot;
-        cr = cr >= nch ? cr - nch : cr;
-        const int ng = min(4, (K - cr * 32 + 7) >> 3);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            if (g < ng) {
-#pragma unroll
-                for (int n = 0; n < NN; ++n) {
-                    const float4 a = smem4[(in[n] >> 2) + a_off4 + cr * 8 + g * 2];
-                    acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b[n][g * 4 + 0], acc0[n], 0, 0, 0);
-                    acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b[n][g * 4 + 1], acc1[n], 0, 0, 0);
-                    acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b[n][g * 4 + 2], acc0[n], 0, 0, 0);
-                    acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b[n][g * 4 + 3], acc1[n], 0, 0, 0);
-                }
-            }
-        }
-    };
-    loadc(c, b0);
-    while (true) {
-        int cn = c + c_step;
-        loadc(cn < nch ? cn : c, b1);
-        compute(c, b0);
-        if (cn >= nch) break;
-        c = cn;
-        cn = c + c_step;
-        loadc(cn < nch ? cn : c, b0);
-        compute(c, b1);
-        if (cn >= nch) break;
-        c = cn;
-    }
+        for (int u = 0; u < 16; ++u) none[n][u] = 0.f;
+    mac_segment<NN>(acc0, acc1, in, ld, K, W, ldw, ncol, T, c_begin, c_step, false, none);
 }
 
 enum WideEpi : int { WIDE_BIAS_ELU = 0, WIDE_MUL_DELU = 1 };
@@ -156,8 +284,17 @@ __device__ inline void wide_linear(const Lanes& T, const WideArgs<NN>& w, int r0
     for (int i = 0; i < NN; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { acc0[i][r] = 0.f; acc1[i][r] = 0.f; }
-    mac_segment<NN>(acc0, acc1, w.in0, w.ld0, w.K0, w.W0, w.ldw, ncol, T, 0, 1);
-    if (w.K1 > 0) mac_segment<NN>(acc0, acc1, w.in1, w.ld1, w.K1, w.W1, w.ldw, ncol, T, 0, 1);
+    if (w.K1 > 0) {
+        // two segments (a critic's first layer: state columns, then action columns): the first chunks
+        // of both are requested together, and the short segment runs while the long one's arrives
+        float bs[NN][16], bf[NN][16];
+        prefetch_first_chunk<NN>(bs, w.W1, w.K1, w.ldw, ncol, T, 0, 1);
+        prefetch_first_chunk<NN>(bf, w.W0, w.K0, w.ldw, ncol, T, 0, 1);
+        mac_segment<NN>(acc0, acc1, w.in1, w.ld1, w.K1, w.W1, w.ldw, ncol, T, 0, 1, true, bs);
+        mac_segment<NN>(acc0, acc1, w.in0, w.ld0, w.K0, w.W0, w.ldw, ncol, T, 0, 1, true, bf);
+    } else {
+        mac_segment<NN>(acc0, acc1, w.in0, w.ld0, w.K0, w.W0, w.ldw, ncol, T, 0, 1);
+    }
     // Epilogue.  Row r of the accumulator sits (8 * (r / 4) + r % 4) rows below the lane's first row
     // (4 * half): offsets from per-lane bases are compile-time multiples of the strides.
     const bool full = r0 + BMF <= B;                      // uniform: every row of the tile is in the batch
@@ -447,7 +584,7 @@ __device__ inline float dist_logit(int scratch, int net, int row, int k) {
 template <bool DIST>
 __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs A) {
     Lanes T;
-    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
+    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = __builtin_amdgcn_readfirstlane(T.tid >> 6); T.l32 = T.lane & 31; T.half = T.lane >> 5;
     const int o = A.o, a = A.a, L = A.L, B = A.B;
     const bool sac = A.sac.on != 0;
     const TileMem m = carve(o, sac ? 2 * a : a, A.hmax);
@@ -745,7 +882,7 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
 template <bool DIST>
 __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs A) {
     Lanes T;
-    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
+    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = __builtin_amdgcn_readfirstlane(T.tid >> 6); T.l32 = T.lane & 31; T.half = T.lane >> 5;
     const int o = A.o, a = A.a, L = A.L, B = A.B;
     const bool sac = A.sac.on != 0;
     const int aw = sac ? 2 * a : a;        // columns of the policy's output layer
@@ -986,7 +1123,7 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
 // =============================================================================================
 __global__ __launch_bounds__(FT) void fused_act_kernel(const FusedActArgs A) {
     Lanes T;
-    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = T.tid >> 6; T.l32 = T.lane & 31; T.half = T.lane >> 5;
+    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = __builtin_amdgcn_readfirstlane(T.tid >> 6); T.l32 = T.lane & 31; T.half = T.lane >> 5;
     const int o = A.o, a = A.a, L = A.L, B = A.B;
     const bool sac = A.sac.on != 0;
     const int aw = sac ? 2 * a : a;
