@@ -32,10 +32,23 @@ extern __shared__ __attribute__((aligned(16))) float smem[];
 
 __device__ inline float elu_f(float x) { return x > 0.f ? x : __expf(x) - 1.f; }
 __device__ inline float delu_h(float h) { return h > 0.f ? 1.f : h + 1.f; }   // ELU'(z) from h = ELU(z)
+// Reductions over the 64 lanes of a wavefront, result in every lane; all lanes must be active.
+// Data-parallel-primitive moves inside each row of 16 lanes (xor 1, xor 2, mirrored half row,
+// mirrored row: after them every lane holds its row's result), then the four rows meet through
+// scalar lane reads.  No LDS traffic, unlike the shuffle-based butterfly.
+template <int CTRL>
+__device__ inline float dpp_move(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+__device__ inline float lane_value(float x, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
+}
 __device__ inline float wsum(float x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-    return x;
+    x += dpp_move<0xB1>(x);      // quad_perm [1, 0, 3, 2]
+    x += dpp_move<0x4E>(x);      // quad_perm [2, 3, 0, 1]
+    x += dpp_move<0x141>(x);     // row_half_mirror
+    x += dpp_move<0x140>(x);     // row_mirror
+    return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
 }
 __device__ inline int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
@@ -532,9 +545,11 @@ __device__ inline float sac_tile_sample(int scratch, int e, int a, const float* 
 
 // ---- distributional critics on a tile (PQL-D) -------------------------------------------------
 __device__ inline float wmax(float x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-    return x;
+    x = fmaxf(x, dpp_move<0xB1>(x));
+    x = fmaxf(x, dpp_move<0x4E>(x));
+    x = fmaxf(x, dpp_move<0x141>(x));
+    x = fmaxf(x, dpp_move<0x140>(x));
+    return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
 }
 
 // Softmax over the lanes < atoms (lane = atom): returns p and, through logp, log p (0 for idle lanes).
