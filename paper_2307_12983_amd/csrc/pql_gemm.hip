@@ -230,39 +230,33 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][u], b[j][u], acc[i][j], 0, 0, 0);
     };
 
+    // Every K-tile runs the full 32 k-values: the tile loads fill k beyond the segment's end with
+    // zeros on both operands, so a short last tile needs no path of its own (a second path makes
+    // the compiler shuttle the accumulators between register sets on every iteration).
     auto compute = [&](int t) {
         const float* Asm = As[t & 1];
         const float* Bsm = Bs[t & 1];
-        const int kvalid = (t < nt0) ? min(BK, s0.kend - (s0.kbeg + t * BK)) : min(BK, s1.kend - (t - nt0) * BK);
         float a[2][TM][4], b[2][TN][4];
-        if (kvalid == BK) {
-            // The fragments of group kg + 1 are read from LDS while group kg feeds the matrix core: the
-            // reads are spread between the MFMAs (one read after every few of them) instead of all being
-            // issued, and waited for, right before their first use.
-            constexpr int NMFMA = 4 * TM * TN;
-            constexpr int NREAD = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);
-            constexpr int PER = NMFMA / (NREAD + 1) > 0 ? NMFMA / (NREAD + 1) : 1;
-            load_frag(Asm, Bsm, 0, a[0], b[0]);
+        // The fragments of group kg + 1 are read from LDS while group kg feeds the matrix core: the
+        // reads are spread between the MFMAs (one read after every few of them) instead of all being
+        // issued, and waited for, right before their first use.
+        constexpr int NMFMA = 4 * TM * TN;
+        constexpr int NREAD = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);
+        constexpr int PER = NMFMA / (NREAD + 1) > 0 ? NMFMA / (NREAD + 1) : 1;
+        load_frag(Asm, Bsm, 0, a[0], b[0]);
 #pragma unroll
-            for (int kg = 0; kg < BK / 8; ++kg) {
-                if (kg + 1 < BK / 8) load_frag(Asm, Bsm, kg + 1, a[(kg + 1) & 1], b[(kg + 1) & 1]);
-                mfma_group(a[kg & 1], b[kg & 1]);
-                if (kg + 1 < BK / 8) {
+        for (int kg = 0; kg < BK / 8; ++kg) {
+            if (kg + 1 < BK / 8) load_frag(Asm, Bsm, kg + 1, a[(kg + 1) & 1], b[(kg + 1) & 1]);
+            mfma_group(a[kg & 1], b[kg & 1]);
+            if (kg + 1 < BK / 8) {
 #pragma unroll
-                    for (int i = 0; i < NREAD; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);    // MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // LDS read
-                    }
+                for (int i = 0; i < NREAD; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);    // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // LDS read
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, NMFMA, 0);
-                __builtin_amdgcn_sched_barrier(0);
             }
-        } else {
-            const int ngroups = (kvalid + 7) >> 3;
-            for (int kg = 0; kg < ngroups; ++kg) {
-                load_frag(Asm, Bsm, kg, a[0], b[0]);
-                mfma_group(a[0], b[0]);
-            }
+            __builtin_amdgcn_sched_group_barrier(0x008, NMFMA, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
