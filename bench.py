@@ -271,7 +271,11 @@ def main():
     tot_gemm_flops = sum(k["flops"] for k in gemm)
     dom = max(gemm, key=lambda k: k["total_ms"])
     achieved = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
-    traffic = profile_tools.stored_traffic(os.path.join(ROOT, "profiles", "bench_%s_traffic.txt" % w.name), dom["name"])
+    # the stored counters were taken on the plain configuration of the workload: a variant (clipping and
+    # normalisation, distributional or stochastic networks, another schedule) runs other kernels
+    variant = args.paper_defaults or args.atoms or args.sac or args.schedule != "serial"
+    traffic = None if variant else profile_tools.stored_traffic(
+        os.path.join(ROOT, "profiles", "bench_%s_traffic.txt" % w.name), dom["name"])
     fl = flops_per_sample(w)
     flops_step = w.batch * (fl["critic_update"] + fl["actor_update"] / POLICY_EVERY) + w.num_envs * fl["act"] / ACTOR_EVERY
     kernels = []
