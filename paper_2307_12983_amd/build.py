@@ -13,9 +13,6 @@ LIB = os.path.join(HERE, "libpql.so")
 SOURCES = ["pql_api.hip", "pql_gemm.hip", "pql_kernels.hip", "pql_fused.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         # MFMA accumulators stay in ordinary vector registers: with the accumulation-register form the
-         # compiler moves every accumulator out and back in around each conditional part of a GEMM loop
-         "-mllvm", "-amdgpu-mfma-vgpr-form",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 

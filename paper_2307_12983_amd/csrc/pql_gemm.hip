@@ -98,6 +98,11 @@ struct TileRegs {
         }
     }
 
+    __device__ inline void zero() {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+
     __device__ inline void store(float* tile, int stride, int tid) const {
         const int c = (tid % C4) * 4;
         const int r = tid / C4;
@@ -184,6 +189,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
     RegsB rb0, rb1;
 
     auto fetch = [&](int t, RegsA& ra, RegsB& rb) {
+        if (t >= nt) { ra.zero(); rb.zero(); return; }       // the padding tile of an odd count
         const bool first = t < nt0;
         const SegRegs& S = first ? s0 : s1;
         const int k0 = first ? s0.kbeg + t * BK : (t - nt0) * BK;
@@ -263,24 +269,27 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmGroup 
     // Software pipeline: while tile t feeds the matrix cores from LDS stage t&1, tile t+2 is requested
     // from memory and tile t+1, requested one step earlier, moves from registers into the other stage
     // after the matrix work (a load has two steps of matrix work to arrive before it is waited for).
+    // The tiles are taken in pairs with nothing conditional around the matrix work (an odd count is
+    // padded with one all-zero tile): a conditional second half makes the compiler move every
+    // accumulator between the accumulation registers and ordinary ones on each iteration.
+    const int nt2 = (nt + 1) & ~1;
     if (nt > 0) {
         fetch(0, ra0, rb0);
-        if (nt > 1) fetch(1, ra1, rb1);
+        fetch(1, ra1, rb1);
         ra0.store(As[0], SA, tid);
         rb0.store(Bs[0], SB, tid);
         __syncthreads();
     }
-    for (int t = 0; t < nt; t += 2) {
-        if (t + 2 < nt) fetch(t + 2, ra0, rb0);
+    for (int t = 0; t < nt2; t += 2) {
+        if (t + 2 < nt2) fetch(t + 2, ra0, rb0);
         compute(t);
-        if (t + 1 < nt) { ra1.store(As[1], SA, tid); rb1.store(Bs[1], SB, tid); }
+        ra1.store(As[1], SA, tid);
+        rb1.store(Bs[1], SB, tid);
         __syncthreads();
-        if (t + 1 < nt) {
-            if (t + 3 < nt) fetch(t + 3, ra1, rb1);
-            compute(t + 1);
-            if (t + 2 < nt) { ra0.store(As[0], SA, tid); rb0.store(Bs[0], SB, tid); }
-            __syncthreads();
-        }
+        if (t + 3 < nt2) fetch(t + 3, ra1, rb1);
+        compute(t + 1);
+        if (t + 2 < nt2) { ra0.store(As[0], SA, tid); rb0.store(Bs[0], SB, tid); }
+        __syncthreads();
     }
 
     // ---- epilogue -------------------------------------------------------------------------
