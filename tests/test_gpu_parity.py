@@ -53,10 +53,17 @@ def small_cases():
                                        hidden=(160,), index=11),
         "fused_l3": Wk["tiny"].replace(name="fused_l3", obs_dim=45, act_dim=11, num_envs=33, capacity=33 * 12, batch=451,
                                        hidden=(128, 96, 64), index=12),
+        # contraction lengths of the row-tile kernels: several whole 32-chunks plus a short tail (211 = 6 * 32 + 19),
+        # a tail only (20), whole chunks only (64, 32), layers narrower than the eight wavefronts' 256 columns
+        "fused_wide_in": Wk["tiny"].replace(name="fused_wide_in", obs_dim=211, act_dim=20, num_envs=40, capacity=40 * 10,
+                                            batch=300, hidden=(192, 128), index=16),
+        "fused_k64": Wk["tiny"].replace(name="fused_k64", obs_dim=64, act_dim=32, num_envs=36, capacity=36 * 9, batch=200,
+                                        hidden=(64, 64), index=17),
     }
 
 
 SMALL = small_cases()
+ROW_TILE_CASES = ["tiny", "ant_s", "fused_l1", "fused_l3", "fused_wide_in", "fused_k64"]
 
 
 # ---------------------------------------------------------------------------------------------
@@ -664,3 +671,25 @@ def test_kernel_profile_reports_launches_and_work(torch_cuda):
     from paper_2307_12983_amd.binding import PqlError
     with pytest.raises(PqlError):
         s.ctx.pql_profile_end()
+
+
+@pytest.mark.parametrize("case", list(SMALL))
+def test_which_cases_take_the_row_tile_kernels(torch_cuda, case):
+    """The cases meant to cover the row-tile kernels really run them (and the others the layered path):
+    the library's own per-kernel profile names what was launched."""
+    w = SMALL[case]
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, w.nstep + 2)
+    s.sample(w.batch)
+    s.ctx.pql_profile_begin(256)
+    s.critic_update(w.batch)
+    s.actor_update(None, w.batch)
+    s.act(s.batch.obs[:min(w.num_envs, w.batch)])
+    torch_cuda.cuda.synchronize()
+    names = {k["name"] for k in s.ctx.pql_profile_end()}
+    say(case, sorted(names))
+    fused = {"fused_critic_kernel", "fused_policy_kernel", "fused_act_kernel"}
+    if case in ROW_TILE_CASES:
+        assert fused <= names and not any(n.startswith("gemm_grouped_n") for n in names)
+    else:
+        assert not (fused & names)
