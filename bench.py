@@ -205,12 +205,15 @@ def main():
     probe_out = torch.empty(probe_blocks * 256, dtype=torch.float32, device="cuda")
     sess.ctx.pql_probe_mfma(probe_out, probe_blocks, 64)
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record()
-    sess.ctx.pql_probe_mfma(probe_out, probe_blocks, probe_iters)
-    ev1.record()
-    torch.cuda.synchronize()
-    mfma_ceiling = probe_blocks * 4 * 4 * probe_iters * 4096.0 / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
+    probe_ms = []
+    for _ in range(4):        # the best of a few launches: the first ones after an idle phase can run at a lower clock
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        sess.ctx.pql_probe_mfma(probe_out, probe_blocks, probe_iters)
+        ev1.record()
+        torch.cuda.synchronize()
+        probe_ms.append(ev0.elapsed_time(ev1))
+    mfma_ceiling = probe_blocks * 4 * 4 * probe_iters * 4096.0 / (min(probe_ms) * 1e-3) / 1e12
     del probe_out
 
     sched = Schedule(sess, env_dev)
