@@ -689,21 +689,32 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
             }
             const float bt0 = A.qt[0].b[L][0], bt1 = A.qt[1].b[L][0];
             const float alpha = sac ? expf(A.sac.log_alpha[0]) : 0.f;
+            // all reads, then all reductions, then all results: the rows' chains (LDS read -> dot product ->
+            // wave reduction) are independent and overlap instead of running one after the other
+            float st[2][BMF / FW];
+#pragma unroll
             for (int rr = 0; rr < BMF / FW; ++rr) {
                 const int row = T.wave * (BMF / FW) + rr;
                 float s0 = 0.f, s1 = 0.f;
-    #pragma unroll
+#pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int c = T.lane + 64 * j;
-                    if (c < HL) {
-                        s0 += smem[m.Ht(0, cur) + row * m.SH + c] * wt0[j];
-                        s1 += smem[m.Ht(1, cur) + row * m.SH + c] * wt1[j];
-                    }
+                    const int cc = c < HL ? c : 0;          // idle lanes read a valid column and multiply by a zero weight
+                    s0 += smem[m.Ht(0, cur) + row * m.SH + cc] * wt0[j];
+                    s1 += smem[m.Ht(1, cur) + row * m.SH + cc] * wt1[j];
                 }
-                s0 = wsum(s0) + bt0;
-                s1 = wsum(s1) + bt1;
+                st[0][rr] = s0; st[1][rr] = s1;
+            }
+#pragma unroll
+            for (int rr = 0; rr < BMF / FW; ++rr) {
+                st[0][rr] = wsum(st[0][rr]) + bt0;
+                st[1][rr] = wsum(st[1][rr]) + bt1;
+            }
+#pragma unroll
+            for (int rr = 0; rr < BMF / FW; ++rr) {
+                const int row = T.wave * (BMF / FW) + rr;
                 if (T.lane == 0) {
-                    float tq = fminf(s0, s1);
+                    float tq = fminf(st[0][rr], st[1][rr]);
                     if (sac) tq -= alpha * sm_logp[row];
                     const float y = sm_ret[row] + sm_boot[row] * tq;
                     sm_y[row] = y;
@@ -781,35 +792,59 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
                 dw_acc[i][j] = 0.f; dbh_acc[i][j] = 0.f;
             }
         }
+        // phases instead of a row-by-row loop: the rows' chains are independent (see the target heads)
+        float hh[2][BMF / FW][4], qv[2][BMF / FW];
+#pragma unroll
         for (int rr = 0; rr < BMF / FW; ++rr) {
             const int row = T.wave * (BMF / FW) + rr;
-            const bool rv = r0 + row < B;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                float* hrow = &smem[m.Ht(i, cur) + row * m.SH];
-                float h[4];
-                float s = 0.f;
+                float sdot = 0.f;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int c = T.lane + 64 * j;
-                    h[j] = c < HL ? hrow[c] : 0.f;
-                    s += h[j] * wq[i][j];
+                    hh[i][rr][j] = c < HL ? smem[m.Ht(i, cur) + row * m.SH + c] : 0.f;
+                    sdot += hh[i][rr][j] * wq[i][j];
                 }
-                const float q = wsum(s) + bq[i];
-                const float e = rv ? q - sm_y[row] : 0.f;
+                qv[i][rr] = sdot;
+            }
+        }
+#pragma unroll
+        for (int rr = 0; rr < BMF / FW; ++rr)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) qv[i][rr] = wsum(qv[i][rr]) + bq[i];
+        // per-lane addresses of this wavefront's first row, formed once: inside the loop the compiler
+        // otherwise fetches the pointers from the argument block again before every store
+        const int row_w = T.wave * (BMF / FW);
+        float* gdq[2];
+        float* gq[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            gdq[i] = A.dQ[i][L] + (size_t)(r0 + row_w) * (size_t)HL + T.lane;
+            gq[i] = A.q_out[i] + r0 + row_w;
+        }
+#pragma unroll
+        for (int rr = 0; rr < BMF / FW; ++rr) {
+            const int row = row_w + rr;
+            const bool rv = r0 + row < B;
+            const float yv = sm_y[row];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int hrow = m.Ht(i, cur) + row * m.SH + T.lane;
+                const float q = qv[i][rr];
+                const float e = rv ? q - yv : 0.f;
                 const float d = 2.f * e * invB;
                 loss_acc[i] += e * e;
                 db_acc[i] += d;
-                if (T.lane == 0 && rv) A.q_out[i][r0 + row] = q;
+                if (T.lane == 0 && rv) gq[i][rr] = q;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int c = T.lane + 64 * j;
-                    if (c < HL) {
-                        const float g = d * wq[i][j] * delu_h(h[j]);
-                        hrow[c] = g;
-                        if (rv) A.dQ[i][L][(size_t)(r0 + row) * HL + c] = g;
+                    if (T.lane + 64 * j < HL) {
+                        const float g = d * wq[i][j] * delu_h(hh[i][rr][j]);
+                        smem[hrow + 64 * j] = g;
+                        if (rv) gdq[i][(size_t)rr * (size_t)HL + 64 * j] = g;
                         dbh_acc[i][j] += g;
-                        dw_acc[i][j] += d * h[j];
+                        dw_acc[i][j] += d * hh[i][rr][j];
                     }
                 }
             }
@@ -993,31 +1028,43 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
 #pragma unroll
             for (int j = 0; j < 4; ++j) wq[i][j] = (T.lane + 64 * j < HL) ? A.q[i].w[L][T.lane + 64 * j] : 0.f;
         }
+        // phases instead of a row-by-row loop: the rows' chains (LDS read -> dot product -> wave reduction)
+        // are independent and overlap
+        float hh[2][BMF / FW][4], qv[2][BMF / FW];
+#pragma unroll
         for (int rr = 0; rr < BMF / FW; ++rr) {
             const int row = T.wave * (BMF / FW) + rr;
-            const bool rv = r0 + row < B;
-            float h[2][4], q[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                float s = 0.f;
+                float sdot = 0.f;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int c = T.lane + 64 * j;
-                    h[i][j] = c < HL ? smem[m.Ht(i, cur) + row * m.SH + c] : 0.f;
-                    s += h[i][j] * wq[i][j];
+                    hh[i][rr][j] = c < HL ? smem[m.Ht(i, cur) + row * m.SH + c] : 0.f;
+                    sdot += hh[i][rr][j] * wq[i][j];
                 }
-                q[i] = wsum(s) + bq[i];
-                if (T.lane == 0 && rv) A.q_out[i][r0 + row] = q[i];
+                qv[i][rr] = sdot;
             }
-            const bool pick0 = q[0] <= q[1];
-            if (rv) loss_acc += pick0 ? q[0] : q[1];
+        }
+#pragma unroll
+        for (int rr = 0; rr < BMF / FW; ++rr)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) qv[i][rr] = wsum(qv[i][rr]) + bq[i];
+#pragma unroll
+        for (int rr = 0; rr < BMF / FW; ++rr) {
+            const int row = T.wave * (BMF / FW) + rr;
+            const bool rv = r0 + row < B;
+            const float q0 = qv[0][rr], q1 = qv[1][rr];
+            if (T.lane == 0 && rv) { A.q_out[0][r0 + row] = q0; A.q_out[1][r0 + row] = q1; }
+            const bool pick0 = q0 <= q1;
+            if (rv) loss_acc += pick0 ? q0 : q1;
             const float d[2] = {(rv && pick0) ? -invB : 0.f, (rv && !pick0) ? -invB : 0.f};
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int c = T.lane + 64 * j;
-                    if (c < HL) smem[m.Ht(i, cur) + row * m.SH + c] = d[i] * wq[i][j] * delu_h(h[i][j]);
+                    if (c < HL) smem[m.Ht(i, cur) + row * m.SH + c] = d[i] * wq[i][j] * delu_h(hh[i][rr][j]);
                 }
         }
     }
