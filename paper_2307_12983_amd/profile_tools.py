@@ -4,6 +4,10 @@
     python -m paper_2307_12983_amd.profile_tools stats   <kernel_stats.csv> <bench.json> <out.md> <title> [bench.py arguments]
     python -m paper_2307_12983_amd.profile_tools traffic <fetch_counter_collection.csv> <write_counter_collection.csv> \
                                                          <kernel name> <out.txt>
+    python -m paper_2307_12983_amd.profile_tools counters <counter_collection.csv> <out.txt> <counters of the pass> [bench.py arguments]
+
+``counters`` averages one pass of shader counters (at most 8 ``SQ_`` counters fit one pass) per
+launch for every kernel of the library and relates them to the busy cycles of the compute units.
 
 ``traffic`` scales the FETCH_SIZE / WRITE_SIZE readings (KiB per dispatch) of the named kernel by
 what the same counters read for bench.py's calibration copy (one ``copy_kernel`` launch that
@@ -121,10 +125,43 @@ def stored_traffic(path, kernel):
     return float(kv["traffic_bytes_per_launch"])
 
 
+def counters_summary(counter_csv, out, counters, bench_args=""):
+    """Per-kernel averages per launch of one --pmc pass (warm-up launches skipped)."""
+    names = counters.split()
+    per = {}                                   # kernel -> dispatch -> counter -> value
+    for r in csv.DictReader(open(counter_csv)):
+        if "pql::" not in r["Kernel_Name"]:
+            continue
+        per.setdefault(short_name(r["Kernel_Name"]), {}).setdefault(r["Dispatch_Id"], {})[r["Counter_Name"]] = float(r["Counter_Value"])
+    with open(out, "w") as f:
+        f.write("# Shader counters per launch (bench.py, one --pmc pass)\n")
+        f.write("# Command (from the repository root, on one MI355X):\n")
+        f.write("#   rocprofv3 --pmc %s --output-format csv -d <out>/pmc_sq -o s -- python3 bench.py%s\n" % (
+            " ".join(names), (" " + bench_args) if bench_args else ""))
+        f.write("#   python -m paper_2307_12983_amd.profile_tools counters <out>/pmc_sq/s_counter_collection.csv <this file> \"<counters>\"\n")
+        f.write("# Values are sums over all compute units / wavefronts of a launch, averaged over the launches after the\n")
+        f.write("# first quarter; `/busy` divides by SQ_BUSY_CU_CYCLES (cycles x compute units with work).\n")
+        f.write("source_sha256=%s\n" % source_hash())
+        order = sorted(per, key=lambda k: -sum(d.get("SQ_BUSY_CU_CYCLES", 0.0) for d in per[k].values()))
+        for k in order:
+            disp = [per[k][d] for d in sorted(per[k], key=int)]
+            disp = disp[len(disp) // 4:]
+            f.write("\n%s  (%d launches)\n" % (k, len(disp)))
+            busy = sum(d.get("SQ_BUSY_CU_CYCLES", 0.0) for d in disp) / len(disp)
+            for c in names:
+                v = sum(d.get(c, 0.0) for d in disp) / len(disp)
+                f.write("    %-28s %16.0f" % (c, v))
+                if busy > 0 and c != "SQ_BUSY_CU_CYCLES":
+                    f.write("   /busy %.4f" % (v / busy))
+                f.write("\n")
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 6 and sys.argv[1] == "stats":
         stats_summary(*sys.argv[2:7])
     elif len(sys.argv) >= 6 and sys.argv[1] == "traffic":
         traffic_summary(*sys.argv[2:6])
+    elif len(sys.argv) >= 5 and sys.argv[1] == "counters":
+        counters_summary(*sys.argv[2:6])
     else:
         raise SystemExit(__doc__)
