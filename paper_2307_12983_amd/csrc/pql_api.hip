@@ -29,6 +29,7 @@ char g_name_buf[64];
 }  // namespace
 
 const char* kernel_name(int kid) {
+    if (kid == KID_GEMM + GEMM_TN * 5 + TILE_64x64) return "gemm_tn_stream_kernel";   // small weight gradients
     if (kid >= KID_GEMM && kid < KID_GEMM + 15) {
         std::snprintf(g_name_buf, sizeof(g_name_buf), "gemm_grouped_%s_%s", k_gemm_mode[kid / 5], k_gemm_tile[kid % 5]);
         return g_name_buf;
@@ -145,7 +146,7 @@ int choose_tile(int mode, const std::vector<GemmProb>& ps) {
         max_m = p.M > max_m ? p.M : max_m;
         tiles128 += (long)((p.M + 127) / 128) * ((p.N + 127) / 128);
     }
-    if (mode == GEMM_TN) return (max_m >= 128 && max_n >= 128) ? TILE_128x128 : TILE_64x64;
+    if (mode == GEMM_TN) return TILE_64x64;      // the streaming weight-gradient kernel
     if (max_n <= 32) return TILE_128x32;
     if (max_n <= 64) return TILE_64x64;
     // measured: the backward-data kernel is at its best with 64x64 tiles at every size; the forward
@@ -156,14 +157,26 @@ int choose_tile(int mode, const std::vector<GemmProb>& ps) {
 
 int colsum_rows(int tile, int M) { return ((M + gemm_tile_m(tile) - 1) / gemm_tile_m(tile)) * gemm_waves_m(tile); }
 
-// Upper bound on split count for K rows of batch and the given total of output tiles.
-int split_target(long tiles, int K, int kmin) {
-    // about four workgroups per compute unit, but at least kmin batch rows per split
-    long s = (1024 + tiles - 1) / (tiles > 0 ? tiles : 1);
-    const long by_k = (K + kmin - 1) / kmin;
-    if (s > by_k) s = by_k;
-    if (s < 1) s = 1;
-    return (int)s;
+// Split count for weight gradients over K batch rows with the given total of 64x64 output tiles.
+// The streaming kernel keeps three workgroups per compute unit resident, so the launch runs in
+// rounds of 768 workgroups and a round lasts as long as one split's rows: the smallest count within
+// 2 % of the cheapest rounds x rows wins (every split costs one more slab for the reduction).
+constexpr int DW_MAX_SPLITS = 32;
+constexpr int DW_MIN_ROWS = 256;
+int dw_max_splits(int K) {
+    const int by_k = K / DW_MIN_ROWS;
+    return by_k < 1 ? 1 : (by_k > DW_MAX_SPLITS ? DW_MAX_SPLITS : by_k);
+}
+int split_target(long tiles, int K) {
+    const int smax = dw_max_splits(K);
+    int best_s = 1;
+    double best = 1e300;
+    for (int s = 1; s <= smax; ++s) {
+        const double rounds = (double)((tiles * s + 767) / 768);
+        const double cost = rounds * (double)((K + s - 1) / s);
+        if (cost < 0.98 * best) { best = cost; best_s = s; }
+    }
+    return best_s;
 }
 
 struct Layout {
@@ -203,44 +216,14 @@ int max_hidden(const pql_config* c) {
     return hmax;
 }
 
-// Weight-gradient problems: a small set (few 128x128 output tiles in total) goes into one launch
-// of 64x64 tiles with long K ranges per split; otherwise large matrices take 128x128 tiles and the
-// rest 64x64 tiles, in two launches.
-struct DwPlan { bool single; int kmin; };
-inline DwPlan dw_plan(const std::vector<std::pair<int, int>>& mn) {
-    long big = 0;
-    for (const auto& d : mn)
-        if (d.first >= 128 && d.second >= 128) big += (long)((d.first + 127) / 128) * ((d.second + 127) / 128);
-    DwPlan p;
-    p.single = big < 32;
-    p.kmin = p.single ? 512 : 128;
-    return p;
-}
-inline int dw_tile_of(const DwPlan& p, int M, int N) {
-    if (p.single) return TILE_64x64;
-    return (M >= 128 && N >= 128) ? TILE_128x128 : TILE_64x64;
-}
-inline long dw_tiles(int tile, int M, int N) {
-    return (long)((M + gemm_tile_m(tile) - 1) / gemm_tile_m(tile)) * ((N + gemm_tile_n(tile) - 1) / gemm_tile_n(tile));
-}
+inline long dw_tiles(int M, int N) { return (long)((M + 63) / 64) * ((N + 63) / 64); }
 
 // Floats of split-K slab space that a list of (M, N) weight-gradient problems can need for any
-// batch size up to K: per pass, (largest split count) x (sum of M*N).
+// batch size up to K: (largest split count) x (sum of M*N).
 size_t dw_slab_bound(const std::vector<std::pair<int, int>>& mn, int K) {
-    size_t total = 0;
-    const DwPlan plan = dw_plan(mn);
-    for (int pass = 0; pass < 2; ++pass) {
-        const int tile = pass == 0 ? TILE_128x128 : TILE_64x64;
-        long tiles = 0;
-        size_t elems = 0;
-        for (const auto& d : mn) {
-            if (dw_tile_of(plan, d.first, d.second) != tile) continue;
-            tiles += dw_tiles(tile, d.first, d.second);
-            elems += (size_t)d.first * d.second;
-        }
-        if (tiles > 0) total += (size_t)split_target(tiles, K, plan.kmin) * elems;
-    }
-    return total;
+    size_t elems = 0;
+    for (const auto& d : mn) elems += (size_t)d.first * d.second;
+    return (size_t)dw_max_splits(K) * elems;
 }
 
 size_t splitk_floats(const pql_config* c, int B) {
@@ -369,38 +352,23 @@ hipError_t run_auto(int mode, std::vector<GemmProb>& ps, hipStream_t st) {
 // reduction entry per problem.  `offsets[i]` is the parameter offset of problem i's tensor.
 hipError_t run_dw(std::vector<GemmProb>& ps, const std::vector<int64_t>& offsets, int K, float* slab,
                   AdamArgs& ad, hipStream_t st) {
-    std::vector<std::pair<int, int>> mn;
-    for (const GemmProb& p : ps) mn.push_back({p.M, p.N});
-    const DwPlan plan = dw_plan(mn);
-    for (int pass = 0; pass < 2; ++pass) {
-        const int tile = pass == 0 ? TILE_128x128 : TILE_64x64;
-        std::vector<GemmProb> sel;
-        std::vector<int64_t> sel_off;
-        long tiles = 0;
-        for (size_t i = 0; i < ps.size(); ++i) {
-            if (dw_tile_of(plan, ps[i].M, ps[i].N) != tile) continue;
-            sel.push_back(ps[i]);
-            sel_off.push_back(offsets[i]);
-            tiles += dw_tiles(tile, ps[i].M, ps[i].N);
-        }
-        if (sel.empty()) continue;
-        int S = split_target(tiles, K, plan.kmin);
-        int chunk = ((K + S - 1) / S + 31) / 32 * 32;
-        S = (K + chunk - 1) / chunk;
-        for (size_t i = 0; i < sel.size(); ++i) {
-            GemmProb& p = sel[i];
-            p.splits = S; p.k_chunk = chunk;
-            p.C = slab; p.ldc = p.N;
-            p.split_stride = (int64_t)p.M * p.N;
-            RedTensor& t = ad.t[ad.ntensors++];
-            t.offset = sel_off[i]; t.stride = p.split_stride; t.partial = slab;
-            t.count = p.M * p.N; t.nparts = S;
-            slab += (size_t)S * p.M * p.N;
-        }
-        const hipError_t e = run(GEMM_TN, tile, sel, nullptr, st);
-        if (e != hipSuccess) return e;
+    if (ps.empty()) return hipSuccess;
+    long tiles = 0;
+    for (const GemmProb& p : ps) tiles += dw_tiles(p.M, p.N);
+    int S = split_target(tiles, K);
+    const int chunk = ((K + S - 1) / S + 31) / 32 * 32;
+    S = (K + chunk - 1) / chunk;
+    for (size_t i = 0; i < ps.size(); ++i) {
+        GemmProb& p = ps[i];
+        p.splits = S; p.k_chunk = chunk;
+        p.C = slab; p.ldc = p.N;
+        p.split_stride = (int64_t)p.M * p.N;
+        RedTensor& t = ad.t[ad.ntensors++];
+        t.offset = offsets[i]; t.stride = p.split_stride; t.partial = slab;
+        t.count = p.M * p.N; t.nparts = S;
+        slab += (size_t)S * p.M * p.N;
     }
-    return hipSuccess;
+    return run(GEMM_TN, TILE_64x64, ps, nullptr, st);
 }
 
 void red(AdamArgs& ad, int64_t offset, const float* partial, int count, int nparts, int64_t stride) {

@@ -4,7 +4,10 @@
 // twin critics forward (X W + b, ELU / tanh), the backward data path (delta W^T times the
 // activation derivative) and the weight gradients (X^T delta, reduced over the batch by
 // split-K).  One launch handles a list of independent problems, so the twin critics, the target
-// critics and the policy share launches.
+// critics and the policy share launches.  Forward and backward-data products go through the
+// LDS-tiled kernel described next; the weight gradients, whose two operands are both contiguous
+// along the MFMA's M / N dimension, go through gemm_tn_stream_kernel further down, which takes its
+// fragments straight from memory.
 //
 // Tiling: a workgroup is 4 wavefronts of 64 lanes.  Global tiles are copied to LDS in their
 // natural orientation (the contiguous dimension stays contiguous, 16-byte loads when the
@@ -351,6 +354,137 @@ int gemm_tile_m(int tile) { return tile == TILE_64x64 ? 64 : 128; }
 int gemm_tile_n(int tile) { return tile == TILE_128x128 ? 128 : (tile == TILE_128x32 ? 32 : 64); }
 int gemm_waves_m(int tile) { return tile == TILE_128x32 ? 4 : 2; }
 
+// =============================================================================================
+// Weight gradients of small layers, dW[M x N] = A^T B over a range of batch rows (the K dimension),
+// 64 x 64 output tile per workgroup.  Both operands are row-major activations [rows x ld] whose
+// contiguous dimension is the MFMA's M resp. N dimension, so the lanes of a wavefront can take
+// their A and B fragments straight from memory (coalesced 128-byte row pieces through buffer
+// descriptors: a scalar row offset plus one lane offset, rows past the range read as zero): no LDS
+// staging and no barrier inside the loop.  The four wavefronts of a workgroup each take a quarter
+// of the split's rows of the same tile (rows in chunks of 8, the next chunk requested while the
+// current one feeds the matrix core); the partial tiles meet in LDS at the end.
+// TM = 32-row tiles of the output per wavefront (1 for outputs of at most 32 rows).
+// =============================================================================================
+__device__ inline float tn_load(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+
+constexpr int TNS = 4;            // MFMA steps (2 rows each) per chunk of the streaming weight-gradient kernel
+
+template <int TM>
+__device__ inline void tn_stream_tile(const GemmProb& P, int split, int m0, int n0, float (*red)[4096]) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int K = P.seg[0].K, lda = P.seg[0].lda, ldb = P.seg[0].ldb;
+    const int kb = split * P.k_chunk, ke = min(K, kb + P.k_chunk);
+    const int kq = (((ke - kb + 3) >> 2) + 2 * TNS - 1) / (2 * TNS) * (2 * TNS);     // rows per wavefront, whole chunks
+    const int k0 = kb + wave * kq, k1 = min(ke, k0 + kq);
+    const int nch = k1 > k0 ? (k1 - k0 + 2 * TNS - 1) / (2 * TNS) : 0;
+    // descriptors end at this wavefront's last row: the rows of a short last chunk read as zero
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(P.seg[0].A), 0,
+                                                                        max(k1, 0) * lda * (int)sizeof(float), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(P.seg[0].B), 0,
+                                                                        max(k1, 0) * ldb * (int)sizeof(float), 0x00020000);
+    // lane (l32, half) holds column l32 of row 2s + half of every step s; columns past the matrix
+    // read neighbouring (finite) activations or zero and only reach output elements that are not stored
+    int va[TM], vb[2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) va[i] = (half * lda + m0 + 32 * i + l32) * (int)sizeof(float);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) vb[j] = (half * ldb + n0 + 32 * j + l32) * (int)sizeof(float);
+    floatx16 acc[TM][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    float a0[TM][TNS], b0[2][TNS], a1[TM][TNS], b1[2][TNS];
+    auto load = [&](int c, float (&a)[TM][TNS], float (&b)[2][TNS]) {
+        const int row = k0 + 2 * TNS * (c < nch ? c : 0);
+#pragma unroll
+        for (int st = 0; st < TNS; ++st) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i][st] = tn_load(ra, va[i], (row + 2 * st) * lda * (int)sizeof(float));
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[j][st] = tn_load(rb, vb[j], (row + 2 * st) * ldb * (int)sizeof(float));
+        }
+    };
+    auto mac = [&](const float (&a)[TM][TNS], const float (&b)[2][TNS]) {
+#pragma unroll
+        for (int st = 0; st < TNS; ++st)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][st], b[j][st], acc[i][j], 0, 0, 0);
+    };
+    if (nch > 0) {
+        load(0, a0, b0);
+        int left = nch, c = 0;
+        // the fences keep the next chunk's requests ahead of the current chunk's MFMAs
+        while (true) {
+            load(c + 1, a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            mac(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (--left == 0) break;
+            ++c;
+            load(c + 1, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            mac(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (--left == 0) break;
+            ++c;
+        }
+    }
+    // partial tiles of wavefronts 1..3 through LDS (index ((i * 2 + j) * 16 + r) * 64 + lane), added in a
+    // fixed order by wavefront 0, which stores the split's slab
+    if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) red[wave - 1][((i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        float* __restrict__ C = P.C + (size_t)split * (size_t)P.split_stride;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = n0 + 32 * j + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int e = ((i * 2 + j) * 16 + r) * 64 + lane;
+                    const float v = ((acc[i][j][r] + red[0][e]) + red[1][e]) + red[2][e];
+                    const int row = m0 + 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
+                    if (row < P.M && col < P.N) C[(size_t)row * (size_t)P.ldc + col] = v;
+                }
+            }
+    }
+}
+
+__global__ __launch_bounds__(NTHREADS, 3) void gemm_tn_stream_kernel(const GemmGroup g) {
+    __shared__ float red[3][4096];
+    const int bid = xcd_remap(blockIdx.x, gridDim.x);
+    int pi = 0;
+    for (int i = 1; i < g.nprob; ++i)
+        if (bid >= g.p[i].tile_begin) pi = i;
+    const GemmProb& P = g.p[pi];
+    int local = bid - P.tile_begin;
+    const int per_split = P.tiles_m * P.tiles_n;
+    const int split = local / per_split;
+    local -= split * per_split;
+    const int tile_m = local / P.tiles_n, tile_n = local % P.tiles_n;
+    const int m0 = tile_m * 64, n0 = tile_n * 64;
+    if (P.M - m0 <= 32) tn_stream_tile<1>(P, split, m0, n0, red);
+    else                tn_stream_tile<2>(P, split, m0, n0, red);
+}
+
 template <int MODE>
 static hipError_t launch_mode(int tile, const GemmGroup& g, bool noise, const ProfSlot& ps, hipStream_t stream) {
     const dim3 grid(g.total_tiles), block(NTHREADS);
@@ -393,7 +527,11 @@ hipError_t gemm_launch(int mode, int tile, GemmGroup& g, hipStream_t stream) {
     switch (mode) {
         case GEMM_NN: e = launch_mode<GEMM_NN>(tile, g, noise, ps, stream); break;
         case GEMM_NT: e = launch_mode<GEMM_NT>(tile, g, noise, ps, stream); break;
-        default:      e = launch_mode<GEMM_TN>(tile, g, noise, ps, stream); break;
+        default:      // weight gradients: always the streaming kernel on 64x64 output tiles
+            if (tile != TILE_64x64) return hipErrorInvalidValue;
+            PQL_LAUNCH(ps, gemm_tn_stream_kernel, dim3(g.total_tiles), dim3(NTHREADS), 0, stream, g);
+            e = hipGetLastError();
+            break;
     }
     prof_commit(ps, KID_GEMM + mode * 5 + (noise ? 4 : tile), flops, 0.0);
     return e;

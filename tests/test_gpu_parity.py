@@ -223,8 +223,11 @@ def one_step(torch, w, rows, check_all=True):
     # Polyak
     s.soft_update_targets()
     L.soft_update_targets()
-    res["target"] = assert_params_close(s.critic_target.cpu().numpy(), L.critic_target, w.critic_dims(), 2,
-                                        TOL_ONE_STEP, "critic target")   # tau * (deviation <= 2 lr) is below tol
+    # theta' = tau * theta + (1 - tau) * theta' is linear in theta: the target inherits tau times the deviation
+    # of each parameter, so the near-zero-gradient entries of the first Adam step get the same treatment with
+    # lr * tau in place of lr (tau * 2 lr is NOT below 1e-4 of the largest weight of a wide layer)
+    res["target"] = assert_first_step_params(s.critic_target.cpu().numpy(), L.critic_target, s.c_g.cpu().numpy(), g,
+                                             w.critic_dims(), 2, w.lr * w.tau, w.eps, TOL_ONE_STEP, "critic target")
     # policy update on the sampled states, then hard sync of the lagged policy
     s.actor_update(None, Bsz)
     J, ga = L.actor_update(batch["obs"])
