@@ -360,6 +360,9 @@ hipError_t run_dw(std::vector<GemmProb>& ps, const std::vector<int64_t>& offsets
     S = (K + chunk - 1) / chunk;
     for (size_t i = 0; i < ps.size(); ++i) {
         GemmProb& p = ps[i];
+        // the kernel addresses a wavefront's rows (a quarter of a split) with 32-bit byte offsets
+        const int64_t ld = p.seg[0].lda > p.seg[0].ldb ? p.seg[0].lda : p.seg[0].ldb;
+        if (((int64_t)chunk / 4 + 16) * (ld + 64) * 4 >= 0x7fffffffLL) return hipErrorInvalidValue;
         p.splits = S; p.k_chunk = chunk;
         p.C = slab; p.ldc = p.N;
         p.split_stride = (int64_t)p.M * p.N;

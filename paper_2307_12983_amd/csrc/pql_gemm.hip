@@ -381,11 +381,13 @@ __device__ inline void tn_stream_tile(const GemmProb& P, int split, int m0, int 
     const int kq = (((ke - kb + 3) >> 2) + 2 * TNS - 1) / (2 * TNS) * (2 * TNS);     // rows per wavefront, whole chunks
     const int k0 = kb + wave * kq, k1 = min(ke, k0 + kq);
     const int nch = k1 > k0 ? (k1 - k0 + 2 * TNS - 1) / (2 * TNS) : 0;
-    // descriptors end at this wavefront's last row: the rows of a short last chunk read as zero
-    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(P.seg[0].A), 0,
-                                                                        max(k1, 0) * lda * (int)sizeof(float), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(P.seg[0].B), 0,
-                                                                        max(k1, 0) * ldb * (int)sizeof(float), 0x00020000);
+    // descriptors start at this wavefront's first row (64-bit address arithmetic; inside them 32-bit byte
+    // offsets suffice) and end at its last one: the rows of a short last chunk read as zero
+    const int nrows = k1 > k0 ? k1 - k0 : 0;
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(P.seg[0].A) + (size_t)k0 * (size_t)lda, 0, nrows * lda * (int)sizeof(float), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(P.seg[0].B) + (size_t)k0 * (size_t)ldb, 0, nrows * ldb * (int)sizeof(float), 0x00020000);
     // lane (l32, half) holds column l32 of row 2s + half of every step s; columns past the matrix
     // read neighbouring (finite) activations or zero and only reach output elements that are not stored
     int va[TM], vb[2];
@@ -402,7 +404,7 @@ __device__ inline void tn_stream_tile(const GemmProb& P, int split, int m0, int 
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     float a0[TM][TNS], b0[2][TNS], a1[TM][TNS], b1[2][TNS];
     auto load = [&](int c, float (&a)[TM][TNS], float (&b)[2][TNS]) {
-        const int row = k0 + 2 * TNS * (c < nch ? c : 0);
+        const int row = 2 * TNS * (c < nch ? c : 0);          // relative to the wavefront's first row
 #pragma unroll
         for (int st = 0; st < TNS; ++st) {
 #pragma unroll
