@@ -447,6 +447,13 @@ __device__ inline TileMem carve(int o, int a, int hmax) {
     return m;
 }
 
+// Whether the scratch region reaches into tile k of the second network.  When it is aliased it starts at
+// that network's tile 0 and is SCRATCH_F floats long: it covers tile 0 and, for tiles shorter than that,
+// the head of tile 1 as well.
+__device__ inline bool scratch_overlaps(const TileMem& m, int k) {
+    return m.scratch == m.Ht(1, 0) && (k == 0 || BMF * m.SH < SCRATCH_F);
+}
+
 size_t fused_lds_bytes(int o, int a, int hmax) { return sizeof(float) * (size_t)tile_floats(o, a, hmax, true); }
 
 // Hidden layers of NN equally shaped networks on the tile: layer 1 reads XA (and XB when
@@ -767,7 +774,7 @@ __global__ __launch_bounds__(FT) void fused_critic_kernel(const FusedCriticArgs 
         smem[m.sm + 160 + (0 * FW + T.wave) * 64 + T.lane] = db_acc[0];
         smem[m.sm + 160 + (1 * FW + T.wave) * 64 + T.lane] = db_acc[1];
         // the partial tiles may have overwritten the second critic's last hidden tile: bring it back
-        if (m.scratch == m.Ht(1, cur)) load_rows(T, m.Ht(1, cur), m.SH, A.hQ[1][L], HL, r0, B);
+        if (scratch_overlaps(m, cur)) load_rows(T, m.Ht(1, cur), m.SH, A.hQ[1][L], HL, r0, B);
         __syncthreads();
         // delta of the last hidden layer: (dlogits W_out^T) * ELU'(h_L), in place over h_L
         WideArgs<2> w;
@@ -1007,7 +1014,7 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
 #pragma unroll
             for (int rr = 0; rr < BMF / FW; ++rr)
                 smem[m.Ht(i, cur ^ 1) + (T.wave * (BMF / FW) + rr) * m.SH + T.lane] = dl[i][rr];
-        if (m.scratch == m.Ht(1, cur)) load_rows(T, m.Ht(1, cur), m.SH, A.hQ[1][L], HL, r0, B);
+        if (scratch_overlaps(m, cur)) load_rows(T, m.Ht(1, cur), m.SH, A.hQ[1][L], HL, r0, B);
         __syncthreads();
         WideArgs<2> w;
         w.ld0 = m.SH; w.K0 = atoms; w.ld1 = 0; w.K1 = 0; w.ldw = HL; w.N = HL; w.epi = WIDE_MUL_DELU;

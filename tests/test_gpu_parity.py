@@ -424,6 +424,12 @@ DIST_CASES = {
     "ant_s_d": (SMALL["ant_s"], 51, -10.0, 10.0),
     "shadow_s_d": (SMALL["shadow_s"], 64, -10.0, 10.0),    # the largest supported atom count
     "fused_l3_d": (SMALL["fused_l3"], 2, -1.0, 1.0),       # the smallest
+    # row-tile path, two layers of 128 / 224 columns: the LDS scratch of the logit products is longer than one
+    # activation tile here and reaches into the tile that holds the second critic's last hidden layer
+    "fused_mid_d": (SMALL["fused_wide_in"].replace(name="fused_mid", obs_dim=109, act_dim=32, hidden=(128, 224), index=18),
+                    51, -2.0, 3.0),
+    "fused_mid4_d": (SMALL["fused_wide_in"].replace(name="fused_mid4", obs_dim=45, act_dim=7, hidden=(160, 192, 128, 160),
+                                                    index=19), 33, -3.0, 3.0),
 }
 
 
