@@ -140,7 +140,7 @@ __device__ inline void load_tail(const ChunkSrc<NN>& s, float (&b)[NN][16]) {
 // prove the alignment and emit ds_read_b128, which the stride-(width + 4) layout serves without
 // bank conflicts).
 template <int NN>
-__device__ inline void mac_full(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], const int (&in)[NN], int ld,
+__device__ inline void mac_full(floatx16 (&acc)[NN], const int (&in)[NN], int ld,
                                 const Lanes& T, int cc, const float (&b)[NN][16]) {
     const float4* smem4 = reinterpret_cast<const float4*>(smem);
     const int a_off4 = T.l32 * (ld >> 2) + T.half + cc * 8;
@@ -153,10 +153,10 @@ __device__ inline void mac_full(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], cons
     for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int n = 0; n < NN; ++n) {
-            acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].x, b[n][g * 4 + 0], acc0[n], 0, 0, 0);
-            acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].y, b[n][g * 4 + 1], acc1[n], 0, 0, 0);
-            acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].z, b[n][g * 4 + 2], acc0[n], 0, 0, 0);
-            acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].w, b[n][g * 4 + 3], acc1[n], 0, 0, 0);
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].x, b[n][g * 4 + 0], acc[n], 0, 0, 0);
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].y, b[n][g * 4 + 1], acc[n], 0, 0, 0);
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].z, b[n][g * 4 + 2], acc[n], 0, 0, 0);
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][n].w, b[n][g * 4 + 3], acc[n], 0, 0, 0);
         }
     // Issue order: two LDS reads ahead, then four MFMAs per read (0x100 = LDS read, 0x008 = MFMA).
     // Left alone, the scheduler places every read directly before its first use.
@@ -171,7 +171,7 @@ __device__ inline void mac_full(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], cons
 
 // The short last chunk: only the groups of 8 k-values that exist.
 template <int NN>
-__device__ inline void mac_tail(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], const int (&in)[NN], int ld,
+__device__ inline void mac_tail(floatx16 (&acc)[NN], const int (&in)[NN], int ld,
                                 const ChunkSrc<NN>& s, const Lanes& T, const float (&b)[NN][16]) {
     const float4* smem4 = reinterpret_cast<const float4*>(smem);
     const int a_off4 = T.l32 * (ld >> 2) + T.half + s.nfull * 8;
@@ -182,10 +182,10 @@ __device__ inline void mac_tail(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], cons
 #pragma unroll
             for (int n = 0; n < NN; ++n) {
                 const float4 a = smem4[(in[n] >> 2) + a_off4 + g * 2];
-                acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b[n][g * 4 + 0], acc0[n], 0, 0, 0);
-                acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b[n][g * 4 + 1], acc1[n], 0, 0, 0);
-                acc0[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b[n][g * 4 + 2], acc0[n], 0, 0, 0);
-                acc1[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b[n][g * 4 + 3], acc1[n], 0, 0, 0);
+                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b[n][g * 4 + 0], acc[n], 0, 0, 0);
+                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b[n][g * 4 + 1], acc[n], 0, 0, 0);
+                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b[n][g * 4 + 2], acc[n], 0, 0, 0);
+                acc[n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b[n][g * 4 + 3], acc[n], 0, 0, 0);
             }
         }
     }
@@ -207,7 +207,7 @@ __device__ inline void prefetch_first_chunk(float (&pre)[NN][16], const float* c
 // then not paid here); a flag and a reference rather than a nullable pointer, which would keep the
 // buffer in private memory.
 template <int NN>
-__device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], const int (&in)[NN], int ld,
+__device__ inline void mac_segment(floatx16 (&acc)[NN], const int (&in)[NN], int ld,
                                    int K, const float* const (&W)[NN], int ldw, int ncol, const Lanes& T, int c_begin,
                                    int c_step, bool use_pre, const float (&pre)[NN][16]) {
     const ChunkSrc<NN> s = chunk_src<NN>(W, K, ldw, ncol, T, c_begin, c_step);
@@ -225,7 +225,7 @@ __device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], c
     }
     if (s.tail_mine) {
         if (s.n_mine > 0) load_full<NN>(s, c_begin, b1);
-        mac_tail<NN>(acc0, acc1, in, ld, s, T, b0);
+        mac_tail<NN>(acc, in, ld, s, T, b0);
         if (s.n_mine == 0) return;
 #pragma unroll
         for (int n = 0; n < NN; ++n)
@@ -238,13 +238,13 @@ __device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], c
     while (true) {                       // b0 holds whole chunk c
         load_full<NN>(s, left > 1 ? c + c_step : c, b1);       // (a repeat at the end keeps the counters uniform)
         __builtin_amdgcn_sched_barrier(0);
-        mac_full<NN>(acc0, acc1, in, ld, T, rotated(s, c), b0);
+        mac_full<NN>(acc, in, ld, T, rotated(s, c), b0);
         __builtin_amdgcn_sched_barrier(0);
         if (--left == 0) break;
         c += c_step;
         load_full<NN>(s, left > 1 ? c + c_step : c, b0);
         __builtin_amdgcn_sched_barrier(0);
-        mac_full<NN>(acc0, acc1, in, ld, T, rotated(s, c), b1);
+        mac_full<NN>(acc, in, ld, T, rotated(s, c), b1);
         __builtin_amdgcn_sched_barrier(0);
         if (--left == 0) break;
         c += c_step;
@@ -252,7 +252,7 @@ __device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], c
 }
 
 template <int NN>
-__device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], const int (&in)[NN], int ld,
+__device__ inline void mac_segment(floatx16 (&acc)[NN], const int (&in)[NN], int ld,
                                    int K, const float* const (&W)[NN], int ldw, int ncol, const Lanes& T, int c_begin,
                                    int c_step) {
     float none[NN][16];
@@ -260,7 +260,7 @@ __device__ inline void mac_segment(floatx16 (&acc0)[NN], floatx16 (&acc1)[NN], c
     for (int n = 0; n < NN; ++n)
 #pragma unroll
         for (int u = 0; u < 16; ++u) none[n][u] = 0.f;
-    mac_segment<NN>(acc0, acc1, in, ld, K, W, ldw, ncol, T, c_begin, c_step, false, none);
+    mac_segment<NN>(acc, in, ld, K, W, ldw, ncol, T, c_begin, c_step, false, none);
 }
 
 enum WideEpi : int { WIDE_BIAS_ELU = 0, WIDE_MUL_DELU = 1 };
@@ -292,21 +292,21 @@ __device__ inline void wide_linear(const Lanes& T, const WideArgs<NN>& w, int r0
     float bv[NN];
 #pragma unroll
     for (int i = 0; i < NN; ++i) bv[i] = (w.epi == WIDE_BIAS_ELU) ? w.bias[i][ncol] : 0.f;   // in flight during the MFMAs
-    floatx16 acc0[NN], acc1[NN];
+    floatx16 acc[NN];
 #pragma unroll
     for (int i = 0; i < NN; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { acc0[i][r] = 0.f; acc1[i][r] = 0.f; }
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
     if (w.K1 > 0) {
         // two segments (a critic's first layer: state columns, then action columns): the first chunks
         // of both are requested together, and the short segment runs while the long one's arrives
         float bs[NN][16], bf[NN][16];
         prefetch_first_chunk<NN>(bs, w.W1, w.K1, w.ldw, ncol, T, 0, 1);
         prefetch_first_chunk<NN>(bf, w.W0, w.K0, w.ldw, ncol, T, 0, 1);
-        mac_segment<NN>(acc0, acc1, w.in1, w.ld1, w.K1, w.W1, w.ldw, ncol, T, 0, 1, true, bs);
-        mac_segment<NN>(acc0, acc1, w.in0, w.ld0, w.K0, w.W0, w.ldw, ncol, T, 0, 1, true, bf);
+        mac_segment<NN>(acc, w.in1, w.ld1, w.K1, w.W1, w.ldw, ncol, T, 0, 1, true, bs);
+        mac_segment<NN>(acc, w.in0, w.ld0, w.K0, w.W0, w.ldw, ncol, T, 0, 1, true, bf);
     } else {
-        mac_segment<NN>(acc0, acc1, w.in0, w.ld0, w.K0, w.W0, w.ldw, ncol, T, 0, 1);
+        mac_segment<NN>(acc, w.in0, w.ld0, w.K0, w.W0, w.ldw, ncol, T, 0, 1);
     }
     // Epilogue.  Row r of the accumulator sits (8 * (r / 4) + r % 4) rows below the lane's first row
     // (4 * half): offsets from per-lane bases are compile-time multiples of the strides.
@@ -321,7 +321,7 @@ __device__ inline void wide_linear(const Lanes& T, const WideArgs<NN>& w, int r0
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int dr = 8 * (r >> 2) + (r & 3);
-            float x = acc0[i][r] + acc1[i][r];
+            float x = acc[i][r];
             if (w.epi == WIDE_BIAS_ELU) x = elu_f(x + bv[i]);
             else x *= delu_h(smem[abase + dr * w.ldaux]);
             const bool rv = full || (r0 + lrow + dr < B);
@@ -344,15 +344,15 @@ __device__ inline void wide_linear(const Lanes& T, const WideArgs<NN>& w, int r0
 // The caller synchronises and finishes with small_sum().
 __device__ inline void small_partial(const Lanes& T, int in0, int ld0, int K0, const float* W0, int ldw, int N,
                                      int scratch) {
-    floatx16 acc0[1], acc1[1];
+    floatx16 acc[1];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { acc0[0][r] = 0.f; acc1[0][r] = 0.f; }
+    for (int r = 0; r < 16; ++r) acc[0][r] = 0.f;
     const int ncol = T.l32 < N ? T.l32 : N - 1;
     const int ins[1] = {in0};
     const float* const ws[1] = {W0};
-    mac_segment<1>(acc0, acc1, ins, ld0, K0, ws, ldw, ncol, T, T.wave, FW);
+    mac_segment<1>(acc, ins, ld0, K0, ws, ldw, ncol, T, T.wave, FW);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) smem[scratch + T.wave * 1024 + r * 64 + T.lane] = acc0[0][r] + acc1[0][r];
+    for (int r = 0; r < 16; ++r) smem[scratch + T.wave * 1024 + r * 64 + T.lane] = acc[0][r];
 }
 
 // Sum of the FW partial tiles for output element e (0..1023): returns the value and its (row, col).
@@ -574,18 +574,18 @@ __device__ inline float lane_softmax_f(float logit, bool live, float& logp) {
 // alias one of the input tiles, hence the barrier between reading and writing.
 __device__ inline void dist_logit_partial(const Lanes& T, const int (&in)[2], int ld, int K, const float* const (&W)[2],
                                           int atoms, int scratch) {
-    floatx16 acc0[1], acc1[1];
+    floatx16 acc[1];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { acc0[0][r] = 0.f; acc1[0][r] = 0.f; }
+    for (int r = 0; r < 16; ++r) acc[0][r] = 0.f;
     const int net = (T.wave >> 1) & 1, tile = T.wave & 1, kh = T.wave >> 2;
     const int n = tile * 32 + T.l32;
     const int ncol = n < atoms ? n : atoms - 1;
     const int ins[1] = {net ? in[1] : in[0]};
     const float* const ws[1] = {net ? W[1] : W[0]};
-    if (tile * 32 < atoms) mac_segment<1>(acc0, acc1, ins, ld, K, ws, atoms, ncol, T, kh, 2);
+    if (tile * 32 < atoms) mac_segment<1>(acc, ins, ld, K, ws, atoms, ncol, T, kh, 2);
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < 16; ++r) smem[scratch + T.wave * 1024 + r * 64 + T.lane] = acc0[0][r] + acc1[0][r];
+    for (int r = 0; r < 16; ++r) smem[scratch + T.wave * 1024 + r * 64 + T.lane] = acc[0][r];
 }
 
 // Logit (before the bias) of network `net` at tile row `row`, atom k < 64, from those partial tiles.
@@ -1099,20 +1099,20 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     }
     // gradient w.r.t. the action input, summed over both critics, through tanh'
     {
-        floatx16 acc0[1], acc1[1];
+        floatx16 acc[1];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { acc0[0][r] = 0.f; acc1[0][r] = 0.f; }
+        for (int r = 0; r < 16; ++r) acc[0][r] = 0.f;
         const int ncol = T.l32 < a ? T.l32 : a - 1;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int ins[1] = {m.Ht(i, cur)};
             const float* const ws[1] = {A.w1aT[i]};
-            mac_segment<1>(acc0, acc1, ins, m.SH, H1, ws, a, ncol, T, T.wave, FW);
+            mac_segment<1>(acc, ins, m.SH, H1, ws, a, ncol, T, T.wave, FW);
         }
         // the scratch region may alias the second network's tiles: everyone must be done reading
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < 16; ++r) smem[m.scratch + T.wave * 1024 + r * 64 + T.lane] = acc0[0][r] + acc1[0][r];
+        for (int r = 0; r < 16; ++r) smem[m.scratch + T.wave * 1024 + r * 64 + T.lane] = acc[0][r];
     }
     __syncthreads();
     const float ab = sac ? expf(A.sac.log_alpha[0]) / (float)B : 0.f;
