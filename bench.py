@@ -197,6 +197,17 @@ def main():
     cal_dst = torch.empty_like(cal_src)
     sess.ctx.pql_soft_update(cal_src, cal_dst, cal_src.numel(), 1.0)
     torch.cuda.synchronize()
+    # The same copy timed: the rate the memory system sustains for a plain stream (read + write), the
+    # achievable ceiling next to the nominal HBM peak for the bandwidth-bound kernels.
+    copy_ms = []
+    for _ in range(3):
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        sess.ctx.pql_soft_update(cal_src, cal_dst, cal_src.numel(), 1.0)
+        ev1.record()
+        torch.cuda.synchronize()
+        copy_ms.append(ev0.elapsed_time(ev1))
+    hbm_copy_gbs = 2.0 * 4.0 * cal_src.numel() / (min(copy_ms) * 1e-3) / 1e9
     del cal_src, cal_dst
 
     # The matrix cores' sustained rate on register operands (no memory): the achievable ceiling next
@@ -288,6 +299,7 @@ def main():
             e["tflops"] = k["flops"] / (k["total_ms"] * 1e-3) / 1e12
         if k["bytes"] > 0:
             e["gbs"] = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9
+            e["hbm_frac"] = e["gbs"] / PEAK_HBM_GBS
         kernels.append(e)
 
     out = {
@@ -310,6 +322,8 @@ def main():
                      "avg_launch_us": 1e3 * dom["total_ms"] / dom["launches"], "launches": dom["launches"],
                      "achievable_peak": mfma_ceiling, "frac_of_achievable": achieved / mfma_ceiling,
                      "all_gemm_tflops": tot_gemm_flops / (tot_gemm_ms * 1e-3) / 1e12},
+        "hbm": {"peak_gbs": PEAK_HBM_GBS, "copy_gbs": hbm_copy_gbs, "copy_frac": hbm_copy_gbs / PEAK_HBM_GBS,
+                "copy_bytes": 8 * profile_tools.CAL_COPY_FLOATS},
         "mfma_util_pct": 100.0 * flops_step * value / (PEAK_FP32_MFMA_TFLOPS * 1e12),
         "actor_actions_per_s": w.num_envs / t_act,
         "actor_act_us": 1e6 * t_act,
