@@ -130,6 +130,34 @@ __global__ __launch_bounds__(256) void sample_kernel(const SampleArgs a) {
         a.out.ret[k] = ret;
         a.out.boot[k] = g * alive;
     }
+    if (VEC_O && VEC_A) {
+        // 16-byte path: the three rows' loads are issued together and the stores follow, so that a
+        // sample costs one memory round trip (row after row, each copy waited for the one before it:
+        // nothing tells the compiler that the batch does not alias the ring)
+        const float4* __restrict__ so = reinterpret_cast<const float4*>(a.st.obs + (size_t)slot * a.o);
+        const float4* __restrict__ sn = reinterpret_cast<const float4*>(a.st.next_obs + (size_t)last * a.o);
+        const float4* __restrict__ sa = reinterpret_cast<const float4*>(a.st.act + (size_t)slot * a.a);
+        float4* __restrict__ d_o = reinterpret_cast<float4*>(a.out.obs + (size_t)k * a.o);
+        float4* __restrict__ d_n = reinterpret_cast<float4*>(a.out.next_obs + (size_t)k * a.o);
+        float4* __restrict__ d_a = reinterpret_cast<float4*>(a.out.act + (size_t)k * a.a);
+        const int no4 = a.o >> 2, na4 = a.a >> 2;
+        const int nmax = no4 > na4 ? no4 : na4;
+        const bool stdz = a.nmean != nullptr;
+        for (int c = gl; c < nmax; c += G) {
+            const bool po = c < no4, pa = c < na4;
+            float4 vo = make_float4(0.f, 0.f, 0.f, 0.f), vn = vo, va = vo, mu = vo, rs = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (po) { vo = so[c]; vn = sn[c]; }
+            if (pa) va = sa[c];
+            if (po && stdz) { mu = reinterpret_cast<const float4*>(a.nmean)[c]; rs = reinterpret_cast<const float4*>(a.nrstd)[c]; }
+            if (stdz) {
+                vo.x = (vo.x - mu.x) * rs.x; vo.y = (vo.y - mu.y) * rs.y; vo.z = (vo.z - mu.z) * rs.z; vo.w = (vo.w - mu.w) * rs.w;
+                vn.x = (vn.x - mu.x) * rs.x; vn.y = (vn.y - mu.y) * rs.y; vn.z = (vn.z - mu.z) * rs.z; vn.w = (vn.w - mu.w) * rs.w;
+            }
+            if (po) { d_o[c] = vo; d_n[c] = vn; }
+            if (pa) d_a[c] = va;
+        }
+        return;
+    }
     copy_row<G, VEC_A>(a.out.act + (size_t)k * a.a, a.st.act + (size_t)slot * a.a, a.a, gl);
     if (a.nmean != nullptr) {
         copy_row_std<G, VEC_O>(a.out.obs + (size_t)k * a.o, a.st.obs + (size_t)slot * a.o, a.o, gl, a.nmean, a.nrstd);
