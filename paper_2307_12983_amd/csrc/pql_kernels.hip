@@ -523,10 +523,24 @@ __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
     const int i = (b - T.block_begin) * E + e;
     const bool live = i < T.count;
     float g = 0.f;
+    // the optimiser state is requested first: its latency hides behind the partial sums
+    const bool step_here = live && q == 0 && !(a.max_norm > 0.f);
+    float m_old = 0.f, v_old = 0.f, th_old = 0.f;
+    if (step_here) {
+        const int64_t k = T.offset + i;
+        m_old = a.m[k]; v_old = a.v[k]; th_old = a.theta[k];
+    }
     if (live) {
         const float* __restrict__ p = T.partial + i;
         const size_t st = (size_t)T.stride;
         int s = q;
+        for (; s + 7 * Q < T.nparts; s += 8 * Q) {      // eight loads in flight
+            const float x0 = p[(size_t)s * st], x1 = p[(size_t)(s + Q) * st];
+            const float x2 = p[(size_t)(s + 2 * Q) * st], x3 = p[(size_t)(s + 3 * Q) * st];
+            const float x4 = p[(size_t)(s + 4 * Q) * st], x5 = p[(size_t)(s + 5 * Q) * st];
+            const float x6 = p[(size_t)(s + 6 * Q) * st], x7 = p[(size_t)(s + 7 * Q) * st];
+            g += ((x0 + x1) + (x2 + x3)) + ((x4 + x5) + (x6 + x7));
+        }
         for (; s + 3 * Q < T.nparts; s += 4 * Q) {
             const float x0 = p[(size_t)s * st], x1 = p[(size_t)(s + Q) * st];
             const float x2 = p[(size_t)(s + 2 * Q) * st], x3 = p[(size_t)(s + 3 * Q) * st];
@@ -551,13 +565,13 @@ __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
         if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = sq;
         __syncthreads();
         if (threadIdx.x == 0) a.sq_partial[b] = (sm[0] + sm[1]) + (sm[2] + sm[3]);
-    } else if (live && q == 0) {
+    } else if (step_here) {
         const int64_t k = T.offset + i;
-        const float m = a.beta1 * a.m[k] + (1.f - a.beta1) * g;
-        const float v = a.beta2 * a.v[k] + (1.f - a.beta2) * g * g;
+        const float m = a.beta1 * m_old + (1.f - a.beta1) * g;
+        const float v = a.beta2 * v_old + (1.f - a.beta2) * g * g;
         const float m_hat = m * a.inv_bc1;
         const float v_hat = v * a.inv_bc2;
-        a.theta[k] = a.theta[k] - a.lr * m_hat / (sqrtf(v_hat) + a.eps);
+        a.theta[k] = th_old - a.lr * m_hat / (sqrtf(v_hat) + a.eps);
         a.m[k] = m;
         a.v[k] = v;
         if (a.g != nullptr) a.g[k] = g;
