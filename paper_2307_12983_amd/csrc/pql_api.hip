@@ -56,6 +56,7 @@ const char* kernel_name(int kid) {
         case KID_SAC_GRAD: return "sac_grad_kernel";
         case KID_SAC_ALPHA: return "sac_alpha_kernel";
         case KID_MFMA_PROBE: return "mfma_probe_kernel";
+        case KID_LAYER_ROWTILE: return "layer_rowtile_kernel";
         default: return "?";
     }
 }
@@ -338,10 +339,22 @@ hipError_t run(int mode, int tile, std::vector<GemmProb>& ps, const GemmNoise* n
         if (nz) g.noise = *nz;
         g.nprob = (int)((ps.size() - i < (size_t)GEMM_MAX_PROB) ? ps.size() - i : GEMM_MAX_PROB);
         for (int k = 0; k < g.nprob; ++k) g.p[k] = ps[i + k];
-        const hipError_t e = gemm_launch(mode, tile, g, st);
+        const hipError_t e = (mode == GEMM_NN && nz == nullptr && layer_rowtile_ok(g)) ? layer_rowtile_launch(g, st)
+                                                                                      : gemm_launch(mode, tile, g, st);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// Whether run(GEMM_NN, ...) sends this list through the row-tile layer kernel (then column-sum
+// partials come one row per 32 batch rows).
+bool takes_row_tiles(const std::vector<GemmProb>& ps) {
+    if (ps.empty() || ps.size() > (size_t)GEMM_MAX_PROB) return false;
+    GemmGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.nprob = (int)ps.size();
+    for (int k = 0; k < g.nprob; ++k) g.p[k] = ps[k];
+    return layer_rowtile_ok(g);
 }
 
 hipError_t run_auto(int mode, std::vector<GemmProb>& ps, hipStream_t st) {
@@ -860,20 +873,44 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
         }
 
         // 5. backward data path: delta_{l-1} = (delta_l W_l^T) * ELU'(z_{l-1}), bias grads as column sums
+        // Wide layers run on row tiles with W^T as a row-major B operand (transposed once per call);
+        // the others take the LDS-tiled kernel on W itself.
+        bool transposed = false;
         for (int l = L; l >= 2; --l) {
-            std::vector<GemmProb> ps;
+            std::vector<GemmProb> ps, pt;
             const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
             for (int i = 0; i < 2; ++i) {
                 GemmProb p = prob(B, Hp, ws + w.dQ[i][l - 1], Hp, EPI_MUL_DELU);
-                add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
                 p.aux = ws + w.hQ[i][l - 1]; p.ldaux = Hp;
                 p.colsum = ws + w.colQ[i][l - 1];
-                ps.push_back(p);
+                GemmProb q = p;
+                add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
+                add_seg(q, ws + w.dQ[i][l], Hl, ws + w.wT[i][l - 1], Hp, Hl);
+                ps.push_back(p); pt.push_back(q);
             }
-            const int tile = choose_tile(GEMM_NT, ps);
-            if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+            int parts;
+            if (takes_row_tiles(pt)) {
+                if (!transposed) {
+                    TransposeArgs tr;
+                    tr.n = 0;
+                    for (int i = 0; i < 2; ++i)
+                        for (int k = 1; k < L; ++k) {
+                            TransposeArgs::Mat& mt = tr.m[tr.n++];
+                            mt.src = critic_params + i * Pc + c->c_w[k]; mt.dst = ws + w.wT[i][k];
+                            mt.rows = c->cfg.hidden[k - 1]; mt.cols = c->cfg.hidden[k];
+                        }
+                    if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
+                    transposed = true;
+                }
+                if ((e = run(GEMM_NN, TILE_64x64, pt, nullptr, st)) != hipSuccess) return E.hip(e, who);
+                parts = (B + FUSED_BM - 1) / FUSED_BM;
+            } else {
+                const int tile = choose_tile(GEMM_NT, ps);
+                if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+                parts = colsum_rows(tile, B);
+            }
             for (int i = 0; i < 2; ++i)
-                red(adm, i * Pc + c->c_b[l - 2], ws + w.colQ[i][l - 1], Hp, colsum_rows(tile, B), Hp);
+                red(adm, i * Pc + c->c_b[l - 2], ws + w.colQ[i][l - 1], Hp, parts, Hp);
         }
     }
     // 6. weight gradients X^T delta (split over the batch)
@@ -1061,17 +1098,37 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
             if ((e = policy_head_launch(h, st)) != hipSuccess) return E.hip(e, who);
             loss_parts = h.nwg;
         }
-        // 4. critic backward data path down to layer 1
+        // 4. critic backward data path down to layer 1 (wide layers on row tiles with W^T as a
+        //    row-major B operand, transposed once per call; the others on the LDS-tiled kernel)
+        bool transposed_q = false;
         for (int l = L; l >= 2; --l) {
-            std::vector<GemmProb> ps;
+            std::vector<GemmProb> ps, pt;
             const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
             for (int i = 0; i < 2; ++i) {
                 GemmProb p = prob(B, Hp, ws + w.dQ[i][l - 1], Hp, EPI_MUL_DELU);
-                add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
                 p.aux = ws + w.hQ[i][l - 1]; p.ldaux = Hp;
-                ps.push_back(p);
+                GemmProb q = p;
+                add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
+                add_seg(q, ws + w.dQ[i][l], Hl, ws + w.wT[i][l - 1], Hp, Hl);
+                ps.push_back(p); pt.push_back(q);
             }
-            if ((e = run_auto(GEMM_NT, ps, st)) != hipSuccess) return E.hip(e, who);
+            if (takes_row_tiles(pt)) {
+                if (!transposed_q) {
+                    TransposeArgs tr;
+                    tr.n = 0;
+                    for (int i = 0; i < 2; ++i)
+                        for (int k = 1; k < L; ++k) {
+                            TransposeArgs::Mat& mt = tr.m[tr.n++];
+                            mt.src = critic_params + i * Pc + c->c_w[k]; mt.dst = ws + w.wT[i][k];
+                            mt.rows = c->cfg.hidden[k - 1]; mt.cols = c->cfg.hidden[k];
+                        }
+                    if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
+                    transposed_q = true;
+                }
+                if ((e = run(GEMM_NN, TILE_64x64, pt, nullptr, st)) != hipSuccess) return E.hip(e, who);
+            } else {
+                if ((e = run_auto(GEMM_NT, ps, st)) != hipSuccess) return E.hip(e, who);
+            }
         }
         // 5. gradient w.r.t. the action input of both critics, through tanh'
         {
@@ -1094,17 +1151,38 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
             red(adm, c->a_b[L], ws + w.p_sc, aw, (B + SAC_ROWS - 1) / SAC_ROWS, aw);
         }
         // 6. policy backward data path
+        bool transposed_a = false;
         for (int l = L + 1; l >= 2; --l) {
-            std::vector<GemmProb> ps;
+            std::vector<GemmProb> ps, pt;
             const int Hl = (l == L + 1) ? aw : c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
             GemmProb p = prob(B, Hp, ws + w.dA[l - 1], Hp, EPI_MUL_DELU);
-            add_seg(p, (l == L + 1) ? d_top : ws + w.dA[l], Hl, actor_params + c->a_w[l - 1], Hl, Hl);
             p.aux = ws + w.hA[l - 1]; p.ldaux = Hp;
             p.colsum = ws + w.colA[l - 1];
-            ps.push_back(p);
-            const int tile = choose_tile(GEMM_NT, ps);
-            if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
-            red(adm, c->a_b[l - 2], ws + w.colA[l - 1], Hp, colsum_rows(tile, B), Hp);
+            GemmProb q = p;
+            add_seg(p, (l == L + 1) ? d_top : ws + w.dA[l], Hl, actor_params + c->a_w[l - 1], Hl, Hl);
+            add_seg(q, (l == L + 1) ? d_top : ws + w.dA[l], Hl, ws + w.waT[l - 1], Hp, Hl);
+            ps.push_back(p); pt.push_back(q);
+            int parts;
+            if (takes_row_tiles(pt)) {
+                if (!transposed_a) {
+                    TransposeArgs tr;
+                    tr.n = 0;
+                    for (int k = 1; k <= L; ++k) {
+                        TransposeArgs::Mat& mt = tr.m[tr.n++];
+                        mt.src = actor_params + c->a_w[k]; mt.dst = ws + w.waT[k];
+                        mt.rows = c->cfg.hidden[k - 1]; mt.cols = k < L ? c->cfg.hidden[k] : aw;
+                    }
+                    if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
+                    transposed_a = true;
+                }
+                if ((e = run(GEMM_NN, TILE_64x64, pt, nullptr, st)) != hipSuccess) return E.hip(e, who);
+                parts = (B + FUSED_BM - 1) / FUSED_BM;
+            } else {
+                const int tile = choose_tile(GEMM_NT, ps);
+                if ((e = run(GEMM_NT, tile, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+                parts = colsum_rows(tile, B);
+            }
+            red(adm, c->a_b[l - 2], ws + w.colA[l - 1], Hp, parts, Hp);
         }
     }
     // 7. policy weight gradients

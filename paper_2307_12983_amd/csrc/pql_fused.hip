@@ -1319,6 +1319,144 @@ hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream) {
 }
 
 // =============================================================================================
+// One wide layer on row tiles, for networks whose layers are too wide for the chained kernels
+// above: Y = act(X W + b), or delta W^T * ELU'(.) with W^T materialised by transpose_kernel, for a list
+// of problems (the twin critics, the target critics and the
+// policy share launches).  A workgroup stages 32 input rows in LDS once and its eight wavefronts
+// sweep the output columns, 32 each per pass, with the weights streamed from L2 as in the chained
+// kernels; nothing but the input rows and the output tile touches memory.  Two workgroups fit a
+// compute unit while the input tile stays below 80 KB, so one's loads and epilogue overlap the
+// other's matrix work.
+// =============================================================================================
+__global__ __launch_bounds__(FT, 4) void layer_rowtile_kernel(const GemmGroup g) {
+    Lanes T;
+    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = __builtin_amdgcn_readfirstlane(T.tid >> 6); T.l32 = T.lane & 31; T.half = T.lane >> 5;
+    const int b = blockIdx.x;
+    int pi = 0;
+    for (int i = 1; i < g.nprob; ++i)
+        if (b >= g.p[i].tile_begin) pi = i;
+    const GemmProb& P = g.p[pi];
+    const int r0 = (b - P.tile_begin) * BMF, M = P.M, N = P.N;
+    const int K0 = P.seg[0].K, K1 = P.nseg > 1 ? P.seg[1].K : 0;
+    const int S0 = ((K0 + 7) & ~7) + 4, S1 = K1 > 0 ? ((K1 + 7) & ~7) + 4 : 0;
+    const int XA = 0, XB = BMF * S0;
+    load_rows(T, XA, S0, P.seg[0].A, K0, r0, M);
+    if (K1 > 0) load_rows(T, XB, S1, P.seg[1].A, K1, r0, M);
+    __syncthreads();
+    const int epi = P.epi;
+    const int ldc = P.ldc, ldaux = P.ldaux;
+    const int lrow = 4 * T.half;
+    const bool full = r0 + BMF <= M;
+    for (int n0 = T.wave * 32; n0 < N; n0 += 32 * FW) {
+        const int n = n0 + T.l32;
+        const bool n_ok = n < N;
+        const int ncol = n_ok ? n : N - 1;
+        const float bv = epi == EPI_MUL_DELU ? 0.f : P.bias[ncol];
+        floatx16 acc[1];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[0][r] = 0.f;
+        const int in0[1] = {XA};
+        const float* const W0[1] = {P.seg[0].B};
+        if (K1 > 0) {
+            float bs[1][16], bf[1][16];
+            const int in1[1] = {XB};
+            const float* const W1[1] = {P.seg[1].B};
+            prefetch_first_chunk<1>(bs, W1, K1, P.seg[1].ldb, ncol, T, 0, 1);
+            prefetch_first_chunk<1>(bf, W0, K0, P.seg[0].ldb, ncol, T, 0, 1);
+            mac_segment<1>(acc, in1, S1, K1, W1, P.seg[1].ldb, ncol, T, 0, 1, true, bs);
+            mac_segment<1>(acc, in0, S0, K0, W0, P.seg[0].ldb, ncol, T, 0, 1, true, bf);
+        } else {
+            mac_segment<1>(acc, in0, S0, K0, W0, P.seg[0].ldb, ncol, T, 0, 1);
+        }
+        float* __restrict__ gbase = P.C + (size_t)(r0 + lrow) * (size_t)ldc + n;
+        if (epi == EPI_MUL_DELU) {
+            // backward data path: delta = acc * ELU'(z) with the activation read from memory; the
+            // tile's column sums are one partial row of the bias gradient
+            const float* __restrict__ abase = P.aux + (size_t)(r0 + lrow) * (size_t)ldaux + ncol;
+            float h[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = 8 * (r >> 2) + (r & 3);
+                h[r] = (full || r0 + lrow + dr < M) ? abase[(size_t)dr * (size_t)ldaux] : 0.f;
+            }
+            float cs = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = 8 * (r >> 2) + (r & 3);
+                const bool rv = full || r0 + lrow + dr < M;
+                const float x = rv ? acc[0][r] * delu_h(h[r]) : 0.f;
+                if (n_ok && rv) gbase[(size_t)dr * (size_t)ldc] = x;
+                cs += x;
+            }
+            if (P.colsum != nullptr) {
+                cs += __shfl_xor(cs, 32);
+                if (T.half == 0 && n_ok) P.colsum[(size_t)(b - P.tile_begin) * (size_t)N + n] = cs;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = 8 * (r >> 2) + (r & 3);
+                float x = acc[0][r] + bv;
+                if (epi == EPI_BIAS_ELU) x = elu_f(x);
+                if (n_ok && (full || r0 + lrow + dr < M)) gbase[(size_t)dr * (size_t)ldc] = x;
+            }
+        }
+    }
+}
+
+// Whether a launch of X W products (B operand [K][N] row-major) can take the row-tile layer kernel:
+// bias (+ ELU) epilogues, or the backward data path's ELU' epilogue with column sums (one partial
+// row per 32 batch rows); dense input rows (row stride = width), enough columns to occupy the eight wavefronts, enough rows to
+// fill the chip, input tiles that fit LDS, and weights within reach of a 32-bit buffer offset.
+bool layer_rowtile_ok(const GemmGroup& g) {
+    long wgs = 0;
+    for (int i = 0; i < g.nprob; ++i) {
+        const GemmProb& p = g.p[i];
+        if (p.epi != EPI_BIAS_ELU && p.epi != EPI_BIAS && p.epi != EPI_MUL_DELU) return false;
+        if (p.epi == EPI_MUL_DELU ? (p.aux == nullptr || p.ldaux < p.N) : (p.bias == nullptr || p.colsum != nullptr)) return false;
+        if (p.nseg < 1 || p.nseg > 2 || p.ldc < p.N) return false;
+        if (p.N < 128 || p.M < 1) return false;
+        size_t floats = 0;
+        for (int s = 0; s < p.nseg; ++s) {
+            const GemmSeg& q = p.seg[s];
+            if (q.K < 1 || q.lda != q.K || q.ldb < p.N) return false;
+            if ((size_t)q.K * (size_t)q.ldb * sizeof(float) >= ((size_t)1 << 31)) return false;
+            floats += (size_t)BMF * (size_t)(((q.K + 7) & ~7) + 4);
+        }
+        if (floats * sizeof(float) > 150 * 1024) return false;
+        wgs += (p.M + BMF - 1) / BMF;
+    }
+    return wgs >= 256;
+}
+
+hipError_t layer_rowtile_launch(GemmGroup& g, hipStream_t stream) {
+    int total = 0;
+    size_t lds = 0;
+    double flops = 0.0;
+    for (int i = 0; i < g.nprob; ++i) {
+        GemmProb& p = g.p[i];
+        p.tile_begin = total;
+        p.tiles_m = (p.M + BMF - 1) / BMF; p.tiles_n = 1; p.splits = 1; p.k_chunk = 0;
+        total += p.tiles_m;
+        size_t floats = 0;
+        for (int s = 0; s < p.nseg; ++s) {
+            floats += (size_t)BMF * (size_t)(((p.seg[s].K + 7) & ~7) + 4);
+            flops += 2.0 * p.M * (double)p.N * p.seg[s].K;
+        }
+        if (floats * sizeof(float) > lds) lds = floats * sizeof(float);
+    }
+    g.total_tiles = total;
+    if (total == 0) return hipSuccess;
+    static size_t configured = 0;
+    const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(layer_rowtile_kernel), lds, configured);
+    if (e != hipSuccess) return e;
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, layer_rowtile_kernel, dim3(total), dim3(FT), lds, stream, g);
+    prof_commit(ps, KID_LAYER_ROWTILE, ps.on ? flops : 0.0, 0.0);
+    return hipGetLastError();
+}
+
+// =============================================================================================
 // Batched 2-D transposes: dst[c][r] = src[r][c] for a list of small matrices.
 // =============================================================================================
 __global__ __launch_bounds__(256) void transpose_kernel(const TransposeArgs a) {

@@ -59,6 +59,11 @@ def small_cases():
                                             batch=300, hidden=(192, 128), index=16),
         "fused_k64": Wk["tiny"].replace(name="fused_k64", obs_dim=64, act_dim=32, num_envs=36, capacity=36 * 9, batch=200,
                                         hidden=(64, 64), index=17),
+        # layers too wide for the chained kernels but with enough rows for the row-tile layer kernel (forward
+        # and backward data products of the layered path): a ragged last row tile (4100 = 128 * 32 + 4), output
+        # widths that are no multiple of 32 or 256 (300, 136), contraction lengths with and without a tail
+        "layer_tiles": Wk["tiny"].replace(name="layer_tiles", obs_dim=41, act_dim=13, num_envs=40, capacity=40 * 8,
+                                          batch=4100, hidden=(300, 136, 160), index=19),
     }
 
 
@@ -702,6 +707,7 @@ def test_which_cases_take_the_row_tile_kernels(torch_cuda, case):
         assert fused <= names and not any(n.startswith("gemm_grouped_n") for n in names)
     else:
         assert not (fused & names)
+    assert ("layer_rowtile_kernel" in names) == (case == "layer_tiles")
 
 
 # ---------------------------------------------------------------------------------------------
