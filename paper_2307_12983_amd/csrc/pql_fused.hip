@@ -1336,18 +1336,27 @@ __global__ __launch_bounds__(FT, 4) void layer_rowtile_kernel(const GemmGroup g)
     for (int i = 1; i < g.nprob; ++i)
         if (b >= g.p[i].tile_begin) pi = i;
     const GemmProb& P = g.p[pi];
-    const int r0 = (b - P.tile_begin) * BMF, M = P.M, N = P.N;
+    // tiles_n holds the row tiles per workgroup: 2 for layers of at most 128 columns (four wavefronts
+    // cover those, the other four take a second row tile), else 1
+    const int RT = P.tiles_n, CW = FW / RT;
+    const int rt = T.wave / CW, cw = T.wave - rt * CW;
+    const int M = P.M, N = P.N;
     const int K0 = P.seg[0].K, K1 = P.nseg > 1 ? P.seg[1].K : 0;
     const int S0 = ((K0 + 7) & ~7) + 4, S1 = K1 > 0 ? ((K1 + 7) & ~7) + 4 : 0;
-    const int XA = 0, XB = BMF * S0;
-    load_rows(T, XA, S0, P.seg[0].A, K0, r0, M);
-    if (K1 > 0) load_rows(T, XB, S1, P.seg[1].A, K1, r0, M);
+    const int rw = (b - P.tile_begin) * BMF * RT;
+    for (int t = 0; t < RT; ++t) {
+        load_rows(T, t * BMF * S0, S0, P.seg[0].A, K0, rw + t * BMF, M);
+        if (K1 > 0) load_rows(T, RT * BMF * S0 + t * BMF * S1, S1, P.seg[1].A, K1, rw + t * BMF, M);
+    }
     __syncthreads();
+    const int r0 = rw + rt * BMF;
+    if (r0 >= M) return;                 // (no barrier follows)
+    const int XA = rt * BMF * S0, XB = RT * BMF * S0 + rt * BMF * S1;
     const int epi = P.epi;
     const int ldc = P.ldc, ldaux = P.ldaux;
     const int lrow = 4 * T.half;
     const bool full = r0 + BMF <= M;
-    for (int n0 = T.wave * 32; n0 < N; n0 += 32 * FW) {
+    for (int n0 = cw * 32; n0 < N; n0 += 32 * CW) {
         const int n = n0 + T.l32;
         const bool n_ok = n < N;
         const int ncol = n_ok ? n : N - 1;
@@ -1390,7 +1399,7 @@ __global__ __launch_bounds__(FT, 4) void layer_rowtile_kernel(const GemmGroup g)
             }
             if (P.colsum != nullptr) {
                 cs += __shfl_xor(cs, 32);
-                if (T.half == 0 && n_ok) P.colsum[(size_t)(b - P.tile_begin) * (size_t)N + n] = cs;
+                if (T.half == 0 && n_ok) P.colsum[(size_t)((b - P.tile_begin) * RT + rt) * (size_t)N + n] = cs;
             }
         } else {
 #pragma unroll
@@ -1429,21 +1438,36 @@ bool layer_rowtile_ok(const GemmGroup& g) {
     return wgs >= 256;
 }
 
+static size_t layer_tile_floats(const GemmProb& p) {
+    size_t floats = 0;
+    for (int s = 0; s < p.nseg; ++s) floats += (size_t)BMF * (size_t)(((p.seg[s].K + 7) & ~7) + 4);
+    return floats;
+}
+
 hipError_t layer_rowtile_launch(GemmGroup& g, hipStream_t stream) {
+    // Narrow layers (at most 128 columns) take two row tiles per workgroup, if the launch still has
+    // a workgroup for every compute unit and the two input tiles fit LDS.
+    long wgs2 = 0;
+    bool fits2 = true;
+    for (int i = 0; i < g.nprob; ++i) {
+        const GemmProb& p = g.p[i];
+        const int rt = p.N <= 128 ? 2 : 1;
+        wgs2 += (p.M + BMF * rt - 1) / (BMF * rt);
+        if (rt == 2 && 2 * layer_tile_floats(p) * sizeof(float) > 150 * 1024) fits2 = false;
+    }
+    const bool pair_rows = fits2 && wgs2 >= 256;
     int total = 0;
     size_t lds = 0;
     double flops = 0.0;
     for (int i = 0; i < g.nprob; ++i) {
         GemmProb& p = g.p[i];
+        const int rt = (pair_rows && p.N <= 128) ? 2 : 1;
         p.tile_begin = total;
-        p.tiles_m = (p.M + BMF - 1) / BMF; p.tiles_n = 1; p.splits = 1; p.k_chunk = 0;
+        p.tiles_m = (p.M + BMF * rt - 1) / (BMF * rt); p.tiles_n = rt; p.splits = 1; p.k_chunk = 0;
         total += p.tiles_m;
-        size_t floats = 0;
-        for (int s = 0; s < p.nseg; ++s) {
-            floats += (size_t)BMF * (size_t)(((p.seg[s].K + 7) & ~7) + 4);
-            flops += 2.0 * p.M * (double)p.N * p.seg[s].K;
-        }
-        if (floats * sizeof(float) > lds) lds = floats * sizeof(float);
+        for (int s = 0; s < p.nseg; ++s) flops += 2.0 * p.M * (double)p.N * p.seg[s].K;
+        const size_t bytes = rt * layer_tile_floats(p) * sizeof(float);
+        if (bytes > lds) lds = bytes;
     }
     g.total_tiles = total;
     if (total == 0) return hipSuccess;
