@@ -5,9 +5,10 @@
 // activation derivative) and the weight gradients (X^T delta, reduced over the batch by
 // split-K).  One launch handles a list of independent problems, so the twin critics, the target
 // critics and the policy share launches.  Forward and backward-data products go through the
-// LDS-tiled kernel described next; the weight gradients, whose two operands are both contiguous
-// along the MFMA's M / N dimension, go through gemm_tn_stream_kernel further down, which takes its
-// fragments straight from memory.
+// LDS-tiled kernel described next when they are narrow or small (launches of wide layers with
+// enough rows take the row-tile layer kernel of pql_fused.hip instead); the weight gradients,
+// whose two operands are both contiguous along the MFMA's M / N dimension, go through
+// gemm_tn_stream_kernel further down, which takes its fragments straight from memory.
 //
 // Tiling: a workgroup is 4 wavefronts of 64 lanes.  Global tiles are copied to LDS in their
 // natural orientation (the contiguous dimension stays contiguous, 16-byte loads when the
