@@ -717,10 +717,15 @@ def test_which_cases_take_the_row_tile_kernels(torch_cuda, case):
 # network); here widths, depths, input sizes, batch sizes, n and the variant are drawn from a seeded
 # generator.  Only what is robust for any shape is compared: the sampled batch, the losses and every
 # gradient tensor of one critic and one policy update (max-norm, 1e-4).
-def random_shape(rnd, it):
-    row_tile = rnd.random() < 0.6                      # all widths multiples of 32 and at most 256: the row-tile kernels
+def random_shape(rnd, it, wide=False):
+    row_tile = rnd.random() < 0.6 and not wide         # all widths multiples of 32 and at most 256: the row-tile kernels
     depth = rnd.choice([1, 2, 2, 3, 4])
-    if row_tile:
+    if wide:                                           # a layer too wide for them and a batch large enough for the row-tile layer kernel
+        hidden = tuple(rnd.choice([128, 136, 160, 200, 260, 288, 300, 320, 384, 512, 516, 640]) for _ in range(depth))
+        if max(hidden) <= 256 and all(h % 32 == 0 for h in hidden):
+            hidden = hidden[:-1] + (300,)
+        act = rnd.randint(1, 40)
+    elif row_tile:
         hidden = tuple(32 * rnd.randint(1, 8) for _ in range(depth))
         act = rnd.randint(1, 32)
     else:
@@ -732,7 +737,8 @@ def random_shape(rnd, it):
     nstep = rnd.choice([1, 2, 3, 3, 5])
     envs = rnd.randint(5, 70)
     kw = dict(name="rand%d" % it, obs_dim=rnd.randint(3, 230), act_dim=act, num_envs=envs,
-              capacity=envs * rnd.randint(nstep + 4, nstep + 10), batch=rnd.choice([31, 33, 64, 100, 257, 333, 512, 777, 1500]),
+              capacity=envs * rnd.randint(nstep + 4, nstep + 10),
+              batch=rnd.choice([2753, 4096, 4100, 5510, 8192, 8195] if wide else [31, 33, 64, 100, 257, 333, 512, 777, 1500]),
               hidden=hidden, index=60 + it, nstep=nstep)
     if variant == "dist":
         kw.update(num_atoms=rnd.choice([2, 11, 51, 64]), v_min=float(np.float32(-2.0)), v_max=float(np.float32(3.0)))
@@ -743,12 +749,13 @@ def random_shape(rnd, it):
     return variant, W.WORKLOADS["tiny"].replace(**kw)
 
 
-@pytest.mark.parametrize("seed", [11, 12, 13])
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
 def test_gradients_on_random_shapes(torch_cuda, seed):
     import random
     rnd = random.Random(seed)
-    for it in range(40):
-        variant, w = random_shape(rnd, it)
+    wide = seed == 14
+    for it in range(24 if wide else 40):
+        variant, w = random_shape(rnd, it, wide)
         say(seed, it, variant, "obs", w.obs_dim, "act", w.act_dim, "envs", w.num_envs, "B", w.batch, "n", w.nstep, "hidden", w.hidden,
             "atoms", w.num_atoms)
         s, ring, nz = make_session(w), oracle_ring(w), oracle_normalizer(w)
