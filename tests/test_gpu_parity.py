@@ -336,6 +336,14 @@ def test_100_updates_reduced_batch(torch_cuda, name):
     say(name, "100 steps", res)
 
 
+def test_100_updates_row_tile_layers(torch_cuda):
+    """100 critic and 20 policy updates at a batch and widths that take the row-tile layer kernel
+    (forward and backward data products of the layered path)."""
+    w = SMALL["layer_tiles"]
+    res = many_steps(torch_cuda, w, w.rows, 100, actor_every=5)
+    say("layer_tiles 100 steps", res)
+
+
 # ---------------------------------------------------------------------------------------------
 # Table B.1 defaults left off in the five workloads: observation standardisation and gradient clipping
 def paper_defaults(w, bound=0.5):
