@@ -1320,13 +1320,13 @@ hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream) {
 
 // =============================================================================================
 // One wide layer on row tiles, for networks whose layers are too wide for the chained kernels
-// above: Y = act(X W + b), or delta W^T * ELU'(.) with W^T materialised by transpose_kernel, for a list
-// of problems (the twin critics, the target critics and the
-// policy share launches).  A workgroup stages 32 input rows in LDS once and its eight wavefronts
-// sweep the output columns, 32 each per pass, with the weights streamed from L2 as in the chained
-// kernels; nothing but the input rows and the output tile touches memory.  Two workgroups fit a
-// compute unit while the input tile stays below 80 KB, so one's loads and epilogue overlap the
-// other's matrix work.
+// above: Y = act(X W + b), or delta W^T * ELU'(.) with W^T materialised by transpose_kernel, for a
+// list of problems (the twin critics, the target critics and the policy share launches).  A
+// workgroup stages 32 input rows in LDS once and its eight wavefronts sweep the output columns, 32
+// each per pass, with the weights streamed from L2 as in the chained kernels; nothing but the input
+// rows and the output tile touches memory.  Two workgroups fit a compute unit while the input tile
+// stays below 80 KB (sixteen wavefronts: the kernel is held to 128 registers, and has none to
+// spare: requesting the first weight chunks ahead of the input rows spilled and ran 6 % slower).
 // =============================================================================================
 __global__ __launch_bounds__(FT, 4) void layer_rowtile_kernel(const GemmGroup g) {
     Lanes T;
