@@ -57,6 +57,7 @@ const char* kernel_name(int kid) {
         case KID_SAC_ALPHA: return "sac_alpha_kernel";
         case KID_MFMA_PROBE: return "mfma_probe_kernel";
         case KID_LAYER_ROWTILE: return "layer_rowtile_kernel";
+        case KID_NARROW_ROWTILE: return "narrow_rowtile_kernel";
         default: return "?";
     }
 }
@@ -339,8 +340,10 @@ hipError_t run(int mode, int tile, std::vector<GemmProb>& ps, const GemmNoise* n
         if (nz) g.noise = *nz;
         g.nprob = (int)((ps.size() - i < (size_t)GEMM_MAX_PROB) ? ps.size() - i : GEMM_MAX_PROB);
         for (int k = 0; k < g.nprob; ++k) g.p[k] = ps[i + k];
-        const hipError_t e = (mode == GEMM_NN && nz == nullptr && layer_rowtile_ok(g)) ? layer_rowtile_launch(g, st)
-                                                                                      : gemm_launch(mode, tile, g, st);
+        hipError_t e;
+        if (mode == GEMM_NN && nz == nullptr && layer_rowtile_ok(g)) e = layer_rowtile_launch(g, st);
+        else if (mode == GEMM_NN && nz == nullptr && narrow_rowtile_ok(g)) e = narrow_rowtile_launch(g, st);
+        else e = gemm_launch(mode, tile, g, st);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -355,6 +358,16 @@ bool takes_row_tiles(const std::vector<GemmProb>& ps) {
     g.nprob = (int)ps.size();
     for (int k = 0; k < g.nprob; ++k) g.p[k] = ps[k];
     return layer_rowtile_ok(g);
+}
+
+// The same for the narrow (action-wide) row-tile kernel.
+bool takes_narrow_tiles(const std::vector<GemmProb>& ps) {
+    if (ps.empty() || ps.size() > (size_t)GEMM_MAX_PROB) return false;
+    GemmGroup g;
+    std::memset(&g, 0, sizeof(g));
+    g.nprob = (int)ps.size();
+    for (int k = 0; k < g.nprob; ++k) g.p[k] = ps[k];
+    return narrow_rowtile_ok(g);
 }
 
 hipError_t run_auto(int mode, std::vector<GemmProb>& ps, hipStream_t st) {
@@ -1132,15 +1145,33 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
         }
         // 5. gradient w.r.t. the action input of both critics, through tanh'
         {
-            std::vector<GemmProb> ps;
+            std::vector<GemmProb> ps, pt;
             GemmProb p = prob(B, ad, ws + w.dPre, ad, EPI_MUL_DTANH);
-            for (int i = 0; i < 2; ++i)
-                add_seg(p, ws + w.dQ[i][1], H1, critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, H1, H1);
             p.aux = ws + w.aOut; p.ldaux = ad;
             if (!sac) p.colsum = ws + w.colA[L + 1];
-            ps.push_back(p);
-            if ((e = run(GEMM_NT, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
-            if (!sac) red(adm, c->a_b[L], ws + w.colA[L + 1], ad, colsum_rows(TILE_128x32, B), ad);
+            GemmProb q = p;
+            for (int i = 0; i < 2; ++i) {
+                add_seg(p, ws + w.dQ[i][1], H1, critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, H1, H1);
+                add_seg(q, ws + w.dQ[i][1], H1, ws + w.w1aT[i], ad, H1);
+            }
+            ps.push_back(p); pt.push_back(q);
+            int parts;
+            if (takes_narrow_tiles(pt)) {      // on row tiles, with the action rows of W_1 transposed
+                TransposeArgs tr;
+                tr.n = 0;
+                for (int i = 0; i < 2; ++i) {
+                    TransposeArgs::Mat& mt = tr.m[tr.n++];
+                    mt.src = critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1; mt.dst = ws + w.w1aT[i];
+                    mt.rows = ad; mt.cols = H1;
+                }
+                if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
+                if ((e = run(GEMM_NN, TILE_128x32, pt, nullptr, st)) != hipSuccess) return E.hip(e, who);
+                parts = (B + FUSED_BM - 1) / FUSED_BM;
+            } else {
+                if ((e = run(GEMM_NT, TILE_128x32, ps, nullptr, st)) != hipSuccess) return E.hip(e, who);
+                parts = colsum_rows(TILE_128x32, B);
+            }
+            if (!sac) red(adm, c->a_b[L], ws + w.colA[L + 1], ad, parts, ad);
         }
         if (sac) {      // add the log-density terms and split into the gradients of mu and raw log sigma
             SacGradArgs ga;

@@ -1481,6 +1481,121 @@ hipError_t layer_rowtile_launch(GemmGroup& g, hipStream_t stream) {
 }
 
 // =============================================================================================
+// Action-wide products of the layered path (at most 32 output columns): the policy's output layer
+// and the gradient with respect to the action.  One wavefront's 32 columns already cover the
+// output, so the eight wavefronts of a row tile split the contraction instead (every eighth chunk
+// of 32 k-values each, as in the chained kernels' narrow layers) and their partial tiles meet in
+// LDS.  Segments (the twin critics' first-layer deltas) pass through the same input tile one after
+// the other.  B operands are row-major [K][N].
+// =============================================================================================
+__global__ __launch_bounds__(FT, 2) void narrow_rowtile_kernel(const GemmGroup g) {
+    Lanes T;
+    T.tid = threadIdx.x; T.lane = T.tid & 63; T.wave = __builtin_amdgcn_readfirstlane(T.tid >> 6); T.l32 = T.lane & 31; T.half = T.lane >> 5;
+    const int b = blockIdx.x;
+    int pi = 0;
+    for (int i = 1; i < g.nprob; ++i)
+        if (b >= g.p[i].tile_begin) pi = i;
+    const GemmProb& P = g.p[pi];
+    const int part = b - P.tile_begin, r0 = part * BMF, M = P.M, N = P.N;
+    int kmax = P.seg[0].K;
+    if (P.nseg > 1 && P.seg[1].K > kmax) kmax = P.seg[1].K;
+    const int S = ((kmax + 7) & ~7) + 4;
+    // input tile; the partial tiles and the 32 x 33 output tile take its place once the products are done
+    const int XA = 0, scratch = 0, red = SCRATCH_F;
+    const int ncol = T.l32 < N ? T.l32 : N - 1;
+    floatx16 acc[1];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][r] = 0.f;
+    for (int sg = 0; sg < P.nseg; ++sg) {
+        if (sg > 0) __syncthreads();                                     // the tile is reused
+        load_rows(T, XA, S, P.seg[sg].A, P.seg[sg].K, r0, M);
+        __syncthreads();
+        const int ins[1] = {XA};
+        const float* const ws[1] = {P.seg[sg].B};
+        mac_segment<1>(acc, ins, S, P.seg[sg].K, ws, P.seg[sg].ldb, ncol, T, T.wave, FW);
+    }
+    __syncthreads();                                                     // every wavefront is done with the input tile
+#pragma unroll
+    for (int r = 0; r < 16; ++r) smem[scratch + T.wave * 1024 + r * 64 + T.lane] = acc[0][r];
+    __syncthreads();
+    const int epi = P.epi;
+    for (int e = T.tid; e < 1024; e += FT) {
+        int row, col;
+        float x = small_sum(scratch, e, row, col);
+        const bool ok = col < N && r0 + row < M;
+        if (ok) {
+            if (epi == EPI_MUL_DTANH) {
+                const float t = P.aux[(size_t)(r0 + row) * (size_t)P.ldaux + col];
+                x *= 1.f - t * t;
+            } else {
+                x = tanhf(x + P.bias[col]);
+            }
+            P.C[(size_t)(r0 + row) * (size_t)P.ldc + col] = x;
+        } else {
+            x = 0.f;
+        }
+        smem[red + row * 33 + col] = x;
+    }
+    if (P.colsum != nullptr) {
+        __syncthreads();
+        if (T.tid < N) {
+            float cs = 0.f;
+            for (int row = 0; row < BMF; ++row) cs += smem[red + row * 33 + T.tid];
+            P.colsum[(size_t)part * (size_t)N + T.tid] = cs;
+        }
+    }
+}
+
+static size_t narrow_lds_bytes(const GemmProb& p) {
+    int kmax = p.seg[0].K;
+    if (p.nseg > 1 && p.seg[1].K > kmax) kmax = p.seg[1].K;
+    const size_t tile = (size_t)BMF * (size_t)(((kmax + 7) & ~7) + 4), tail = (size_t)SCRATCH_F + BMF * 33;
+    return sizeof(float) * (tile > tail ? tile : tail);
+}
+
+// Whether a launch of X W products (B operand [K][N] row-major) can take the narrow row-tile kernel.
+bool narrow_rowtile_ok(const GemmGroup& g) {
+    long wgs = 0;
+    for (int i = 0; i < g.nprob; ++i) {
+        const GemmProb& p = g.p[i];
+        if (p.epi != EPI_BIAS_TANH && p.epi != EPI_MUL_DTANH) return false;
+        if (p.epi == EPI_MUL_DTANH ? (p.aux == nullptr || p.ldaux < p.N) : (p.bias == nullptr || p.colsum != nullptr)) return false;
+        if (p.N < 1 || p.N > 32 || p.M < 1 || p.nseg < 1 || p.nseg > 2 || p.ldc < p.N) return false;
+        for (int s = 0; s < p.nseg; ++s) {
+            const GemmSeg& q = p.seg[s];
+            if (q.K < 1 || q.lda != q.K || q.ldb < p.N) return false;
+            if ((size_t)q.K * (size_t)q.ldb * sizeof(float) >= ((size_t)1 << 31)) return false;
+        }
+        if (narrow_lds_bytes(p) > 150 * 1024) return false;
+        wgs += (p.M + BMF - 1) / BMF;
+    }
+    return wgs >= 256;
+}
+
+hipError_t narrow_rowtile_launch(GemmGroup& g, hipStream_t stream) {
+    int total = 0;
+    size_t lds = 0;
+    double flops = 0.0;
+    for (int i = 0; i < g.nprob; ++i) {
+        GemmProb& p = g.p[i];
+        p.tile_begin = total;
+        p.tiles_m = (p.M + BMF - 1) / BMF; p.tiles_n = 1; p.splits = 1; p.k_chunk = 0;
+        total += p.tiles_m;
+        for (int s = 0; s < p.nseg; ++s) flops += 2.0 * p.M * (double)p.N * p.seg[s].K;
+        if (narrow_lds_bytes(p) > lds) lds = narrow_lds_bytes(p);
+    }
+    g.total_tiles = total;
+    if (total == 0) return hipSuccess;
+    static size_t configured = 0;
+    const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(narrow_rowtile_kernel), lds, configured);
+    if (e != hipSuccess) return e;
+    const ProfSlot ps = prof_slot();
+    PQL_LAUNCH(ps, narrow_rowtile_kernel, dim3(total), dim3(FT), lds, stream, g);
+    prof_commit(ps, KID_NARROW_ROWTILE, ps.on ? flops : 0.0, 0.0);
+    return hipGetLastError();
+}
+
+// =============================================================================================
 // Batched 2-D transposes: dst[c][r] = src[r][c] for a list of small matrices.
 // =============================================================================================
 __global__ __launch_bounds__(256) void transpose_kernel(const TransposeArgs a) {

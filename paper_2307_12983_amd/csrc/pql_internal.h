@@ -18,7 +18,7 @@ enum KernelId : int {
     KID_ADAM = 19, KID_SOFT_UPDATE = 20, KID_COPY = 21, KID_FUSED_CRITIC = 22, KID_FUSED_POLICY = 23,
     KID_FUSED_ACT = 24, KID_TRANSPOSE = 25, KID_ADAM_CLIP = 26, KID_OBS_STATS = 27, KID_OBS_MERGE = 28,
     KID_NORMALIZE = 29, KID_DIST_CRITIC = 30, KID_DIST_POLICY = 31, KID_SAC_SAMPLE = 32, KID_SAC_GRAD = 33,
-    KID_SAC_ALPHA = 34, KID_MFMA_PROBE = 35, KID_LAYER_ROWTILE = 36, KID_COUNT = 37
+    KID_SAC_ALPHA = 34, KID_MFMA_PROBE = 35, KID_LAYER_ROWTILE = 36, KID_NARROW_ROWTILE = 37, KID_COUNT = 38
 };
 const char* kernel_name(int kid);
 bool prof_active();
@@ -345,5 +345,8 @@ hipError_t transpose_launch(TransposeArgs& a, hipStream_t stream);
 // Forward layers too wide for the chained kernels, on row tiles (pql_fused.hip).
 bool layer_rowtile_ok(const GemmGroup& g);
 hipError_t layer_rowtile_launch(GemmGroup& g, hipStream_t stream);
+// Action-wide products (at most 32 columns) of the layered path on row tiles.
+bool narrow_rowtile_ok(const GemmGroup& g);
+hipError_t narrow_rowtile_launch(GemmGroup& g, hipStream_t stream);
 
 }  // namespace pql

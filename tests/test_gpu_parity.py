@@ -60,11 +60,12 @@ def small_cases():
         "fused_k64": Wk["tiny"].replace(name="fused_k64", obs_dim=64, act_dim=32, num_envs=36, capacity=36 * 9, batch=200,
                                         hidden=(64, 64), index=17),
         # layers too wide for the chained kernels but with enough rows for the row-tile layer kernel (forward
-        # and backward data products of the layered path): a ragged last row tile (5510 = 172 * 32 + 6, an odd
-        # number of row tiles: the 128-column layer pairs row tiles per workgroup and the last pair is half empty),
-        # output widths that are no multiple of 32 or 256 (300, 136), contraction lengths with and without a tail
+        # and backward data products of the layered path) and the narrow one (policy output, action gradient),
+        # single-network launches included: a ragged last row tile (8195 = 256 * 32 + 3, an odd number of row
+        # tiles: the 128-column layer pairs row tiles per workgroup and the last pair is half empty), output
+        # widths that are no multiple of 32 or 256 (300, 136), contraction lengths with and without a tail
         "layer_tiles": Wk["tiny"].replace(name="layer_tiles", obs_dim=41, act_dim=13, num_envs=40, capacity=40 * 8,
-                                          batch=5510, hidden=(300, 136, 128), index=19),
+                                          batch=8195, hidden=(300, 136, 128), index=19),
     }
 
 
@@ -717,6 +718,7 @@ def test_which_cases_take_the_row_tile_kernels(torch_cuda, case):
     else:
         assert not (fused & names)
     assert ("layer_rowtile_kernel" in names) == (case == "layer_tiles")
+    assert ("narrow_rowtile_kernel" in names) == (case == "layer_tiles")
 
 
 # ---------------------------------------------------------------------------------------------
