@@ -342,7 +342,7 @@ hipError_t run(int mode, int tile, std::vector<GemmProb>& ps, const GemmNoise* n
         for (int k = 0; k < g.nprob; ++k) g.p[k] = ps[i + k];
         hipError_t e;
         if (mode == GEMM_NN && nz == nullptr && layer_rowtile_ok(g)) e = layer_rowtile_launch(g, st);
-        else if (mode == GEMM_NN && nz == nullptr && narrow_rowtile_ok(g)) e = narrow_rowtile_launch(g, st);
+        else if (mode == GEMM_NN && narrow_rowtile_ok(g)) e = narrow_rowtile_launch(g, st);
         else e = gemm_launch(mode, tile, g, st);
         if (e != hipSuccess) return e;
     }

@@ -1482,7 +1482,7 @@ hipError_t layer_rowtile_launch(GemmGroup& g, hipStream_t stream) {
 
 // =============================================================================================
 // Action-wide products of the layered path (at most 32 output columns): the policy's output layer
-// and the gradient with respect to the action.  One wavefront's 32 columns already cover the
+// (with the Actor's exploration noise where asked for) and the gradient with respect to the action.  One wavefront's 32 columns already cover the
 // output, so the eight wavefronts of a row tile split the contraction instead (every eighth chunk
 // of 32 k-values each, as in the chained kernels' narrow layers) and their partial tiles meet in
 // LDS.  Segments (the twin critics' first-layer deltas) pass through the same input tile one after
@@ -1529,6 +1529,21 @@ __global__ __launch_bounds__(FT, 2) void narrow_rowtile_kernel(const GemmGroup g
                 x *= 1.f - t * t;
             } else {
                 x = tanhf(x + P.bias[col]);
+                if (epi == EPI_BIAS_TANH_NOISE) {
+                    // Actor step (Section 3.3): a = clip(pi(s) + sigma_i * eps, -1, 1), sigma_i linear in the
+                    // environment index, eps from Philox-4x32-10 (stream 2) by Box-Muller, as in fused_act_kernel
+                    const GemmNoise& nz = g.noise;
+                    const int env = r0 + row;
+                    uint32_t w0, w1;
+                    philox4x32_10_f((uint32_t)(env * nz.act_dim + col), 2u, nz.ctr2, nz.ctr3, nz.key0, nz.key1, w0, w1);
+                    const double u1 = ((double)(w0 >> 8) + 0.5) * 0x1p-24;
+                    const double u2 = ((double)(w1 >> 8) + 0.5) * 0x1p-24;
+                    const double eps = sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925286766559 * u2);
+                    double sigma = (double)nz.sigma_min;
+                    if (nz.sigma_rows > 1)
+                        sigma += ((double)env / (double)(nz.sigma_rows - 1)) * ((double)nz.sigma_max - (double)nz.sigma_min);
+                    x = fminf(fmaxf(x + (float)(sigma * eps), -1.f), 1.f);
+                }
             }
             P.C[(size_t)(r0 + row) * (size_t)P.ldc + col] = x;
         } else {
@@ -1558,7 +1573,8 @@ bool narrow_rowtile_ok(const GemmGroup& g) {
     long wgs = 0;
     for (int i = 0; i < g.nprob; ++i) {
         const GemmProb& p = g.p[i];
-        if (p.epi != EPI_BIAS_TANH && p.epi != EPI_MUL_DTANH) return false;
+        if (p.epi != EPI_BIAS_TANH && p.epi != EPI_BIAS_TANH_NOISE && p.epi != EPI_MUL_DTANH) return false;
+        if (p.epi == EPI_BIAS_TANH_NOISE && (g.nprob != 1 || g.noise.act_dim != p.N)) return false;
         if (p.epi == EPI_MUL_DTANH ? (p.aux == nullptr || p.ldaux < p.N) : (p.bias == nullptr || p.colsum != nullptr)) return false;
         if (p.N < 1 || p.N > 32 || p.M < 1 || p.nseg < 1 || p.nseg > 2 || p.ldc < p.N) return false;
         for (int s = 0; s < p.nseg; ++s) {

@@ -186,7 +186,8 @@ def test_actor_act_matches_oracle(torch_cuda, case):
     w = SMALL[case]
     s = make_session(w)
     rng = np.random.default_rng(7)
-    for call, num in enumerate((w.num_envs, 1, min(s.max_batch, 333))):
+    # (the last call of layer_tiles is large enough for the row-tile layer kernels, noise epilogue included)
+    for call, num in enumerate((w.num_envs, 1, min(s.max_batch, 333)) + ((s.max_batch,) if case == "layer_tiles" else ())):
         obs = rng.standard_normal((num, w.obs_dim), dtype=np.float32)
         got = s.act(torch.from_numpy(obs).cuda(), 0.05, 0.8).cpu().numpy()
         ref = O.actor_act(s.actor_init, w.actor_dims(), obs, float(np.float32(0.05)), float(np.float32(0.8)),
@@ -489,7 +490,8 @@ def test_sac_actor_step_is_a_policy_sample(torch_cuda, case):
     w = with_sac(SMALL[case])
     s = make_session(w)
     rng = np.random.default_rng(7)
-    for call, num in enumerate((w.num_envs, 1, min(s.max_batch, 333))):
+    # (the last call of layer_tiles is large enough for the row-tile layer kernels, noise epilogue included)
+    for call, num in enumerate((w.num_envs, 1, min(s.max_batch, 333)) + ((s.max_batch,) if case == "layer_tiles" else ())):
         obs = rng.standard_normal((num, w.obs_dim), dtype=np.float32)
         got = s.act(torch.from_numpy(obs).cuda()).cpu().numpy()
         ref = O.sac_actor_act(s.actor_init, w.actor_dims(), obs, w.rng_seed, call)
