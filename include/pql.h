@@ -65,6 +65,8 @@ extern "C" {
 #define PQL_ERR_BATCH_TOO_LARGE   -4   /* batch exceeds cfg.max_batch (workspace sizing)        */
 #define PQL_ERR_HIP               -5   /* a HIP runtime call failed; see pql_last_error         */
 #define PQL_ERR_ALIGNMENT         -6   /* a device pointer is not aligned as required           */
+#define PQL_ERR_SCRATCH_TOO_SMALL -7   /* the configuration needs more scratch than a fixed-size */
+                                       /* buffer of the library holds                            */
 
 #define PQL_MAX_HIDDEN 8
 
@@ -197,6 +199,28 @@ int32_t pql_critic_update(pql_ctx* ctx, float* critic_params, const float* criti
                           const float* actor_target_params, float* adam_m, float* adam_v, float* grads_out,
                           pql_batch batch, int32_t batch_size, pql_adam opt, float* loss_out,
                           void* workspace, void* stream);
+
+/* ---- V-learner step for callers that cannot allocate device memory ----------------------- */
+
+/* pql_critic_update without the workspace argument, for callers that may not call hipMalloc (or any
+ * allocating routine) and have no scratch buffer to hand over: code under HIP graph capture, tight
+ * serving / training loops, harnesses that forbid allocation.  The scratch that pql_critic_update
+ * takes from its caller comes from a device array of pql_static_scratch_bytes() bytes (64 MiB) that is
+ * part of the library's code object instead: every GPU the library runs on holds one copy from the
+ * first call on it until the process ends.  The call allocates and frees nothing and makes no
+ * synchronising call; apart from one address lookup on the first call on a device it only enqueues the
+ * same kernels as pql_critic_update on `stream`, with the same arguments, results, state changes and
+ * errors (the device that owns `stream` must be the current one).
+ * Limit: configurations with pql_workspace_bytes(cfg) > pql_static_scratch_bytes() are rejected with
+ * PQL_ERR_SCRATCH_TOO_SMALL before anything is launched (the need grows with cfg.max_batch and the layer
+ * widths: obs_dim 60, act_dim 8, two hidden layers of 256 fit up to max_batch 3416).
+ * All calls on one GPU, from any context, share that GPU's array: its contents are undefined between
+ * calls (nothing in it has to start at zero), and two such calls that overlap on one GPU (different
+ * streams or threads) race and give undefined results; order them on one stream. */
+int64_t pql_static_scratch_bytes(void);
+int32_t pql_critic_update_static(pql_ctx* ctx, float* critic_params, const float* critic_target_params,
+                                 const float* actor_target_params, float* adam_m, float* adam_v, float* grads_out,
+                                 pql_batch batch, int32_t batch_size, pql_adam opt, float* loss_out, void* stream);
 
 /* ---- P-learner step (Algorithm 2 "update pi by maximizing min_i Q_i(s, pi(s))") ---------- */
 

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libpql.so")
 
 PQL_MAX_HIDDEN = 8
 ERRORS = {0: "PQL_OK", -1: "PQL_ERR_INVALID_ARG", -2: "PQL_ERR_NULL", -3: "PQL_ERR_NOT_ENOUGH_DATA",
-          -4: "PQL_ERR_BATCH_TOO_LARGE", -5: "PQL_ERR_HIP", -6: "PQL_ERR_ALIGNMENT"}
+          -4: "PQL_ERR_BATCH_TOO_LARGE", -5: "PQL_ERR_HIP", -6: "PQL_ERR_ALIGNMENT", -7: "PQL_ERR_SCRATCH_TOO_SMALL"}
 
 # every symbol include/pql.h declares
 EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_count", "pql_critic_param_count",
@@ -24,7 +24,7 @@ EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_coun
            "pql_sample_nstep", "pql_gather_nstep", "pql_actor_act", "pql_critic_update", "pql_actor_update",
            "pql_soft_update", "pql_adam_step", "pql_profile_begin", "pql_profile_end",
            "pql_obs_norm_bytes", "pql_obs_norm_attach", "pql_obs_norm_reset", "pql_sample_states", "pql_sac_attach",
-           "pql_sac_attach_lagged", "pql_probe_mfma"]
+           "pql_sac_attach_lagged", "pql_probe_mfma", "pql_static_scratch_bytes", "pql_critic_update_static"]
 
 
 class PqlConfig(C.Structure):
@@ -91,6 +91,8 @@ def load_library() -> C.CDLL:
         "pql_sample_states": (I32, [P, PqlStorage, I32, P, P, P]),
         "pql_actor_act": (I32, [P, P, P, I32, F, F, P, P, P]),
         "pql_critic_update": (I32, [P, P, P, P, P, P, P, PqlBatch, I32, PqlAdam, P, P, P]),
+        "pql_critic_update_static": (I32, [P, P, P, P, P, P, P, PqlBatch, I32, PqlAdam, P, P]),
+        "pql_static_scratch_bytes": (I64, []),
         "pql_actor_update": (I32, [P, P, P, P, P, P, P, I32, PqlAdam, P, P, P]),
         "pql_soft_update": (I32, [P, P, P, I64, F, P]),
         "pql_adam_step": (I32, [P, P, P, P, P, I64, PqlAdam, I64, P]),
@@ -248,6 +250,16 @@ class Context:
                                                _ptr(actor_target_params), _ptr(adam_m), _ptr(adam_v), _ptr(grads_out),
                                                batch.c(), batch_size, opt, _ptr(loss_out), _ptr(workspace),
                                                _stream(stream)))
+
+    def pql_critic_update_static(self, critic_params, critic_target_params, actor_target_params, adam_m, adam_v,
+                                 grads_out, batch, batch_size, opt: PqlAdam, loss_out, stream=None):
+        self._check(self.lib.pql_critic_update_static(self.h, _ptr(critic_params), _ptr(critic_target_params),
+                                                      _ptr(actor_target_params), _ptr(adam_m), _ptr(adam_v),
+                                                      _ptr(grads_out), batch.c(), batch_size, opt, _ptr(loss_out),
+                                                      _stream(stream)))
+
+    def static_scratch_bytes(self) -> int:
+        return self.lib.pql_static_scratch_bytes()
 
     def pql_actor_update(self, actor_params, critic_params, adam_m, adam_v, grads_out, obs, batch_size, opt: PqlAdam,
                          loss_out, workspace, stream=None):

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <utility>
@@ -77,6 +78,36 @@ void prof_commit(const ProfSlot& s, int kid, double flops, double bytes) {
     if (s.on) g_prof.recs.push_back({kid, flops, bytes});
 }
 }  // namespace pql
+
+// ---- scratch of pql_critic_update_static -------------------------------------------------------
+// A device array of fixed size that takes the place of the caller's workspace.  Each GPU the library
+// runs on holds one copy until the process ends.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int STATIC_MAX_DEVICES = 64;
+void* g_scratch_ptr[STATIC_MAX_DEVICES];      // per device: the address of that device's copy, once known
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch` (looked up on the first call on that device).
+hipError_t static_scratch_address(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr || (((uintptr_t)p) & 255)) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
 
 struct pql_ctx {
     pql_config cfg;
@@ -725,18 +756,27 @@ int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, i
 }
 
 // ---------------------------------------------------------------------------------------------
-int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_target_params,
-                          const float* actor_target_params, float* adam_m, float* adam_v, float* grads_out,
-                          pql_batch batch, int32_t B, pql_adam opt, float* loss_out, void* workspace, void* stream) {
-    if (!c) return PQL_ERR_NULL;
+// Host-side argument checks of the V-learner step (everything but the scratch buffer).
+static int32_t critic_update_check(pql_ctx* c, const float* critic_params, const float* critic_target_params,
+                                   const float* actor_target_params, const float* adam_m, const float* adam_v,
+                                   const float* grads_out, const pql_batch& batch, int32_t B, const pql_adam& opt,
+                                   const float* loss_out) {
     Err E{c};
     if (!critic_params || !critic_target_params || !actor_target_params || !adam_m || !adam_v || !grads_out ||
-        !batch.obs || !batch.act || !batch.ret || !batch.next_obs || !batch.boot || !loss_out || !workspace)
+        !batch.obs || !batch.act || !batch.ret || !batch.next_obs || !batch.boot || !loss_out)
         return E.fail(PQL_ERR_NULL, "pql_critic_update: null pointer");
     if (B < 1 || !adam_ok(opt)) return E.fail(PQL_ERR_INVALID_ARG, "pql_critic_update: bad batch size or Adam constants");
     if (c->cfg.stochastic_policy && !c->temperature) return E.fail(PQL_ERR_NULL, "pql_critic_update: no temperature attached");
     if (B > c->cfg.max_batch) return E.fail(PQL_ERR_BATCH_TOO_LARGE, "pql_critic_update: batch > max_batch");
-    if (((uintptr_t)workspace) & 255) return E.fail(PQL_ERR_ALIGNMENT, "pql_critic_update: workspace not 256-byte aligned");
+    return PQL_OK;
+}
+
+// The launch sequence of the V-learner step on a checked argument list; `workspace` is device
+// memory of at least pql_workspace_bytes(cfg) bytes, 256-byte aligned, whoever owns it.
+static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* critic_target_params,
+                                 const float* actor_target_params, float* adam_m, float* adam_v, float* grads_out,
+                                 pql_batch batch, int32_t B, pql_adam opt, float* loss_out, void* workspace, void* stream) {
+    Err E{c};
     hipStream_t st = (hipStream_t)stream;
     float* ws = (float*)workspace;
     Layout w;
@@ -974,6 +1014,51 @@ int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
     c->critic_t += 1;
     return PQL_OK;
+}
+
+int32_t pql_critic_update(pql_ctx* c, float* critic_params, const float* critic_target_params,
+                          const float* actor_target_params, float* adam_m, float* adam_v, float* grads_out,
+                          pql_batch batch, int32_t B, pql_adam opt, float* loss_out, void* workspace, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!workspace) return E.fail(PQL_ERR_NULL, "pql_critic_update: null pointer");
+    const int32_t rc = critic_update_check(c, critic_params, critic_target_params, actor_target_params, adam_m, adam_v,
+                                           grads_out, batch, B, opt, loss_out);
+    if (rc != PQL_OK) return rc;
+    if (((uintptr_t)workspace) & 255) return E.fail(PQL_ERR_ALIGNMENT, "pql_critic_update: workspace not 256-byte aligned");
+    return critic_update_run(c, critic_params, critic_target_params, actor_target_params, adam_m, adam_v, grads_out, batch,
+                             B, opt, loss_out, workspace, stream);
+}
+
+// ---- the same step on the library's own scratch --------------------------------------------
+// For callers that cannot allocate device memory (code under graph capture, tight serving loops):
+// the workspace of pql_critic_update is replaced by a file-scope device array.  Every GPU holds its
+// own copy of that array at its own address, looked up once per device with that device current;
+// host code only ever uses the looked-up address (the array's name is a host-side stand-in here).
+int64_t pql_static_scratch_bytes(void) { return (int64_t)STATIC_SCRATCH_BYTES; }
+
+int32_t pql_critic_update_static(pql_ctx* c, float* critic_params, const float* critic_target_params,
+                                 const float* actor_target_params, float* adam_m, float* adam_v, float* grads_out,
+                                 pql_batch batch, int32_t B, pql_adam opt, float* loss_out, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    const int32_t rc = critic_update_check(c, critic_params, critic_target_params, actor_target_params, adam_m, adam_v,
+                                           grads_out, batch, B, opt, loss_out);
+    if (rc != PQL_OK) return rc;
+    Layout w;
+    make_layout(&c->cfg, w);
+    if (w.total * sizeof(float) > STATIC_SCRATCH_BYTES) {
+        char msg[192];
+        std::snprintf(msg, sizeof(msg), "pql_critic_update_static: this configuration needs %zu bytes of scratch, the static "
+                      "array holds %zu (lower cfg.max_batch or use pql_critic_update)", w.total * sizeof(float),
+                      (size_t)STATIC_SCRATCH_BYTES);
+        return E.fail(PQL_ERR_SCRATCH_TOO_SMALL, msg);
+    }
+    void* ws = nullptr;
+    const hipError_t e = static_scratch_address(&ws);
+    if (e != hipSuccess) return E.hip(e, "pql_critic_update_static: scratch address");
+    return critic_update_run(c, critic_params, critic_target_params, actor_target_params, adam_m, adam_v, grads_out, batch,
+                             B, opt, loss_out, ws, stream);
 }
 
 // ---------------------------------------------------------------------------------------------

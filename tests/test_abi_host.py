@@ -26,7 +26,7 @@ def cfg_of(w, max_batch=None):
 def test_library_exports_every_declared_symbol():
     lib = B.load_library()
     names = header_functions()
-    assert len(names) == 26 and sorted(B.EXPORTS) == names
+    assert len(names) == 28 and sorted(B.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -194,3 +194,29 @@ def test_state_sampling_and_probe_argument_errors():
     assert lib.pql_probe_mfma(ctx.h, p, 0, 8, None) == -1
     assert ctx.get_state() == [0] * 8
     ctx.close()
+
+
+def test_static_scratch_variant_checks_arguments_and_size_on_the_host():
+    """pql_critic_update_static: argument errors as pql_critic_update's, and a configuration whose
+    workspace exceeds the library's fixed scratch array is refused before any device call."""
+    lib = B.load_library()
+    limit = lib.pql_static_scratch_bytes()
+    assert limit == 64 << 20
+    p = C.c_void_p(0x1000)
+    batch = B.PqlBatch(p, p, p, p, p, p)
+    opt = B.PqlAdam(1e-3, 0.9, 0.999, 1e-8, 0.0)
+    small = B.Context(cfg_of(W.WORKLOADS["tiny"]))
+    assert small.workspace_bytes() <= limit
+    assert lib.pql_critic_update_static(small.h, p, p, None, p, p, p, batch, 8, opt, p, None) == -2
+    assert lib.pql_critic_update_static(small.h, p, p, p, p, p, p, batch, 0, opt, p, None) == -1
+    assert lib.pql_critic_update_static(small.h, p, p, p, p, p, p, batch, W.WORKLOADS["tiny"].batch + 1, opt, p, None) == -4
+    assert small.get_state() == [0] * 8
+    big = B.Context(cfg_of(W.WORKLOADS["humanoid"]))
+    assert big.workspace_bytes() > limit
+    assert lib.pql_critic_update_static(big.h, p, p, p, p, p, p, batch, 8, opt, p, None) == -7
+    assert "static" in big.last_error() and str(limit) in big.last_error()
+    assert big.get_state() == [0] * 8
+    # the largest ant-shaped batch bound the header names
+    w = W.WORKLOADS["ant"]
+    assert B.Context(cfg_of(w, 3416)).workspace_bytes() <= limit < B.Context(cfg_of(w, 3417 + 31)).workspace_bytes()
+    small.close(); big.close()
