@@ -18,7 +18,12 @@
  *   Return value   Every function returning int32_t returns PQL_OK (0) or a negative PQL_ERR_*
  *                  code.  Nothing aborts or throws across this boundary.  Argument errors are
  *                  found on the host before any kernel is launched and leave all state
- *                  (context counters and device buffers) unchanged.
+ *                  (context counters and device buffers) unchanged.  PQL_ERR_HIP means the HIP
+ *                  runtime refused a launch part-way through a call: the device buffers the
+ *                  call writes are then undefined and its counter is not advanced, with one
+ *                  exception: pql_replay_push counts the row as soon as its copy is enqueued,
+ *                  so a failure of the statistics update that follows leaves ring and cursor
+ *                  consistent (the statistics block must then be reset).
  *   Memory         The library allocates NO device memory.  Every pointer marked [device] is
  *                  caller-owned device memory (fp32 unless stated) that must stay valid until
  *                  the stream has drained; the library never frees it.  Pointers marked [host]
@@ -81,7 +86,10 @@ typedef struct {
     float    gamma;                   /* discount in (0, 1]                                      */
     int32_t  n_hidden;                /* 1..PQL_MAX_HIDDEN hidden layers, same for actor/critic  */
     int32_t  hidden[PQL_MAX_HIDDEN];  /* widths, each >= 1                                       */
-    int32_t  max_batch;               /* largest batch_size / num_envs any call will use         */
+    int32_t  max_batch;               /* largest batch_size / num_envs any call will use;        */
+                                      /* (max_batch / 4 + 24) * (widest layer or input + 64) * 4 */
+                                      /* must stay below 2^31 (32-bit row offsets of the weight-  */
+                                      /* gradient kernel)                                         */
     uint64_t seed;                    /* key of the counter-based generator                      */
     int32_t  num_atoms;               /* 0 or 1: scalar critics.  2..64: distributional critics  */
                                       /* (PQL-D; the paper's appendix uses 51) with that many     */
@@ -299,6 +307,24 @@ int32_t pql_obs_norm_reset(pql_ctx* ctx, void* stream);
  * overlap).  tau = 1 copies src bit-exactly, tau = 0 leaves dst bit-exactly unchanged.
  * 0 <= tau <= 1. */
 int32_t pql_soft_update(pql_ctx* ctx, const float* src, float* dst, int64_t count, float tau, void* stream);
+
+/* ---- inspection aid ----------------------------------------------------------------------- */
+
+/* Where the per-row results of the last update lie inside that call's workspace (Algorithm 3: the
+ * target y; Algorithms 2 and 3: Q_1, Q_2).  *offset_bytes receives the byte offset, from the start of
+ * the workspace, of a float[batch_size] array:
+ *   PQL_VIEW_TD_TARGET  y_b = ret_b + boot_b * min_i Q'_i(next_obs_b, pi^v(next_obs_b)) of the last
+ *                       pql_critic_update (with the entropy term when the policy is stochastic);
+ *                       scalar critics only;
+ *   PQL_VIEW_Q1, _Q2    Q_i(obs_b, act_b) as evaluated by the last pql_critic_update before its step
+ *                       (scalar critics only), or Q_i(obs_b, pi(obs_b)) of the last pql_actor_update
+ *                       (the distribution's mean for distributional critics).
+ * Valid once the stream has drained and until the next call that uses the workspace.  Host-side only.
+ * Errors: PQL_ERR_NULL, PQL_ERR_INVALID_ARG (bad cfg or `what`). */
+#define PQL_VIEW_TD_TARGET 0
+#define PQL_VIEW_Q1        1
+#define PQL_VIEW_Q2        2
+int32_t pql_workspace_view(const pql_config* cfg, int32_t what, int64_t* offset_bytes);
 
 /* ---- measurement aid -------------------------------------------------------------------- */
 

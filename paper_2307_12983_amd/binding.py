@@ -24,7 +24,8 @@ EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_coun
            "pql_sample_nstep", "pql_gather_nstep", "pql_actor_act", "pql_critic_update", "pql_actor_update",
            "pql_soft_update", "pql_adam_step", "pql_profile_begin", "pql_profile_end",
            "pql_obs_norm_bytes", "pql_obs_norm_attach", "pql_obs_norm_reset", "pql_sample_states", "pql_sac_attach",
-           "pql_sac_attach_lagged", "pql_probe_mfma", "pql_static_scratch_bytes", "pql_critic_update_static"]
+           "pql_sac_attach_lagged", "pql_probe_mfma", "pql_static_scratch_bytes", "pql_critic_update_static",
+           "pql_workspace_view"]
 
 
 class PqlConfig(C.Structure):
@@ -82,6 +83,7 @@ def load_library() -> C.CDLL:
         "pql_actor_param_count": (I64, [cfgp]),
         "pql_critic_param_count": (I64, [cfgp]),
         "pql_workspace_bytes": (I64, [cfgp]),
+        "pql_workspace_view": (I32, [cfgp, I32, C.POINTER(I64)]),
         "pql_last_error": (C.c_char_p, [P]),
         "pql_get_state": (I32, [P, C.POINTER(I64)]),
         "pql_set_state": (I32, [P, C.POINTER(I64)]),
@@ -209,6 +211,12 @@ class Context:
 
     def workspace_bytes(self) -> int:
         return self.lib.pql_workspace_bytes(C.byref(self.cfg))
+
+    def workspace_view(self, what: int) -> int:
+        """Byte offset inside the workspace of y (0), Q_1 (1) or Q_2 (2) of the last update."""
+        off = C.c_int64(0)
+        self._check(self.lib.pql_workspace_view(C.byref(self.cfg), what, C.byref(off)))
+        return off.value
 
     def obs_norm_bytes(self) -> int:
         return self.lib.pql_obs_norm_bytes(C.byref(self.cfg))

@@ -147,6 +147,14 @@ int validate_cfg(const pql_config* c) {
     if (c->stochastic_policy != 0 && c->stochastic_policy != 1) return PQL_ERR_INVALID_ARG;
     // the stochastic policy is built for scalar critics; its gradient kernel keeps 2a + 1 columns of 256 rows in LDS
     if (c->stochastic_policy && (c->num_atoms >= 2 || c->act_dim > 31)) return PQL_ERR_INVALID_ARG;
+    // The weight-gradient kernel addresses the rows of one wavefront's share of a split (at most a quarter of
+    // the batch, when the batch is not split at all) with 32-bit byte offsets: the widest operand row
+    // times that many rows must stay below 2 GiB for every batch the context may see.
+    int64_t ld = c->obs_dim > c->act_dim ? c->obs_dim : c->act_dim;
+    for (int i = 0; i < c->n_hidden; ++i) ld = c->hidden[i] > ld ? c->hidden[i] : ld;
+    if (c->num_atoms > ld) ld = c->num_atoms;
+    if (2 * (int64_t)c->act_dim > ld) ld = 2 * (int64_t)c->act_dim;
+    if ((((int64_t)c->max_batch + 31) / 4 + 16) * (ld + 64) * 4 >= 0x7fffffffLL) return PQL_ERR_INVALID_ARG;
     return PQL_OK;
 }
 
@@ -417,7 +425,8 @@ hipError_t run_dw(std::vector<GemmProb>& ps, const std::vector<int64_t>& offsets
     S = (K + chunk - 1) / chunk;
     for (size_t i = 0; i < ps.size(); ++i) {
         GemmProb& p = ps[i];
-        // the kernel addresses a wavefront's rows (a quarter of a split) with 32-bit byte offsets
+        // the kernel addresses a wavefront's rows (a quarter of a split) with 32-bit byte offsets; pql_create
+        // has refused configurations that could exceed them (validate_cfg), so this cannot trigger
         const int64_t ld = p.seg[0].lda > p.seg[0].ldb ? p.seg[0].lda : p.seg[0].ldb;
         if (((int64_t)chunk / 4 + 16) * (ld + 64) * 4 >= 0x7fffffffLL) return hipErrorInvalidValue;
         p.splits = S; p.k_chunk = chunk;
@@ -512,6 +521,23 @@ int64_t pql_workspace_bytes(const pql_config* cfg) {
     return (int64_t)(w.total * sizeof(float));
 }
 
+int32_t pql_workspace_view(const pql_config* cfg, int32_t what, int64_t* offset_bytes) {
+    if (!offset_bytes) return PQL_ERR_NULL;
+    const int rc = validate_cfg(cfg);
+    if (rc != PQL_OK) return rc;
+    Layout w;
+    make_layout(cfg, w);
+    size_t off;
+    switch (what) {
+        case PQL_VIEW_TD_TARGET: off = w.y; break;
+        case PQL_VIEW_Q1: off = w.q[0]; break;
+        case PQL_VIEW_Q2: off = w.q[1]; break;
+        default: return PQL_ERR_INVALID_ARG;
+    }
+    *offset_bytes = (int64_t)(off * sizeof(float));
+    return PQL_OK;
+}
+
 const char* pql_last_error(const pql_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
 int32_t pql_get_state(const pql_ctx* c, int64_t out[8]) {
@@ -549,13 +575,14 @@ int32_t pql_replay_push(pql_ctx* c, pql_replay_storage st, const float* obs, con
     p.src[4] = done;     p.dst[4] = st.done + base;          p.count[4] = N;
     hipError_t e = push_launch(p, (hipStream_t)stream);
     if (e != hipSuccess) return E.hip(e, "pql_replay_push");
-    if (c->obs_norm) {
-        e = obs_stats_update_launch(obs_stats_view(c->obs_norm, (int)o), obs, (int)N, (int)o, c->obs_eps, (hipStream_t)stream);
-        if (e != hipSuccess) return E.hip(e, "pql_replay_push");
-    }
+    // the row copy is enqueued: the cursor covers the row from here on, whatever happens to the statistics
     c->head = (c->head + 1) % c->T;
     c->count = c->count + 1 < c->T ? c->count + 1 : c->T;
     c->pushes += 1;
+    if (c->obs_norm) {
+        e = obs_stats_update_launch(obs_stats_view(c->obs_norm, (int)o), obs, (int)N, (int)o, c->obs_eps, (hipStream_t)stream);
+        if (e != hipSuccess) return E.hip(e, "pql_replay_push: observation statistics (the row itself was stored)");
+    }
     return PQL_OK;
 }
 

@@ -9,6 +9,7 @@ from paper_2307_12983_amd import workloads as W
 
 TOL_ONE_STEP = 1e-4     # max relative error after one step (per tensor, max-norm)
 TOL_100_STEPS = 1e-3    # after 100 steps
+EXEMPT_SHARE = 0.003    # largest share of a network's entries that may need the first-step bound (see assert_first_step_params)
 
 
 def rel_err(x, ref):
@@ -34,10 +35,28 @@ def split_tensors(flat, dims, nets=1):
     return out
 
 
+def joint_scales(ref, dims, nets):
+    """Reference scale of every tensor for the max-norm relative error: max |ref| of the tensor itself,
+    except for one-element tensors (the scalar critic's output bias).  There the max-norm rule would
+    degenerate to the relative error of a single number, and for the gradient that number is
+    sum_b delta_b, which can cancel to orders of magnitude below its terms (and below the fp32 rounding of
+    the q_b it is made of).  A bias is the weight of a constant input 1: the one-element tensor is judged
+    as that extra row of its layer's weight matrix, i.e. on the scale max(max |W_l|, |b_l|)."""
+    tensors = split_tensors(ref, dims, nets)
+    scales = []
+    for k, (name, r) in enumerate(tensors):
+        sc = float(np.max(np.abs(np.asarray(r, np.float64)))) if r.size else 0.0
+        if r.size == 1 and ".b" in name:
+            sc = max(sc, float(np.max(np.abs(np.asarray(tensors[k - 1][1], np.float64)))))    # W_l precedes b_l
+        scales.append(max(sc, 1e-30))
+    return scales
+
+
 def assert_params_close(got, ref, dims, nets, tol, what):
     worst = 0.0
-    for (name, g), (_, r) in zip(split_tensors(got, dims, nets), split_tensors(ref, dims, nets)):
-        e = rel_err(g, r)
+    scales = joint_scales(ref, dims, nets)
+    for (name, g), (_, r), sc in zip(split_tensors(got, dims, nets), split_tensors(ref, dims, nets), scales):
+        e = float(np.max(np.abs(np.asarray(g, np.float64) - np.asarray(r, np.float64)))) / sc if r.size else 0.0
         worst = max(worst, e)
         assert e <= tol, "%s %s: rel err %.3e > %.1e" % (what, name, e, tol)
     return worst
@@ -50,14 +69,15 @@ def assert_first_step_params(theta, theta_ref, g, g_ref, dims, nets, lr, eps, to
     of the batch reduction moves such a parameter by up to lr.  Entries whose guaranteed bound
     lr * eps * dg / (max(|g| - dg, 0) + eps)^2 (dg = measured max gradient error of the tensor,
     itself required to be within tolerance) exceeds half the tolerance are compared against the
-    hard bound 2 * lr instead, counted and reported; all other entries must meet `tol`."""
+    hard bound 2 * lr instead, counted and reported; all other entries must meet `tol`.  One-element
+    tensors take their scale from joint_scales()."""
     total = exempt_total = 0
     worst = worst_exempt = 0.0
-    for (name, t), (_, tr), (_, gg), (_, gr) in zip(split_tensors(theta, dims, nets), split_tensors(theta_ref, dims, nets),
-                                                    split_tensors(g, dims, nets), split_tensors(g_ref, dims, nets)):
+    scales = joint_scales(theta_ref, dims, nets)
+    for (name, t), (_, tr), (_, gg), (_, gr), scale in zip(split_tensors(theta, dims, nets), split_tensors(theta_ref, dims, nets),
+                                                           split_tensors(g, dims, nets), split_tensors(g_ref, dims, nets), scales):
         t, tr, gg, gr = (np.asarray(x, np.float64) for x in (t, tr, gg, gr))
         dg = float(np.max(np.abs(gg - gr)))
-        scale = max(float(np.max(np.abs(tr))), 1e-30)
         amp = lr * eps * dg / (np.maximum(np.abs(gr) - dg, 0.0) + eps) ** 2
         exempt = amp > 0.5 * tol * scale
         err = np.abs(t - tr)
@@ -70,7 +90,8 @@ def assert_first_step_params(theta, theta_ref, g, g_ref, dims, nets, lr, eps, to
         if exempt.any():
             worst_exempt = max(worst_exempt, float(err[exempt].max()))
             assert err[exempt].max() <= 2.0 * lr * (1 + 1e-6), "%s %s: near-zero-gradient entry moved more than 2*lr" % (what, name)
-    assert exempt_total <= max(8, 0.005 * total), "%s: %d of %d entries need the near-zero-gradient bound" % (what, exempt_total, total)
+    # measured shares are 0.01 - 0.15 % of a network; twice the largest is the cap (small networks: 8 entries)
+    assert exempt_total <= max(8, EXEMPT_SHARE * total), "%s: %d of %d entries need the near-zero-gradient bound" % (what, exempt_total, total)
     return dict(rel=worst, near_zero_grad_entries=exempt_total, of=total, worst_abs_dev_there=worst_exempt)
 
 

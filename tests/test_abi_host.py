@@ -26,7 +26,7 @@ def cfg_of(w, max_batch=None):
 def test_library_exports_every_declared_symbol():
     lib = B.load_library()
     names = header_functions()
-    assert len(names) == 28 and sorted(B.EXPORTS) == names
+    assert len(names) == 29 and sorted(B.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -61,6 +61,15 @@ def test_create_rejects_bad_configs():
     cfg = cfg_of(w)
     cfg.hidden[1] = 2048                       # last hidden layer wider than the head kernel supports
     assert lib.pql_create(C.byref(cfg), C.byref(h)) == -1
+    # a first hidden layer of 65536 columns is fine at a small batch bound, but not at 32768 rows: a quarter
+    # of the batch times that row length leaves the 32-bit offsets of the weight-gradient kernel
+    cfg = cfg_of(w)
+    cfg.hidden[0] = 65536
+    assert lib.pql_create(C.byref(cfg), C.byref(h)) == 0
+    lib.pql_destroy(h)
+    cfg.max_batch = 32768
+    assert lib.pql_create(C.byref(cfg), C.byref(h)) == -1
+    assert lib.pql_workspace_bytes(C.byref(cfg)) == -1
 
 
 def test_argument_errors_are_caught_on_the_host_and_leave_state_unchanged():
@@ -220,3 +229,14 @@ def test_static_scratch_variant_checks_arguments_and_size_on_the_host():
     w = W.WORKLOADS["ant"]
     assert B.Context(cfg_of(w, 3416)).workspace_bytes() <= limit < B.Context(cfg_of(w, 3417 + 31)).workspace_bytes()
     small.close(); big.close()
+
+
+def test_workspace_view_offsets():
+    lib = B.load_library()
+    ctx = B.Context(cfg_of(W.WORKLOADS["ant"]))
+    offs = [ctx.workspace_view(k) for k in range(3)]
+    assert len(set(offs)) == 3 and all(o % 256 == 0 and 0 <= o < ctx.workspace_bytes() for o in offs)
+    off = C.c_int64(0)
+    assert lib.pql_workspace_view(C.byref(ctx.cfg), 3, C.byref(off)) == -1
+    assert lib.pql_workspace_view(C.byref(ctx.cfg), 0, None) == -2
+    ctx.close()

@@ -200,6 +200,41 @@ def test_actor_act_matches_oracle(torch_cuda, case):
     assert rel_err(got, O.actor_forward(s.actor_init, w.actor_dims(), obs)) <= TOL_ONE_STEP
 
 
+@pytest.mark.parametrize("name", ["ant", "humanoid", "scale"])
+def test_actor_act_at_the_workloads_own_num_envs(torch_cuda, name):
+    """The Actor step at the number of environments each workload names (4096 / 16384 / 32768: the
+    launch shapes the benchmark times), with the mixed noise scales of Section 3.3 (sigma_i from 0.05
+    to 0.8, linear in the environment index): two calls (two call numbers of the generator), then
+    sigma = 0, which must give the deterministic policy."""
+    torch = torch_cuda
+    w = W.WORKLOADS[name]
+    s = make_session(w)
+    rng = np.random.default_rng(11)
+    lo, hi = float(np.float32(0.05)), float(np.float32(0.8))
+    for call in range(2):
+        obs = rng.standard_normal((w.num_envs, w.obs_dim), dtype=np.float32)
+        s.ctx.pql_profile_begin(64)
+        got = s.act(torch.from_numpy(obs).cuda(), lo, hi).cpu().numpy()
+        names = {k["name"] for k in s.ctx.pql_profile_end()}
+        ref = O.actor_act(s.actor_init, w.actor_dims(), obs, lo, hi, w.rng_seed, call)
+        e = rel_err(got, ref)
+        # per environment: the noise scale is the one of ITS index (a wrong sigma_i or element counter shows in
+        # the rows it belongs to, whatever the tensor-wide maximum is)
+        row_err = np.abs(got.astype(np.float64) - ref).max(axis=1)
+        say(name, "act call", call, "N", w.num_envs, "rel err %.2e" % e, "worst row", int(row_err.argmax()), sorted(names))
+        assert e <= TOL_ONE_STEP and row_err.max() <= TOL_ONE_STEP and got.min() >= -1.0 and got.max() <= 1.0
+        if name == "ant":
+            assert names == {"fused_act_kernel"}
+        else:
+            assert {"layer_rowtile_kernel", "narrow_rowtile_kernel"} <= names
+    sig = O.exploration_sigma(w.num_envs, lo, hi)
+    assert sig[0] == lo and abs(sig[-1] - hi) <= 1e-15 and sig.shape == (w.num_envs,)
+    obs = rng.standard_normal((w.num_envs, w.obs_dim), dtype=np.float32)
+    got = s.act(torch.from_numpy(obs).cuda(), 0.0, 0.0).cpu().numpy()
+    assert rel_err(got, O.actor_forward(s.actor_init, w.actor_dims(), obs)) <= TOL_ONE_STEP
+    assert s.ctx.get_state()[4] == 3
+
+
 # ---------------------------------------------------------------------------------------------
 def one_step(torch, w, rows, check_all=True):
     """One sample + critic update + Polyak + policy update + sync on both sides.  The workload's
@@ -272,6 +307,76 @@ def test_one_update_small_cases(torch_cuda, case):
     say(case, res)
 
 
+def workspace_rows(s, what, B):
+    """y (0), Q_1 (1) or Q_2 (2) of the last update, read from the workspace at the offset the library names."""
+    off = s.ctx.workspace_view(what)
+    assert off % 4 == 0
+    return s.workspace[off // 4: off // 4 + B].cpu().numpy()
+
+
+@pytest.mark.parametrize("case,Bsz", [("ant_s", 1000), ("humanoid_s", 1200), ("layer_tiles", 8195)])
+def test_td_target_and_q_values_row_by_row(torch_cuda, case, Bsz):
+    """Algorithm 3's target y_b and both critics' Q_i(s_b, a_b), and Algorithm 2's Q_i(s_b, pi(s_b)), compared
+    row by row with the oracle (the update tests see them only through batch means and weighted sums):
+    the row-tile kernels (ant_s), the per-layer path with the grouped GEMMs (humanoid_s) and with the
+    row-tile layer kernels (layer_tiles)."""
+    w = SMALL[case].replace(batch=Bsz, done_p=0.05)        # enough terminations for some windows to hold one
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, min(w.rows, w.nstep + 4))
+    s.sample(Bsz)
+    batch = oracle_batch(ring, w, Bsz, 0)
+    critic0 = s.critic.cpu().numpy().copy()
+    s.critic_update(Bsz)
+    y_ref = O.td_target(batch, s.actor_init, s.critic_init, w.actor_dims(), w.critic_dims())
+    y = workspace_rows(s, 0, Bsz)
+    q_ref = [O.critic_forward(p, w.critic_dims(), batch["obs"], batch["act"]) for p in O.split_twin(critic0)]
+    q = [workspace_rows(s, 1 + i, Bsz) for i in range(2)]
+    errs = dict(y=rel_err(y, y_ref), q1=rel_err(q[0], q_ref[0]), q2=rel_err(q[1], q_ref[1]))
+    # rows whose window holds a termination: the target is the reward sum alone
+    term = batch["boot"] == 0.0
+    assert term.any() and not term.all()
+    assert np.array_equal(y[term], s.batch.ret[:Bsz].cpu().numpy()[term])
+    s.actor_update(None, Bsz)
+    critic1 = s.critic.cpu().numpy()
+    a_pi = O.actor_forward(s.actor_init, w.actor_dims(), batch["obs"])
+    qp_ref = [O.critic_forward(p, w.critic_dims(), batch["obs"], a_pi) for p in O.split_twin(critic1)]
+    qp = [workspace_rows(s, 1 + i, Bsz) for i in range(2)]
+    errs.update(qpi1=rel_err(qp[0], qp_ref[0]), qpi2=rel_err(qp[1], qp_ref[1]))
+    say(case, "B", Bsz, {k: "%.2e" % v for k, v in errs.items()}, "terminal rows", int(term.sum()))
+    assert max(errs.values()) <= TOL_ONE_STEP
+
+
+def test_cancelling_output_bias_gradient(torch_cuda):
+    """A fixed case in which the scalar critic's output-bias gradient sum_b delta_b cancels to 1e-4 of the
+    largest gradient entry (found by a sweep over random shapes): its relative error as a single number was
+    1e-3 with an absolute error of 3e-8.  The one-element rule of parity_util.joint_scales judges it on the
+    scale of its layer, and here the sum is also held to what its conditioning allows:
+    |error| <= 1e-6 * sum_b |delta_b|."""
+    w = W.WORKLOADS["tiny"].replace(name="cancel", obs_dim=82, act_dim=16, num_envs=46, capacity=414, batch=100,
+                                    hidden=(128, 128, 192, 64), index=108, nstep=1)
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, min(w.rows, w.nstep + 3))
+    L = oracle_learner(w, s.actor_init, s.critic_init)
+    s.sample(w.batch)
+    batch = oracle_batch(ring, w, w.batch, 0)
+    assert_batch_matches(batch_to_numpy(s.batch, w.batch), batch)
+    y = O.td_target(batch, s.actor_init, s.critic_init, w.actor_dims(), w.critic_dims())
+    s.critic_update(w.batch)
+    losses, g = L.critic_update(batch)
+    got = s.c_g.cpu().numpy().astype(np.float64)
+    Pc = g.size // 2
+    for i, p in enumerate(O.split_twin(s.critic_init)):
+        delta = 2.0 * (O.critic_forward(p, w.critic_dims(), batch["obs"], batch["act"]) - y) / w.batch
+        ref_b = g[(i + 1) * Pc - 1]
+        assert abs(ref_b - delta.sum()) <= 1e-12 * np.abs(delta).sum()
+        err = abs(got[(i + 1) * Pc - 1] - ref_b)
+        say("critic", i, "db_out", ref_b, "sum |delta|", np.abs(delta).sum(), "abs err %.2e" % err,
+            "as a single number %.2e" % (err / abs(ref_b)), "max |g| %.3f" % np.abs(g[i * Pc:(i + 1) * Pc]).max())
+        assert err <= 1e-6 * np.abs(delta).sum()
+    assert rel_err(s.critic_loss.cpu().numpy(), losses) <= TOL_ONE_STEP
+    assert_params_close(got, g, w.critic_dims(), 2, TOL_ONE_STEP, "critic grad")
+
+
 @pytest.mark.parametrize("name", ["ant", "humanoid", "shadow", "scale"])
 def test_one_update_full_size(torch_cuda, name):
     """Full batch and network sizes of each workload.  The ring keeps its full number of rows
@@ -283,13 +388,18 @@ def test_one_update_full_size(torch_cuda, name):
 
 
 # ---------------------------------------------------------------------------------------------
-def many_steps(torch, w, rows, steps, actor_every=0):
+def many_steps(torch, w, rows, steps, actor_every=0, must_run=()):
+    """`must_run`: kernels that the library's own per-launch profile must name during the first iteration
+    that holds every kind of update."""
     s, ring, nz = make_session(w), oracle_ring(w), oracle_normalizer(w)
     fill_both(s, ring, w, rows, normalizer=nz)
     L = oracle_learner(w, s.actor_init, s.critic_init)
     Bsz = w.batch
     worst_loss = 0.0
+    prof_it = (actor_every - 1) if actor_every else 0
     for it in range(steps):
+        if must_run and it == prof_it:
+            s.ctx.pql_profile_begin(512)
         s.sample(Bsz)
         s.critic_update(Bsz)
         s.soft_update_targets()
@@ -301,6 +411,11 @@ def many_steps(torch, w, rows, steps, actor_every=0):
             s.sync_lagged_policy()
             L.actor_update(batch["obs"])
             L.sync_lagged_policy()
+        if must_run and it == prof_it:
+            torch.cuda.synchronize()
+            ran = {k["name"]: k["launches"] for k in s.ctx.pql_profile_end()}
+            say("  kernels of iteration", it, ran)
+            assert set(must_run) <= set(ran), "expected kernels did not run: %s" % sorted(set(must_run) - set(ran))
         if it % 10 == 9 or it == steps - 1:
             e = rel_err(s.critic_loss.cpu().numpy(), losses)
             worst_loss = max(worst_loss, e)
@@ -336,6 +451,21 @@ def test_100_updates_reduced_batch(torch_cuda, name):
     w = W.WORKLOADS[name].replace(num_envs=256, capacity=256 * 16, batch=1024)
     res = many_steps(torch_cuda, w, w.rows, 100, actor_every=0)
     say(name, "100 steps", res)
+
+
+@pytest.mark.parametrize("name,Bsz,actor_every", [("humanoid", 8192, 10), ("shadow", 8192, 0), ("scale", 8192, 0)])
+def test_100_updates_through_the_row_tile_layer_kernels(torch_cuda, name, Bsz, actor_every):
+    """100 critic updates with the networks of the large workloads at a batch size that takes the kernels the
+    benchmark runs them on: humanoid at its own batch 8192 (with a policy update every 10th step, so the
+    policy path's single-network launches take them too), shadow and scale at batch 8192 instead of 16384 /
+    32768 (the float64 oracle needs 0.5 - 0.8 s per update at 8192; every launch of the critic update then
+    has the 256 row tiles from which the row-tile layer kernels are used; the full batches are covered by
+    the one-step test).  The library's per-launch profile must name the row-tile kernels."""
+    base = W.WORKLOADS[name]
+    w = base.replace(num_envs=1024, capacity=1024 * (base.nstep + 9), batch=Bsz)
+    need = ("layer_rowtile_kernel", "narrow_rowtile_kernel", "gemm_tn_stream_kernel")
+    res = many_steps(torch_cuda, w, w.rows, 100, actor_every=actor_every, must_run=need)
+    say(name, "batch", Bsz, "100 steps", res)
 
 
 def test_100_updates_row_tile_layers(torch_cuda):
