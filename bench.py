@@ -135,57 +135,57 @@ def cpu_baseline(w: W.Workload, fill_rows, env_rows_host, budget_s=20.0, paralle
                 sample="%d steps of the same schedule at batch %d (numpy float64, %.1f s)" % (done_steps, w.batch, el))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=800)
-    ap.add_argument("--warmup", type=int, default=80)
-    ap.add_argument("--workload", default="ant", choices=list(W.WORKLOADS))
-    ap.add_argument("--fill-rows", type=int, default=0, help="ring rows to fill before timing (0 = all)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-steps", type=int, default=48)
-    ap.add_argument("--paper-defaults", action="store_true",
-                    help="switch on the two Table B.1 defaults that the five workloads leave off: observation "
-                         "standardisation and gradient clipping at 0.5")
-    ap.add_argument("--atoms", type=int, default=0,
-                    help="distributional critics (PQL-D) with this many atoms on (-10, 10); the paper uses 51")
-    ap.add_argument("--sac", action="store_true",
-                    help="PQL + SAC: tanh-Gaussian policy, soft target, learnable temperature")
-    ap.add_argument("--schedule", default="serial", choices=["serial", "parallel", "parallel-1stream"],
-                    help="serial: every call on one stream, networks shared by all parts (default).  parallel: the "
-                         "Actor, V-learner and P-learner on three streams with local network copies exchanged once "
-                         "per Actor step (Section 3.1 / 3.2), same 1 : 8 : 4 rates.  parallel-1stream: that schedule "
-                         "enqueued on one stream")
-    ap.add_argument("--no-isolated", dest="isolated", action="store_false",
-                    help="skip the extra loops that time the V-learner alone (sample + critic update + Polyak) and "
-                         "the policy update alone")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
+def host_info():
+    """What the CPU baseline ran on: model name, logical CPUs, the CPUs this process may use, BLAS threads."""
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    blas, threads = "unknown", 1
+    try:
+        from threadpoolctl import threadpool_info
+        for p in threadpool_info():
+            if p.get("user_api") == "blas":
+                blas, threads = "%s %s" % (p.get("internal_api", "?"), p.get("version", "")), int(p.get("num_threads", 1))
+    except Exception:
+        pass
+    return dict(cpu_model=model, os_cpu_count=os.cpu_count(), sched_affinity=len(os.sched_getaffinity(0)),
+                blas=blas.strip(), blas_threads=threads)
 
+
+def cpu_actions_per_s(w: W.Workload, obs, budget_s=3.0):
+    """The oracle's Actor step (Section 3.3) on one row of N observations."""
+    from oracle import pql_oracle as O
+    actor, _ = W.init_networks(w)
+    n, t0 = 0, time.perf_counter()
+    while True:
+        if w.sac:
+            O.sac_actor_act(actor, w.actor_dims(), obs, w.rng_seed, n)
+        else:
+            O.actor_act(actor, w.actor_dims(), obs, w.sigma_min, w.sigma_max, w.rng_seed, n)
+        n += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or n >= 50:
+            return w.num_envs * n / el
+
+
+def run_workload(w, args, steps, warmup, profile_steps, isolated, keep_rows, schedule="serial", variant=False):
+    """Fills the ring, times `steps` steps of the schedule and one per-kernel event pass.  Returns the
+    fields of the JSON line for this workload, plus the host copies the CPU baseline needs."""
     import torch
     from paper_2307_12983_amd.session import LearnerSession
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(1)
-
-    w = W.WORKLOADS[args.workload]
-    if args.paper_defaults:
-        w = w.replace(max_grad_norm=0.5, obs_norm=True)
-    if args.atoms >= 2:
-        w = w.replace(num_atoms=args.atoms)
-    if args.sac:
-        w = w.replace(sac=True)
     sess = LearnerSession(w)
     rng = W.data_rng(w)
     n_fill = args.fill_rows or w.rows
     keep = []                                   # host copy of the filled rows for the CPU baseline
-    keep_all = not args.no_cpu_baseline
     for r in range(n_fill):
         row = W.transition_rows(w, rng, 1)[0]
         sess.push(row)
-        if keep_all:
+        if keep_rows:
             keep.append(row)
     env_host = W.transition_rows(w, rng, 8)
     env_dev = [sess.to_device(r) for r in env_host]
@@ -228,34 +228,31 @@ def main():
     del probe_out
 
     sched = Schedule(sess, env_dev)
-    if args.schedule == "serial":
-        for i in range(args.warmup):
+    if schedule == "serial":
+        for i in range(warmup):
             sched.step(i)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(args.warmup, args.warmup + args.steps):
+        for i in range(warmup, warmup + steps):
             sched.step(i)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
     else:
         from paper_2307_12983_amd.scheme import ParallelSchemeSession
-        if args.steps % ACTOR_EVERY or args.warmup % ACTOR_EVERY:
-            print("--steps and --warmup must be multiples of %d for the parallel schedule" % ACTOR_EVERY, file=sys.stderr)
-            sys.exit(2)
         ps = ParallelSchemeSession(sess, env_dev, horizon=1, v_updates=ACTOR_EVERY, p_updates=ACTOR_EVERY // POLICY_EVERY,
-                                   concurrent=args.schedule == "parallel")
-        for _ in range(args.warmup // ACTOR_EVERY):
+                                   concurrent=schedule == "parallel")
+        for _ in range(warmup // ACTOR_EVERY):
             ps.run_period()
         ps.finish()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps // ACTOR_EVERY):
+        for _ in range(steps // ACTOR_EVERY):
             ps.run_period()
         ps.finish()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-    ms_per_step = 1e3 * dt / args.steps
-    value = args.steps / dt
+    ms_per_step = 1e3 * dt / steps
+    value = steps / dt
 
     # ---- isolated rates (same buffers): critic-only loop and the Actor step
     def timed(fn, reps):
@@ -269,14 +266,14 @@ def main():
     def critic_only():
         sess.sample(w.batch); sess.critic_update(w.batch); sess.soft_update_targets()
     t_act = timed(lambda: sess.act(env_dev[0]["obs"]), 100)
-    t_critic = timed(critic_only, max(50, args.steps // 4)) if args.isolated else None
-    t_actor_upd = timed(lambda: sess.actor_update(None, w.batch), max(50, args.steps // 8)) if args.isolated else None
+    t_critic = timed(critic_only, max(50, steps // 4)) if isolated else None
+    t_actor_upd = timed(lambda: sess.actor_update(None, w.batch), max(50, steps // 8)) if isolated else None
 
     # ---- per-kernel durations from HIP events on the launch stream, same schedule
     sess.ctx.pql_profile_begin(4096 * 4)
-    base = args.warmup + args.steps
+    base = warmup + steps
     base += (-base) % ACTOR_EVERY
-    for i in range(base, base + args.profile_steps):
+    for i in range(base, base + profile_steps):
         sched.step(i)
     torch.cuda.synchronize()
     stats = sess.ctx.pql_profile_end()
@@ -285,11 +282,12 @@ def main():
     tot_gemm_flops = sum(k["flops"] for k in gemm)
     dom = max(gemm, key=lambda k: k["total_ms"])
     achieved = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
-    # the stored counters were taken on the plain configuration of the workload: a variant (clipping and
-    # normalisation, distributional or stochastic networks, another schedule) runs other kernels
-    variant = args.paper_defaults or args.atoms or args.sac or args.schedule != "serial"
-    traffic = None if variant else profile_tools.stored_traffic(
-        os.path.join(ROOT, "profiles", "bench_%s_traffic.txt" % w.name), dom["name"])
+    # HBM bytes per launch of the dominant kernel: NOT measured in this run.  It is the figure stored by the
+    # two counter passes whose commands the file names (profiles/), and is dropped (null) once a kernel source
+    # has changed since, or for a variant (clipping and normalisation, distributional or stochastic networks,
+    # another schedule), which runs other kernels.
+    traffic_file = os.path.join(ROOT, "profiles", "bench_%s_traffic.txt" % w.name)
+    traffic = None if variant else profile_tools.stored_traffic(traffic_file, dom["name"])
     fl = flops_per_sample(w)
     flops_step = w.batch * (fl["critic_update"] + fl["actor_update"] / POLICY_EVERY) + w.num_envs * fl["act"] / ACTOR_EVERY
     kernels = []
@@ -301,12 +299,8 @@ def main():
             e["gbs"] = k["bytes"] / (k["total_ms"] * 1e-3) / 1e9
             e["hbm_frac"] = e["gbs"] / PEAK_HBM_GBS
         kernels.append(e)
-
     out = {
-        "metric": "V-learner critic updates/s at batch %d" % w.batch,
-        "value": value, "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "value": value, "unit": "updates/s", "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "config": {"workload": "%s-shaped: obs %d, act %d, %d envs, replay %d, batch %d, n=%d, MLP %s ELU fp32; "
                                "per critic update: sample + update + Polyak, policy update every %d, "
                                "Actor step + push every %d%s" % (w.name, w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.batch,
@@ -316,9 +310,12 @@ def main():
                                + ("; distributional critics, %d atoms on (%g, %g)" % (w.num_atoms, w.v_min, w.v_max)
                                   if w.num_atoms >= 2 else "")
                                + ("; SAC variant (stochastic policy, learnable temperature)" if w.sac else ""),
-                   "rows_filled": n_fill, "schedule": args.schedule},
+                   "rows_filled": n_fill, "ring_bytes": n_fill * w.num_envs * (2 * w.obs_dim + w.act_dim + 2) * 4,
+                   "schedule": schedule},
         "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
+                     "traffic_source": (None if traffic is None else
+                                        "stored: profiles/%s (two rocprofv3 --pmc passes, not this run)" % os.path.basename(traffic_file)),
                      "avg_launch_us": 1e3 * dom["total_ms"] / dom["launches"], "launches": dom["launches"],
                      "achievable_peak": mfma_ceiling, "frac_of_achievable": achieved / mfma_ceiling,
                      "all_gemm_tflops": tot_gemm_flops / (tot_gemm_ms * 1e-3) / 1e12},
@@ -329,12 +326,91 @@ def main():
         "actor_act_us": 1e6 * t_act,
         "kernels": kernels,
     }
-    if args.isolated:
+    if isolated:
         out["critic_only_updates_per_s"] = 1.0 / t_critic
         out["critic_only_mfma_util_pct"] = 100.0 * w.batch * fl["critic_update"] / t_critic / (PEAK_FP32_MFMA_TFLOPS * 1e12)
         out["actor_update_per_s"] = 1.0 / t_actor_upd
+    del sess, env_dev
+    torch.cuda.empty_cache()
+    return out, keep, env_host
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=800)
+    ap.add_argument("--warmup", type=int, default=80)
+    ap.add_argument("--workload", default="ant", choices=list(W.WORKLOADS))
+    ap.add_argument("--fill-rows", type=int, default=0, help="ring rows to fill before timing (0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=48)
+    ap.add_argument("--paper-defaults", action="store_true",
+                    help="switch on the two Table B.1 defaults that the five workloads leave off: observation "
+                         "standardisation and gradient clipping at 0.5")
+    ap.add_argument("--atoms", type=int, default=0,
+                    help="distributional critics (PQL-D) with this many atoms on (-10, 10); the paper uses 51")
+    ap.add_argument("--sac", action="store_true",
+                    help="PQL + SAC: tanh-Gaussian policy, soft target, learnable temperature")
+    ap.add_argument("--schedule", default="serial", choices=["serial", "parallel", "parallel-1stream"],
+                    help="serial: every call on one stream, networks shared by all parts (default).  parallel: the "
+                         "Actor, V-learner and P-learner on three streams with local network copies exchanged once "
+                         "per Actor step (Section 3.1 / 3.2), same 1 : 8 : 4 rates.  parallel-1stream: that schedule "
+                         "enqueued on one stream")
+    ap.add_argument("--no-isolated", dest="isolated", action="store_false",
+                    help="skip the extra loops that time the V-learner alone (sample + critic update + Polyak) and "
+                         "the policy update alone")
+    ap.add_argument("--no-secondary", dest="secondary", action="store_false",
+                    help="skip the second batch-8192 workload (humanoid-shaped) that the default run reports in "
+                         "the `secondary` block")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    if args.schedule != "serial" and (args.steps % ACTOR_EVERY or args.warmup % ACTOR_EVERY):
+        print("--steps and --warmup must be multiples of %d for the parallel schedule" % ACTOR_EVERY, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+
+    w = W.WORKLOADS[args.workload]
+    if args.paper_defaults:
+        w = w.replace(max_grad_norm=0.5, obs_norm=True)
+    if args.atoms >= 2:
+        w = w.replace(num_atoms=args.atoms)
+    if args.sac:
+        w = w.replace(sac=True)
+    variant = bool(args.paper_defaults or args.atoms or args.sac or args.schedule != "serial")
+    res, keep, env_host = run_workload(w, args, args.steps, args.warmup, args.profile_steps, args.isolated,
+                                       keep_rows=not args.no_cpu_baseline, schedule=args.schedule, variant=variant)
+    out = {"metric": "V-learner critic updates/s at batch %d" % w.batch, "value": res.pop("value"), "unit": res.pop("unit"),
+           "n_gpus": 1, "steps": res.pop("steps"), "warmup": res.pop("warmup"), "ms_per_step": res.pop("ms_per_step"),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
+    out.update(res)
+    if args.secondary and args.workload == "ant" and not variant:
+        # the other workload the metric's batch size names (humanoid-shaped, batch 8192), full ring, fewer steps
+        w2 = W.WORKLOADS["humanoid"]
+        r2, _, _ = run_workload(w2, args, 160, 16, 16, False, keep_rows=False)
+        out["secondary"] = {"metric": "V-learner critic updates/s at batch %d" % w2.batch, "value": r2["value"],
+                            "unit": r2["unit"], "steps": r2["steps"], "warmup": r2["warmup"], "ms_per_step": r2["ms_per_step"],
+                            "config": r2["config"], "roofline": r2["roofline"], "mfma_util_pct": r2["mfma_util_pct"],
+                            "actor_actions_per_s": r2["actor_actions_per_s"], "kernels": r2["kernels"]}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, keep, env_host, parallel=args.schedule != "serial")
+        cb = cpu_baseline(w, keep, env_host, parallel=args.schedule != "serial")
+        cb.update(host_info())
+        cb["cores"] = cb["blas_threads"] if cb["blas_threads"] > 1 else cb["cores"]
+        cb["actions_per_s"] = cpu_actions_per_s(w, env_host[0]["obs"])
+        if w.name in ("tiny", "ant") and args.schedule == "serial":
+            try:
+                from threadpoolctl import threadpool_limits
+                with threadpool_limits(limits=1):
+                    one = cpu_baseline(w, keep, env_host, budget_s=8.0)
+                cb["single_thread"] = {"value": one["value"], "unit": one["unit"], "cores": 1, "sample": one["sample"]}
+            except ImportError:
+                cb["single_thread"] = None
+        out["cpu_baseline"] = cb
     print(json.dumps(out))
 
 
