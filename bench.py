@@ -6,8 +6,12 @@ the paper's default rates (Table B.1 / Section 4: 8 critic updates per Actor ste
 update per 2 critic updates):
 
     every 8th step : pql_actor_act on N environments + pql_replay_push of that Actor step
-    every step     : pql_sample_nstep + pql_critic_update + pql_soft_update (Polyak on Q')
-    every 2nd step : pql_actor_update + hard sync of the lagged policy (pql_soft_update, tau = 1)
+    every step     : pql_sample_nstep + pql_critic_update + Polyak update of Q'
+    every 2nd step : pql_actor_update + hard copy of the policy into the lagged policy pi^v
+
+By default the Polyak update and the policy copy are performed by the optimiser kernel of the update they
+follow (pql_track_attach) and the transposed weights of the backward pass are kept between calls
+(pql_weight_cache_*); --plain-calls makes them the separate pql_soft_update calls / launches instead.
 
 All inputs are synthetic and resident in HBM before the timed region starts.  Prints ONE JSON
 line.  `value` = critic updates per second of that whole schedule.
@@ -179,6 +183,11 @@ def run_workload(w, args, steps, warmup, profile_steps, isolated, keep_rows, sch
     import torch
     from paper_2307_12983_amd.session import LearnerSession
     sess = LearnerSession(w)
+    if not args.plain_calls:
+        # the Polyak step of Q', the hard copy pi -> pi^v and the transposed weights of the next backward pass
+        # are produced by the optimiser kernels of the updates (pql_track_attach, pql_weight_cache_*): same
+        # results bit for bit, three small launches fewer per critic update and two per policy update
+        sess.fold_followups()
     rng = W.data_rng(w)
     n_fill = args.fill_rows or w.rows
     keep = []                                   # host copy of the filled rows for the CPU baseline
@@ -311,7 +320,8 @@ def run_workload(w, args, steps, warmup, profile_steps, isolated, keep_rows, sch
                                   if w.num_atoms >= 2 else "")
                                + ("; SAC variant (stochastic policy, learnable temperature)" if w.sac else ""),
                    "rows_filled": n_fill, "ring_bytes": n_fill * w.num_envs * (2 * w.obs_dim + w.act_dim + 2) * 4,
-                   "schedule": schedule},
+                   "schedule": schedule,
+                   "followups": "separate launches" if args.plain_calls else "folded into the optimiser kernels"},
         "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
                      "traffic_source": (None if traffic is None else
@@ -359,6 +369,10 @@ def main():
     ap.add_argument("--no-isolated", dest="isolated", action="store_false",
                     help="skip the extra loops that time the V-learner alone (sample + critic update + Polyak) and "
                          "the policy update alone")
+    ap.add_argument("--plain-calls", action="store_true",
+                    help="make the Polyak update, the policy copy and the weight transposes separate launches "
+                         "(pql_soft_update after every update, transposes inside it) instead of folding them into "
+                         "the optimiser kernels")
     ap.add_argument("--no-secondary", dest="secondary", action="store_false",
                     help="skip the second batch-8192 workload (humanoid-shaped) that the default run reports in "
                          "the `secondary` block")

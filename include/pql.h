@@ -308,6 +308,43 @@ int32_t pql_obs_norm_reset(pql_ctx* ctx, void* stream);
  * 0 <= tau <= 1. */
 int32_t pql_soft_update(pql_ctx* ctx, const float* src, float* dst, int64_t count, float tau, void* stream);
 
+/* ---- work that follows an optimiser step, folded into it ----------------------------------- */
+
+/* Algorithm 3 moves the target critics Q' towards Q after every critic update (Table B.1 target update
+ * rate), and Section 3.2 has the lagged policy pi^v follow pi by hard copies.  Done with pql_soft_update,
+ * each is one more pass over a few MB right after the optimiser's; while a vector is attached here, the
+ * optimiser kernel of the update itself performs it on the parameters it has just computed:
+ *   PQL_TRACK_CRITIC_TARGETS  at the end of every pql_critic_update: dst (2 * pql_critic_param_count floats)
+ *                             = tau * critic_params + (1 - tau) * dst.  dst may be the call's own
+ *                             critic_target_params (the target path has read them by then).
+ *   PQL_TRACK_LAGGED_POLICY   at the end of every pql_actor_update: dst (pql_actor_param_count floats)
+ *                             = tau * actor_params + (1 - tau) * dst (tau = 1: the hard copy).
+ * The result equals, bit for bit, that of pql_soft_update(params, dst, count, tau) enqueued right after the
+ * update; the caller then omits that call.  tau = 0 and dst = NULL switch it off.  With gradient clipping on,
+ * the update enqueues the separate pass itself (same result).  Host-side only.
+ * Errors: PQL_ERR_INVALID_ARG (unknown vector, tau outside [0, 1]). */
+#define PQL_TRACK_CRITIC_TARGETS 0
+#define PQL_TRACK_LAGGED_POLICY  1
+int32_t pql_track_attach(pql_ctx* ctx, int32_t which, float* dst, float tau);
+
+/* The backward products delta * W^T read transposed copies of the online critics' and the policy's weight
+ * matrices.  Without a cache every update transposes them into its workspace first (one small launch per
+ * call).  With a caller-owned [device] block of pql_weight_cache_bytes(cfg) bytes, 256-byte aligned,
+ * attached, the copies live there between calls: pql_weight_cache_refresh(ctx, critic_params, actor_params)
+ * fills it from the given vectors (either may be NULL) and remembers their addresses; a later
+ * pql_critic_update / pql_actor_update whose critic_params / actor_params argument is that same address
+ * reads the block instead of transposing, and the optimiser kernel writes the transposes of the parameters
+ * it has just updated back into it.  Calls with other parameter vectors (a snapshot, another network) are
+ * unaffected: they transpose into their workspace as before.
+ * The caller must call pql_weight_cache_refresh again after changing a remembered vector by any other
+ * means (a copy into it, pql_adam_step, pql_soft_update with it as dst, loading a checkpoint) and before
+ * the first update; attaching (also NULL, which detaches) forgets both vectors.  Results are the same with
+ * and without the cache, bit for bit.
+ * Errors: PQL_ERR_ALIGNMENT, PQL_ERR_NULL (refresh with no block attached). */
+int64_t pql_weight_cache_bytes(const pql_config* cfg);
+int32_t pql_weight_cache_attach(pql_ctx* ctx, void* cache);
+int32_t pql_weight_cache_refresh(pql_ctx* ctx, const float* critic_params, const float* actor_params, void* stream);
+
 /* ---- inspection aid ----------------------------------------------------------------------- */
 
 /* Where the per-row results of the last update lie inside that call's workspace (Algorithm 3: the

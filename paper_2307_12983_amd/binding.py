@@ -25,7 +25,8 @@ EXPORTS = ["pql_create", "pql_destroy", "pql_replay_rows", "pql_actor_param_coun
            "pql_soft_update", "pql_adam_step", "pql_profile_begin", "pql_profile_end",
            "pql_obs_norm_bytes", "pql_obs_norm_attach", "pql_obs_norm_reset", "pql_sample_states", "pql_sac_attach",
            "pql_sac_attach_lagged", "pql_probe_mfma", "pql_static_scratch_bytes", "pql_critic_update_static",
-           "pql_workspace_view"]
+           "pql_workspace_view", "pql_track_attach", "pql_weight_cache_bytes", "pql_weight_cache_attach",
+           "pql_weight_cache_refresh"]
 
 
 class PqlConfig(C.Structure):
@@ -103,6 +104,10 @@ def load_library() -> C.CDLL:
         "pql_obs_norm_bytes": (I64, [cfgp]),
         "pql_obs_norm_attach": (I32, [P, P, F]),
         "pql_obs_norm_reset": (I32, [P, P]),
+        "pql_track_attach": (I32, [P, I32, P, F]),
+        "pql_weight_cache_bytes": (I64, [cfgp]),
+        "pql_weight_cache_attach": (I32, [P, P]),
+        "pql_weight_cache_refresh": (I32, [P, P, P, P]),
         "pql_sac_attach": (I32, [P, P, F]),
         "pql_sac_attach_lagged": (I32, [P, P]),
         "pql_probe_mfma": (I32, [P, P, I32, I32, P]),
@@ -297,6 +302,18 @@ class Context:
 
     def pql_obs_norm_reset(self, stream=None):
         self._check(self.lib.pql_obs_norm_reset(self.h, _stream(stream)))
+
+    def pql_track_attach(self, which, dst, tau):
+        self._check(self.lib.pql_track_attach(self.h, which, _ptr(dst), tau))
+
+    def weight_cache_bytes(self) -> int:
+        return self.lib.pql_weight_cache_bytes(C.byref(self.cfg))
+
+    def pql_weight_cache_attach(self, cache):
+        self._check(self.lib.pql_weight_cache_attach(self.h, _ptr(cache)))
+
+    def pql_weight_cache_refresh(self, critic_params, actor_params, stream=None):
+        self._check(self.lib.pql_weight_cache_refresh(self.h, _ptr(critic_params), _ptr(actor_params), _stream(stream)))
 
     def pql_sac_attach(self, temperature, target_entropy):
         self._check(self.lib.pql_sac_attach(self.h, _ptr(temperature), target_entropy))

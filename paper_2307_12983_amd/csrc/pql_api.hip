@@ -122,6 +122,13 @@ struct pql_ctx {
     float* temperature;          // caller-owned device floats {log alpha, Adam m, Adam v, -} of the SAC variant, or NULL
     const float* temperature_v;  // the V-learner's copy of log alpha (defaults to the one above)
     float target_entropy;
+    // vectors that follow an optimiser step (index 0: the critics' targets, 1: the lagged policy), or NULL
+    float* track[2];
+    float track_tau[2];
+    // caller-owned block of transposed weights and the parameter vectors whose transposes it holds
+    float* wcache;
+    const float* wcache_critic;
+    const float* wcache_actor;
     std::string err;
 };
 
@@ -347,6 +354,27 @@ void make_layout(const pql_config* c, Layout& w) {
     w.total = off;
 }
 
+// Transposed weights kept between calls (pql_weight_cache_*): the same matrices the workspace holds as
+// wT / w1aT / woT / waT, in a block of the caller's.
+struct CacheLayout {
+    size_t wT[2][PQL_MAX_HIDDEN + 1], w1aT[2], woT[2], waT[PQL_MAX_HIDDEN + 1];
+    size_t total;
+};
+
+void make_cache_layout(const pql_config* c, CacheLayout& w) {
+    std::memset(&w, 0, sizeof(w));
+    const int L = c->n_hidden;
+    size_t off = 0;
+    auto take = [&](size_t n) { const size_t o = off; off += up(n); return o; };
+    for (int i = 0; i < 2; ++i) {
+        for (int l = 1; l < L; ++l) w.wT[i][l] = take((size_t)c->hidden[l - 1] * c->hidden[l]);
+        w.w1aT[i] = take((size_t)c->act_dim * c->hidden[0]);
+        w.woT[i] = take((size_t)critic_out(c) * c->hidden[L - 1]);
+    }
+    for (int l = 1; l <= L; ++l) w.waT[l] = take((size_t)c->hidden[l - 1] * (l < L ? c->hidden[l] : actor_out(c)));
+    w.total = off;
+}
+
 inline int vec_ok(const float* p, int ld) { return ((((uintptr_t)p) & 15) == 0 && (ld % 4) == 0) ? 1 : 0; }
 
 GemmProb prob(int M, int N, float* C, int ldc, int epi) {
@@ -416,7 +444,7 @@ hipError_t run_auto(int mode, std::vector<GemmProb>& ps, hipStream_t st) {
 // Weight-gradient problems: assigns split counts and slab addresses, launches, and appends one
 // reduction entry per problem.  `offsets[i]` is the parameter offset of problem i's tensor.
 hipError_t run_dw(std::vector<GemmProb>& ps, const std::vector<int64_t>& offsets, int K, float* slab,
-                  AdamArgs& ad, hipStream_t st) {
+                  AdamArgs& ad, hipStream_t st, const std::vector<float*>* tdst = nullptr) {
     if (ps.empty()) return hipSuccess;
     long tiles = 0;
     for (const GemmProb& p : ps) tiles += dw_tiles(p.M, p.N);
@@ -435,6 +463,7 @@ hipError_t run_dw(std::vector<GemmProb>& ps, const std::vector<int64_t>& offsets
         RedTensor& t = ad.t[ad.ntensors++];
         t.offset = offsets[i]; t.stride = p.split_stride; t.partial = slab;
         t.count = p.M * p.N; t.nparts = S;
+        if (tdst != nullptr && (*tdst)[i] != nullptr) { t.tdst = (*tdst)[i]; t.trows = p.M; t.tcols = p.N; }
         slab += (size_t)S * p.M * p.N;
     }
     return run(GEMM_TN, TILE_64x64, ps, nullptr, st);
@@ -465,6 +494,38 @@ struct FwdNet {
     float* out;
 };
 
+// Fills the critic part / the policy part of a block of transposed weights (layout `cl` at `dst`).
+hipError_t transpose_critic_weights(const pql_ctx* c, const float* critic_params, float* dst, const CacheLayout& cl,
+                                    hipStream_t st) {
+    const int L = c->L, o = c->cfg.obs_dim, ad = c->cfg.act_dim, H1 = c->cfg.hidden[0];
+    TransposeArgs tr;
+    tr.n = 0;
+    auto add = [&](const float* src, float* to, int rows, int cols) {
+        TransposeArgs::Mat& mt = tr.m[tr.n++];
+        mt.src = src; mt.dst = to; mt.rows = rows; mt.cols = cols;
+    };
+    for (int i = 0; i < 2; ++i) {
+        const float* q = critic_params + i * c->c_total;
+        for (int l = 1; l < L; ++l) add(q + c->c_w[l], dst + cl.wT[i][l], c->cfg.hidden[l - 1], c->cfg.hidden[l]);
+        add(q + c->c_w[0] + (int64_t)o * H1, dst + cl.w1aT[i], ad, H1);
+        if (distributional(&c->cfg)) add(q + c->c_w[L], dst + cl.woT[i], c->cfg.hidden[L - 1], c->cfg.num_atoms);
+    }
+    return transpose_launch(tr, st);
+}
+
+hipError_t transpose_actor_weights(const pql_ctx* c, const float* actor_params, float* dst, const CacheLayout& cl,
+                                   hipStream_t st) {
+    const int L = c->L;
+    TransposeArgs tr;
+    tr.n = 0;
+    for (int l = 1; l <= L; ++l) {
+        TransposeArgs::Mat& mt = tr.m[tr.n++];
+        mt.src = actor_params + c->a_w[l]; mt.dst = dst + cl.waT[l];
+        mt.rows = c->cfg.hidden[l - 1]; mt.cols = l < L ? c->cfg.hidden[l] : actor_out(&c->cfg);
+    }
+    return transpose_launch(tr, st);
+}
+
 }  // namespace
 
 // =============================================================================================
@@ -487,6 +548,10 @@ int32_t pql_create(const pql_config* cfg, pql_ctx** out) {
     c->temperature = nullptr;
     c->temperature_v = nullptr;
     c->target_entropy = 0.f;
+    c->track[0] = c->track[1] = nullptr;
+    c->track_tau[0] = c->track_tau[1] = 0.f;
+    c->wcache = nullptr;
+    c->wcache_critic = c->wcache_actor = nullptr;
     c->c_total = net_params(cfg->obs_dim + cfg->act_dim, cfg, critic_out(cfg), c->c_w, c->c_b);
     *out = c;
     return PQL_OK;
@@ -817,6 +882,14 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
     std::memset(&adm, 0, sizeof(adm));
     int head_parts = 0;
     const bool dist = distributional(&c->cfg);
+    // Transposed weights: from the caller's cache when it holds those of this parameter vector (then the
+    // optimiser kernel refreshes them at the end of the call), else transposed into the workspace here.
+    const bool cached = c->wcache != nullptr && c->wcache_critic == critic_params;
+    const bool clipped = opt.max_grad_norm > 0.f;
+    CacheLayout cl;
+    make_cache_layout(&c->cfg, cl);
+    auto WT = [&](int i, int l) { return cached ? c->wcache + cl.wT[i][l] : ws + w.wT[i][l]; };
+    auto WOT = [&](int i) { return cached ? c->wcache + cl.woT[i] : ws + w.woT[i]; };
     if (fused_ok(&c->cfg)) {
         // One launch per row tile: target path, forward, heads and backward data path.
         TransposeArgs tr;
@@ -834,10 +907,12 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
         }
         for (int i = 0; i < 2; ++i) {
             for (int l = 1; l < L; ++l) {
-                TransposeArgs::Mat& mt = tr.m[tr.n++];
-                mt.src = critic_params + i * Pc + c->c_w[l]; mt.dst = ws + w.wT[i][l];
-                mt.rows = c->cfg.hidden[l - 1]; mt.cols = c->cfg.hidden[l];
-                fa.wT[i][l] = ws + w.wT[i][l];
+                if (!cached) {
+                    TransposeArgs::Mat& mt = tr.m[tr.n++];
+                    mt.src = critic_params + i * Pc + c->c_w[l]; mt.dst = ws + w.wT[i][l];
+                    mt.rows = c->cfg.hidden[l - 1]; mt.cols = c->cfg.hidden[l];
+                }
+                fa.wT[i][l] = WT(i, l);
             }
             for (int l = 1; l <= L; ++l) {
                 fa.hQ[i][l] = ws + w.hQ[i][l]; fa.dQ[i][l] = ws + w.dQ[i][l]; fa.colQ[i][l] = ws + w.colQ[i][l];
@@ -851,9 +926,11 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
         if (dist) {
             fa.atoms = c->cfg.num_atoms; fa.v_min = c->cfg.v_min; fa.v_max = c->cfg.v_max;
             for (int i = 0; i < 2; ++i) {
-                TransposeArgs::Mat& mt = tr.m[tr.n++];
-                mt.src = critic_params + i * Pc + c->c_w[L]; mt.dst = ws + w.woT[i]; mt.rows = HL; mt.cols = fa.atoms;
-                fa.woT[i] = ws + w.woT[i]; fa.dlg[i] = ws + w.lgQ[i]; fa.p_dbo[i] = ws + w.p_dbo[i];
+                if (!cached) {
+                    TransposeArgs::Mat& mt = tr.m[tr.n++];
+                    mt.src = critic_params + i * Pc + c->c_w[L]; mt.dst = ws + w.woT[i]; mt.rows = HL; mt.cols = fa.atoms;
+                }
+                fa.woT[i] = WOT(i); fa.dlg[i] = ws + w.lgQ[i]; fa.p_dbo[i] = ws + w.p_dbo[i];
             }
         }
         if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
@@ -955,7 +1032,7 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
         // 5. backward data path: delta_{l-1} = (delta_l W_l^T) * ELU'(z_{l-1}), bias grads as column sums
         // Wide layers run on row tiles with W^T as a row-major B operand (transposed once per call);
         // the others take the LDS-tiled kernel on W itself.
-        bool transposed = false;
+        bool transposed = cached;
         for (int l = L; l >= 2; --l) {
             std::vector<GemmProb> ps, pt;
             const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
@@ -965,7 +1042,7 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
                 p.colsum = ws + w.colQ[i][l - 1];
                 GemmProb q = p;
                 add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
-                add_seg(q, ws + w.dQ[i][l], Hl, ws + w.wT[i][l - 1], Hp, Hl);
+                add_seg(q, ws + w.dQ[i][l], Hl, WT(i, l - 1), Hp, Hl);
                 ps.push_back(p); pt.push_back(q);
             }
             int parts;
@@ -997,21 +1074,25 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
     {
         std::vector<GemmProb> ps;
         std::vector<int64_t> offs;
+        std::vector<float*> tds;         // where the optimiser kernel leaves the transposed copy of the updated tensor
+        const bool keep_t = cached && !clipped;
         for (int i = 0; i < 2; ++i) {
             for (int l = 1; l <= L; ++l) {
                 const int Hl = c->cfg.hidden[l - 1];
                 if (l == 1) {
                     GemmProb p = prob(o, Hl, nullptr, Hl, EPI_STORE);
                     add_seg(p, batch.obs, o, ws + w.dQ[i][1], Hl, B);
-                    ps.push_back(p); offs.push_back(i * Pc + c->c_w[0]);
+                    ps.push_back(p); offs.push_back(i * Pc + c->c_w[0]); tds.push_back(nullptr);
                     GemmProb p2 = prob(ad, Hl, nullptr, Hl, EPI_STORE);
                     add_seg(p2, batch.act, ad, ws + w.dQ[i][1], Hl, B);
                     ps.push_back(p2); offs.push_back(i * Pc + c->c_w[0] + (int64_t)o * Hl);
+                    tds.push_back(keep_t ? c->wcache + cl.w1aT[i] : nullptr);
                 } else {
                     const int Hp = c->cfg.hidden[l - 2];
                     GemmProb p = prob(Hp, Hl, nullptr, Hl, EPI_STORE);
                     add_seg(p, ws + w.hQ[i][l - 1], Hp, ws + w.dQ[i][l], Hl, B);
                     ps.push_back(p); offs.push_back(i * Pc + c->c_w[l - 1]);
+                    tds.push_back(keep_t ? c->wcache + cl.wT[i][l - 1] : nullptr);
                 }
             }
             if (dist) {
@@ -1019,9 +1100,10 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
                 GemmProb p = prob(HL, la, nullptr, la, EPI_STORE);
                 add_seg(p, ws + w.hQ[i][L], HL, ws + w.lgQ[i], la, B);
                 ps.push_back(p); offs.push_back(i * Pc + c->c_w[L]);
+                tds.push_back(keep_t ? c->wcache + cl.woT[i] : nullptr);
             }
         }
-        if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st)) != hipSuccess) return E.hip(e, who);
+        if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st, &tds)) != hipSuccess) return E.hip(e, who);
     }
     // 7. remaining reductions (last hidden bias, output layer) + Adam + loss scalars
     for (int i = 0; i < 2; ++i) {
@@ -1037,8 +1119,17 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
     adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
     adm.theta = critic_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
     adm.max_norm = opt.max_grad_norm; adm.sq_partial = ws + w.sqp; adm.norm_out = loss_out + 2;
+    // what follows the step (target tracking, transposed weights for the next call) rides on the optimiser
+    // kernel's pass; a clipped step ends in a kernel of its own, after which both are launched separately
+    const bool tracked = c->track[0] != nullptr && c->track_tau[0] > 0.f;
+    if (tracked && !clipped) { adm.track = c->track[0]; adm.tau = c->track_tau[0]; }
     fill_adam(adm, opt, c->critic_t + 1);
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
+    if (clipped) {
+        if (tracked && (e = soft_update_launch(critic_params, c->track[0], 2 * Pc, c->track_tau[0], st)) != hipSuccess)
+            return E.hip(e, who);
+        if (cached && (e = transpose_critic_weights(c, critic_params, c->wcache, cl, st)) != hipSuccess) return E.hip(e, who);
+    }
     c->critic_t += 1;
     return PQL_OK;
 }
@@ -1116,6 +1207,16 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     const int aw = actor_out(&c->cfg);                          // width of the policy's output layer
     const float* d_top = sac ? ws + w.dOut : ws + w.dPre;       // gradient at that layer
     int logp_parts = (B + SAC_ROWS - 1) / SAC_ROWS;             // partial sums of log pi (stochastic policy)
+    // Transposed weights from the caller's cache where it holds those of these parameter vectors
+    const bool cached_q = c->wcache != nullptr && c->wcache_critic == critic_params;
+    const bool cached_a = c->wcache != nullptr && c->wcache_actor == actor_params;
+    const bool clipped = opt.max_grad_norm > 0.f;
+    CacheLayout cl;
+    make_cache_layout(&c->cfg, cl);
+    auto WT = [&](int i, int l) { return cached_q ? c->wcache + cl.wT[i][l] : ws + w.wT[i][l]; };
+    auto W1AT = [&](int i) { return cached_q ? c->wcache + cl.w1aT[i] : ws + w.w1aT[i]; };
+    auto WOT = [&](int i) { return cached_q ? c->wcache + cl.woT[i] : ws + w.woT[i]; };
+    auto WAT = [&](int l) { return cached_a ? c->wcache + cl.waT[l] : ws + w.waT[l]; };
     if (fused_ok(&c->cfg)) {
         TransposeArgs tr;
         tr.n = 0;
@@ -1133,22 +1234,22 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
         };
         for (int i = 0; i < 2; ++i) {
             for (int l = 1; l < L; ++l) {
-                add_tr(critic_params + i * Pc + c->c_w[l], ws + w.wT[i][l], c->cfg.hidden[l - 1], c->cfg.hidden[l]);
-                fa.wT[i][l] = ws + w.wT[i][l];
+                if (!cached_q) add_tr(critic_params + i * Pc + c->c_w[l], ws + w.wT[i][l], c->cfg.hidden[l - 1], c->cfg.hidden[l]);
+                fa.wT[i][l] = WT(i, l);
             }
-            add_tr(critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, ws + w.w1aT[i], ad, H1);
-            fa.w1aT[i] = ws + w.w1aT[i];
+            if (!cached_q) add_tr(critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, ws + w.w1aT[i], ad, H1);
+            fa.w1aT[i] = W1AT(i);
             for (int l = 1; l <= L; ++l) fa.hQ[i][l] = ws + w.hQ[i][l];
             fa.q_out[i] = ws + w.q[i];
             if (distributional(&c->cfg)) {
-                add_tr(critic_params + i * Pc + c->c_w[L], ws + w.woT[i], HL, c->cfg.num_atoms);
-                fa.woT[i] = ws + w.woT[i];
+                if (!cached_q) add_tr(critic_params + i * Pc + c->c_w[L], ws + w.woT[i], HL, c->cfg.num_atoms);
+                fa.woT[i] = WOT(i);
             }
         }
         if (distributional(&c->cfg)) { fa.atoms = c->cfg.num_atoms; fa.v_min = c->cfg.v_min; fa.v_max = c->cfg.v_max; }
         for (int l = 1; l <= L; ++l) {
-            add_tr(actor_params + c->a_w[l], ws + w.waT[l], c->cfg.hidden[l - 1], l < L ? c->cfg.hidden[l] : aw);
-            fa.waT[l] = ws + w.waT[l];
+            if (!cached_a) add_tr(actor_params + c->a_w[l], ws + w.waT[l], c->cfg.hidden[l - 1], l < L ? c->cfg.hidden[l] : aw);
+            fa.waT[l] = WAT(l);
             fa.hA[l] = ws + w.hA[l]; fa.dA[l] = ws + w.dA[l]; fa.colA[l] = ws + w.colA[l];
         }
         fa.colA[L + 1] = ws + w.colA[L + 1];
@@ -1225,7 +1326,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
         }
         // 4. critic backward data path down to layer 1 (wide layers on row tiles with W^T as a
         //    row-major B operand, transposed once per call; the others on the LDS-tiled kernel)
-        bool transposed_q = false;
+        bool transposed_q = cached_q;
         for (int l = L; l >= 2; --l) {
             std::vector<GemmProb> ps, pt;
             const int Hl = c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
@@ -1234,7 +1335,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
                 p.aux = ws + w.hQ[i][l - 1]; p.ldaux = Hp;
                 GemmProb q = p;
                 add_seg(p, ws + w.dQ[i][l], Hl, critic_params + i * Pc + c->c_w[l - 1], Hl, Hl);
-                add_seg(q, ws + w.dQ[i][l], Hl, ws + w.wT[i][l - 1], Hp, Hl);
+                add_seg(q, ws + w.dQ[i][l], Hl, WT(i, l - 1), Hp, Hl);
                 ps.push_back(p); pt.push_back(q);
             }
             if (takes_row_tiles(pt)) {
@@ -1264,14 +1365,14 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
             GemmProb q = p;
             for (int i = 0; i < 2; ++i) {
                 add_seg(p, ws + w.dQ[i][1], H1, critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1, H1, H1);
-                add_seg(q, ws + w.dQ[i][1], H1, ws + w.w1aT[i], ad, H1);
+                add_seg(q, ws + w.dQ[i][1], H1, W1AT(i), ad, H1);
             }
             ps.push_back(p); pt.push_back(q);
             int parts;
             if (takes_narrow_tiles(pt)) {      // on row tiles, with the action rows of W_1 transposed
                 TransposeArgs tr;
                 tr.n = 0;
-                for (int i = 0; i < 2; ++i) {
+                for (int i = 0; i < 2 && !cached_q; ++i) {
                     TransposeArgs::Mat& mt = tr.m[tr.n++];
                     mt.src = critic_params + i * Pc + c->c_w[0] + (int64_t)o * H1; mt.dst = ws + w.w1aT[i];
                     mt.rows = ad; mt.cols = H1;
@@ -1294,7 +1395,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
             red(adm, c->a_b[L], ws + w.p_sc, aw, (B + SAC_ROWS - 1) / SAC_ROWS, aw);
         }
         // 6. policy backward data path
-        bool transposed_a = false;
+        bool transposed_a = cached_a;
         for (int l = L + 1; l >= 2; --l) {
             std::vector<GemmProb> ps, pt;
             const int Hl = (l == L + 1) ? aw : c->cfg.hidden[l - 1], Hp = c->cfg.hidden[l - 2];
@@ -1303,7 +1404,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
             p.colsum = ws + w.colA[l - 1];
             GemmProb q = p;
             add_seg(p, (l == L + 1) ? d_top : ws + w.dA[l], Hl, actor_params + c->a_w[l - 1], Hl, Hl);
-            add_seg(q, (l == L + 1) ? d_top : ws + w.dA[l], Hl, ws + w.waT[l - 1], Hp, Hl);
+            add_seg(q, (l == L + 1) ? d_top : ws + w.dA[l], Hl, WAT(l - 1), Hp, Hl);
             ps.push_back(p); pt.push_back(q);
             int parts;
             if (takes_row_tiles(pt)) {
@@ -1332,21 +1433,30 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     {
         std::vector<GemmProb> ps;
         std::vector<int64_t> offs;
+        std::vector<float*> tds;         // transposed copies of W_1 .. W_L left by the optimiser kernel
         for (int l = 1; l <= L + 1; ++l) {
             const int Hl = (l == L + 1) ? aw : c->cfg.hidden[l - 1];
             const int Hp = (l == 1) ? o : c->cfg.hidden[l - 2];
             GemmProb p = prob(Hp, Hl, nullptr, Hl, EPI_STORE);
             add_seg(p, (l == 1) ? obs : ws + w.hA[l - 1], Hp, (l == L + 1) ? d_top : ws + w.dA[l], Hl, B);
             ps.push_back(p); offs.push_back(c->a_w[l - 1]);
+            tds.push_back((cached_a && !clipped && l >= 2) ? c->wcache + cl.waT[l - 1] : nullptr);
         }
-        if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st)) != hipSuccess) return E.hip(e, who);
+        if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st, &tds)) != hipSuccess) return E.hip(e, who);
     }
     adm.nloss = 1; adm.loss_parts = loss_parts; adm.loss_scale = -1.f / (float)B;
     adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
     adm.theta = actor_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
     adm.max_norm = opt.max_grad_norm; adm.sq_partial = ws + w.sqp; adm.norm_out = loss_out + 1;
+    const bool tracked = c->track[1] != nullptr && c->track_tau[1] > 0.f;
+    if (tracked && !clipped) { adm.track = c->track[1]; adm.tau = c->track_tau[1]; }
     fill_adam(adm, opt, c->actor_t + 1);
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
+    if (clipped) {
+        if (tracked && (e = soft_update_launch(actor_params, c->track[1], c->a_total, c->track_tau[1], st)) != hipSuccess)
+            return E.hip(e, who);
+        if (cached_a && (e = transpose_actor_weights(c, actor_params, c->wcache, cl, st)) != hipSuccess) return E.hip(e, who);
+    }
     if (sac) {      // temperature step on the log-densities of this batch
         SacAlphaArgs al;
         al.B = B; al.nparts = logp_parts; al.p_logp = ws + w.p_lp; al.temperature = c->temperature;
@@ -1440,6 +1550,56 @@ int32_t pql_sac_attach_lagged(pql_ctx* c, const float* log_alpha) {
     Err E{c};
     if (!c->cfg.stochastic_policy) return E.fail(PQL_ERR_INVALID_ARG, "pql_sac_attach_lagged: the policy of this context is deterministic");
     c->temperature_v = log_alpha ? log_alpha : c->temperature;
+    return PQL_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+int32_t pql_track_attach(pql_ctx* c, int32_t which, float* dst, float tau) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (which != PQL_TRACK_CRITIC_TARGETS && which != PQL_TRACK_LAGGED_POLICY)
+        return E.fail(PQL_ERR_INVALID_ARG, "pql_track_attach: unknown vector");
+    if (dst != nullptr && (!(tau >= 0.f) || tau > 1.f)) return E.fail(PQL_ERR_INVALID_ARG, "pql_track_attach: tau outside [0, 1]");
+    c->track[which] = dst;
+    c->track_tau[which] = dst ? tau : 0.f;
+    return PQL_OK;
+}
+
+int64_t pql_weight_cache_bytes(const pql_config* cfg) {
+    const int rc = validate_cfg(cfg);
+    if (rc != PQL_OK) return rc;
+    CacheLayout cl;
+    make_cache_layout(cfg, cl);
+    return (int64_t)(cl.total * sizeof(float));
+}
+
+int32_t pql_weight_cache_attach(pql_ctx* c, void* cache) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (cache && (((uintptr_t)cache) & 255)) return E.fail(PQL_ERR_ALIGNMENT, "pql_weight_cache_attach: block not 256-byte aligned");
+    c->wcache = (float*)cache;
+    c->wcache_critic = c->wcache_actor = nullptr;       // nothing in the block is current yet
+    return PQL_OK;
+}
+
+int32_t pql_weight_cache_refresh(pql_ctx* c, const float* critic_params, const float* actor_params, void* stream) {
+    if (!c) return PQL_ERR_NULL;
+    Err E{c};
+    if (!c->wcache) return E.fail(PQL_ERR_NULL, "pql_weight_cache_refresh: no block attached");
+    CacheLayout cl;
+    make_cache_layout(&c->cfg, cl);
+    hipError_t e;
+    c->wcache_critic = c->wcache_actor = nullptr;
+    if (critic_params) {
+        if ((e = transpose_critic_weights(c, critic_params, c->wcache, cl, (hipStream_t)stream)) != hipSuccess)
+            return E.hip(e, "pql_weight_cache_refresh");
+        c->wcache_critic = critic_params;
+    }
+    if (actor_params) {
+        if ((e = transpose_actor_weights(c, actor_params, c->wcache, cl, (hipStream_t)stream)) != hipSuccess)
+            return E.hip(e, "pql_weight_cache_refresh");
+        c->wcache_actor = actor_params;
+    }
     return PQL_OK;
 }
 

@@ -121,6 +121,10 @@ struct RedTensor {
     int nparts;
     int block_begin;        // first workgroup of this tensor (filled by adam_reduce_launch)
     int qlog2;              // log2 of the number of lanes that share one element's partial sum
+    // Optional transposed copy of the updated parameters: the tensor read as [trows][tcols] row-major
+    // goes to tdst[tcols][trows] (the B operand of the next backward products); NULL: none.
+    float* tdst;
+    int trows, tcols;
 };
 
 constexpr int RED_MAX_TENSORS = 48;
@@ -139,6 +143,10 @@ struct AdamArgs {
     float max_norm;
     float* sq_partial;      // at least adam_reduce_blocks(a) floats
     float* norm_out;        // receives the norm before clipping
+    // Optional tracking vector (target network, lagged policy), updated in the same pass (unclipped
+    // steps only): track[k] = tau * theta_new[k] + (1 - tau) * track[k]; NULL: none.
+    float* track;
+    float tau;
     RedTensor t[RED_MAX_TENSORS];
 };
 
@@ -239,6 +247,11 @@ struct SampleArgs {
 hipError_t sample_launch(const SampleArgs& a, hipStream_t stream);
 
 hipError_t soft_update_launch(const float* src, float* dst, int64_t count, float tau, hipStream_t stream);
+// dst <- tau * src + (1 - tau) * dst, one rounding per operation in this order everywhere it is computed
+// (the stand-alone kernel and the optimiser kernel's tracking epilogue give the same bits).
+__device__ inline float polyak_mix(float tau, float keep, float src, float dst) {
+    return __fmaf_rn(tau, src, __fmul_rn(keep, dst));
+}
 
 // ---- running observation statistics --------------------------------------------------------
 // Device block handed over by the caller (all offsets in bytes from its 256-byte aligned start):

@@ -525,10 +525,12 @@ __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
     float g = 0.f;
     // the optimiser state is requested first: its latency hides behind the partial sums
     const bool step_here = live && q == 0 && !(a.max_norm > 0.f);
-    float m_old = 0.f, v_old = 0.f, th_old = 0.f;
+    const bool track = step_here && a.track != nullptr;
+    float m_old = 0.f, v_old = 0.f, th_old = 0.f, tr_old = 0.f;
     if (step_here) {
         const int64_t k = T.offset + i;
         m_old = a.m[k]; v_old = a.v[k]; th_old = a.theta[k];
+        if (track) tr_old = a.track[k];
     }
     if (live) {
         const float* __restrict__ p = T.partial + i;
@@ -571,10 +573,18 @@ __global__ __launch_bounds__(256) void adam_reduce_kernel(const AdamArgs a) {
         const float v = a.beta2 * v_old + (1.f - a.beta2) * g * g;
         const float m_hat = m * a.inv_bc1;
         const float v_hat = v * a.inv_bc2;
-        a.theta[k] = th_old - a.lr * m_hat / (sqrtf(v_hat) + a.eps);
+        const float th = th_old - a.lr * m_hat / (sqrtf(v_hat) + a.eps);
+        a.theta[k] = th;
         a.m[k] = m;
         a.v[k] = v;
         if (a.g != nullptr) a.g[k] = g;
+        // what usually follows the step, in the same pass: the tracking vector (Polyak / hard copy) and the
+        // transposed copy of the weights that the next backward products read
+        if (track) a.track[k] = a.tau == 1.f ? th : polyak_mix(a.tau, 1.f - a.tau, th, tr_old);
+        if (T.tdst != nullptr) {
+            const int r = i / T.tcols, cc = i - r * T.tcols;
+            T.tdst[(size_t)cc * (size_t)T.trows + r] = th;
+        }
     }
     if (b == 0) {
         const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -629,9 +639,12 @@ __global__ __launch_bounds__(256) void adam_clip_kernel(const AdamClipArgs a) {
 // Algorithmic traffic of the optimiser: read theta, g, m, v and write theta, m, v = 28 bytes per
 // parameter (the partial-sum reads that replace the single read of g are not counted).
 double adam_bytes(const AdamArgs& a) {
-    double n = 0.0;
-    for (int i = 0; i < a.ntensors; ++i) n += a.t[i].count;
-    return 28.0 * n;
+    double n = 0.0, extra = 0.0;
+    for (int i = 0; i < a.ntensors; ++i) {
+        n += a.t[i].count;
+        if (a.t[i].tdst != nullptr) extra += 4.0 * a.t[i].count;     // the transposed copy
+    }
+    return (a.track != nullptr ? 36.0 : 28.0) * n + extra;           // tracking vector: one more read and write
 }
 
 hipError_t adam_reduce_launch(const AdamArgs& args, hipStream_t stream) {
@@ -681,11 +694,11 @@ __global__ __launch_bounds__(256) void soft_update_kernel(const float* __restric
     for (int64_t i = t0; i < n4; i += stride) {
         const float4 s = reinterpret_cast<const float4*>(src)[i];
         float4 d = reinterpret_cast<float4*>(dst)[i];
-        d.x = tau * s.x + keep * d.x; d.y = tau * s.y + keep * d.y;
-        d.z = tau * s.z + keep * d.z; d.w = tau * s.w + keep * d.w;
+        d.x = polyak_mix(tau, keep, s.x, d.x); d.y = polyak_mix(tau, keep, s.y, d.y);
+        d.z = polyak_mix(tau, keep, s.z, d.z); d.w = polyak_mix(tau, keep, s.w, d.w);
         reinterpret_cast<float4*>(dst)[i] = d;
     }
-    for (int64_t i = n4 * 4 + t0; i < n; i += stride) dst[i] = tau * src[i] + keep * dst[i];
+    for (int64_t i = n4 * 4 + t0; i < n; i += stride) dst[i] = polyak_mix(tau, keep, src[i], dst[i]);
 }
 
 __global__ __launch_bounds__(256) void copy_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n,

@@ -48,12 +48,32 @@ class LearnerSession:
             self.temperature = torch.tensor([float(np.log(np.float64(w.init_alpha))), 0.0, 0.0, 0.0], dtype=torch.float32,
                                             device=device)
             self.ctx.pql_sac_attach(self.temperature, w.target_entropy)
+        self.folded = False
         self.obs_stats = None
         if w.obs_norm:
             self.obs_stats = torch.zeros(self.ctx.obs_norm_bytes() // 8 + 32, dtype=torch.float64, device=device)
             assert self.obs_stats.data_ptr() % 256 == 0
             self.ctx.pql_obs_norm_attach(self.obs_stats, w.obs_norm_eps)
             self.ctx.pql_obs_norm_reset()
+
+    def fold_followups(self, on: bool = True):
+        """Lets the optimiser kernels carry what follows them in the plain call sequence: the Polyak step of
+        the target critics, the hard copy into the lagged policy and the transposed weights of the next
+        backward pass (pql_track_attach, pql_weight_cache_*).  soft_update_targets() and
+        sync_lagged_policy() then have nothing left to do."""
+        torch = self.torch
+        self.folded = bool(on)
+        if not on:
+            self.ctx.pql_track_attach(0, None, 0.0)
+            self.ctx.pql_track_attach(1, None, 0.0)
+            self.ctx.pql_weight_cache_attach(None)
+            return
+        self.weight_cache = torch.zeros(self.ctx.weight_cache_bytes() // 4 + 64, dtype=torch.float32, device=self.device)
+        assert self.weight_cache.data_ptr() % 256 == 0
+        self.ctx.pql_weight_cache_attach(self.weight_cache)
+        self.ctx.pql_weight_cache_refresh(self.critic, self.actor)
+        self.ctx.pql_track_attach(0, self.critic_target, self.w.tau)
+        self.ctx.pql_track_attach(1, self.actor_lag, 1.0)
 
     def obs_statistics(self):
         """(count, mean[o], m2[o]) in float64 and (mean32[o], rstd32[o]) as stored on the device."""
@@ -84,6 +104,8 @@ class LearnerSession:
                                    self.workspace, stream)
 
     def soft_update_targets(self, stream=None):
+        if self.folded:
+            return                          # done by pql_critic_update's optimiser kernel
         self.ctx.pql_soft_update(self.critic, self.critic_target, self.critic.numel(), self.w.tau, stream)
 
     def actor_update(self, obs=None, batch_size: Optional[int] = None, stream=None):
@@ -92,6 +114,8 @@ class LearnerSession:
                                   int(batch_size or self.w.batch), self.opt, self.actor_loss, self.workspace, stream)
 
     def sync_lagged_policy(self, stream=None):
+        if self.folded:
+            return                          # done by pql_actor_update's optimiser kernel
         self.ctx.pql_soft_update(self.actor, self.actor_lag, self.actor.numel(), 1.0, stream)
 
     def act(self, obs, sigma_min=None, sigma_max=None, stream=None):

@@ -26,7 +26,7 @@ def cfg_of(w, max_batch=None):
 def test_library_exports_every_declared_symbol():
     lib = B.load_library()
     names = header_functions()
-    assert len(names) == 29 and sorted(B.EXPORTS) == names
+    assert len(names) == 33 and sorted(B.EXPORTS) == names
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -239,4 +239,26 @@ def test_workspace_view_offsets():
     off = C.c_int64(0)
     assert lib.pql_workspace_view(C.byref(ctx.cfg), 3, C.byref(off)) == -1
     assert lib.pql_workspace_view(C.byref(ctx.cfg), 0, None) == -2
+    ctx.close()
+
+
+def test_followup_attachments_are_validated_on_the_host():
+    lib = B.load_library()
+    w = W.WORKLOADS["ant"]
+    ctx = B.Context(cfg_of(w))
+    p = C.c_void_p(0x1000)
+    assert lib.pql_track_attach(ctx.h, 2, p, 0.5) == -1                       # unknown vector
+    assert lib.pql_track_attach(ctx.h, 0, p, 1.5) == -1
+    assert lib.pql_track_attach(ctx.h, 0, p, -0.1) == -1
+    assert lib.pql_track_attach(ctx.h, 0, p, 0.05) == 0 and lib.pql_track_attach(ctx.h, 1, p, 1.0) == 0
+    assert lib.pql_track_attach(ctx.h, 0, None, 7.0) == 0                     # detaching ignores tau
+    n = ctx.weight_cache_bytes()
+    # per critic: W_2^T (256 x 256), the action rows of W_1 (8 x 256), W_out (256 x 1); the policy's W_2^T, W_out^T
+    assert n == 4 * (2 * (256 * 256 + 8 * 256 + 256) + 256 * 256 + 256 * 8)
+    assert lib.pql_weight_cache_refresh(ctx.h, p, p, None) == -2              # nothing attached
+    assert lib.pql_weight_cache_attach(ctx.h, C.c_void_p(0x1010)) == -6
+    assert lib.pql_weight_cache_attach(ctx.h, None) == 0
+    bad = cfg_of(w)
+    bad.n_hidden = 0
+    assert lib.pql_weight_cache_bytes(C.byref(bad)) == -1
     ctx.close()

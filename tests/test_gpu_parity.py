@@ -388,11 +388,14 @@ def test_one_update_full_size(torch_cuda, name):
 
 
 # ---------------------------------------------------------------------------------------------
-def many_steps(torch, w, rows, steps, actor_every=0, must_run=()):
-    """`must_run`: kernels that the library's own per-launch profile must name during the first iteration
-    that holds every kind of update."""
+def many_steps(torch, w, rows, steps, actor_every=0, must_run=(), must_not_run=(), fold=False):
+    """`must_run` / `must_not_run`: kernels that the library's own per-launch profile must / must not name
+    during the first iteration that holds every kind of update.  `fold`: the Polyak step, the policy copy
+    and the transposes ride on the optimiser kernels (LearnerSession.fold_followups)."""
     s, ring, nz = make_session(w), oracle_ring(w), oracle_normalizer(w)
     fill_both(s, ring, w, rows, normalizer=nz)
+    if fold:
+        s.fold_followups()
     L = oracle_learner(w, s.actor_init, s.critic_init)
     Bsz = w.batch
     worst_loss = 0.0
@@ -416,6 +419,7 @@ def many_steps(torch, w, rows, steps, actor_every=0, must_run=()):
             ran = {k["name"]: k["launches"] for k in s.ctx.pql_profile_end()}
             say("  kernels of iteration", it, ran)
             assert set(must_run) <= set(ran), "expected kernels did not run: %s" % sorted(set(must_run) - set(ran))
+            assert not (set(must_not_run) & set(ran)), "kernels that should be gone: %s" % sorted(set(must_not_run) & set(ran))
         if it % 10 == 9 or it == steps - 1:
             e = rel_err(s.critic_loss.cpu().numpy(), losses)
             worst_loss = max(worst_loss, e)
@@ -795,6 +799,110 @@ def test_runs_are_bit_reproducible_and_resumable(torch_cuda):
     for x, y, z in zip(a, b, c):
         assert torch.equal(x, y), "two identical runs differ"
         assert torch.equal(x, z), "resumed run differs"
+
+
+def transposed_blocks(s, w):
+    """What the block of transposed weights must hold for the session's current parameters, in the order
+    the library lays it out (each matrix starts on a 256-byte boundary)."""
+    torch = s.torch
+    up = lambda n: (n + 63) // 64 * 64
+    out, off = [], 0
+    Pc = s.critic.numel() // 2
+    o, a, H = w.obs_dim, w.act_dim, w.hidden
+    outs = w.num_atoms if w.num_atoms >= 2 else 1
+    for i in range(2):
+        q = s.critic[i * Pc:(i + 1) * Pc]
+        pos = (o + a) * H[0] + H[0]
+        for l in range(1, len(H)):
+            out.append((off, q[pos:pos + H[l - 1] * H[l]].view(H[l - 1], H[l]).t().contiguous().view(-1)))
+            off += up(H[l - 1] * H[l]); pos += H[l - 1] * H[l] + H[l]
+        out.append((off, q[o * H[0]:(o + a) * H[0]].view(a, H[0]).t().contiguous().view(-1)))
+        off += up(a * H[0])
+        if w.num_atoms >= 2:
+            out.append((off, q[pos:pos + H[-1] * outs].view(H[-1], outs).t().contiguous().view(-1)))
+        off += up(outs * H[-1])
+    pos = o * H[0] + H[0]
+    aw = 2 * a if w.sac else a
+    for l in range(1, len(H) + 1):
+        cols = H[l] if l < len(H) else aw
+        out.append((off, s.actor[pos:pos + H[l - 1] * cols].view(H[l - 1], cols).t().contiguous().view(-1)))
+        off += up(H[l - 1] * cols); pos += H[l - 1] * cols + cols
+    return out, off
+
+
+FOLD_CASES = {
+    "ant_s": lambda: SMALL["ant_s"],
+    "fused_l3": lambda: SMALL["fused_l3"],
+    "humanoid_s": lambda: SMALL["humanoid_s"],
+    "layer_tiles": lambda: SMALL["layer_tiles"].replace(batch=8195),
+    "fused_l3_dist": lambda: distributional(SMALL["fused_l3"], 33, -3.0, 3.0),
+    "ragged_dist": lambda: distributional(SMALL["ragged"], 11, -4.0, 4.0),
+    "ant_s_sac": lambda: with_sac(SMALL["ant_s"]),
+    "ant_s_clipped": lambda: paper_defaults(SMALL["ant_s"]),
+    "humanoid_s_clipped": lambda: paper_defaults(SMALL["humanoid_s"], 0.01),
+}
+
+
+@pytest.mark.parametrize("case", list(FOLD_CASES))
+def test_folded_followups_equal_the_separate_calls(torch_cuda, case):
+    """pql_track_attach + pql_weight_cache_*: the Polyak step of the target critics, the hard copy into the
+    lagged policy and the transposed weights ride on the optimiser kernels.  Against a second session that
+    makes the separate calls (pql_soft_update twice, transposes inside every update): every parameter,
+    target, moment and loss bit for bit over six critic and three policy updates, and the block of
+    transposed weights equals the transposes of the current parameters after every step."""
+    torch = torch_cuda
+    w = FOLD_CASES[case]()
+    a, b = make_session(w), make_session(w)
+    nz = oracle_normalizer(w)
+    fill_both(a, oracle_ring(w), w, min(w.rows, w.nstep + 4), normalizer=nz)
+    fill_both(b, oracle_ring(w), w, min(w.rows, w.nstep + 4))
+    b.fold_followups()
+    assert b.ctx.weight_cache_bytes() == 4 * transposed_blocks(b, w)[1]
+    for it in range(6):
+        for s in (a, b):
+            s.sample(w.batch)
+            s.critic_update(w.batch)
+            s.soft_update_targets()                       # a: pql_soft_update; b: nothing left to do
+            if it % 2 == 1:
+                s.actor_update(None, w.batch)
+                s.sync_lagged_policy()
+        torch.cuda.synchronize()
+        for name in ("critic", "critic_target", "actor", "actor_lag", "c_m", "c_v", "c_g", "a_m", "a_v", "a_g",
+                     "critic_out", "actor_out"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), "%s differs after step %d" % (name, it)
+        for off, ref in transposed_blocks(b, w)[0]:
+            assert torch.equal(b.weight_cache[off:off + ref.numel()], ref), "transposed weights at %d, step %d" % (off, it)
+    # a parameter vector changed behind the library's back needs a refresh; after it the two agree again
+    for s in (a, b):
+        s.critic.mul_(0.5)
+        s.actor.mul_(-1.0)
+    b.ctx.pql_weight_cache_refresh(b.critic, b.actor)
+    for s in (a, b):
+        s.sample(w.batch)
+        s.critic_update(w.batch)
+        s.soft_update_targets()
+        s.actor_update(None, w.batch)
+        s.sync_lagged_policy()
+    torch.cuda.synchronize()
+    for name in ("critic", "critic_target", "actor", "actor_lag"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), "%s differs after the refresh" % name
+    # another parameter vector (a snapshot) is not served from the block
+    snap = b.critic.clone()
+    b.ctx.pql_actor_update(b.actor, snap, b.a_m, b.a_v, b.a_g, b.batch.obs, w.batch, b.opt, b.actor_loss, b.workspace)
+    a.ctx.pql_actor_update(a.actor, a.critic, a.a_m, a.a_v, a.a_g, a.batch.obs, w.batch, a.opt, a.actor_loss, a.workspace)
+    a.sync_lagged_policy()
+    torch.cuda.synchronize()
+    assert torch.equal(a.actor, b.actor) and torch.equal(a.actor_lag, b.actor_lag)
+
+
+def test_folded_followups_100_steps_against_the_oracle(torch_cuda):
+    """The benchmark's configuration of the calls (follow-ups folded into the optimiser kernels) through 100
+    critic and 10 policy updates of the ant-shaped workload at batch 8192 against the oracle."""
+    w = W.WORKLOADS["ant"]
+    res = many_steps(torch_cuda, w, w.nstep + 8, 100, actor_every=10, fold=True,
+                     must_run=("fused_critic_kernel", "fused_policy_kernel", "adam_reduce_kernel"),
+                     must_not_run=("soft_update_kernel", "copy_kernel", "transpose_kernel"))
+    say("ant 100 steps, folded follow-ups", res)
 
 
 def test_kernel_profile_reports_launches_and_work(torch_cuda):
