@@ -59,6 +59,9 @@ const char* kernel_name(int kid) {
         case KID_MFMA_PROBE: return "mfma_probe_kernel";
         case KID_LAYER_ROWTILE: return "layer_rowtile_kernel";
         case KID_NARROW_ROWTILE: return "narrow_rowtile_kernel";
+        case KID_CHAIN_CRITIC: return "chain_critic_kernel";
+        case KID_CHAIN_POLICY: return "chain_policy_kernel";
+        case KID_CHAIN_ACT: return "chain_act_kernel";
         default: return "?";
     }
 }
@@ -257,6 +260,15 @@ bool fused_ok(const pql_config* c) {
     if (aw > FUSED_MAX_ACT || c->obs_dim > 1024) return false;
     if (distributional(c) && hmax < 64) return false;   // the dlogits of a row tile borrow 64 columns of an activation tile
     return fused_lds_bytes(c->obs_dim, aw, hmax) <= 160 * 1024;
+}
+// The row-tile chain kernels take networks with a layer too wide for the kernels above (up to 512 columns),
+// scalar critics and a deterministic policy, once the batch has a row tile for at least half the compute
+// units (below that the LDS-tiled kernels, which spread one layer over more workgroups, are the better fit).
+constexpr int CHAIN_MIN_TILES = 128;
+bool chain_ok(const pql_config* c, int rows) {
+    if (fused_ok(c) || distributional(c) || c->stochastic_policy) return false;
+    if ((rows + FUSED_BM - 1) / FUSED_BM < CHAIN_MIN_TILES) return false;
+    return chain_shape_ok(c->obs_dim, c->act_dim, c->hidden, c->n_hidden);
 }
 int max_hidden(const pql_config* c) {
     int hmax = 0;
@@ -796,7 +808,8 @@ int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, i
     float* ws = (float*)workspace;
     Layout w;
     make_layout(&c->cfg, w);
-    if (fused_ok(&c->cfg)) {
+    const bool chain = chain_ok(&c->cfg, num);
+    if (fused_ok(&c->cfg) || chain) {
         FusedActArgs fa;
         std::memset(&fa, 0, sizeof(fa));
         fa.B = num; fa.o = c->cfg.obs_dim; fa.a = c->cfg.act_dim; fa.L = c->L; fa.hmax = max_hidden(&c->cfg);
@@ -811,7 +824,7 @@ int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, i
         fa.noise.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); fa.noise.key1 = (uint32_t)(c->cfg.seed >> 32);
         fa.noise.ctr2 = (uint32_t)((uint64_t)c->acts & 0xffffffffu); fa.noise.ctr3 = (uint32_t)((uint64_t)c->acts >> 32);
         fa.sac = fused_sac(c, 2u, c->acts, nullptr);
-        const hipError_t fe = fused_act_launch(fa, st);
+        const hipError_t fe = chain ? chain_act_launch(fa, st) : fused_act_launch(fa, st);
         if (fe != hipSuccess) return E.hip(fe, "pql_actor_act");
         c->acts += 1;
         return PQL_OK;
@@ -890,7 +903,8 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
     make_cache_layout(&c->cfg, cl);
     auto WT = [&](int i, int l) { return cached ? c->wcache + cl.wT[i][l] : ws + w.wT[i][l]; };
     auto WOT = [&](int i) { return cached ? c->wcache + cl.woT[i] : ws + w.woT[i]; };
-    if (fused_ok(&c->cfg)) {
+    const bool chain = chain_ok(&c->cfg, B);
+    if (fused_ok(&c->cfg) || chain) {
         // One launch per row tile: target path, forward, heads and backward data path.
         TransposeArgs tr;
         tr.n = 0;
@@ -934,7 +948,7 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
             }
         }
         if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
-        if ((e = fused_critic_launch(fa, st)) != hipSuccess) return E.hip(e, who);
+        if ((e = chain ? chain_critic_launch(fa, st) : fused_critic_launch(fa, st)) != hipSuccess) return E.hip(e, who);
         head_parts = fa.nwg;
         for (int i = 0; i < 2; ++i) {
             for (int l = 1; l < L; ++l)
@@ -1217,7 +1231,8 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     auto W1AT = [&](int i) { return cached_q ? c->wcache + cl.w1aT[i] : ws + w.w1aT[i]; };
     auto WOT = [&](int i) { return cached_q ? c->wcache + cl.woT[i] : ws + w.woT[i]; };
     auto WAT = [&](int l) { return cached_a ? c->wcache + cl.waT[l] : ws + w.waT[l]; };
-    if (fused_ok(&c->cfg)) {
+    const bool chain = chain_ok(&c->cfg, B);
+    if (fused_ok(&c->cfg) || chain) {
         TransposeArgs tr;
         tr.n = 0;
         FusedPolicyArgs fa;
@@ -1257,7 +1272,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
         fa.sac = fused_sac(c, 5u, c->actor_t, c->temperature);
         fa.p_logp = sac ? ws + w.p_lp : nullptr;
         if ((e = transpose_launch(tr, st)) != hipSuccess) return E.hip(e, who);
-        if ((e = fused_policy_launch(fa, st)) != hipSuccess) return E.hip(e, who);
+        if ((e = chain ? chain_policy_launch(fa, st) : fused_policy_launch(fa, st)) != hipSuccess) return E.hip(e, who);
         loss_parts = fa.nwg;
         logp_parts = fa.nwg;
         red(adm, c->a_b[L], ws + w.colA[L + 1], aw, fa.nwg, aw);

@@ -18,7 +18,8 @@ enum KernelId : int {
     KID_ADAM = 19, KID_SOFT_UPDATE = 20, KID_COPY = 21, KID_FUSED_CRITIC = 22, KID_FUSED_POLICY = 23,
     KID_FUSED_ACT = 24, KID_TRANSPOSE = 25, KID_ADAM_CLIP = 26, KID_OBS_STATS = 27, KID_OBS_MERGE = 28,
     KID_NORMALIZE = 29, KID_DIST_CRITIC = 30, KID_DIST_POLICY = 31, KID_SAC_SAMPLE = 32, KID_SAC_GRAD = 33,
-    KID_SAC_ALPHA = 34, KID_MFMA_PROBE = 35, KID_LAYER_ROWTILE = 36, KID_NARROW_ROWTILE = 37, KID_COUNT = 38
+    KID_SAC_ALPHA = 34, KID_MFMA_PROBE = 35, KID_LAYER_ROWTILE = 36, KID_NARROW_ROWTILE = 37, KID_CHAIN_CRITIC = 38,
+    KID_CHAIN_POLICY = 39, KID_CHAIN_ACT = 40, KID_COUNT = 41
 };
 const char* kernel_name(int kid);
 bool prof_active();
@@ -345,6 +346,14 @@ struct FusedActArgs {
     FusedSac sac;                   // on: the action is a sample of the policy, `noise` is unused
 };
 hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream);
+
+// Row-tile chains for networks with layers up to 512 columns wide (pql_chain.hip): same argument blocks,
+// scalar critics and deterministic policy only.
+bool chain_shape_ok(int o, int a, const int* H, int L);
+size_t chain_lds_bytes(int o, int a, const int* H, int L);
+hipError_t chain_critic_launch(const FusedCriticArgs& a, hipStream_t stream);
+hipError_t chain_policy_launch(const FusedPolicyArgs& a, hipStream_t stream);
+hipError_t chain_act_launch(const FusedActArgs& a, hipStream_t stream);
 
 struct TransposeArgs {
     struct Mat { const float* src; float* dst; int rows, cols, block_begin, pad_; };

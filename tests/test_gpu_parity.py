@@ -225,6 +225,8 @@ def test_actor_act_at_the_workloads_own_num_envs(torch_cuda, name):
         assert e <= TOL_ONE_STEP and row_err.max() <= TOL_ONE_STEP and got.min() >= -1.0 and got.max() <= 1.0
         if name == "ant":
             assert names == {"fused_act_kernel"}
+        elif name == "humanoid":
+            assert names == {"chain_act_kernel"}
         else:
             assert {"layer_rowtile_kernel", "narrow_rowtile_kernel"} <= names
     sig = O.exploration_sigma(w.num_envs, lo, hi)
@@ -388,6 +390,88 @@ def test_one_update_full_size(torch_cuda, name):
 
 
 # ---------------------------------------------------------------------------------------------
+# Networks with a layer of 512 columns at batches of at least 4096 rows: the row-tile chain kernels (one launch
+# per learner step, the networks pass through the tile one after the other, 512-column layers as two halves)
+def chain_cases():
+    t = W.WORKLOADS["tiny"]
+    return {
+        # the humanoid-shaped networks, a ragged last row tile (4100 = 128 * 32 + 4)
+        "chain_humanoid": W.WORKLOADS["humanoid"].replace(name="chain_humanoid", num_envs=64, capacity=64 * 9, batch=4100),
+        # two 512-column layers in a row (the widest pair of tiles), a wide observation with a short tail chunk
+        "chain_shadow": W.WORKLOADS["shadow"].replace(name="chain_shadow", num_envs=40, capacity=40 * 10, batch=4097),
+        # two hidden layers (the last one, at most 256 wide, is the scalar heads' input); the most action columns
+        "chain_l2": t.replace(name="chain_l2", obs_dim=41, act_dim=32, num_envs=50, capacity=50 * 8, batch=4128,
+                              hidden=(512, 96), index=41),
+        # a narrow layer before a wide one, four layers (tiles alternate twice), one action column
+        "chain_l4": t.replace(name="chain_l4", obs_dim=77, act_dim=1, num_envs=33, capacity=33 * 9, batch=4500,
+                              hidden=(64, 512, 32, 256), index=42, nstep=2),
+    }
+
+
+CHAIN = chain_cases()
+
+
+@pytest.mark.parametrize("case", list(CHAIN))
+def test_one_update_chain_kernels(torch_cuda, case):
+    w = CHAIN[case]
+    say("case", case, "B", w.batch, "hidden", w.hidden)
+    s = make_session(w)
+    for row in W.transition_rows(w, W.data_rng(w), w.nstep + 2):
+        s.push(row)
+    s.sample(w.batch)
+    s.ctx.pql_profile_begin(256)
+    s.critic_update(w.batch)
+    s.actor_update(None, w.batch)
+    s.act(s.batch.obs[:w.batch])
+    torch_cuda.cuda.synchronize()
+    names = {k["name"] for k in s.ctx.pql_profile_end()}
+    say(case, sorted(names))
+    assert {"chain_critic_kernel", "chain_policy_kernel", "chain_act_kernel"} <= names
+    assert not any(n.startswith(("gemm_grouped_n", "layer_rowtile", "narrow_rowtile", "head_kernel")) for n in names)
+    res = one_step(torch_cuda, w, min(w.rows, w.nstep + 4))
+    say(case, res)
+
+
+@pytest.mark.parametrize("case", ["chain_humanoid", "chain_l4"])
+def test_chain_kernels_row_by_row_and_actor_step(torch_cuda, case):
+    """y_b, Q_i(s_b, a_b) and Q_i(s_b, pi(s_b)) of the chain kernels row by row, and the Actor step at a number
+    of environments that takes the chain kernel (two call numbers, then sigma = 0)."""
+    torch = torch_cuda
+    w = CHAIN[case].replace(done_p=0.05)
+    Bsz = w.batch
+    s, ring = make_session(w), oracle_ring(w)
+    fill_both(s, ring, w, min(w.rows, w.nstep + 4))
+    s.sample(Bsz)
+    batch = oracle_batch(ring, w, Bsz, 0)
+    s.critic_update(Bsz)
+    y = workspace_rows(s, 0, Bsz)
+    q = [workspace_rows(s, 1 + i, Bsz) for i in range(2)]
+    y_ref = O.td_target(batch, s.actor_init, s.critic_init, w.actor_dims(), w.critic_dims())
+    q_ref = [O.critic_forward(p, w.critic_dims(), batch["obs"], batch["act"]) for p in O.split_twin(s.critic_init)]
+    errs = dict(y=rel_err(y, y_ref), q1=rel_err(q[0], q_ref[0]), q2=rel_err(q[1], q_ref[1]))
+    term = batch["boot"] == 0.0
+    assert term.any() and np.array_equal(y[term], s.batch.ret[:Bsz].cpu().numpy()[term])
+    critic1 = s.critic.cpu().numpy()
+    s.actor_update(None, Bsz)
+    a_pi = O.actor_forward(s.actor_init, w.actor_dims(), batch["obs"])
+    qp_ref = [O.critic_forward(p, w.critic_dims(), batch["obs"], a_pi) for p in O.split_twin(critic1)]
+    qp = [workspace_rows(s, 1 + i, Bsz) for i in range(2)]
+    errs.update(qpi1=rel_err(qp[0], qp_ref[0]), qpi2=rel_err(qp[1], qp_ref[1]))
+    say(case, {k: "%.2e" % v for k, v in errs.items()}, "terminal rows", int(term.sum()))
+    assert max(errs.values()) <= TOL_ONE_STEP
+    rng = np.random.default_rng(5)
+    lo, hi = float(np.float32(0.05)), float(np.float32(0.8))
+    a0 = s.actor.cpu().numpy()
+    for call in range(2):
+        obs = rng.standard_normal((Bsz, w.obs_dim), dtype=np.float32)
+        got = s.act(torch.from_numpy(obs).cuda(), lo, hi).cpu().numpy()
+        ref = O.actor_act(a0, w.actor_dims(), obs, lo, hi, w.rng_seed, call)
+        assert np.abs(got - ref).max() <= TOL_ONE_STEP and np.abs(got).max() <= 1.0
+    got = s.act(torch.from_numpy(obs).cuda(), 0.0, 0.0).cpu().numpy()
+    assert rel_err(got, O.actor_forward(a0, w.actor_dims(), obs)) <= TOL_ONE_STEP
+
+
+# ---------------------------------------------------------------------------------------------
 def many_steps(torch, w, rows, steps, actor_every=0, must_run=(), must_not_run=(), fold=False):
     """`must_run` / `must_not_run`: kernels that the library's own per-launch profile must / must not name
     during the first iteration that holds every kind of update.  `fold`: the Polyak step, the policy copy
@@ -467,7 +551,8 @@ def test_100_updates_through_the_row_tile_layer_kernels(torch_cuda, name, Bsz, a
     the one-step test).  The library's per-launch profile must name the row-tile kernels."""
     base = W.WORKLOADS[name]
     w = base.replace(num_envs=1024, capacity=1024 * (base.nstep + 9), batch=Bsz)
-    need = ("layer_rowtile_kernel", "narrow_rowtile_kernel", "gemm_tn_stream_kernel")
+    need = (("chain_critic_kernel",) + (("chain_policy_kernel",) if actor_every else ()) if name != "scale" else
+            ("layer_rowtile_kernel", "narrow_rowtile_kernel")) + ("gemm_tn_stream_kernel",)
     res = many_steps(torch_cuda, w, w.rows, 100, actor_every=actor_every, must_run=need)
     say(name, "batch", Bsz, "100 steps", res)
 
@@ -840,6 +925,8 @@ FOLD_CASES = {
     "ant_s_sac": lambda: with_sac(SMALL["ant_s"]),
     "ant_s_clipped": lambda: paper_defaults(SMALL["ant_s"]),
     "humanoid_s_clipped": lambda: paper_defaults(SMALL["humanoid_s"], 0.01),
+    "chain_humanoid": lambda: CHAIN["chain_humanoid"],
+    "chain_l4": lambda: CHAIN["chain_l4"],
 }
 
 
