@@ -3,7 +3,7 @@
 
     python -m paper_2307_12983_amd.profile_tools stats   <kernel_stats.csv> <bench.json> <out.md> <title> [bench.py arguments]
     python -m paper_2307_12983_amd.profile_tools traffic <fetch_counter_collection.csv> <write_counter_collection.csv> \
-                                                         <kernel name> <out.txt>
+                                                         <kernel name> <out.txt> [bench.py arguments]
     python -m paper_2307_12983_amd.profile_tools counters <counter_collection.csv> <out.txt> <counters of the pass> [bench.py arguments]
 
 ``counters`` averages one pass of shader counters (at most 8 ``SQ_`` counters fit one pass) per
@@ -85,7 +85,7 @@ def _per_dispatch(counter_csv, counter):
     return [(r["Kernel_Name"], int(r["Grid_Size"]), float(r["Counter_Value"])) for r in rows]
 
 
-def traffic_summary(fetch_csv, write_csv, kernel, out):
+def traffic_summary(fetch_csv, write_csv, kernel, out, bench_args="--steps 96 --warmup 16 --no-cpu-baseline --no-secondary"):
     res = {}
     for label, path, counter in (("fetch", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
         d = _per_dispatch(path, counter)
@@ -99,10 +99,10 @@ def traffic_summary(fetch_csv, write_csv, kernel, out):
         res[label] = dict(avg_kib=avg_kib, cal_kib=cal[2], scale=scale, bytes=avg_kib * 1024.0 * scale, n=len(mine))
     total = res["fetch"]["bytes"] + res["write"]["bytes"]
     with open(out, "w") as f:
-        f.write("# HBM traffic per launch of %s (bench.py, default workload)\n" % kernel)
+        f.write("# HBM traffic per launch of %s (bench.py %s)\n" % (kernel, bench_args))
         f.write("# Commands (two counter passes, each its own run; from the repository root on one MI355X):\n")
-        f.write("#   rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out>/pmc_fetch -o b -- python3 bench.py --steps 96 --warmup 16 --no-cpu-baseline\n")
-        f.write("#   rocprofv3 --pmc WRITE_SIZE --output-format csv -d <out>/pmc_write -o b -- python3 bench.py --steps 96 --warmup 16 --no-cpu-baseline\n")
+        f.write("#   rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out>/pmc_fetch -o b -- python3 bench.py %s\n" % bench_args)
+        f.write("#   rocprofv3 --pmc WRITE_SIZE --output-format csv -d <out>/pmc_write -o b -- python3 bench.py %s\n" % bench_args)
         f.write("#   python -m paper_2307_12983_amd.profile_tools traffic <out>/pmc_fetch/b_counter_collection.csv <out>/pmc_write/b_counter_collection.csv %s <this file>\n" % kernel)
         f.write("# Each counter (KiB per dispatch) is scaled by what it reads for the calibration copy of %d floats\n" % CAL_COPY_FLOATS)
         f.write("# (%d bytes read, as many written).\n" % (CAL_COPY_FLOATS * 4))
@@ -160,7 +160,7 @@ if __name__ == "__main__":
     if len(sys.argv) >= 6 and sys.argv[1] == "stats":
         stats_summary(*sys.argv[2:7])
     elif len(sys.argv) >= 6 and sys.argv[1] == "traffic":
-        traffic_summary(*sys.argv[2:6])
+        traffic_summary(*sys.argv[2:7])
     elif len(sys.argv) >= 5 and sys.argv[1] == "counters":
         counters_summary(*sys.argv[2:6])
     else:
