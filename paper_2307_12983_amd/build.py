@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpql.so")
-SOURCES = ["pql_api.hip", "pql_gemm.hip", "pql_kernels.hip", "pql_fused.hip", "pql_chain.hip"]
+SOURCES = ["pql_api.hip", "pql_gemm.hip", "pql_kernels.hip", "pql_fused.hip", "pql_chain.hip", "pql_act16.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

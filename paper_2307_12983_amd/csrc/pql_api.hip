@@ -62,6 +62,7 @@ const char* kernel_name(int kid) {
         case KID_CHAIN_CRITIC: return "chain_critic_kernel";
         case KID_CHAIN_POLICY: return "chain_policy_kernel";
         case KID_CHAIN_ACT: return "chain_act_kernel";
+        case KID_FUSED_ACT16: return "fused_act16_kernel";
         default: return "?";
     }
 }
@@ -824,7 +825,8 @@ int32_t pql_actor_act(pql_ctx* c, const float* actor_params, const float* obs, i
         fa.noise.key0 = (uint32_t)(c->cfg.seed & 0xffffffffu); fa.noise.key1 = (uint32_t)(c->cfg.seed >> 32);
         fa.noise.ctr2 = (uint32_t)((uint64_t)c->acts & 0xffffffffu); fa.noise.ctr3 = (uint32_t)((uint64_t)c->acts >> 32);
         fa.sac = fused_sac(c, 2u, c->acts, nullptr);
-        const hipError_t fe = chain ? chain_act_launch(fa, st) : fused_act_launch(fa, st);
+        // up to 4096 environments the 32-row tiles leave compute units idle: 16-row tiles where that kernel applies
+        const hipError_t fe = chain ? chain_act_launch(fa, st) : (act16_ok(fa) ? fused_act16_launch(fa, st) : fused_act_launch(fa, st));
         if (fe != hipSuccess) return E.hip(fe, "pql_actor_act");
         c->acts += 1;
         return PQL_OK;

@@ -19,7 +19,7 @@ enum KernelId : int {
     KID_FUSED_ACT = 24, KID_TRANSPOSE = 25, KID_ADAM_CLIP = 26, KID_OBS_STATS = 27, KID_OBS_MERGE = 28,
     KID_NORMALIZE = 29, KID_DIST_CRITIC = 30, KID_DIST_POLICY = 31, KID_SAC_SAMPLE = 32, KID_SAC_GRAD = 33,
     KID_SAC_ALPHA = 34, KID_MFMA_PROBE = 35, KID_LAYER_ROWTILE = 36, KID_NARROW_ROWTILE = 37, KID_CHAIN_CRITIC = 38,
-    KID_CHAIN_POLICY = 39, KID_CHAIN_ACT = 40, KID_COUNT = 41
+    KID_CHAIN_POLICY = 39, KID_CHAIN_ACT = 40, KID_FUSED_ACT16 = 41, KID_COUNT = 42
 };
 const char* kernel_name(int kid);
 bool prof_active();
@@ -346,6 +346,9 @@ struct FusedActArgs {
     FusedSac sac;                   // on: the action is a sample of the policy, `noise` is unused
 };
 hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream);
+// The same step on 16-row tiles (pql_act16.hip), for up to 4096 environments.
+bool act16_ok(const FusedActArgs& a);
+hipError_t fused_act16_launch(const FusedActArgs& a, hipStream_t stream);
 
 // Row-tile chains for networks with layers up to 512 columns wide (pql_chain.hip): same argument blocks,
 // scalar critics and deterministic policy only.

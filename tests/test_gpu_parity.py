@@ -224,7 +224,7 @@ def test_actor_act_at_the_workloads_own_num_envs(torch_cuda, name):
         say(name, "act call", call, "N", w.num_envs, "rel err %.2e" % e, "worst row", int(row_err.argmax()), sorted(names))
         assert e <= TOL_ONE_STEP and row_err.max() <= TOL_ONE_STEP and got.min() >= -1.0 and got.max() <= 1.0
         if name == "ant":
-            assert names == {"fused_act_kernel"}
+            assert names == {"fused_act16_kernel"}           # 4096 environments: 256 tiles of 16 rows
         elif name == "humanoid":
             assert names == {"chain_act_kernel"}
         else:
@@ -235,6 +235,34 @@ def test_actor_act_at_the_workloads_own_num_envs(torch_cuda, name):
     got = s.act(torch.from_numpy(obs).cuda(), 0.0, 0.0).cpu().numpy()
     assert rel_err(got, O.actor_forward(s.actor_init, w.actor_dims(), obs)) <= TOL_ONE_STEP
     assert s.ctx.get_state()[4] == 3
+
+
+@pytest.mark.parametrize("case,num,kernel", [("ant_s", 4096, "fused_act16_kernel"), ("ant_s", 4097, "fused_act_kernel"),
+                                             ("ant_s", 6001, "fused_act_kernel"), ("fused_l3", 4000, "fused_act16_kernel"),
+                                             ("fused_wide_in", 2049, "fused_act16_kernel"), ("fused_k64", 4099, "fused_act_kernel")])
+def test_actor_act_tile_heights(torch_cuda, case, num, kernel):
+    """Up to 4096 environments the Actor step of narrow networks runs on 16-row tiles, above on 32-row tiles:
+    both sides of the switch, ragged last tiles, odd input widths (45, 211), 32 action columns (fused_k64),
+    with mixed noise scales and, for the second call, standardised observations."""
+    torch = torch_cuda
+    w = SMALL[case].replace(batch=num, obs_norm=True, obs_loc=1.0, obs_scale=2.0)
+    s, nz = make_session(w), oracle_normalizer(w)
+    row = W.transition_rows(w, W.data_rng(w), 1)[0]
+    rng = np.random.default_rng(13)
+    lo, hi = float(np.float32(0.05)), float(np.float32(0.8))
+    for call in range(2):
+        if call == 1:                      # statistics of one pushed row: the second call standardises with them
+            s.push(row)
+            nz.update(row["obs"])
+        obs = (1.0 + 2.0 * rng.standard_normal((num, w.obs_dim))).astype(np.float32)
+        s.ctx.pql_profile_begin(16)
+        got = s.act(torch.from_numpy(obs).cuda(), lo, hi).cpu().numpy()
+        names = {k["name"] for k in s.ctx.pql_profile_end()}
+        ref = O.actor_act(s.actor_init, w.actor_dims(), nz.normalize(obs), lo, hi, w.rng_seed, call)
+        err = np.abs(got.astype(np.float64) - ref).max()
+        say(case, "num", num, "call", call, sorted(names), "max abs err %.2e" % err)
+        assert names == {kernel}
+        assert err <= TOL_ONE_STEP and np.abs(got).max() <= 1.0
 
 
 # ---------------------------------------------------------------------------------------------
@@ -1039,11 +1067,11 @@ def test_which_cases_take_the_row_tile_kernels(torch_cuda, case):
     torch_cuda.cuda.synchronize()
     names = {k["name"] for k in s.ctx.pql_profile_end()}
     say(case, sorted(names))
-    fused = {"fused_critic_kernel", "fused_policy_kernel", "fused_act_kernel"}
+    fused = {"fused_critic_kernel", "fused_policy_kernel", "fused_act16_kernel"}     # (few environments: 16-row tiles)
     if case in ROW_TILE_CASES:
         assert fused <= names and not any(n.startswith("gemm_grouped_n") for n in names)
     else:
-        assert not (fused & names)
+        assert not ((fused | {"fused_act_kernel"}) & names)
     assert ("layer_rowtile_kernel" in names) == (case == "layer_tiles")
     assert ("narrow_rowtile_kernel" in names) == (case == "layer_tiles")
 
