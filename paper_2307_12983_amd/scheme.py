@@ -40,6 +40,12 @@ class ParallelSchemeSession:
         self.env = env_rows                       # device-resident synthetic simulator output, cycled
         self.horizon, self.v_updates, self.p_updates = int(horizon), int(v_updates), int(p_updates)
         self.concurrent = concurrent
+        # With the follow-ups folded into the optimiser kernels (LearnerSession.fold_followups) the Polyak step
+        # of Q' rides on every critic update; the lagged policy, however, follows pi only at the period
+        # boundaries here, through the snapshots below, so its per-update tracking is switched off.
+        self.folded = bool(getattr(sess, "folded", False))
+        if self.folded:
+            sess.ctx.pql_track_attach(1, None, 0.0)
         dev = sess.device
         w = self.w
         self.pi_snap = [sess.actor.clone(), sess.actor.clone()]       # pi^a = pi^v: the P-learner's last hand-over
@@ -112,7 +118,8 @@ class ParallelSchemeSession:
             c.pql_sample_nstep(s.storage, w.batch, s.batch, st_v)
             c.pql_critic_update(s.critic, s.critic_target, pi_lag, s.c_m, s.c_v, s.c_g, s.batch, w.batch, s.opt,
                                 s.critic_out, s.workspace, st_v)
-            c.pql_soft_update(s.critic, s.critic_target, s.critic.numel(), w.tau, st_v)
+            if not self.folded:
+                c.pql_soft_update(s.critic, s.critic_target, s.critic.numel(), w.tau, st_v)
             want_p = (self.p_updates * (k + 1)) // self.v_updates
             while done_p < want_p:
                 self._policy_update(q_p, st_p)

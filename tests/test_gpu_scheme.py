@@ -49,10 +49,12 @@ def cases():
 CASES = cases()
 
 
-def build(torch, w, concurrent, horizon=1):
+def build(torch, w, concurrent, horizon=1, fold=False):
     from paper_2307_12983_amd.scheme import ParallelSchemeSession
     from paper_2307_12983_amd.session import LearnerSession
     s, ring, nz = LearnerSession(w), oracle_ring(w), oracle_normalizer(w)
+    if fold:                # Polyak step and transposed weights carried by the optimiser kernels
+        s.fold_followups()
     rng = fill_both(s, ring, w, w.nstep + 1, normalizer=nz)
     env_host = W.transition_rows(w, rng, 6)
     env_dev = [s.to_device(r) for r in env_host]
@@ -60,12 +62,14 @@ def build(torch, w, concurrent, horizon=1):
     return s, ps, ring, nz, env_host
 
 
-@pytest.mark.parametrize("case,horizon", [("tiny", 1), ("ragged", 2), ("ant_s", 1), ("tiny_defaults", 1), ("ragged_dist", 1), ("ragged_sac", 1)])
-def test_scheme_matches_oracle(torch_cuda, case, horizon):
+@pytest.mark.parametrize("case,horizon,fold", [("tiny", 1, False), ("ragged", 2, False), ("ant_s", 1, False), ("tiny_defaults", 1, False),
+                                               ("ragged_dist", 1, False), ("ragged_sac", 1, False), ("ant_s", 1, True),
+                                               ("tiny_defaults", 2, True)])
+def test_scheme_matches_oracle(torch_cuda, case, horizon, fold):
     torch = torch_cuda
     w = CASES[case]
     periods = 4
-    s, ps, ring, nz, env_host = build(torch, w, True, horizon)
+    s, ps, ring, nz, env_host = build(torch, w, True, horizon, fold)
     L = oracle_learner(w, s.actor_init, s.critic_init)
     S = O.ParallelScheme(L, ring, w.nstep, w.batch, w.rng_seed, w.sigma_min, w.sigma_max, normalizer=nz, horizon=horizon)
     for p in range(periods):
@@ -107,13 +111,14 @@ def test_scheme_matches_oracle(torch_cuda, case, horizon):
     say(case, res)
 
 
-@pytest.mark.parametrize("case", ["ragged", "ant_s", "tiny_defaults", "ragged_sac"])
-def test_three_streams_equal_one_stream_bit_for_bit(torch_cuda, case):
+@pytest.mark.parametrize("case,fold", [("ragged", False), ("ant_s", False), ("tiny_defaults", False), ("ragged_sac", False),
+                                       ("ant_s", True), ("ragged", True)])
+def test_three_streams_equal_one_stream_bit_for_bit(torch_cuda, case, fold):
     torch = torch_cuda
     w = CASES[case]
     out = []
     for concurrent in (False, True):
-        s, ps, _, _, _ = build(torch, w, concurrent, horizon=2)
+        s, ps, _, _, _ = build(torch, w, concurrent, horizon=2, fold=fold)
         for p in range(6):
             ps.run_period()
         ps.finish()
