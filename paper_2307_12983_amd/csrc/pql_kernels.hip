@@ -113,48 +113,79 @@ __global__ __launch_bounds__(256) void sample_kernel(const SampleArgs a) {
     }
     const int64_t row0 = slot / a.N;
     const int64_t env = slot - row0 * a.N;
+    // slot of the window's last row (its s' is the batch's next state): index arithmetic only
+    int64_t last;
+    {
+        int64_t r = row0 + (a.nstep - 1);
+        if (r >= a.T) r -= a.T;
+        last = r * (int64_t)a.N + env;
+    }
+    // 16-byte path with at most one granule per lane and row: the three rows' loads are issued BEFORE the
+    // window's rewards and termination flags are read, so that a sample costs one memory round trip (rows,
+    // rewards and flags arrive together) instead of two; the stores follow the fold
+    const int no4 = a.o >> 2, na4 = a.a >> 2;
+    const bool one_pass = VEC_O && VEC_A && no4 <= G && na4 <= G;
+    const bool stdz = a.nmean != nullptr;
+    float4 vo = make_float4(0.f, 0.f, 0.f, 0.f), vn = vo, va = vo;
+    if (one_pass) {
+        if (gl < no4) {
+            vo = reinterpret_cast<const float4*>(a.st.obs + (size_t)slot * a.o)[gl];
+            vn = reinterpret_cast<const float4*>(a.st.next_obs + (size_t)last * a.o)[gl];
+        }
+        if (gl < na4) va = reinterpret_cast<const float4*>(a.st.act + (size_t)slot * a.a)[gl];
+    }
 
     // fold rewards and termination flags over the window (every lane of the group reads the
     // same addresses; lane 0 writes)
     float ret = 0.f, alive = 1.f, g = 1.f;
-    int64_t last = slot;
     for (int s = 0; s < a.nstep; ++s) {
         int64_t r = row0 + s;
         if (r >= a.T) r -= a.T;
-        last = r * (int64_t)a.N + env;
-        ret += g * a.st.rew[last] * alive;
-        alive *= (1.f - a.st.done[last]);
+        const int64_t at = r * (int64_t)a.N + env;
+        ret += g * a.st.rew[at] * alive;
+        alive *= (1.f - a.st.done[at]);
         g *= a.gamma;
     }
     if (gl == 0) {
         a.out.ret[k] = ret;
         a.out.boot[k] = g * alive;
     }
+    if (one_pass) {
+        if (gl < no4) {
+            if (stdz) {
+                const float4 mu = reinterpret_cast<const float4*>(a.nmean)[gl], rs = reinterpret_cast<const float4*>(a.nrstd)[gl];
+                vo.x = (vo.x - mu.x) * rs.x; vo.y = (vo.y - mu.y) * rs.y; vo.z = (vo.z - mu.z) * rs.z; vo.w = (vo.w - mu.w) * rs.w;
+                vn.x = (vn.x - mu.x) * rs.x; vn.y = (vn.y - mu.y) * rs.y; vn.z = (vn.z - mu.z) * rs.z; vn.w = (vn.w - mu.w) * rs.w;
+            }
+            reinterpret_cast<float4*>(a.out.obs + (size_t)k * a.o)[gl] = vo;
+            reinterpret_cast<float4*>(a.out.next_obs + (size_t)k * a.o)[gl] = vn;
+        }
+        if (gl < na4) reinterpret_cast<float4*>(a.out.act + (size_t)k * a.a)[gl] = va;
+        return;
+    }
     if (VEC_O && VEC_A) {
-        // 16-byte path: the three rows' loads are issued together and the stores follow, so that a
-        // sample costs one memory round trip (row after row, each copy waited for the one before it:
-        // nothing tells the compiler that the batch does not alias the ring)
+        // 16-byte path, several granules per lane: the three rows' loads of a pass are issued together and
+        // the stores follow (row after row, each copy waited for the one before it: nothing tells the
+        // compiler that the batch does not alias the ring)
         const float4* __restrict__ so = reinterpret_cast<const float4*>(a.st.obs + (size_t)slot * a.o);
         const float4* __restrict__ sn = reinterpret_cast<const float4*>(a.st.next_obs + (size_t)last * a.o);
         const float4* __restrict__ sa = reinterpret_cast<const float4*>(a.st.act + (size_t)slot * a.a);
         float4* __restrict__ d_o = reinterpret_cast<float4*>(a.out.obs + (size_t)k * a.o);
         float4* __restrict__ d_n = reinterpret_cast<float4*>(a.out.next_obs + (size_t)k * a.o);
         float4* __restrict__ d_a = reinterpret_cast<float4*>(a.out.act + (size_t)k * a.a);
-        const int no4 = a.o >> 2, na4 = a.a >> 2;
         const int nmax = no4 > na4 ? no4 : na4;
-        const bool stdz = a.nmean != nullptr;
         for (int c = gl; c < nmax; c += G) {
             const bool po = c < no4, pa = c < na4;
-            float4 vo = make_float4(0.f, 0.f, 0.f, 0.f), vn = vo, va = vo, mu = vo, rs = make_float4(1.f, 1.f, 1.f, 1.f);
-            if (po) { vo = so[c]; vn = sn[c]; }
-            if (pa) va = sa[c];
+            float4 xo = make_float4(0.f, 0.f, 0.f, 0.f), xn = xo, xa = xo, mu = xo, rs = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (po) { xo = so[c]; xn = sn[c]; }
+            if (pa) xa = sa[c];
             if (po && stdz) { mu = reinterpret_cast<const float4*>(a.nmean)[c]; rs = reinterpret_cast<const float4*>(a.nrstd)[c]; }
             if (stdz) {
-                vo.x = (vo.x - mu.x) * rs.x; vo.y = (vo.y - mu.y) * rs.y; vo.z = (vo.z - mu.z) * rs.z; vo.w = (vo.w - mu.w) * rs.w;
-                vn.x = (vn.x - mu.x) * rs.x; vn.y = (vn.y - mu.y) * rs.y; vn.z = (vn.z - mu.z) * rs.z; vn.w = (vn.w - mu.w) * rs.w;
+                xo.x = (xo.x - mu.x) * rs.x; xo.y = (xo.y - mu.y) * rs.y; xo.z = (xo.z - mu.z) * rs.z; xo.w = (xo.w - mu.w) * rs.w;
+                xn.x = (xn.x - mu.x) * rs.x; xn.y = (xn.y - mu.y) * rs.y; xn.z = (xn.z - mu.z) * rs.z; xn.w = (xn.w - mu.w) * rs.w;
             }
-            if (po) { d_o[c] = vo; d_n[c] = vn; }
-            if (pa) d_a[c] = va;
+            if (po) { d_o[c] = xo; d_n[c] = xn; }
+            if (pa) d_a[c] = xa;
         }
         return;
     }
@@ -190,8 +221,10 @@ hipError_t sample_launch(const SampleArgs& a, hipStream_t stream) {
     const double bytes = a.only_obs ? (double)a.batch * (8.0 * a.o + 8.0)
                                     : (double)a.batch * (4.0 * (2 * a.o + a.a + 2 * a.nstep) + 4.0 * (2 * a.o + a.a + 2) + 8.0);
     const ProfSlot ps = prof_slot();
-    if (per_row <= 32) sample_dispatch<16>(a, vo, va, ps, stream);
-    else               sample_dispatch<64>(a, vo, va, ps, stream);
+    // lanes per sample: enough for one 16-byte granule per lane and row where the rows are short enough
+    if (per_row <= 16)      sample_dispatch<16>(a, vo, va, ps, stream);
+    else if (per_row <= 32) sample_dispatch<32>(a, vo, va, ps, stream);
+    else                    sample_dispatch<64>(a, vo, va, ps, stream);
     prof_commit(ps, KID_SAMPLE, 0.0, bytes);
     return hipGetLastError();
 }
