@@ -320,8 +320,8 @@ int32_t pql_soft_update(pql_ctx* ctx, const float* src, float* dst, int64_t coun
  *   PQL_TRACK_LAGGED_POLICY   at the end of every pql_actor_update: dst (pql_actor_param_count floats)
  *                             = tau * actor_params + (1 - tau) * dst (tau = 1: the hard copy).
  * The result equals, bit for bit, that of pql_soft_update(params, dst, count, tau) enqueued right after the
- * update; the caller then omits that call.  tau = 0 and dst = NULL switch it off.  With gradient clipping on,
- * the update enqueues the separate pass itself (same result).  Host-side only.
+ * update; the caller then omits that call.  tau = 0 and dst = NULL switch it off.  With gradient clipping on
+ * it rides on the kernel that applies the clipped step (same result).  Host-side only.
  * Errors: PQL_ERR_INVALID_ARG (unknown vector, tau outside [0, 1]). */
 #define PQL_TRACK_CRITIC_TARGETS 0
 #define PQL_TRACK_LAGGED_POLICY  1

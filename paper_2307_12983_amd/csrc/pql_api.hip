@@ -900,7 +900,6 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
     // Transposed weights: from the caller's cache when it holds those of this parameter vector (then the
     // optimiser kernel refreshes them at the end of the call), else transposed into the workspace here.
     const bool cached = c->wcache != nullptr && c->wcache_critic == critic_params;
-    const bool clipped = opt.max_grad_norm > 0.f;
     CacheLayout cl;
     make_cache_layout(&c->cfg, cl);
     auto WT = [&](int i, int l) { return cached ? c->wcache + cl.wT[i][l] : ws + w.wT[i][l]; };
@@ -1091,7 +1090,7 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
         std::vector<GemmProb> ps;
         std::vector<int64_t> offs;
         std::vector<float*> tds;         // where the optimiser kernel leaves the transposed copy of the updated tensor
-        const bool keep_t = cached && !clipped;
+        const bool keep_t = cached;
         for (int i = 0; i < 2; ++i) {
             for (int l = 1; l <= L; ++l) {
                 const int Hl = c->cfg.hidden[l - 1];
@@ -1135,17 +1134,11 @@ static int32_t critic_update_run(pql_ctx* c, float* critic_params, const float* 
     adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
     adm.theta = critic_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
     adm.max_norm = opt.max_grad_norm; adm.sq_partial = ws + w.sqp; adm.norm_out = loss_out + 2;
-    // what follows the step (target tracking, transposed weights for the next call) rides on the optimiser
-    // kernel's pass; a clipped step ends in a kernel of its own, after which both are launched separately
-    const bool tracked = c->track[0] != nullptr && c->track_tau[0] > 0.f;
-    if (tracked && !clipped) { adm.track = c->track[0]; adm.tau = c->track_tau[0]; }
+    // what follows the step (target tracking, transposed weights for the next call) rides on the pass that
+    // writes the parameters: the optimiser kernel's, or the second kernel's of a clipped step
+    if (c->track[0] != nullptr && c->track_tau[0] > 0.f) { adm.track = c->track[0]; adm.tau = c->track_tau[0]; }
     fill_adam(adm, opt, c->critic_t + 1);
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
-    if (clipped) {
-        if (tracked && (e = soft_update_launch(critic_params, c->track[0], 2 * Pc, c->track_tau[0], st)) != hipSuccess)
-            return E.hip(e, who);
-        if (cached && (e = transpose_critic_weights(c, critic_params, c->wcache, cl, st)) != hipSuccess) return E.hip(e, who);
-    }
     c->critic_t += 1;
     return PQL_OK;
 }
@@ -1226,7 +1219,6 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     // Transposed weights from the caller's cache where it holds those of these parameter vectors
     const bool cached_q = c->wcache != nullptr && c->wcache_critic == critic_params;
     const bool cached_a = c->wcache != nullptr && c->wcache_actor == actor_params;
-    const bool clipped = opt.max_grad_norm > 0.f;
     CacheLayout cl;
     make_cache_layout(&c->cfg, cl);
     auto WT = [&](int i, int l) { return cached_q ? c->wcache + cl.wT[i][l] : ws + w.wT[i][l]; };
@@ -1457,7 +1449,7 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
             GemmProb p = prob(Hp, Hl, nullptr, Hl, EPI_STORE);
             add_seg(p, (l == 1) ? obs : ws + w.hA[l - 1], Hp, (l == L + 1) ? d_top : ws + w.dA[l], Hl, B);
             ps.push_back(p); offs.push_back(c->a_w[l - 1]);
-            tds.push_back((cached_a && !clipped && l >= 2) ? c->wcache + cl.waT[l - 1] : nullptr);
+            tds.push_back((cached_a && l >= 2) ? c->wcache + cl.waT[l - 1] : nullptr);
         }
         if ((e = run_dw(ps, offs, B, ws + w.splitk, adm, st, &tds)) != hipSuccess) return E.hip(e, who);
     }
@@ -1465,15 +1457,9 @@ int32_t pql_actor_update(pql_ctx* c, float* actor_params, const float* critic_pa
     adm.loss_partial = ws + w.p_loss; adm.loss_out = loss_out;
     adm.theta = actor_params; adm.m = adam_m; adm.v = adam_v; adm.g = grads_out;
     adm.max_norm = opt.max_grad_norm; adm.sq_partial = ws + w.sqp; adm.norm_out = loss_out + 1;
-    const bool tracked = c->track[1] != nullptr && c->track_tau[1] > 0.f;
-    if (tracked && !clipped) { adm.track = c->track[1]; adm.tau = c->track_tau[1]; }
+    if (c->track[1] != nullptr && c->track_tau[1] > 0.f) { adm.track = c->track[1]; adm.tau = c->track_tau[1]; }
     fill_adam(adm, opt, c->actor_t + 1);
     if ((e = adam_reduce_launch(adm, st)) != hipSuccess) return E.hip(e, who);
-    if (clipped) {
-        if (tracked && (e = soft_update_launch(actor_params, c->track[1], c->a_total, c->track_tau[1], st)) != hipSuccess)
-            return E.hip(e, who);
-        if (cached_a && (e = transpose_actor_weights(c, actor_params, c->wcache, cl, st)) != hipSuccess) return E.hip(e, who);
-    }
     if (sac) {      // temperature step on the log-densities of this batch
         SacAlphaArgs al;
         al.B = B; al.nparts = logp_parts; al.p_logp = ws + w.p_lp; al.temperature = c->temperature;

@@ -144,8 +144,9 @@ struct AdamArgs {
     float max_norm;
     float* sq_partial;      // at least adam_reduce_blocks(a) floats
     float* norm_out;        // receives the norm before clipping
-    // Optional tracking vector (target network, lagged policy), updated in the same pass (unclipped
-    // steps only): track[k] = tau * theta_new[k] + (1 - tau) * track[k]; NULL: none.
+    // Optional tracking vector (target network, lagged policy), updated in the pass that writes theta
+    // (the second kernel's when the step is clipped): track[k] = tau * theta_new[k] + (1 - tau) * track[k];
+    // NULL: none.
     float* track;
     float tau;
     RedTensor t[RED_MAX_TENSORS];

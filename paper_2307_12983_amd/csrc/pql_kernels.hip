@@ -639,6 +639,10 @@ struct AdamClipArgs {
     const float* sq_partial; float* norm_out;
     int64_t n; int nparts;
     float lr, beta1, beta2, eps, inv_bc1, inv_bc2, max_norm;
+    // what follows the step, as in adam_reduce_kernel: tracking vector and transposed copies of some tensors
+    float* track; float tau;
+    int ntr;
+    struct Tr { int64_t offset; float* tdst; int count, trows, tcols, pad_; } tr[RED_MAX_TENSORS];
 };
 
 __global__ __launch_bounds__(256) void adam_clip_kernel(const AdamClipArgs a) {
@@ -662,10 +666,19 @@ __global__ __launch_bounds__(256) void adam_clip_kernel(const AdamClipArgs a) {
         const float g = a.g[k] * scale;
         const float m = a.beta1 * a.m[k] + (1.f - a.beta1) * g;
         const float v = a.beta2 * a.v[k] + (1.f - a.beta2) * g * g;
-        a.theta[k] = a.theta[k] - a.lr * (m * a.inv_bc1) / (sqrtf(v * a.inv_bc2) + a.eps);
+        const float th = a.theta[k] - a.lr * (m * a.inv_bc1) / (sqrtf(v * a.inv_bc2) + a.eps);
+        a.theta[k] = th;
         a.m[k] = m;
         a.v[k] = v;
         a.g[k] = g;
+        if (a.track != nullptr) a.track[k] = a.tau == 1.f ? th : polyak_mix(a.tau, 1.f - a.tau, th, a.track[k]);
+        for (int i = 0; i < a.ntr; ++i) {           // the few tensors whose transposes the next backward pass reads
+            const int64_t e = k - a.tr[i].offset;
+            if (e >= 0 && e < a.tr[i].count) {
+                const int r = (int)e / a.tr[i].tcols, cc = (int)e - r * a.tr[i].tcols;
+                a.tr[i].tdst[(size_t)cc * (size_t)a.tr[i].trows + r] = th;
+            }
+        }
     }
 }
 
@@ -705,6 +718,13 @@ hipError_t adam_reduce_launch(const AdamArgs& args, hipStream_t stream) {
     c.nparts = blocks;
     c.lr = a.lr; c.beta1 = a.beta1; c.beta2 = a.beta2; c.eps = a.eps; c.inv_bc1 = a.inv_bc1; c.inv_bc2 = a.inv_bc2;
     c.max_norm = a.max_norm;
+    c.track = a.track; c.tau = a.tau;
+    c.ntr = 0;
+    for (int i = 0; i < a.ntensors; ++i)
+        if (a.t[i].tdst != nullptr) {
+            AdamClipArgs::Tr& t = c.tr[c.ntr++];
+            t.offset = a.t[i].offset; t.tdst = a.t[i].tdst; t.count = a.t[i].count; t.trows = a.t[i].trows; t.tcols = a.t[i].tcols;
+        }
     const ProfSlot pc = prof_slot();
     PQL_LAUNCH(pc, adam_clip_kernel, dim3((unsigned)((c.n + 1023) / 1024)), block, 0, stream, c);
     prof_commit(pc, KID_ADAM_CLIP, 0.0, 32.0 * (double)c.n);   // theta, m, v, g read and written
