@@ -372,6 +372,37 @@ __device__ inline float tn_load(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
 
 constexpr int TNS = 4;            // MFMA steps (2 rows each) per chunk of the streaming weight-gradient kernel
 
+// Quarter Q of a wavefront's TM x 2 accumulator tiles: registers f in [Q * NQ, (Q + 1) * NQ), NQ = TM * 8.
+template <int TM, int Q>
+__device__ inline void tn_park(const floatx16 (&acc)[TM][2], float (*red)[4096], int lane) {
+    constexpr int NQ = TM * 8;
+#pragma unroll
+    for (int f = 0; f < TM * 32; ++f) {
+        const int q = f / NQ;                       // owner of this register (a constant after unrolling)
+        if (q != Q) red[Q - (Q > q ? 1 : 0)][f * 64 + lane] = acc[f >> 5][(f >> 4) & 1][f & 15];
+    }
+}
+
+template <int TM, int Q>
+__device__ inline void tn_sum_store(const floatx16 (&acc)[TM][2], float (*red)[4096], int lane, int l32, int half,
+                                    float* __restrict__ C, int M, int N, int ldc, int m0, int n0) {
+    constexpr int NQ = TM * 8;
+#pragma unroll
+    for (int f = Q * NQ; f < (Q + 1) * NQ; ++f) {
+        const int i = f >> 5, j = (f >> 4) & 1, r = f & 15;
+        const int e = f * 64 + lane;
+        float v = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {               // contributions in wavefront order, whoever owns the register
+            const float x = (s == Q) ? acc[i][j][r] : red[s - (s > Q ? 1 : 0)][e];
+            v = (s == 0) ? x : v + x;
+        }
+        const int row = m0 + 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
+        const int col = n0 + 32 * j + l32;
+        if (row < M && col < N) C[(size_t)row * (size_t)ldc + col] = v;
+    }
+}
+
 template <int TM>
 __device__ inline void tn_stream_tile(const GemmProb& P, int split, int m0, int n0, float (*red)[4096]) {
     const int tid = threadIdx.x, lane = tid & 63;
@@ -442,33 +473,20 @@ __device__ inline void tn_stream_tile(const GemmProb& P, int split, int m0, int 
             ++c;
         }
     }
-    // partial tiles of wavefronts 1..3 through LDS (index ((i * 2 + j) * 16 + r) * 64 + lane), added in a
-    // fixed order by wavefront 0, which stores the split's slab
-    if (wave > 0) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) red[wave - 1][((i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
-    }
+    // The four partial tiles meet in LDS.  Every wavefront owns a quarter of the tile's accumulator registers
+    // (flattened as f = (i * 2 + j) * 16 + r): it parks the other three quarters in LDS (slot = source wavefront,
+    // skipping the owner: three slots of 64 x 64 floats), then adds the four contributions to its own quarter
+    // in wavefront order and stores that part of the split's slab - all four wavefronts reduce and store.
+    if (wave == 0)      tn_park<TM, 0>(acc, red, lane);
+    else if (wave == 1) tn_park<TM, 1>(acc, red, lane);
+    else if (wave == 2) tn_park<TM, 2>(acc, red, lane);
+    else                tn_park<TM, 3>(acc, red, lane);
     __syncthreads();
-    if (wave == 0) {
-        float* __restrict__ C = P.C + (size_t)split * (size_t)P.split_stride;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int col = n0 + 32 * j + l32;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int e = ((i * 2 + j) * 16 + r) * 64 + lane;
-                    const float v = ((acc[i][j][r] + red[0][e]) + red[1][e]) + red[2][e];
-                    const int row = m0 + 32 * i + 8 * (r >> 2) + 4 * half + (r & 3);
-                    if (row < P.M && col < P.N) C[(size_t)row * (size_t)P.ldc + col] = v;
-                }
-            }
-    }
+    float* __restrict__ C = P.C + (size_t)split * (size_t)P.split_stride;
+    if (wave == 0)      tn_sum_store<TM, 0>(acc, red, lane, l32, half, C, P.M, P.N, P.ldc, m0, n0);
+    else if (wave == 1) tn_sum_store<TM, 1>(acc, red, lane, l32, half, C, P.M, P.N, P.ldc, m0, n0);
+    else if (wave == 2) tn_sum_store<TM, 2>(acc, red, lane, l32, half, C, P.M, P.N, P.ldc, m0, n0);
+    else                tn_sum_store<TM, 3>(acc, red, lane, l32, half, C, P.M, P.N, P.ldc, m0, n0);
 }
 
 __global__ __launch_bounds__(NTHREADS, 3) void gemm_tn_stream_kernel(const GemmGroup g) {
