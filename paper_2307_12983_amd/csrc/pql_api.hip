@@ -1,6 +1,8 @@
 // C interface of libpql: context, argument validation, workspace layout and the launch
-// sequences of the learner steps.  All device work is done by the kernels in pql_gemm.hip and
-// pql_kernels.hip; this file only decides which problems go into which launch.
+// sequences of the learner steps.  All device work is done by the kernels in pql_fused.hip and
+// pql_chain.hip (row-tile kernels: one launch per learner step), pql_act16.hip (Actor step on 16-row
+// tiles), pql_gemm.hip (LDS-tiled GEMMs, streaming weight gradients) and pql_kernels.hip (replay,
+// heads, optimiser, statistics); this file only decides which problems go into which launch.
 #include <cmath>
 #include <cstdio>
 #include <cstring>
