@@ -9,7 +9,6 @@ from paper_2307_12983_amd import workloads as W
 
 TOL_ONE_STEP = 1e-4     # max relative error after one step (per tensor, max-norm)
 TOL_100_STEPS = 1e-3    # after 100 steps
-EXEMPT_SHARE = 0.003    # largest share of a network's entries that may need the first-step bound (see assert_first_step_params)
 
 
 def rel_err(x, ref):
@@ -62,37 +61,43 @@ def assert_params_close(got, ref, dims, nets, tol, what):
     return worst
 
 
-def assert_first_step_params(theta, theta_ref, g, g_ref, dims, nets, lr, eps, tol, what):
+def assert_first_step_params(theta, theta_ref, g, g_ref, dims, nets, lr, eps, tol, what, from_grad):
     """Parameters after the FIRST Adam step (m = v = 0 before it), where the update is
     -lr * g / (|g| + eps).  That map has slope lr * eps / (|g| + eps)^2, i.e. up to lr / eps = 5e4
     for gradient entries that happen to be ~0: a gradient error dg far inside the fp32 rounding
-    of the batch reduction moves such a parameter by up to lr.  Entries whose guaranteed bound
+    of the batch reduction moves such a parameter by up to 2 lr (the sign of the entry), which is more
+    than `tol` of the largest weight of a layer.  Entries whose guaranteed bound
     lr * eps * dg / (max(|g| - dg, 0) + eps)^2 (dg = measured max gradient error of the tensor,
-    itself required to be within tolerance) exceeds half the tolerance are compared against the
-    hard bound 2 * lr instead, counted and reported; all other entries must meet `tol`.  One-element
-    tensors take their scale from joint_scales()."""
+    itself required to be within tolerance) stays below half the tolerance must agree with the
+    oracle's parameters to `tol`.  For the others the oracle's parameters say nothing about the
+    optimiser (they follow a gradient entry that differs in sign or by its own magnitude), so they
+    are compared, to the same `tol`, with what the ORACLE's step makes of the gradient the GPU itself
+    reports: ``from_grad(g)`` returns those parameters for a flat gradient vector (oracle code:
+    adam_step, and soft_update for target networks).  Their gradient entries are covered by the
+    gradient comparison; their count is returned.  One-element tensors take their scale from
+    joint_scales()."""
     total = exempt_total = 0
     worst = worst_exempt = 0.0
     scales = joint_scales(theta_ref, dims, nets)
-    for (name, t), (_, tr), (_, gg), (_, gr), scale in zip(split_tensors(theta, dims, nets), split_tensors(theta_ref, dims, nets),
-                                                           split_tensors(g, dims, nets), split_tensors(g_ref, dims, nets), scales):
-        t, tr, gg, gr = (np.asarray(x, np.float64) for x in (t, tr, gg, gr))
+    theta_own = from_grad(np.asarray(g, np.float64))
+    for (name, t), (_, tr), (_, to), (_, gg), (_, gr), scale in zip(
+            split_tensors(theta, dims, nets), split_tensors(theta_ref, dims, nets), split_tensors(theta_own, dims, nets),
+            split_tensors(g, dims, nets), split_tensors(g_ref, dims, nets), scales):
+        t, tr, to, gg, gr = (np.asarray(x, np.float64) for x in (t, tr, to, gg, gr))
         dg = float(np.max(np.abs(gg - gr)))
         amp = lr * eps * dg / (np.maximum(np.abs(gr) - dg, 0.0) + eps) ** 2
         exempt = amp > 0.5 * tol * scale
-        err = np.abs(t - tr)
         total += t.size
         exempt_total += int(exempt.sum())
         if (~exempt).any():
-            e = float(err[~exempt].max()) / scale
+            e = float(np.abs(t - tr)[~exempt].max()) / scale
             worst = max(worst, e)
             assert e <= tol, "%s %s: rel err %.3e > %.1e" % (what, name, e, tol)
         if exempt.any():
-            worst_exempt = max(worst_exempt, float(err[exempt].max()))
-            assert err[exempt].max() <= 2.0 * lr * (1 + 1e-6), "%s %s: near-zero-gradient entry moved more than 2*lr" % (what, name)
-    # measured shares are 0.01 - 0.15 % of a network; twice the largest is the cap (small networks: 8 entries)
-    assert exempt_total <= max(8, EXEMPT_SHARE * total), "%s: %d of %d entries need the near-zero-gradient bound" % (what, exempt_total, total)
-    return dict(rel=worst, near_zero_grad_entries=exempt_total, of=total, worst_abs_dev_there=worst_exempt)
+            e = float(np.abs(t - to)[exempt].max()) / scale
+            worst_exempt = max(worst_exempt, e)
+            assert e <= tol, "%s %s: near-zero-gradient entry: rel err %.3e to the step on the reported gradient" % (what, name, e)
+    return dict(rel=worst, near_zero_grad_entries=exempt_total, of=total, rel_there=worst_exempt)
 
 
 def oracle_ring(w: W.Workload):
@@ -134,15 +139,24 @@ def batch_to_numpy(batch, B):
                 boot=batch.boot[:B].cpu().numpy())
 
 
-def assert_batch_matches(got, ref, normalized=False):
+def assert_batch_matches(got, ref, normalized=False, ring=None):
     """Copies are bit-exact; standardised observations (normalized=True) are fp32 arithmetic on
-    one subtraction and one product per element: 1e-6 of the tensor's largest value."""
+    one subtraction and one product per element: 1e-6 of the tensor's largest value.  The n-step
+    return is a sum of at most n terms gamma^k r_k that may cancel: it is judged on the scale of its
+    terms (the largest |r| stored in `ring`) when that exceeds the largest return of the batch, which
+    it does for a batch of one row whose rewards happen to cancel."""
     assert np.array_equal(got["idx"], ref["idx"]), "sampled indices differ"
     for k in ("obs", "act", "next_obs"):
         if normalized and k != "act":
             assert rel_err(got[k], ref[k]) <= 1e-6, "standardised %s: rel err %.2e" % (k, rel_err(got[k], ref[k]))
             continue
         assert np.array_equal(got[k], ref[k]), "gathered %s differs (must be bit-exact)" % k
-    assert rel_err(got["ret"], ref["ret"]) <= 1e-6
+    ret, ret_ref = np.asarray(got["ret"], np.float64), np.asarray(ref["ret"], np.float64)
+    if ret_ref.size:
+        scale = float(np.max(np.abs(ret_ref)))
+        if ring is not None:
+            scale = max(scale, float(np.max(np.abs(ring.rew))))
+        err = float(np.max(np.abs(ret - ret_ref)))
+        assert err <= 1e-6 * max(scale, 1e-30), "n-step return: error %.3e on scale %.3e" % (err, scale)
     assert rel_err(got["boot"], ref["boot"]) <= 1e-6
     assert np.array_equal(got["boot"] == 0.0, ref["boot"] == 0.0)

@@ -99,7 +99,7 @@ def test_sample_nstep_indices_and_gather(torch_cuda, case, fill):
         Bsz = w.batch if call < 2 else 7
         s.sample(Bsz)
         ref = O.gather_nstep(ring, O.sample_indices(ring, w.nstep, Bsz, w.rng_seed, call), w.nstep, w.gamma)
-        assert_batch_matches(batch_to_numpy(s.batch, Bsz), ref)
+        assert_batch_matches(batch_to_numpy(s.batch, Bsz), ref, ring=ring)
     assert s.ctx.get_state()[3] == 3
 
 
@@ -110,12 +110,12 @@ def test_gather_with_given_indices_and_degenerate_window(torch_cuda):
     s.sample(64)
     ref_idx = O.sample_indices(ring, w.nstep, 64, w.rng_seed, 0)
     assert np.all(ref_idx // w.num_envs == ring.physical_row(0))
-    assert_batch_matches(batch_to_numpy(s.batch, 64), O.gather_nstep(ring, ref_idx, w.nstep, w.gamma))
+    assert_batch_matches(batch_to_numpy(s.batch, 64), O.gather_nstep(ring, ref_idx, w.nstep, w.gamma), ring=ring)
     idx = np.arange(w.num_envs, dtype=np.int64)[::-1].copy()
     s.gather(torch_cuda.from_numpy(idx).cuda())
     got = batch_to_numpy(s.batch, idx.size)
     got["idx"] = idx
-    assert_batch_matches(got, O.gather_nstep(ring, idx, w.nstep, w.gamma))
+    assert_batch_matches(got, O.gather_nstep(ring, idx, w.nstep, w.gamma), ring=ring)
     assert s.ctx.get_state()[3] == 1        # gather does not advance the sample counter
 
 
@@ -275,7 +275,7 @@ def one_step(torch, w, rows, check_all=True):
     Bsz = w.batch
     s.sample(Bsz)
     batch = oracle_batch(ring, w, Bsz, 0, nz)
-    assert_batch_matches(batch_to_numpy(s.batch, Bsz), batch, normalized=nz is not None)
+    assert_batch_matches(batch_to_numpy(s.batch, Bsz), batch, normalized=nz is not None, ring=ring)
     # critic update
     s.critic_update(Bsz)
     losses, g = L.critic_update(batch)
@@ -288,8 +288,13 @@ def one_step(torch, w, rows, check_all=True):
     else:
         assert float(s.critic_grad_norm.cpu()[0]) == 0.0
     res["grad"] = assert_params_close(s.c_g.cpu().numpy(), g, w.critic_dims(), 2, TOL_ONE_STEP, "critic grad")
+    c0 = np.asarray(s.critic_init, np.float64)
+
+    def critic_from(gg):        # the oracle's first step on a given gradient
+        return O.adam_step(c0, gg, 0.0, 0.0, 1, w.lr, w.beta1, w.beta2, w.eps)[0]
+
     res["theta"] = assert_first_step_params(s.critic.cpu().numpy(), L.critic, s.c_g.cpu().numpy(), g, w.critic_dims(), 2,
-                                            w.lr, w.eps, TOL_ONE_STEP, "critic params")
+                                            w.lr, w.eps, TOL_ONE_STEP, "critic params", critic_from)
     res["m"] = assert_params_close(s.c_m.cpu().numpy(), L.c_m, w.critic_dims(), 2, TOL_ONE_STEP, "critic adam m")
     res["v"] = assert_params_close(s.c_v.cpu().numpy(), L.c_v, w.critic_dims(), 2, TOL_ONE_STEP, "critic adam v")
     assert res["loss"] <= TOL_ONE_STEP
@@ -298,9 +303,11 @@ def one_step(torch, w, rows, check_all=True):
     L.soft_update_targets()
     # theta' = tau * theta + (1 - tau) * theta' is linear in theta: the target inherits tau times the deviation
     # of each parameter, so the near-zero-gradient entries of the first Adam step get the same treatment with
-    # lr * tau in place of lr (tau * 2 lr is NOT below 1e-4 of the largest weight of a wide layer)
+    # lr * tau in place of lr (tau * 2 lr is NOT below 1e-4 of the largest weight of a wide layer); the targets
+    # start as copies of the critics
     res["target"] = assert_first_step_params(s.critic_target.cpu().numpy(), L.critic_target, s.c_g.cpu().numpy(), g,
-                                             w.critic_dims(), 2, w.lr * w.tau, w.eps, TOL_ONE_STEP, "critic target")
+                                             w.critic_dims(), 2, w.lr * w.tau, w.eps, TOL_ONE_STEP, "critic target",
+                                             lambda gg: O.soft_update(critic_from(gg), c0, w.tau))
     # policy update on the sampled states, then hard sync of the lagged policy
     s.actor_update(None, Bsz)
     J, ga = L.actor_update(batch["obs"])
@@ -319,8 +326,10 @@ def one_step(torch, w, rows, check_all=True):
     else:
         assert float(s.actor_grad_norm.cpu()[0]) == 0.0
     res["a_grad"] = assert_params_close(s.a_g.cpu().numpy(), ga, w.actor_dims(), 1, TOL_ONE_STEP, "actor grad")
+    a0 = np.asarray(s.actor_init, np.float64)
     res["a_theta"] = assert_first_step_params(s.actor.cpu().numpy(), L.actor, s.a_g.cpu().numpy(), ga, w.actor_dims(), 1,
-                                              w.lr, w.eps, TOL_ONE_STEP, "actor params")
+                                              w.lr, w.eps, TOL_ONE_STEP, "actor params",
+                                              lambda gg: O.adam_step(a0, gg, 0.0, 0.0, 1, w.lr, w.beta1, w.beta2, w.eps)[0])
     assert res["J"] <= TOL_ONE_STEP
     s.sync_lagged_policy()
     assert torch.equal(s.actor, s.actor_lag)
@@ -389,7 +398,7 @@ def test_cancelling_output_bias_gradient(torch_cuda):
     L = oracle_learner(w, s.actor_init, s.critic_init)
     s.sample(w.batch)
     batch = oracle_batch(ring, w, w.batch, 0)
-    assert_batch_matches(batch_to_numpy(s.batch, w.batch), batch)
+    assert_batch_matches(batch_to_numpy(s.batch, w.batch), batch, ring=ring)
     y = O.td_target(batch, s.actor_init, s.critic_init, w.actor_dims(), w.critic_dims())
     s.critic_update(w.batch)
     losses, g = L.critic_update(batch)
@@ -405,6 +414,32 @@ def test_cancelling_output_bias_gradient(torch_cuda):
         assert err <= 1e-6 * np.abs(delta).sum()
     assert rel_err(s.critic_loss.cpu().numpy(), losses) <= TOL_ONE_STEP
     assert_params_close(got, g, w.critic_dims(), 2, TOL_ONE_STEP, "critic grad")
+
+
+SWEEP_FINDS = {
+    # a batch of one row whose three rewards nearly cancel: the n-step return as a single number missed 1e-6
+    # (it is judged on the scale of its terms, parity_util.assert_batch_matches)
+    "cancelling_return": dict(obs_dim=117, act_dim=32, num_envs=40, capacity=480, batch=1, hidden=(320, 512, 40),
+                              index=62, nstep=3, num_atoms=51, v_min=-2.0, v_max=3.0),
+    # a batch of one row (the gradient is an outer product): 0.54 % of the critics' entries have a gradient so
+    # close to zero that the first Adam step follows its rounding; they are held to the oracle's step on the
+    # gradient the GPU reports (parity_util.assert_first_step_params)
+    "many_near_zero_gradients": dict(obs_dim=36, act_dim=2, num_envs=51, capacity=357, batch=1, hidden=(32, 128),
+                                     index=91, nstep=1, num_atoms=51, v_min=-2.0, v_max=3.0),
+    "near_zero_gradients_batch_512": dict(obs_dim=158, act_dim=31, num_envs=23, capacity=23 * 9, batch=512, hidden=(128,),
+                                          index=75, nstep=3),
+}
+
+
+@pytest.mark.parametrize("case", list(SWEEP_FINDS))
+def test_cases_found_by_sweeps_over_random_shapes(torch_cuda, case):
+    """Fixed configurations on which an earlier form of a comparison rule failed although the results were
+    right (sweeps over seeded random shapes; see the rules named in SWEEP_FINDS)."""
+    w = W.WORKLOADS["tiny"].replace(name=case, **SWEEP_FINDS[case])
+    res = one_step(torch_cuda, w, min(w.rows, w.nstep + 3))
+    say(case, {k: v for k, v in res.items() if isinstance(v, dict)})
+    if case == "many_near_zero_gradients":
+        assert res["theta"]["near_zero_grad_entries"] > 0.003 * res["theta"]["of"]      # the case still is what it was found as
 
 
 @pytest.mark.parametrize("name", ["ant", "humanoid", "shadow", "scale"])
@@ -629,12 +664,12 @@ def test_standardised_sampling_and_actor_step(torch_cuda, case):
     for call in range(2):
         Bsz = w.batch if call == 0 else 7
         s.sample(Bsz)
-        assert_batch_matches(batch_to_numpy(s.batch, Bsz), oracle_batch(ring, w, Bsz, call, nz), normalized=True)
+        assert_batch_matches(batch_to_numpy(s.batch, Bsz), oracle_batch(ring, w, Bsz, call, nz), normalized=True, ring=ring)
     idx = np.arange(w.num_envs, dtype=np.int64)
     s.gather(torch.from_numpy(idx).cuda())
     got = batch_to_numpy(s.batch, idx.size)
     got["idx"] = idx
-    assert_batch_matches(got, O.normalize_batch(O.gather_nstep(ring, idx, w.nstep, w.gamma), nz), normalized=True)
+    assert_batch_matches(got, O.normalize_batch(O.gather_nstep(ring, idx, w.nstep, w.gamma), nz), normalized=True, ring=ring)
     assert np.array_equal(s.storage.obs.cpu().numpy(), ring.obs)          # the ring keeps raw observations
     row = W.transition_rows(w, np.random.default_rng(3), 1)[0]
     for call, num in enumerate((w.num_envs, 5)):
@@ -648,7 +683,7 @@ def test_standardised_sampling_and_actor_step(torch_cuda, case):
     # detaching restores the raw path bit for bit
     s.ctx.pql_obs_norm_attach(None, 0.0)
     s.sample(w.batch)
-    assert_batch_matches(batch_to_numpy(s.batch, w.batch), oracle_batch(ring, w, w.batch, 2, None))
+    assert_batch_matches(batch_to_numpy(s.batch, w.batch), oracle_batch(ring, w, w.batch, 2, None), ring=ring)
 
 
 @pytest.mark.parametrize("case,bound", [("tiny", 0.5), ("ragged", 0.5), ("ant_s", 0.5), ("fused_l3", 0.01),
@@ -834,7 +869,7 @@ def test_empty_batch_and_single_environment(torch_cuda):
         assert torch.equal(getattr(s.batch, k), v), k
     assert s.ctx.get_state()[3] == 1
     s.sample(w.batch)                                  # the next draw is call number 1 on both sides
-    assert_batch_matches(batch_to_numpy(s.batch, w.batch), oracle_batch(ring, w, w.batch, 1))
+    assert_batch_matches(batch_to_numpy(s.batch, w.batch), oracle_batch(ring, w, w.batch, 1), ring=ring)
     # one environment: its noise scale is sigma_min (Section 3.3 with N = 1)
     obs = np.random.default_rng(2).standard_normal((1, w.obs_dim), dtype=np.float32)
     got = s.act(torch.from_numpy(obs).cuda(), 0.3, 0.9).cpu().numpy()
@@ -1128,7 +1163,7 @@ def test_gradients_on_random_shapes(torch_cuda, seed):
         L = oracle_learner(w, s.actor_init, s.critic_init)
         s.sample(w.batch)
         batch = oracle_batch(ring, w, w.batch, 0, nz)
-        assert_batch_matches(batch_to_numpy(s.batch, w.batch), batch, normalized=nz is not None)
+        assert_batch_matches(batch_to_numpy(s.batch, w.batch), batch, normalized=nz is not None, ring=ring)
         s.critic_update(w.batch)
         losses, g = L.critic_update(batch)
         assert rel_err(s.critic_loss.cpu().numpy(), losses) <= TOL_ONE_STEP
