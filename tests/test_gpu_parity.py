@@ -275,7 +275,7 @@ def one_step(torch, w, rows, check_all=True):
     Bsz = w.batch
     s.sample(Bsz)
     batch = oracle_batch(ring, w, Bsz, 0, nz)
-    assert_batch_matches(batch_to_numpy(s.batch, Bsz), batch, normalized=nz is not None, ring=ring)
+    assert_batch_matches(batch_to_numpy(s.batch, Bsz), batch, normalized=nz is not None, ring=ring, normalizer=nz)
     # critic update
     s.critic_update(Bsz)
     losses, g = L.critic_update(batch)
@@ -664,12 +664,12 @@ def test_standardised_sampling_and_actor_step(torch_cuda, case):
     for call in range(2):
         Bsz = w.batch if call == 0 else 7
         s.sample(Bsz)
-        assert_batch_matches(batch_to_numpy(s.batch, Bsz), oracle_batch(ring, w, Bsz, call, nz), normalized=True, ring=ring)
+        assert_batch_matches(batch_to_numpy(s.batch, Bsz), oracle_batch(ring, w, Bsz, call, nz), normalized=True, ring=ring, normalizer=nz)
     idx = np.arange(w.num_envs, dtype=np.int64)
     s.gather(torch.from_numpy(idx).cuda())
     got = batch_to_numpy(s.batch, idx.size)
     got["idx"] = idx
-    assert_batch_matches(got, O.normalize_batch(O.gather_nstep(ring, idx, w.nstep, w.gamma), nz), normalized=True, ring=ring)
+    assert_batch_matches(got, O.normalize_batch(O.gather_nstep(ring, idx, w.nstep, w.gamma), nz), normalized=True, ring=ring, normalizer=nz)
     assert np.array_equal(s.storage.obs.cpu().numpy(), ring.obs)          # the ring keeps raw observations
     row = W.transition_rows(w, np.random.default_rng(3), 1)[0]
     for call, num in enumerate((w.num_envs, 5)):
@@ -1163,7 +1163,7 @@ def test_gradients_on_random_shapes(torch_cuda, seed):
         L = oracle_learner(w, s.actor_init, s.critic_init)
         s.sample(w.batch)
         batch = oracle_batch(ring, w, w.batch, 0, nz)
-        assert_batch_matches(batch_to_numpy(s.batch, w.batch), batch, normalized=nz is not None, ring=ring)
+        assert_batch_matches(batch_to_numpy(s.batch, w.batch), batch, normalized=nz is not None, ring=ring, normalizer=nz)
         s.critic_update(w.batch)
         losses, g = L.critic_update(batch)
         assert rel_err(s.critic_loss.cpu().numpy(), losses) <= TOL_ONE_STEP
