@@ -246,7 +246,20 @@ def run_workload(w, args, steps, warmup, profile_steps, isolated, keep_rows, sch
             sched.step(i)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        # four more regions of the same length, untouched by `value`: the spread of the measurement
+        rates = [steps / dt]
+        nxt = warmup + steps
+        for _ in range(max(1, args.repeats) - 1):
+            nxt += (-nxt) % ACTOR_EVERY
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for i in range(nxt, nxt + steps):
+                sched.step(i)
+            torch.cuda.synchronize()
+            rates.append(steps / (time.perf_counter() - t1))
+            nxt += steps
     else:
+        rates = None
         from paper_2307_12983_amd.scheme import ParallelSchemeSession
         ps = ParallelSchemeSession(sess, env_dev, horizon=1, v_updates=ACTOR_EVERY, p_updates=ACTOR_EVERY // POLICY_EVERY,
                                    concurrent=schedule == "parallel")
@@ -280,7 +293,7 @@ def run_workload(w, args, steps, warmup, profile_steps, isolated, keep_rows, sch
 
     # ---- per-kernel durations from HIP events on the launch stream, same schedule
     sess.ctx.pql_profile_begin(4096 * 4)
-    base = warmup + steps
+    base = nxt if rates is not None else warmup + steps
     base += (-base) % ACTOR_EVERY
     for i in range(base, base + profile_steps):
         sched.step(i)
@@ -336,6 +349,10 @@ def run_workload(w, args, steps, warmup, profile_steps, isolated, keep_rows, sch
         "actor_act_us": 1e6 * t_act,
         "kernels": kernels,
     }
+    if rates is not None:
+        # `value` is the first region (exactly `steps` steps after the warm-up); the others follow it directly
+        out["repeats"] = {"n": len(rates), "values": rates, "median": sorted(rates)[len(rates) // 2],
+                          "min": min(rates), "max": max(rates)}
     if isolated:
         out["critic_only_updates_per_s"] = 1.0 / t_critic
         out["critic_only_mfma_util_pct"] = 100.0 * w.batch * fl["critic_update"] / t_critic / (PEAK_FP32_MFMA_TFLOPS * 1e12)
@@ -366,6 +383,9 @@ def main():
                          "Actor, V-learner and P-learner on three streams with local network copies exchanged once "
                          "per Actor step (Section 3.1 / 3.2), same 1 : 8 : 4 rates.  parallel-1stream: that schedule "
                          "enqueued on one stream")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="timed regions of the serial schedule: the first one is `value`, the others (same length, "
+                         "run directly after it) are reported as `repeats` to show the spread")
     ap.add_argument("--no-isolated", dest="isolated", action="store_false",
                     help="skip the extra loops that time the V-learner alone (sample + critic update + Polyak) and "
                          "the policy update alone")
@@ -410,7 +430,8 @@ def main():
         out["secondary"] = {"metric": "V-learner critic updates/s at batch %d" % w2.batch, "value": r2["value"],
                             "unit": r2["unit"], "steps": r2["steps"], "warmup": r2["warmup"], "ms_per_step": r2["ms_per_step"],
                             "config": r2["config"], "roofline": r2["roofline"], "mfma_util_pct": r2["mfma_util_pct"],
-                            "actor_actions_per_s": r2["actor_actions_per_s"], "kernels": r2["kernels"]}
+                            "actor_actions_per_s": r2["actor_actions_per_s"], "kernels": r2["kernels"],
+                            "repeats": r2.get("repeats")}
     if not args.no_cpu_baseline:
         cb = cpu_baseline(w, keep, env_host, parallel=args.schedule != "serial")
         cb.update(host_info())
