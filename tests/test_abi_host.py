@@ -262,3 +262,69 @@ def test_followup_attachments_are_validated_on_the_host():
     bad.n_hidden = 0
     assert lib.pql_weight_cache_bytes(C.byref(bad)) == -1
     ctx.close()
+
+
+def test_header_is_plain_c_and_the_ctypes_structures_have_its_layout(tmp_path):
+    """include/pql.h must compile as C99 and as C++ on its own, and the binding's ctypes mirrors must have
+    the header's sizes and field offsets (a program compiled against the header prints them)."""
+    import shutil
+    import subprocess
+    gcc, gxx = shutil.which("gcc"), shutil.which("g++")
+    if not gcc or not gxx:
+        pytest.skip("no host C compiler")
+    header = os.path.join(ROOT, "include", "pql.h")
+    for cc, std, lang in ((gcc, "-std=c99", "c"), (gxx, "-std=c++11", "c++")):
+        r = subprocess.run([cc, std, "-x", lang, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", header],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+    mirrors = {"pql_config": B.PqlConfig, "pql_replay_storage": B.PqlStorage, "pql_batch": B.PqlBatch,
+               "pql_adam": B.PqlAdam, "pql_kernel_stat": B.PqlKernelStat}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "pql.h"', 'int main(void) {']
+    for cname, cls in mirrors.items():
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (cname, cname))
+        for field, _ in cls._fields_:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (cname, field, cname, field))
+    lines.append('printf("PQL_MAX_HIDDEN %d\\n", PQL_MAX_HIDDEN); return 0; }')
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    r = subprocess.run([gcc, "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    got = dict(l.split() for l in subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.splitlines())
+    assert int(got["PQL_MAX_HIDDEN"]) == B.PQL_MAX_HIDDEN
+    for cname, cls in mirrors.items():
+        assert int(got[cname]) == C.sizeof(cls), cname
+        for field, _ in cls._fields_:
+            assert int(got["%s.%s" % (cname, field)]) == getattr(cls, field).offset, "%s.%s" % (cname, field)
+
+
+def test_ctypes_prototypes_match_the_header():
+    """Every prototype of include/pql.h against the binding's restype / argtypes: same number of parameters,
+    scalars of the same width, structures by value of the mirrored class, pointers where the header has pointers."""
+    text = open(os.path.join(ROOT, "include", "pql.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    protos = re.findall(r"\b(int32_t|int64_t|const\s+char\s*\*)\s*(pql_[a-z_]+)\s*\(([^)]*)\)\s*;", text)
+    assert sorted(n for _, n, _ in protos) == sorted(B.EXPORTS)
+    scalars = {"int32_t": C.c_int32, "int64_t": C.c_int64, "float": C.c_float}
+    by_value = {"pql_replay_storage": B.PqlStorage, "pql_batch": B.PqlBatch, "pql_adam": B.PqlAdam}
+    lib = B.load_library()
+
+    def is_pointer(t):
+        return t in (C.c_void_p, C.c_char_p) or isinstance(t, type) and issubclass(t, C._Pointer)
+
+    for ret, name, params in protos:
+        fn = getattr(lib, name)
+        want_ret = C.c_char_p if "char" in ret else scalars[ret]
+        assert fn.restype is want_ret, name
+        plist = [p.strip() for p in params.split(",")] if params.strip() not in ("", "void") else []
+        assert len(plist) == len(fn.argtypes), "%s: %d parameters in the header, %d in the binding" % (name, len(plist), len(fn.argtypes))
+        for k, (p, t) in enumerate(zip(plist, fn.argtypes)):
+            where = "%s parameter %d (%s)" % (name, k, p)
+            if "*" in p or "[" in p:
+                assert is_pointer(t), where
+                continue
+            base = [tok for tok in p.split() if tok != "const"][0]
+            if base in by_value:
+                assert t is by_value[base], where
+            else:
+                assert t is scalars[base], where
