@@ -328,3 +328,51 @@ def test_ctypes_prototypes_match_the_header():
                 assert t is by_value[base], where
             else:
                 assert t is scalars[base], where
+
+
+def test_a_plain_c_program_links_against_the_library(tmp_path):
+    """The boundary from C itself (no Python, no torch): a C99 program includes the header, links libpql.so and
+    calls the host-side queries; its answers must be those the binding gets."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if not gcc:
+        pytest.skip("no host C compiler")
+    w = W.WORKLOADS["tiny"]
+    src = tmp_path / "client.c"
+    src.write_text('''
+#include <stdio.h>
+#include <string.h>
+#include "pql.h"
+int main(void) {
+    pql_config c;
+    pql_ctx *ctx = NULL, *none = NULL;
+    int64_t st[8];
+    memset(&c, 0, sizeof(c));
+    c.obs_dim = %d; c.act_dim = %d; c.num_envs = %d; c.capacity = %d; c.nstep = %d; c.gamma = 0.99f;
+    c.n_hidden = 2; c.hidden[0] = %d; c.hidden[1] = %d; c.max_batch = %d; c.seed = 7;
+    printf("%%d\\n", (int)pql_create(&c, &ctx));
+    printf("%%lld %%lld %%lld %%lld\\n", (long long)pql_replay_rows(&c), (long long)pql_actor_param_count(&c),
+           (long long)pql_critic_param_count(&c), (long long)pql_workspace_bytes(&c));
+    printf("%%d %%lld\\n", (int)pql_get_state(ctx, st), (long long)st[1]);
+    c.obs_dim = 0;
+    printf("%%d %%d\\n", (int)pql_create(&c, &none), none == NULL);
+    printf("%%s\\n", pql_last_error(NULL));
+    return pql_destroy(ctx) == PQL_OK ? 0 : 1;
+}
+''' % (w.obs_dim, w.act_dim, w.num_envs, w.capacity, w.nstep, w.hidden[0], w.hidden[1], max(w.batch, w.num_envs)))
+    libdir = os.path.dirname(B.LIB_PATH)
+    exe = tmp_path / "client"
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                        "-L", libdir, "-l:libpql.so", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    run = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert run.returncode == 0, run.stderr
+    out = run.stdout.splitlines()
+    ctx = B.Context(cfg_of(w))
+    assert out[0] == "0"
+    assert [int(x) for x in out[1].split()] == [ctx.replay_rows(), ctx.actor_param_count(), ctx.critic_param_count(),
+                                                ctx.workspace_bytes()]
+    assert out[2] == "0 0" and out[3] == "-1 1" and out[4] == "null context"
+    ctx.close()
