@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import shutil
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -47,7 +48,29 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
         print("built", LIB)
+    build_c_client(verbose)
     return LIB
+
+
+def build_c_client(verbose: bool = True) -> str:
+    """The plain C99 client of the library that tests/test_zy_c_client.py runs on the GPU (host compiler only:
+    it holds no device code; the run-time search path is relative to the binary, so the tree can be moved)."""
+    src = os.path.join(ROOT, "tests", "c_client", "pql_client.c")
+    exe = os.path.join(ROOT, "tests", "c_client", "pql_client")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cc = next((c for c in ("gcc", "cc", os.path.join(rocm, "lib", "llvm", "bin", "clang")) if shutil.which(c)), None)
+    if cc is None:
+        raise RuntimeError("no host C compiler found for tests/c_client/pql_client.c")
+    cmd = [cc, "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__",
+           "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(rocm, "include"), src, "-o", exe,
+           "-L" + HERE, "-l:libpql.so", "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2307_12983_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building the C client failed:\n" + r.stderr)
+    if verbose:
+        print("built", exe)
+    return exe
 
 
 if __name__ == "__main__":
