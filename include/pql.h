@@ -224,7 +224,11 @@ int32_t pql_critic_update(pql_ctx* ctx, float* critic_params, const float* criti
  * widths: obs_dim 60, act_dim 8, two hidden layers of 256 fit up to max_batch 3416).
  * All calls on one GPU, from any context, share that GPU's array: its contents are undefined between
  * calls (nothing in it has to start at zero), and two such calls that overlap on one GPU (different
- * streams or threads) race and give undefined results; order them on one stream. */
+ * streams or threads) race and give undefined results; order them on one stream.
+ * Under graph capture the scalars of the captured call are part of the graph, as with every call of this
+ * library: the step number of Adam's bias correction (and, with a stochastic policy, the call number
+ * that selects the draws) are those of the capture, and the context's counters advance once, at capture
+ * time; a replay repeats exactly that step. */
 int64_t pql_static_scratch_bytes(void);
 int32_t pql_critic_update_static(pql_ctx* ctx, float* critic_params, const float* critic_target_params,
                                  const float* actor_target_params, float* adam_m, float* adam_v, float* grads_out,
