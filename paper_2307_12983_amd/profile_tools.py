@@ -113,6 +113,20 @@ def traffic_summary(fetch_csv, write_csv, kernel, out, bench_args="--steps 96 --
             f.write("%s_kib_per_launch=%.1f\n%s_calibration_kib=%.1f\n%s_scale=%.4f\n%s_bytes_per_launch=%.0f\n" % (
                 label, r["avg_kib"], label, r["cal_kib"], label, r["scale"], label, r["bytes"]))
         f.write("traffic_bytes_per_launch=%.0f\n" % total)
+        # the other kernels of the library in the same two passes (same scaling, launches after the first quarter)
+        f.write("# Other kernels of the same passes, bytes per launch (fetch, write), launches averaged:\n")
+        per = {}
+        for label, path, counter in (("fetch", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
+            for name, _, val in _per_dispatch(path, counter):
+                if "pql::" in name and short_name(name) != kernel and "copy_kernel" not in name and "mfma_probe" not in name:
+                    per.setdefault(short_name(name), {}).setdefault(label, []).append(val)
+        for name in sorted(per):
+            vals = {}
+            for label in ("fetch", "write"):
+                v = per[name].get(label, [])
+                v = v[len(v) // 4:]
+                vals[label] = (sum(v) / len(v) * 1024.0 * res[label]["scale"], len(v)) if v else (0.0, 0)
+            f.write("other.%s=%.0f,%.0f,%d\n" % (name, vals["fetch"][0], vals["write"][0], vals["fetch"][1]))
 
 
 def stored_traffic(path, kernel):
