@@ -60,9 +60,9 @@ size_t fused_lds_bytes(int o, int a, int hmax) { return sizeof(float) * (size_t)
 
 // Hidden layers of NN equally shaped networks on the tile: layer 1 reads XA (and XB when
 // a_cols > 0), later layers ping-pong between the two tiles of each network.  Returns the index of
-// the tile holding the last hidden activations.  With keep_hidden, hG[n][l] (l = 1..L-1, and L with
-// store_last) receives h_l; the flag is separate from the pointers so that no address derived from
-// the kernel's argument block is ever compared (that would force a private copy of the block).
+// the tile holding the last hidden activations.  With keep_hidden, hG[n][l] (l = 1..keep_upto, L - 1 by
+// default, and L with store_last) receives h_l; the flag is separate from the pointers so that no address
+// derived from the kernel's argument block is ever compared (that would force a private copy of the block).
 // Rows to bring into XA / XB as soon as the first layer has consumed them (their load latency then
 // hides behind the remaining layers instead of standing alone before the next chain).
 struct NextInputs { const float* xa; int xa_cols; const float* xb; int xb_cols; };
@@ -70,8 +70,9 @@ struct NextInputs { const float* xa; int xa_cols; const float* xb; int xb_cols; 
 template <int NN>
 __device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const FusedNet* const (&nets)[NN], const int* Hw,
                                      int L, int o, int a_cols, bool keep_hidden, float* const* const (&hG)[NN], int r0,
-                                     int B, bool store_last = false, const NextInputs* next = nullptr) {
+                                     int B, bool store_last = false, const NextInputs* next = nullptr, int keep_upto = -1) {
     int cur = 0;
+    const int kept = keep_upto < 0 ? L - 1 : keep_upto;
     for (int l = 0; l < L; ++l) {
         const int N = Hw[l];
         WideArgs<NN> w;
@@ -88,7 +89,7 @@ __device__ inline int hidden_forward(const Lanes& T, const TileMem& m, const Fus
             }
             w.bias[n] = nets[n]->b[l]; w.aux[n] = 0;
             w.outL[n] = m.Ht(n, dst);
-            w.outG[n] = (keep_hidden && (l < L - 1 || store_last)) ? hG[n][l + 1] : nullptr;
+            w.outG[n] = (keep_hidden && (l < kept || (store_last && l == L - 1))) ? hG[n][l + 1] : nullptr;
             w.colsum[n] = nullptr;
         }
         if (l == 0) { w.ld0 = m.SXA; w.K0 = o; w.ld1 = m.SXB; w.K1 = a_cols; }
@@ -568,9 +569,11 @@ __global__ __launch_bounds__(FT) void fused_policy_kernel(const FusedPolicyArgs 
     }
     __syncthreads();
     {
+        // the critics' activations leave the chip only where the backward pass below reads them back: h_{L-1}
+        // is still in its tile when that pass starts (unless the dlogits of distributional critics took it)
         const FusedNet* const nets[2] = {&A.q[0], &A.q[1]};
         float* const* const hg[2] = {A.hQ[0], A.hQ[1]};
-        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, true, hg, r0, B, DIST);
+        cur = hidden_forward<2>(T, m, nets, A.H, L, o, a, true, hg, r0, B, DIST, nullptr, DIST ? L - 1 : L - 2);
     }
     float loss_acc = 0.f;
     if (DIST) {
