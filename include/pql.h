@@ -32,6 +32,11 @@
  *   Streams        `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device
  *                  calls enqueue work and return; none of them synchronises.  Scalar results
  *                  (losses) are written to caller-provided device floats.
+ *   Threads        A context is plain host state without locks: calls on one context must not overlap
+ *                  in time.  Different contexts may be driven from different threads; what the
+ *                  library keeps per process (the address of each device's static scratch, the
+ *                  dynamic-LDS grants of its kernels per device) is locked.  The per-launch timing
+ *                  of pql_profile_begin / pql_profile_end is process-wide and meant for one thread.
  *   Workspace      pql_actor_act, pql_critic_update and pql_actor_update take a caller-owned
  *                  [device] scratch buffer of at least pql_workspace_bytes(cfg) bytes, 256-byte
  *                  aligned.  Its contents are undefined between calls.  Two calls that use the

@@ -28,15 +28,21 @@ struct Profiler {
 } g_prof;
 const char* const k_gemm_mode[3] = {"nn", "nt", "tn"};
 const char* const k_gemm_tile[5] = {"128x128", "64x64", "128x32", "128x64", "128x32_noise"};
-char g_name_buf[64];
+
+// Names of the 15 (mode, tile) instances of the LDS-tiled GEMM kernel, built once (thread-safe: a function-local static).
+const std::vector<std::string>& gemm_names() {
+    static const std::vector<std::string> names = [] {
+        std::vector<std::string> v;
+        for (int k = 0; k < 15; ++k) v.push_back(std::string("gemm_grouped_") + k_gemm_mode[k / 5] + "_" + k_gemm_tile[k % 5]);
+        return v;
+    }();
+    return names;
+}
 }  // namespace
 
 const char* kernel_name(int kid) {
     if (kid == KID_GEMM + GEMM_TN * 5 + TILE_64x64) return "gemm_tn_stream_kernel";   // small weight gradients
-    if (kid >= KID_GEMM && kid < KID_GEMM + 15) {
-        std::snprintf(g_name_buf, sizeof(g_name_buf), "gemm_grouped_%s_%s", k_gemm_mode[kid / 5], k_gemm_tile[kid % 5]);
-        return g_name_buf;
-    }
+    if (kid >= KID_GEMM && kid < KID_GEMM + 15) return gemm_names()[kid - KID_GEMM].c_str();
     switch (kid) {
         case KID_PUSH: return "push_kernel";
         case KID_SAMPLE: return "sample_kernel";

@@ -452,18 +452,12 @@ __global__ __launch_bounds__(FT) void chain_act_kernel(const FusedActArgs A, con
 }
 
 // ---- launches ------------------------------------------------------------------------------------
-static hipError_t chain_lds_limit(const void* fn, size_t lds, size_t& configured) {
-    if (lds <= configured) return hipSuccess;
-    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e == hipSuccess) configured = lds;
-    return e;
-}
 
 hipError_t chain_critic_launch(const FusedCriticArgs& a, hipStream_t stream) {
     if (!chain_shape_ok(a.o, a.a, a.H, a.L) || a.atoms >= 2 || a.sac.on) return hipErrorInvalidValue;
     const size_t lds = chain_lds_bytes(a.o, a.a, a.H, a.L);
-    static size_t configured = 0;
-    const hipError_t le = chain_lds_limit(reinterpret_cast<const void*>(chain_critic_kernel), lds, configured);
+    static LdsLimit configured;
+    const hipError_t le = set_lds_limit(reinterpret_cast<const void*>(chain_critic_kernel), lds, configured);
     if (le != hipSuccess) return le;
     const int pool = chain_pool_floats(a.o, a.H, a.L);
     const ProfSlot ps = prof_slot();
@@ -482,8 +476,8 @@ hipError_t chain_critic_launch(const FusedCriticArgs& a, hipStream_t stream) {
 hipError_t chain_policy_launch(const FusedPolicyArgs& a, hipStream_t stream) {
     if (!chain_shape_ok(a.o, a.a, a.H, a.L) || a.atoms >= 2 || a.sac.on) return hipErrorInvalidValue;
     const size_t lds = chain_lds_bytes(a.o, a.a, a.H, a.L);
-    static size_t configured = 0;
-    const hipError_t le = chain_lds_limit(reinterpret_cast<const void*>(chain_policy_kernel), lds, configured);
+    static LdsLimit configured;
+    const hipError_t le = set_lds_limit(reinterpret_cast<const void*>(chain_policy_kernel), lds, configured);
     if (le != hipSuccess) return le;
     const int pool = chain_pool_floats(a.o, a.H, a.L);
     const ProfSlot ps = prof_slot();
@@ -502,8 +496,8 @@ hipError_t chain_policy_launch(const FusedPolicyArgs& a, hipStream_t stream) {
 hipError_t chain_act_launch(const FusedActArgs& a, hipStream_t stream) {
     if (!chain_shape_ok(a.o, a.a, a.H, a.L) || a.sac.on) return hipErrorInvalidValue;
     const size_t lds = chain_lds_bytes(a.o, a.a, a.H, a.L);
-    static size_t configured = 0;
-    const hipError_t le = chain_lds_limit(reinterpret_cast<const void*>(chain_act_kernel), lds, configured);
+    static LdsLimit configured;
+    const hipError_t le = set_lds_limit(reinterpret_cast<const void*>(chain_act_kernel), lds, configured);
     if (le != hipSuccess) return le;
     const int pool = chain_pool_floats(a.o, a.H, a.L);
     const ProfSlot ps = prof_slot();

@@ -838,17 +838,9 @@ __global__ __launch_bounds__(FT) void fused_act_kernel(const FusedActArgs A) {
     }
 }
 
-static hipError_t set_lds_limit(const void* fn, size_t lds, size_t& configured) {
-    if (lds <= configured) return hipSuccess;
-    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e == hipSuccess) configured = lds;
-    return e;
-}
-
 hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream) {
     const size_t lds = fused_lds_bytes(a.o, a.sac.on ? 2 * a.a : a.a, a.hmax);
-    static size_t configured = 0;
-    static size_t configured_d = 0;
+    static LdsLimit configured, configured_d;
     const bool dist = a.atoms >= 2;
     const hipError_t e = dist ? set_lds_limit(reinterpret_cast<const void*>(fused_policy_kernel<true>), lds, configured_d)
                               : set_lds_limit(reinterpret_cast<const void*>(fused_policy_kernel<false>), lds, configured);
@@ -873,7 +865,7 @@ hipError_t fused_policy_launch(const FusedPolicyArgs& a, hipStream_t stream) {
 
 hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream) {
     const size_t lds = fused_lds_bytes(a.o, a.sac.on ? 2 * a.a : a.a, a.hmax);
-    static size_t configured = 0;
+    static LdsLimit configured;
     const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(fused_act_kernel), lds, configured);
     if (e != hipSuccess) return e;
     const ProfSlot ps = prof_slot();
@@ -891,7 +883,7 @@ hipError_t fused_act_launch(const FusedActArgs& a, hipStream_t stream) {
 
 hipError_t fused_critic_launch(const FusedCriticArgs& a, hipStream_t stream) {
     const size_t lds = fused_lds_bytes(a.o, a.sac.on ? 2 * a.a : a.a, a.hmax);
-    static size_t configured = 0, configured_d = 0;
+    static LdsLimit configured, configured_d;
     const bool dist = a.atoms >= 2;
     const hipError_t le = dist ? set_lds_limit(reinterpret_cast<const void*>(fused_critic_kernel<true>), lds, configured_d)
                                : set_lds_limit(reinterpret_cast<const void*>(fused_critic_kernel<false>), lds, configured);
@@ -1065,7 +1057,7 @@ hipError_t layer_rowtile_launch(GemmGroup& g, hipStream_t stream) {
     }
     g.total_tiles = total;
     if (total == 0) return hipSuccess;
-    static size_t configured = 0;
+    static LdsLimit configured;
     const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(layer_rowtile_kernel), lds, configured);
     if (e != hipSuccess) return e;
     const ProfSlot ps = prof_slot();
@@ -1196,7 +1188,7 @@ hipError_t narrow_rowtile_launch(GemmGroup& g, hipStream_t stream) {
     }
     g.total_tiles = total;
     if (total == 0) return hipSuccess;
-    static size_t configured = 0;
+    static LdsLimit configured;
     const hipError_t e = set_lds_limit(reinterpret_cast<const void*>(narrow_rowtile_kernel), lds, configured);
     if (e != hipSuccess) return e;
     const ProfSlot ps = prof_slot();

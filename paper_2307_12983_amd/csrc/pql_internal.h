@@ -6,6 +6,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "pql.h"
 
 namespace pql {
@@ -38,6 +40,25 @@ void prof_commit(const ProfSlot& s, int kid, double flops, double bytes);
         else                                                                                                 \
             hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                               \
     } while (0)
+
+// Largest dynamic-LDS size granted so far to one kernel, per device (the attribute belongs to the device's
+// copy of the function).  The grant only grows, under a lock, so that launches of the same kernel from several
+// threads with different tile sizes never see it shrink between their request and their launch.
+struct LdsLimit {
+    std::mutex mu;
+    size_t granted[64] = {};
+};
+inline hipError_t set_lds_limit(const void* fn, size_t lds, LdsLimit& lim) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(lim.mu);
+    if (lds <= lim.granted[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) lim.granted[dev] = lds;
+    return e;
+}
 
 // ---- grouped fp32 MFMA GEMM ------------------------------------------------------------
 // One launch computes several independent problems C_p = epi(sum_seg A_seg * B_seg).  A problem

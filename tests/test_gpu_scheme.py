@@ -135,3 +135,64 @@ def test_three_streams_equal_one_stream_bit_for_bit(torch_cuda, case, fold):
             continue
         assert torch.equal(a[k], b[k]), "%s differs between the one-stream and the three-stream run" % k
     say(case, "bit-identical over 6 periods; critic moved by", float((a["critic"] - torch.from_numpy(s.critic_init).cuda()).abs().max()))
+
+
+def test_two_contexts_driven_from_two_threads(torch_cuda):
+    """Two learners with their own contexts, buffers and streams, driven from two host threads at the same time
+    (ctypes releases the interpreter lock during a call, so the library's calls do overlap), must end where
+    the same two learners end when run one after the other: the library keeps nothing per process that one
+    context's calls could disturb for another's."""
+    import threading
+    torch = torch_cuda
+    from paper_2307_12983_amd.session import LearnerSession
+    shapes = [CASES["ant_s"], CASES["ragged"]]
+
+    def learner(w):
+        s = LearnerSession(w)
+        for row in W.transition_rows(w, W.data_rng(w), w.nstep + 4):
+            s.push(row)
+        torch.cuda.synchronize()
+        return s
+
+    def run(s, stream, steps=24):
+        w = s.w
+        with torch.cuda.stream(stream):
+            for it in range(steps):
+                s.sample(w.batch)
+                s.critic_update(w.batch)
+                s.soft_update_targets()
+                if it % 2 == 1:
+                    s.actor_update(None, w.batch)
+                    s.sync_lagged_policy()
+            stream.synchronize()
+
+    def state(s):
+        return [t.clone() for t in (s.critic, s.critic_target, s.actor, s.actor_lag, s.c_m, s.c_v, s.a_m, s.a_v)]
+
+    # one after the other, each on a stream of its own
+    ref = []
+    for w in shapes:
+        s = learner(w)
+        run(s, torch.cuda.Stream())
+        ref.append(state(s))
+    # both at once, one host thread each
+    sessions = [learner(w) for w in shapes]
+    errors = []
+
+    def worker(s):
+        try:
+            run(s, torch.cuda.Stream())
+        except Exception as e:      # reported by the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(s,)) for s in sessions]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+        assert not t.is_alive(), "a learner thread did not finish"
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for s, r in zip(sessions, ref):
+        for got, want in zip(state(s), r):
+            assert torch.equal(got, want)
