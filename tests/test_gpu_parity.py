@@ -604,20 +604,22 @@ def test_100_updates_reduced_batch(torch_cuda, name):
     say(name, "100 steps", res)
 
 
-@pytest.mark.parametrize("name,Bsz,actor_every", [("humanoid", 8192, 10), ("shadow", 8192, 0), ("scale", 8192, 0)])
-def test_100_updates_through_the_row_tile_layer_kernels(torch_cuda, name, Bsz, actor_every):
-    """100 critic updates with the networks of the large workloads at a batch size that takes the kernels the
-    benchmark runs them on: humanoid at its own batch 8192 (with a policy update every 10th step, so the
-    policy path's single-network launches take them too), shadow and scale at batch 8192 instead of 16384 /
-    32768 (the float64 oracle needs 0.5 - 0.8 s per update at 8192; every launch of the critic update then
-    has the 256 row tiles from which the row-tile layer kernels are used; the full batches are covered by
-    the one-step test).  The library's per-launch profile must name the row-tile kernels."""
+@pytest.mark.parametrize("name,Bsz,actor_every,steps", [("humanoid", 8192, 10, 100), ("shadow", 16384, 0, 100),
+                                                        ("scale", 8192, 0, 100), ("scale", 32768, 0, 16)])
+def test_100_updates_through_the_row_tile_layer_kernels(torch_cuda, name, Bsz, actor_every, steps):
+    """Many critic updates with the networks of the large workloads on the kernels the benchmark runs them on:
+    humanoid (batch 8192, with a policy update every 10th step, so the policy path's launches are covered too)
+    and shadow (batch 16384) at their own batch sizes for 100 steps; scale for 100 steps at batch 8192 instead of
+    32768 (the float64 oracle needs 0.8 s per update there and 3 s at 32768) and for 16 steps at its own batch.
+    Every launch of the critic update has at least the 256 row tiles from which the row-tile kernels are used;
+    the library's per-launch profile must name them.  (The ring is shortened to 1024 environments: the
+    full rings are covered by the one-step tests.)"""
     base = W.WORKLOADS[name]
     w = base.replace(num_envs=1024, capacity=1024 * (base.nstep + 9), batch=Bsz)
     need = (("chain_critic_kernel",) + (("chain_policy_kernel",) if actor_every else ()) if name != "scale" else
             ("layer_rowtile_kernel", "narrow_rowtile_kernel")) + ("gemm_tn_stream_kernel",)
-    res = many_steps(torch_cuda, w, w.rows, 100, actor_every=actor_every, must_run=need)
-    say(name, "batch", Bsz, "100 steps", res)
+    res = many_steps(torch_cuda, w, w.rows, steps, actor_every=actor_every, must_run=need)
+    say(name, "batch", Bsz, steps, "steps", res)
 
 
 def test_100_updates_row_tile_layers(torch_cuda):
